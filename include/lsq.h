@@ -1,0 +1,191 @@
+/*
+ * lsq.h — C-ABI of the fused, memory-bound (non-GEMM) kernels of one Transformer
+ * training step on AMD MI355X (gfx950): LayerNorm, bias+dropout+residual,
+ * attention softmax, label-smoothed cross-entropy and the mixed-precision Adam
+ * trainer, each forward and backward, as the LightSeq2 paper (arXiv 2110.05722)
+ * states them in Sec. IV-A (computational graph optimisations), Sec. IV-B
+ * (dependent reduction rewriting) and Sec. IV-C (mixed-precision trainer).
+ *
+ * Conventions that hold for every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller; the library
+ *     allocates nothing, frees nothing and never synchronises.  Work is
+ *     enqueued on `stream` (a hipStream_t passed as void*; NULL = the null
+ *     stream) and the call returns as soon as the launches are queued.
+ *   - Tensors are dense, row-major, innermost dimension contiguous.  Base
+ *     pointers must be 16-byte aligned (LSQ_MISALIGNED otherwise); inner
+ *     dimensions are arbitrary (the paper's "arbitrary shape of inputs",
+ *     Sec. III).
+ *   - `dt` is the storage type of activations / gradients / parameters
+ *     (LSQ_F16, LSQ_BF16, or LSQ_F32).  All arithmetic and accumulation is
+ *     fp32 (Sec. IV-B, last paragraph on LayerNorm: low-precision storage,
+ *     single-precision computation).  Results are rounded once, to nearest
+ *     even, when stored.
+ *   - Outputs must not alias inputs except where a comment says they may.
+ *   - Results are bit-reproducible from run to run: no floating-point atomics.
+ *   - Return value: LSQ_OK, or an error code; on error nothing was launched.
+ *     Sizes of zero (rows == 0, n == 0, ...) are valid and launch nothing.
+ *
+ * Dropout contract (the paper fixes no generator; Sec. IV-A only names the op)
+ *   Philox4x32-10 (Salmon et al., SC'11) keyed by `seed`, one call per group of
+ *   8 consecutive elements: for flat element index e (row-major over the whole
+ *   tensor), group g = e / 8, key = (seed_lo, seed_hi),
+ *   counter = (g_lo, g_hi, offset_lo, offset_hi).  The four 32-bit output words
+ *   w0..w3 are cut into eight 16-bit lanes; element e uses lane e % 8, i.e.
+ *   r16 = (w[(e%8)/2] >> (16*(e%2))) & 0xFFFF.  With T16 = round(p * 65536)
+ *   (host double arithmetic, clamped to [0, 65535]) the element is KEPT iff
+ *   r16 >= T16, and kept values are scaled by 1/(1-p) (inverted dropout, the
+ *   nominal p).  p == 0 keeps everything and draws nothing.  Nothing is stored:
+ *   the backward entry points regenerate the mask from (seed, offset).
+ */
+#ifndef LSQ_H_
+#define LSQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LSQ_OK = 0,
+    LSQ_INVALID_ARG = 1,         /* null pointer, negative size, p outside [0,1), step < 1 ... */
+    LSQ_UNSUPPORTED_DTYPE = 2,
+    LSQ_MISALIGNED = 3,          /* a base pointer is not 16-byte aligned */
+    LSQ_WORKSPACE_TOO_SMALL = 4,
+    LSQ_LAUNCH_FAILED = 5        /* the HIP runtime rejected a launch */
+} lsq_status;
+
+typedef enum { LSQ_F16 = 0, LSQ_BF16 = 1, LSQ_F32 = 2 } lsq_dtype;
+
+/* Operators that need a caller-supplied device workspace (column reductions). */
+typedef enum { LSQ_OP_LAYERNORM_BWD = 0, LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD = 1 } lsq_op;
+
+/* Bytes of device workspace `op` needs for a [rows, cols] problem (0 if none).
+ * Contents on entry are ignored; contents on exit are unspecified. */
+size_t lsq_workspace_bytes(int32_t op, int64_t rows, int32_t cols);
+
+/* Static, human-readable name of a status code. */
+const char* lsq_status_string(lsq_status s);
+
+/* LayerNorm forward (Sec. IV-B, LayerNorm equation):
+ *   y[r,i] = gamma[i] * (x[r,i] - mean[r]) * rstd[r] + beta[i],
+ *   mean[r] = sum_i x[r,i] / hidden,  rstd[r] = 1/sqrt(var[r] + eps),
+ *   var = biased variance (divide by hidden), as the paper's mu(x^2)-mu(x)^2
+ *   form implies.  The variance is taken about the mean in a second pass over
+ *   registers, so it cannot go negative.
+ * x, y: [rows, hidden] dt;  gamma, beta: [hidden] dt;  mean, rstd: [rows] fp32
+ * (saved for backward).  Errors: null pointers, rows < 0, hidden <= 0, eps < 0. */
+lsq_status lsq_layernorm_fwd(void* y, float* mean, float* rstd,
+                             const void* x, const void* gamma, const void* beta,
+                             int64_t rows, int32_t hidden, float eps,
+                             lsq_dtype dt, void* stream);
+
+/* LayerNorm backward (Sec. IV-B, the gradient equation after "the final gradient"):
+ *   xhat = (x - mean) * rstd,  g_i = gamma_i * dy_i,
+ *   dx_i = rstd * (g_i - (sum_j g_j + xhat_i * sum_j g_j xhat_j) / hidden) [+ dres_in_i]
+ *   dgamma_i = sum_rows dy_i * xhat_i,   dbeta_i = sum_rows dy_i
+ * (dgamma/dbeta are the standard parameter gradients; the paper prints only dx).
+ * dy, x, dx: [rows, hidden] dt;  gamma: [hidden] dt;  mean, rstd: [rows] fp32 as
+ * written by the forward;  dgamma, dbeta: [hidden] fp32, overwritten;
+ * dres_in: nullable [rows, hidden] dt, added into dx (gradient arriving over the
+ * residual branch of a pre-LayerNorm block).  dx may alias dy or dres_in.
+ * workspace: >= lsq_workspace_bytes(LSQ_OP_LAYERNORM_BWD, rows, hidden) bytes. */
+lsq_status lsq_layernorm_bwd(void* dx, float* dgamma, float* dbeta,
+                             const void* dy, const void* x, const void* gamma,
+                             const float* mean, const float* rstd, const void* dres_in,
+                             void* workspace, size_t workspace_bytes,
+                             int64_t rows, int32_t hidden, lsq_dtype dt, void* stream);
+
+/* Fused bias + dropout + residual, forward (Sec. IV-A, Transformer layers: the
+ * last kernel of the self-attention block):
+ *   out[r,i] = residual[r,i] + keep[r,i] * (x[r,i] + bias[i]) / (1 - p)
+ * x, residual, out: [rows, hidden] dt;  bias: nullable [hidden] dt.
+ * out may alias x or residual.  p in [0,1).  Dropout contract above, flat index
+ * e = r*hidden + i. */
+lsq_status lsq_bias_dropout_residual_fwd(void* out, const void* x, const void* bias,
+                                         const void* residual, int64_t rows, int32_t hidden,
+                                         float p, uint64_t seed, uint64_t offset,
+                                         lsq_dtype dt, void* stream);
+
+/* Backward of the above: dx = keep * dy / (1-p) with the mask regenerated from
+ * (seed, offset);  dbias[i] = sum_rows dx[r,i] (nullable; fp32 [hidden],
+ * overwritten).  The gradient of `residual` is dy itself: the caller aliases it.
+ * dx may alias dy.  workspace: >= lsq_workspace_bytes(LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD,
+ * rows, hidden) bytes, only read when dbias != NULL. */
+lsq_status lsq_bias_dropout_residual_bwd(void* dx, float* dbias, const void* dy,
+                                         int64_t rows, int32_t hidden,
+                                         float p, uint64_t seed, uint64_t offset,
+                                         void* workspace, size_t workspace_bytes,
+                                         lsq_dtype dt, void* stream);
+
+/* Attention softmax forward (Sec. IV-B, Softmax: the three-step stable form) over
+ * the last axis of x[batch, heads, q_len, k_len], restricted to the allowed set
+ *   A(b,i) = { j : j < key_len[b] }  intersected, if causal != 0, with
+ *            { j : j <= i + (k_len - q_len) }:
+ *   m = max_{j in A} scale*x_j;  Z = sum_{j in A} exp(scale*x_j - m);
+ *   y_j = exp(scale*x_j - m) / Z for j in A, and exactly +0 for j not in A
+ * (an empty A gives an all-zero row).  If p_attn > 0, y_drop = keep * y / (1-p_attn)
+ * is written as well (dropout contract above, flat index over the whole tensor).
+ * key_len: nullable int32[batch] (NULL = every key allowed), values clamped to
+ * [0, k_len].  y_drop must be non-NULL iff p_attn > 0.  y may alias x. */
+lsq_status lsq_softmax_fwd(void* y, void* y_drop, const void* x, const int32_t* key_len,
+                           int32_t batch, int32_t heads, int32_t q_len, int32_t k_len,
+                           int32_t causal, float scale,
+                           float p_attn, uint64_t seed, uint64_t offset,
+                           lsq_dtype dt, void* stream);
+
+/* Attention softmax backward (the softmax Jacobian of Sec. IV-A, criterion layer,
+ * contracted with the upstream gradient):
+ *   dx_j = scale * y_j * (dyy_j - sum_{k in A} dyy_k y_k),  0 outside A,
+ * where dyy = dy if p_attn == 0, else keep * dy / (1-p_attn) with dy the
+ * gradient of y_drop.  y is the tensor the forward stored.  dx may alias dy. */
+lsq_status lsq_softmax_bwd(void* dx, const void* dy, const void* y, const int32_t* key_len,
+                           int32_t batch, int32_t heads, int32_t q_len, int32_t k_len,
+                           int32_t causal, float scale,
+                           float p_attn, uint64_t seed, uint64_t offset,
+                           lsq_dtype dt, void* stream);
+
+/* Label-smoothed cross-entropy forward (Sec. IV-A, criterion layer): per token,
+ * with q = softmax(h) over the whole vocabulary and p = (1-alpha)*onehot(k) + alpha/V,
+ *   loss = -sum_i p_i log q_i = lse - (1-alpha)*h_k - (alpha/V) * sum_i h_i,
+ *   lse  = log sum_i exp(h_i).
+ * logits: [tokens, vocab] dt;  target: int32[tokens];  loss, lse: fp32[tokens].
+ * A token whose target equals ignore_index or lies outside [0, vocab) is ignored:
+ * loss = 0 (lse is still written).  sums: nullable fp32[3] = { sum loss,
+ * sum of -log q_k, number of non-ignored tokens }, reduced in a fixed order. */
+lsq_status lsq_ls_xent_fwd(float* loss, float* lse, float* sums,
+                           const void* logits, const int32_t* target,
+                           int64_t tokens, int32_t vocab, float alpha, int32_t ignore_index,
+                           lsq_dtype dt, void* stream);
+
+/* Backward of the criterion (Sec. IV-A, the final gradient to the decoder output):
+ *   dlogits_i = grad_scale * (exp(h_i - lse) - alpha/V - (1-alpha)*[i == k]),
+ * all zero for ignored tokens.  lse: as written by the forward.  dlogits may
+ * alias logits (in-place). */
+lsq_status lsq_ls_xent_bwd(void* dlogits, const void* logits, const float* lse,
+                           const int32_t* target, int64_t tokens, int32_t vocab,
+                           float alpha, int32_t ignore_index, float grad_scale,
+                           lsq_dtype dt, void* stream);
+
+/* Mixed-precision Adam over one flat workspace, one launch (Sec. IV-C): the
+ * low-precision gradient is converted on the fly, the update runs in fp32
+ * registers, and each element is read and written once.
+ *   ghat = g * inv_grad_scale (+ weight_decay * p if adamw == 0)
+ *   m = beta1*m + (1-beta1)*ghat;  v = beta2*v + (1-beta2)*ghat^2
+ *   c1 = 1 - beta1^step, c2 = 1 - beta2^step (both 1 if bias_correction == 0)
+ *   p = p - lr * ( (m/c1) / (sqrt(v/c2) + eps) + (adamw ? weight_decay*p : 0) )
+ *   p_lp = round-to-nearest-even(p) in p_lp_dt   (nullable: the copy the next
+ *   forward pass reads)
+ * p, m, v: fp32[n], updated in place;  g: [n] g_dt (LSQ_F32 allowed);
+ * p_lp: nullable [n] p_lp_dt.  Errors: step < 1, n < 0, beta outside [0,1). */
+lsq_status lsq_adam_step(float* p, float* m, float* v, const void* g, void* p_lp,
+                         int64_t n, float lr, float beta1, float beta2, float eps,
+                         float weight_decay, int32_t step, int32_t adamw,
+                         int32_t bias_correction, float inv_grad_scale,
+                         lsq_dtype g_dt, lsq_dtype p_lp_dt, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSQ_H_ */
