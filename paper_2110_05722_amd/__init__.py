@@ -1,0 +1,31 @@
+"""MI355X-native fused non-GEMM Transformer training kernels (LightSeq2's hot path).
+
+Thin Python binding over the C-ABI library `liblsq.so` (declared in
+`include/lsq.h`).  PyTorch is used for device memory and streams only: every
+function below marshals pointers and sizes and calls the entry point of the
+same name; all arithmetic runs in the hand-written gfx950 kernels.  There is no
+CPU fallback: if the library is missing, or a tensor is not on the GPU, the call
+raises.
+"""
+from .binding import (  # noqa: F401
+    LsqError,
+    lib_path,
+    load,
+    lsq_adam_step,
+    lsq_bias_dropout_residual_bwd,
+    lsq_bias_dropout_residual_fwd,
+    lsq_layernorm_bwd,
+    lsq_layernorm_fwd,
+    lsq_ls_xent_bwd,
+    lsq_ls_xent_fwd,
+    lsq_softmax_bwd,
+    lsq_softmax_fwd,
+    lsq_status_string,
+    lsq_workspace_bytes,
+)
+
+__all__ = [
+    "LsqError", "lib_path", "load", "lsq_adam_step", "lsq_bias_dropout_residual_bwd",
+    "lsq_bias_dropout_residual_fwd", "lsq_layernorm_bwd", "lsq_layernorm_fwd", "lsq_ls_xent_bwd",
+    "lsq_ls_xent_fwd", "lsq_softmax_bwd", "lsq_softmax_fwd", "lsq_status_string", "lsq_workspace_bytes",
+]

@@ -1,0 +1,215 @@
+"""ctypes binding of include/lsq.h.  Argument marshalling only.
+
+Every wrapper takes torch tensors that already live on the GPU, passes their
+device pointers, the sizes and the current HIP stream to the C entry point of
+the same name, and returns the output tensors.  Optional `out=`-style arguments
+let a caller (the benchmark) reuse buffers so that a call allocates nothing.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liblsq.so")
+_lib = None
+
+LSQ_F16, LSQ_BF16, LSQ_F32 = 0, 1, 2
+LSQ_OP_LAYERNORM_BWD, LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD = 0, 1
+_DT = {torch.float16: LSQ_F16, torch.bfloat16: LSQ_BF16, torch.float32: LSQ_F32}
+
+EXPORTS = [
+    "lsq_workspace_bytes", "lsq_status_string", "lsq_layernorm_fwd", "lsq_layernorm_bwd",
+    "lsq_bias_dropout_residual_fwd", "lsq_bias_dropout_residual_bwd", "lsq_softmax_fwd", "lsq_softmax_bwd",
+    "lsq_ls_xent_fwd", "lsq_ls_xent_bwd", "lsq_adam_step",
+]
+
+
+class LsqError(RuntimeError):
+    pass
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Load liblsq.so (built by `python -m paper_2110_05722_amd.build`).  Raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise LsqError(f"{_LIB_PATH} is missing: build it with `python -m paper_2110_05722_amd.build` "
+                       "(there is no fallback path)")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32, i64, u64, f32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float, C.c_size_t
+    sig = {
+        "lsq_workspace_bytes": (sz, [i32, i64, i32]),
+        "lsq_status_string": (C.c_char_p, [C.c_int]),
+        "lsq_layernorm_fwd": (C.c_int, [vp, vp, vp, vp, vp, vp, i64, i32, f32, C.c_int, vp]),
+        "lsq_layernorm_bwd": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, i64, i32, C.c_int, vp]),
+        "lsq_bias_dropout_residual_fwd": (C.c_int, [vp, vp, vp, vp, i64, i32, f32, u64, u64, C.c_int, vp]),
+        "lsq_bias_dropout_residual_bwd": (C.c_int, [vp, vp, vp, i64, i32, f32, u64, u64, vp, sz, C.c_int, vp]),
+        "lsq_softmax_fwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64, C.c_int, vp]),
+        "lsq_softmax_bwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64, C.c_int, vp]),
+        "lsq_ls_xent_fwd": (C.c_int, [vp, vp, vp, vp, vp, i64, i32, f32, i32, C.c_int, vp]),
+        "lsq_ls_xent_bwd": (C.c_int, [vp, vp, vp, vp, i64, i32, f32, i32, f32, C.c_int, vp]),
+        "lsq_adam_step": (C.c_int, [vp, vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, i32, i32, i32, f32,
+                                    C.c_int, C.c_int, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def lsq_status_string(code: int) -> str:
+    return load().lsq_status_string(code).decode()
+
+
+def lsq_workspace_bytes(op: int, rows: int, cols: int) -> int:
+    return int(load().lsq_workspace_bytes(op, rows, cols))
+
+
+def _check(code: int, name: str):
+    if code != 0:
+        raise LsqError(f"{name} failed: {lsq_status_string(code)}")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise LsqError("tensors must live on the GPU (there is no CPU path)")
+    if not t.is_contiguous():
+        raise LsqError("tensors must be contiguous")
+    return C.c_void_p(t.data_ptr())
+
+
+def _dt(t) -> int:
+    try:
+        return _DT[t.dtype]
+    except KeyError:
+        raise LsqError(f"unsupported dtype {t.dtype}") from None
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _workspace(nbytes: int, like, ws):
+    if ws is not None:
+        return ws
+    return torch.empty(max(nbytes, 16), dtype=torch.uint8, device=like.device)
+
+
+# ---------------------------------------------------------------------------
+def lsq_layernorm_fwd(x, gamma, beta, eps: float = 1e-5, y=None, mean=None, rstd=None):
+    """x: [rows, hidden] -> (y, mean[rows] fp32, rstd[rows] fp32)."""
+    rows, hidden = x.shape
+    y = torch.empty_like(x) if y is None else y
+    mean = torch.empty(rows, dtype=torch.float32, device=x.device) if mean is None else mean
+    rstd = torch.empty(rows, dtype=torch.float32, device=x.device) if rstd is None else rstd
+    _check(load().lsq_layernorm_fwd(_ptr(y), _ptr(mean), _ptr(rstd), _ptr(x), _ptr(gamma), _ptr(beta), rows, hidden,
+                                    eps, _dt(x), _stream()), "lsq_layernorm_fwd")
+    return y, mean, rstd
+
+
+def lsq_layernorm_bwd(dy, x, gamma, mean, rstd, dres_in=None, dx=None, dgamma=None, dbeta=None, workspace=None):
+    """-> (dx, dgamma[hidden] fp32, dbeta[hidden] fp32)."""
+    rows, hidden = x.shape
+    dx = torch.empty_like(x) if dx is None else dx
+    dgamma = torch.empty(hidden, dtype=torch.float32, device=x.device) if dgamma is None else dgamma
+    dbeta = torch.empty(hidden, dtype=torch.float32, device=x.device) if dbeta is None else dbeta
+    ws = _workspace(lsq_workspace_bytes(LSQ_OP_LAYERNORM_BWD, rows, hidden), x, workspace)
+    _check(load().lsq_layernorm_bwd(_ptr(dx), _ptr(dgamma), _ptr(dbeta), _ptr(dy), _ptr(x), _ptr(gamma), _ptr(mean),
+                                    _ptr(rstd), _ptr(dres_in), _ptr(ws), ws.numel() * ws.element_size(), rows, hidden,
+                                    _dt(x), _stream()), "lsq_layernorm_bwd")
+    return dx, dgamma, dbeta
+
+
+def lsq_bias_dropout_residual_fwd(x, bias, residual, p: float, seed: int, offset: int, out=None):
+    rows, hidden = x.shape
+    out = torch.empty_like(x) if out is None else out
+    _check(load().lsq_bias_dropout_residual_fwd(_ptr(out), _ptr(x), _ptr(bias), _ptr(residual), rows, hidden, p, seed,
+                                                offset, _dt(x), _stream()), "lsq_bias_dropout_residual_fwd")
+    return out
+
+
+def lsq_bias_dropout_residual_bwd(dy, p: float, seed: int, offset: int, want_dbias: bool = True, dx=None, dbias=None,
+                                  workspace=None):
+    """-> (dx, dbias[hidden] fp32 or None)."""
+    rows, hidden = dy.shape
+    dx = torch.empty_like(dy) if dx is None else dx
+    if want_dbias and dbias is None:
+        dbias = torch.empty(hidden, dtype=torch.float32, device=dy.device)
+    ws = _workspace(lsq_workspace_bytes(LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD, rows, hidden), dy, workspace)
+    _check(load().lsq_bias_dropout_residual_bwd(_ptr(dx), _ptr(dbias) if want_dbias else None, _ptr(dy), rows, hidden,
+                                                p, seed, offset, _ptr(ws), ws.numel() * ws.element_size(), _dt(dy),
+                                                _stream()), "lsq_bias_dropout_residual_bwd")
+    return dx, (dbias if want_dbias else None)
+
+
+def lsq_softmax_fwd(x, key_len=None, causal: bool = False, scale: float = 1.0, p_attn: float = 0.0, seed: int = 0,
+                    offset: int = 0, y=None, y_drop=None):
+    """x: [batch, heads, q_len, k_len]; key_len: int32[batch] or None -> (y, y_drop or None)."""
+    B, N, Lq, Lk = x.shape
+    y = torch.empty_like(x) if y is None else y
+    if p_attn > 0 and y_drop is None:
+        y_drop = torch.empty_like(x)
+    _check(load().lsq_softmax_fwd(_ptr(y), _ptr(y_drop) if p_attn > 0 else None, _ptr(x), _ptr(key_len), B, N, Lq, Lk,
+                                  int(causal), scale, p_attn, seed, offset, _dt(x), _stream()), "lsq_softmax_fwd")
+    return y, (y_drop if p_attn > 0 else None)
+
+
+def lsq_softmax_bwd(dy, y, key_len=None, causal: bool = False, scale: float = 1.0, p_attn: float = 0.0, seed: int = 0,
+                    offset: int = 0, dx=None):
+    B, N, Lq, Lk = y.shape
+    dx = torch.empty_like(y) if dx is None else dx
+    _check(load().lsq_softmax_bwd(_ptr(dx), _ptr(dy), _ptr(y), _ptr(key_len), B, N, Lq, Lk, int(causal), scale, p_attn,
+                                  seed, offset, _dt(y), _stream()), "lsq_softmax_bwd")
+    return dx
+
+
+def lsq_ls_xent_fwd(logits, target, alpha: float, ignore_index: int = -100, want_sums: bool = True, loss=None,
+                    lse=None, sums=None):
+    """logits: [tokens, vocab]; target: int32[tokens] -> (loss[tokens], lse[tokens], sums[3] or None), fp32."""
+    T, V = logits.shape
+    loss = torch.empty(T, dtype=torch.float32, device=logits.device) if loss is None else loss
+    lse = torch.empty(T, dtype=torch.float32, device=logits.device) if lse is None else lse
+    if want_sums and sums is None:
+        sums = torch.empty(3, dtype=torch.float32, device=logits.device)
+    if target.dtype != torch.int32:
+        raise LsqError("target must be int32")
+    _check(load().lsq_ls_xent_fwd(_ptr(loss), _ptr(lse), _ptr(sums) if want_sums else None, _ptr(logits), _ptr(target),
+                                  T, V, alpha, ignore_index, _dt(logits), _stream()), "lsq_ls_xent_fwd")
+    return loss, lse, (sums if want_sums else None)
+
+
+def lsq_ls_xent_bwd(logits, lse, target, alpha: float, ignore_index: int = -100, grad_scale: float = 1.0,
+                    dlogits=None):
+    T, V = logits.shape
+    dlogits = torch.empty_like(logits) if dlogits is None else dlogits
+    if target.dtype != torch.int32:
+        raise LsqError("target must be int32")
+    _check(load().lsq_ls_xent_bwd(_ptr(dlogits), _ptr(logits), _ptr(lse), _ptr(target), T, V, alpha, ignore_index,
+                                  grad_scale, _dt(logits), _stream()), "lsq_ls_xent_bwd")
+    return dlogits
+
+
+def lsq_adam_step(p, m, v, g, p_lp=None, *, lr: float, beta1: float, beta2: float, eps: float, step: int,
+                  weight_decay: float = 0.0, adamw: bool = False, bias_correction: bool = True,
+                  inv_grad_scale: float = 1.0):
+    """In place on fp32 p, m, v (flat); g low precision (or fp32); p_lp optional low-precision copy out."""
+    for t in (p, m, v):
+        if t.dtype != torch.float32:
+            raise LsqError("p, m, v must be fp32")
+    n = p.numel()
+    _check(load().lsq_adam_step(_ptr(p), _ptr(m), _ptr(v), _ptr(g), _ptr(p_lp), n, lr, beta1, beta2, eps, weight_decay,
+                                step, int(adamw), int(bias_correction), inv_grad_scale, _dt(g),
+                                _dt(p_lp) if p_lp is not None else LSQ_F16, _stream()), "lsq_adam_step")
+    return p, m, v, p_lp

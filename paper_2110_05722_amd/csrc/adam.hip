@@ -1,0 +1,118 @@
+// Mixed-precision Adam over one flat workspace (Sec. IV-C of the paper): the
+// low-precision gradient is widened in registers, the fp32 master parameter and
+// both moments are read once and written once, and the low-precision copy of the
+// parameter that the next forward pass reads is produced by the same pass.
+// One launch per step, whatever the number of parameter tensors in the workspace.
+//
+// HBM-bound: 28 bytes per parameter (26 without the low-precision copy).  Each
+// thread owns 8 consecutive parameters: 2x128-bit loads of p, m, v, one 128-bit
+// load of g, the mirror-image stores.
+#include "host.hpp"
+
+namespace lsq {
+
+struct AdamParams {
+    float lr, beta1, beta2, omb1, omb2, eps, wd, rc1, rc2, inv_scale;
+    int adamw;
+};
+
+__device__ __forceinline__ void adam_update(float& p, float& m, float& v, float g, const AdamParams& a)
+{
+    float gh = g * a.inv_scale;
+    if (!a.adamw) gh = fmaf(a.wd, p, gh);
+    m = fmaf(a.beta1, m, a.omb1 * gh);
+    v = fmaf(a.beta2, v, a.omb2 * gh * gh);
+    float upd = (m * a.rc1) / (sqrtf(v * a.rc2) + a.eps);
+    if (a.adamw) upd = fmaf(a.wd, p, upd);
+    p = fmaf(-a.lr, upd, p);
+}
+
+template <typename G, typename PL, bool HAS_PL>
+__global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ p, float* __restrict__ m,
+                                                   float* __restrict__ v, const G* __restrict__ g,
+                                                   PL* __restrict__ plp, int64_t n, AdamParams a)
+{
+    const int64_t e = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * kPack;
+    if (e + kPack <= n) {
+        float pf[8], mf[8], vf[8], gf[8];
+        load8<float>(p + e, pf);
+        load8<float>(m + e, mf);
+        load8<float>(v + e, vf);
+        load8<G>(g + e, gf);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            adam_update(pf[j], mf[j], vf[j], gf[j], a);
+            // pin the fp32 value: without this the compiler folds the last fma into the
+            // fp16 conversion (one rounding of the exact result), and the low-precision
+            // copy would no longer be the rounded image of the stored fp32 parameter
+            asm volatile("" : "+v"(pf[j]));
+        }
+        store8<float>(p + e, pf);
+        store8<float>(m + e, mf);
+        store8<float>(v + e, vf);
+        if constexpr (HAS_PL) store8<PL>(plp + e, pf);
+    } else {
+        for (int64_t i = e; i < n; ++i) {      // ragged tail: at most 7 elements, one thread
+            float pf = p[i], mf = m[i], vf = v[i];
+            adam_update(pf, mf, vf, to_f32<G>(g[i]), a);
+            asm volatile("" : "+v"(pf));
+            p[i] = pf; m[i] = mf; v[i] = vf;
+            if constexpr (HAS_PL) plp[i] = from_f32<PL>(pf);
+        }
+    }
+}
+
+template <typename G>
+static lsq_status adam_dispatch(float* p, float* m, float* v, const void* g, void* plp, int64_t n,
+                                const AdamParams& a, int p_lp_dt, hipStream_t s)
+{
+    const int64_t packs = ceil_div(n, kPack);
+    const dim3 grid(static_cast<unsigned>(ceil_div(packs, 256))), block(256);
+    const G* gp = static_cast<const G*>(g);
+    if (!plp)
+        hipLaunchKernelGGL((adam_kernel<G, f16, false>), grid, block, 0, s, p, m, v, gp, static_cast<f16*>(nullptr), n, a);
+    else if (p_lp_dt == LSQ_F16)
+        hipLaunchKernelGGL((adam_kernel<G, f16, true>), grid, block, 0, s, p, m, v, gp, static_cast<f16*>(plp), n, a);
+    else
+        hipLaunchKernelGGL((adam_kernel<G, bf16, true>), grid, block, 0, s, p, m, v, gp, static_cast<bf16*>(plp), n, a);
+    return launch_status();
+}
+
+}  // namespace lsq
+
+extern "C" lsq_status lsq_adam_step(float* p, float* m, float* v, const void* g, void* p_lp, int64_t n,
+                                    float lr, float beta1, float beta2, float eps, float weight_decay,
+                                    int32_t step, int32_t adamw, int32_t bias_correction,
+                                    float inv_grad_scale, lsq_dtype g_dt, lsq_dtype p_lp_dt, void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(n >= 0 && step >= 1);
+    LSQ_REQUIRE(beta1 >= 0.0f && beta1 < 1.0f && beta2 >= 0.0f && beta2 < 1.0f);
+    LSQ_REQUIRE(eps >= 0.0f);
+    if (!valid_dtype(g_dt)) return LSQ_UNSUPPORTED_DTYPE;
+    if (p_lp && p_lp_dt != LSQ_F16 && p_lp_dt != LSQ_BF16) return LSQ_UNSUPPORTED_DTYPE;
+    if (n == 0) return LSQ_OK;
+    LSQ_REQUIRE(p && m && v && g);
+    LSQ_ALIGNED(p); LSQ_ALIGNED(m); LSQ_ALIGNED(v); LSQ_ALIGNED(g); LSQ_ALIGNED(p_lp);
+    LSQ_REQUIRE(ceil_div(ceil_div(n, kPack), 256) <= 0x7FFFFFFF);
+
+    AdamParams a;
+    a.lr = lr; a.beta1 = beta1; a.beta2 = beta2;
+    a.omb1 = 1.0f - beta1; a.omb2 = 1.0f - beta2;
+    a.eps = eps; a.wd = weight_decay; a.inv_scale = inv_grad_scale; a.adamw = adamw != 0;
+    // bias corrections in double on the host; the kernel multiplies by their reciprocals
+    double c1 = 1.0, c2 = 1.0;
+    if (bias_correction) {
+        c1 = 1.0 - pow(static_cast<double>(beta1), static_cast<double>(step));
+        c2 = 1.0 - pow(static_cast<double>(beta2), static_cast<double>(step));
+    }
+    a.rc1 = static_cast<float>(1.0 / c1);
+    a.rc2 = static_cast<float>(1.0 / c2);
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (g_dt) {
+        case LSQ_F16: return adam_dispatch<f16>(p, m, v, g, p_lp, n, a, p_lp_dt, s);
+        case LSQ_BF16: return adam_dispatch<bf16>(p, m, v, g, p_lp, n, a, p_lp_dt, s);
+        default: return adam_dispatch<float>(p, m, v, g, p_lp, n, a, p_lp_dt, s);
+    }
+}

@@ -1,0 +1,31 @@
+// Entry points that launch nothing: workspace sizing and status names.
+#include "host.hpp"
+
+extern "C" size_t lsq_workspace_bytes(int32_t op, int64_t rows, int32_t cols)
+{
+    using namespace lsq;
+    if (rows <= 0 || cols <= 0) return 0;
+    switch (op) {
+        case LSQ_OP_LAYERNORM_BWD:
+            // one [2][cols] fp32 partial row (dgamma, dbeta) per workgroup
+            return static_cast<size_t>(ln_bwd_blocks(rows, cols)) * 2u * static_cast<size_t>(cols) * sizeof(float);
+        case LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD:
+            // one [cols] fp32 partial row (dbias) per row block
+            return static_cast<size_t>(bdr_bwd_row_blocks(rows, cols)) * static_cast<size_t>(cols) * sizeof(float);
+        default:
+            return 0;
+    }
+}
+
+extern "C" const char* lsq_status_string(lsq_status s)
+{
+    switch (s) {
+        case LSQ_OK: return "LSQ_OK";
+        case LSQ_INVALID_ARG: return "LSQ_INVALID_ARG";
+        case LSQ_UNSUPPORTED_DTYPE: return "LSQ_UNSUPPORTED_DTYPE";
+        case LSQ_MISALIGNED: return "LSQ_MISALIGNED";
+        case LSQ_WORKSPACE_TOO_SMALL: return "LSQ_WORKSPACE_TOO_SMALL";
+        case LSQ_LAUNCH_FAILED: return "LSQ_LAUNCH_FAILED";
+        default: return "LSQ_UNKNOWN_STATUS";
+    }
+}

@@ -1,0 +1,165 @@
+// Device-side building blocks for the gfx950 kernels: storage types, 8-element
+// packs (one 128-bit access for fp16/bf16), wave64 reductions on DPP, and the
+// Philox4x32-10 dropout stream.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lsq {
+
+using f16 = _Float16;
+using bf16 = __bf16;
+
+constexpr int kWave = 64;
+constexpr int kPack = 8;   // elements per pack == elements per Philox call
+
+template <typename T> struct alignas(sizeof(T) * 8 > 16 ? 16 : sizeof(T) * 8) Raw8 { T v[8]; };
+
+template <typename T> __device__ __forceinline__ float to_f32(T v) { return static_cast<float>(v); }
+template <typename T> __device__ __forceinline__ T from_f32(float v) { return static_cast<T>(v); }
+
+// 8 consecutive elements starting at a pack-aligned address, widened to fp32.
+// fp16/bf16: one global_load_dwordx4; fp32: two.
+template <typename T>
+__device__ __forceinline__ void load8(const T* __restrict__ p, float (&f)[8])
+{
+    if constexpr (sizeof(T) == 2) {
+        Raw8<T> r = *reinterpret_cast<const Raw8<T>*>(p);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) f[j] = to_f32<T>(r.v[j]);
+    } else {
+        const float4 a = reinterpret_cast<const float4*>(p)[0];
+        const float4 b = reinterpret_cast<const float4*>(p)[1];
+        f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w;
+        f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+    }
+}
+
+template <typename T>
+__device__ __forceinline__ void store8(T* __restrict__ p, const float (&f)[8])
+{
+    if constexpr (sizeof(T) == 2) {
+        Raw8<T> r;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r.v[j] = from_f32<T>(f[j]);
+        *reinterpret_cast<Raw8<T>*>(p) = r;
+    } else {
+        reinterpret_cast<float4*>(p)[0] = make_float4(f[0], f[1], f[2], f[3]);
+        reinterpret_cast<float4*>(p)[1] = make_float4(f[4], f[5], f[6], f[7]);
+    }
+}
+
+// ---------------------------------------------------------------- reductions
+// All-reduce over aligned groups of WIDTH lanes (a power of two <= 64) inside one
+// wave64.  Lanes 1..15 apart are reached with DPP (quad permutes and row mirrors,
+// no LDS traffic); 16 apart with a 32-lane swizzle; the last step of a full-wave
+// reduction reads the four row results through scalar registers.
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+
+struct OpSum { static __device__ __forceinline__ float apply(float a, float b) { return a + b; } };
+struct OpMax { static __device__ __forceinline__ float apply(float a, float b) { return fmaxf(a, b); } };
+
+template <int WIDTH, typename Op>
+__device__ __forceinline__ float group_allreduce(float v)
+{
+    static_assert(WIDTH == 1 || WIDTH == 2 || WIDTH == 4 || WIDTH == 8 || WIDTH == 16 || WIDTH == 32 || WIDTH == 64, "");
+    if constexpr (WIDTH >= 2) v = Op::apply(v, dpp_mov<0xB1>(v));    // quad_perm [1,0,3,2]
+    if constexpr (WIDTH >= 4) v = Op::apply(v, dpp_mov<0x4E>(v));    // quad_perm [2,3,0,1]
+    if constexpr (WIDTH >= 8) v = Op::apply(v, dpp_mov<0x141>(v));   // row_half_mirror
+    if constexpr (WIDTH >= 16) v = Op::apply(v, dpp_mov<0x140>(v));  // row_mirror
+    if constexpr (WIDTH == 32) {
+        // swap with the lane 16 away inside each half-wave (bit-mask mode: and 0x1F, xor 0x10)
+        float o = __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));
+        v = Op::apply(v, o);
+    }
+    if constexpr (WIDTH == 64) {
+        const int iv = __builtin_bit_cast(int, v);
+        float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 0));
+        float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 16));
+        float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32));
+        float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48));
+        v = Op::apply(Op::apply(r0, r1), Op::apply(r2, r3));
+    }
+    return v;
+}
+
+template <int WIDTH> __device__ __forceinline__ float group_sum(float v) { return group_allreduce<WIDTH, OpSum>(v); }
+template <int WIDTH> __device__ __forceinline__ float group_max(float v) { return group_allreduce<WIDTH, OpMax>(v); }
+
+// Block-wide all-reduce for NWAVES waves; `scratch` holds NWAVES floats of LDS.
+// Every thread of the block must call it; it contains two barriers.
+template <int NWAVES, typename Op>
+__device__ __forceinline__ float block_allreduce(float v, float* scratch)
+{
+    v = group_allreduce<64, Op>(v);
+    if constexpr (NWAVES == 1) return v;
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();                    // scratch may still be read from a previous call
+    if ((threadIdx.x & 63) == 0) scratch[wave] = v;
+    __syncthreads();
+    float r = scratch[0];
+#pragma unroll
+    for (int w = 1; w < NWAVES; ++w) r = Op::apply(r, scratch[w]);
+    return r;
+}
+
+// -------------------------------------------------------------------- Philox
+// Philox4x32-10 (Salmon et al., SC'11).  One call yields 128 bits = eight 16-bit
+// dropout lanes, so a pack of 8 elements costs one call.
+struct DropoutParams {
+    uint32_t key0, key1;      // seed
+    uint32_t ctr2, ctr3;      // offset
+    uint32_t t16;             // keep iff r16 >= t16; 0 means "no dropout, draw nothing"
+    float scale;              // 1 / (1 - p)
+};
+
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&out)[4])
+{
+    constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+    constexpr uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t p0 = static_cast<uint64_t>(M0) * c0;
+        const uint64_t p1 = static_cast<uint64_t>(M1) * c2;
+        const uint32_t n0 = static_cast<uint32_t>(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = static_cast<uint32_t>(p0 >> 32) ^ c3 ^ k1;
+        c1 = static_cast<uint32_t>(p1);
+        c3 = static_cast<uint32_t>(p0);
+        c0 = n0;
+        c2 = n2;
+        k0 += W0;
+        k1 += W1;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// keep[j] (as 0.0f / scale) for the 8 elements of pack `g` (flat element index / 8).
+__device__ __forceinline__ void dropout_factors8(const DropoutParams& d, uint64_t g, float (&k)[8])
+{
+    uint32_t w[4];
+    philox4x32_10(static_cast<uint32_t>(g), static_cast<uint32_t>(g >> 32), d.ctr2, d.ctr3, d.key0, d.key1, w);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        k[2 * j] = (w[j] & 0xFFFFu) >= d.t16 ? d.scale : 0.0f;
+        k[2 * j + 1] = (w[j] >> 16) >= d.t16 ? d.scale : 0.0f;
+    }
+}
+
+// The factor for one element (generic, unaligned paths: one Philox call per element).
+__device__ __forceinline__ float dropout_factor1(const DropoutParams& d, uint64_t e)
+{
+    uint32_t w[4];
+    const uint64_t g = e >> 3;
+    philox4x32_10(static_cast<uint32_t>(g), static_cast<uint32_t>(g >> 32), d.ctr2, d.ctr3, d.key0, d.key1, w);
+    const uint32_t lane = static_cast<uint32_t>(e) & 7u;
+    const uint32_t word = lane < 2 ? w[0] : lane < 4 ? w[1] : lane < 6 ? w[2] : w[3];
+    const uint32_t r16 = (word >> (16u * (lane & 1u))) & 0xFFFFu;
+    return r16 >= d.t16 ? d.scale : 0.0f;
+}
+
+}  // namespace lsq

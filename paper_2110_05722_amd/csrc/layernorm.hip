@@ -1,0 +1,435 @@
+// LayerNorm forward and backward (Sec. IV-B of the paper, "dependent reduction
+// rewriting").
+//
+// The paper merges the mean and variance reductions by computing E[x^2]-E[x]^2
+// so that neither waits for the other.  Here a row lives in registers after one
+// 128-bit load per lane and pack, so the second reduction costs no memory traffic
+// at all; it is therefore taken about the mean (two passes over registers), which
+// cannot cancel catastrophically.  Backward uses the xhat form of the gradient:
+// its two row sums (sum g, sum g*xhat) are independent given the saved mean and
+// rstd, and run side by side in the same DPP reduction steps.
+//
+// Layout: LPR lanes share a row (8..64 lanes of one wave, or a whole 256-thread
+// workgroup for very wide rows); each lane holds VPL packs of 8 columns, strided
+// by LPR packs so that a wave's loads are contiguous.  gamma/beta stay in
+// registers while the workgroup walks down its rows.  dgamma/dbeta: every lane
+// accumulates its own columns over its rows, the row slots of a workgroup are
+// summed in a fixed order through LDS, one partial row per workgroup goes to the
+// workspace and a second small kernel sums the partial rows in order.  No atomics.
+#include "host.hpp"
+
+namespace lsq {
+
+template <int LPR>
+__device__ __forceinline__ float row_sum(float v, float* lds)
+{
+    if constexpr (LPR == 256) return block_allreduce<4, OpSum>(v, lds);
+    else return group_sum<LPR>(v);
+}
+
+template <typename T, int LPR, int VPL>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(T* __restrict__ y, float* __restrict__ mean,
+                                                     float* __restrict__ rstd, const T* __restrict__ x,
+                                                     const T* __restrict__ gamma, const T* __restrict__ beta,
+                                                     int64_t rows, int hidden, float eps)
+{
+    __shared__ float lds[4];
+    constexpr int RPB = 256 / LPR;            // rows a workgroup handles at a time
+    const int sub = threadIdx.x % LPR;
+    const int slot = threadIdx.x / LPR;
+    const int nv = hidden / kPack;
+    const float inv_h = 1.0f / static_cast<float>(hidden);
+
+    float gm[VPL][8], bt[VPL][8];
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        const int idx = sub + k * LPR;
+        if (idx < nv) {
+            load8<T>(gamma + idx * kPack, gm[k]);
+            load8<T>(beta + idx * kPack, bt[k]);
+        }
+    }
+
+    for (int64_t base = static_cast<int64_t>(blockIdx.x) * RPB; base < rows; base += static_cast<int64_t>(gridDim.x) * RPB) {
+        const int64_t r = base + slot;
+        const bool rv = r < rows;
+        const T* xr = x + r * hidden;
+        float xv[VPL][8];
+        float s = 0.0f;
+#pragma unroll
+        for (int k = 0; k < VPL; ++k) {
+            const int idx = sub + k * LPR;
+            if (rv && idx < nv) {
+                load8<T>(xr + idx * kPack, xv[k]);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) s += xv[k][j];
+            }
+        }
+        s = row_sum<LPR>(s, lds);
+        const float mu = s * inv_h;
+        float q = 0.0f;
+#pragma unroll
+        for (int k = 0; k < VPL; ++k) {
+            const int idx = sub + k * LPR;
+            if (rv && idx < nv) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float dlt = xv[k][j] - mu;
+                    xv[k][j] = dlt;
+                    q = fmaf(dlt, dlt, q);
+                }
+            }
+        }
+        q = row_sum<LPR>(q, lds);
+        const float rs = 1.0f / sqrtf(fmaf(q, inv_h, eps));
+        if (rv && sub == 0) {
+            mean[r] = mu;
+            rstd[r] = rs;
+        }
+        T* yr = y + r * hidden;
+#pragma unroll
+        for (int k = 0; k < VPL; ++k) {
+            const int idx = sub + k * LPR;
+            if (rv && idx < nv) {
+                float o[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) o[j] = fmaf(xv[k][j] * rs, gm[k][j], bt[k][j]);
+                store8<T>(yr + idx * kPack, o);
+            }
+        }
+    }
+}
+
+// partial: [gridDim.x][2][hidden] fp32 (dgamma row, then dbeta row).
+template <typename T, int LPR, int VPL, bool HAS_RES>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(T* dx, float* __restrict__ partial, const T* dy,
+                                                     const T* __restrict__ x, const T* __restrict__ gamma,
+                                                     const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                     const T* dres, int64_t rows, int hidden)
+{
+    extern __shared__ float colbuf[];         // [2][hidden] when LPR < 256
+    __shared__ float lds[4];
+    constexpr int RPB = 256 / LPR;
+    const int sub = threadIdx.x % LPR;
+    const int slot = threadIdx.x / LPR;
+    const int nv = hidden / kPack;
+    const float inv_h = 1.0f / static_cast<float>(hidden);
+
+    float gm[VPL][8], dg[VPL][8], db[VPL][8];
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        const int idx = sub + k * LPR;
+        if (idx < nv) load8<T>(gamma + idx * kPack, gm[k]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { dg[k][j] = 0.0f; db[k][j] = 0.0f; }
+    }
+
+    for (int64_t base = static_cast<int64_t>(blockIdx.x) * RPB; base < rows; base += static_cast<int64_t>(gridDim.x) * RPB) {
+        const int64_t r = base + slot;
+        const bool rv = r < rows;
+        const int64_t ro = r * hidden;
+        float g[VPL][8], xh[VPL][8];
+        float mu = 0.0f, rs = 0.0f;
+        if (rv) { mu = mean[r]; rs = rstd[r]; }
+        float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+        for (int k = 0; k < VPL; ++k) {
+            const int idx = sub + k * LPR;
+            if (rv && idx < nv) {
+                load8<T>(dy + ro + idx * kPack, g[k]);
+                load8<T>(x + ro + idx * kPack, xh[k]);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float xhat = (xh[k][j] - mu) * rs;
+                    const float gy = g[k][j];
+                    dg[k][j] = fmaf(gy, xhat, dg[k][j]);
+                    db[k][j] += gy;
+                    const float gg = gy * gm[k][j];
+                    s1 += gg;
+                    s2 = fmaf(gg, xhat, s2);
+                    xh[k][j] = xhat;
+                    g[k][j] = gg;
+                }
+            }
+        }
+        s1 = row_sum<LPR>(s1, lds);
+        s2 = row_sum<LPR>(s2, lds);
+        const float a = s1 * inv_h, b = s2 * inv_h;
+#pragma unroll
+        for (int k = 0; k < VPL; ++k) {
+            const int idx = sub + k * LPR;
+            if (rv && idx < nv) {
+                float o[8];
+                if constexpr (HAS_RES) load8<T>(dres + ro + idx * kPack, o);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float v = rs * (g[k][j] - fmaf(xh[k][j], b, a));
+                    o[j] = HAS_RES ? o[j] + v : v;
+                }
+                store8<T>(dx + ro + idx * kPack, o);
+            }
+        }
+    }
+
+    float* prow = partial + static_cast<int64_t>(blockIdx.x) * 2 * hidden;
+    if constexpr (LPR == 256) {
+#pragma unroll
+        for (int k = 0; k < VPL; ++k) {
+            const int idx = sub + k * LPR;
+            if (idx < nv) {
+                store8<float>(prow + idx * kPack, dg[k]);
+                store8<float>(prow + hidden + idx * kPack, db[k]);
+            }
+        }
+    } else {
+        // sum the RPB row slots in slot order through LDS
+        for (int turn = 0; turn < RPB; ++turn) {
+            if (slot == turn) {
+#pragma unroll
+                for (int k = 0; k < VPL; ++k) {
+                    const int idx = sub + k * LPR;
+                    if (idx < nv) {
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            const int c = idx * kPack + j;
+                            if (turn == 0) { colbuf[c] = dg[k][j]; colbuf[hidden + c] = db[k][j]; }
+                            else { colbuf[c] += dg[k][j]; colbuf[hidden + c] += db[k][j]; }
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+        }
+        for (int c = threadIdx.x; c < 2 * hidden; c += 256) prow[c] = colbuf[c];
+    }
+}
+
+// Sum P partial rows of `ncols` columns in row order.  64 columns per workgroup,
+// SLICES waves each take every SLICES-th row; the slices are combined in order.
+template <int SLICES>
+__global__ __launch_bounds__(64 * SLICES) void ln_bwd_finalize(float* __restrict__ dgamma, float* __restrict__ dbeta,
+                                                              const float* __restrict__ partial, int P, int hidden)
+{
+    __shared__ float sm[SLICES][64];
+    const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + lane;
+    const int ncols = 2 * hidden;
+    float s = 0.0f;
+    if (c < ncols)
+        for (int y = slice; y < P; y += SLICES) s += partial[static_cast<int64_t>(y) * ncols + c];
+    sm[slice][lane] = s;
+    __syncthreads();
+    if (slice == 0 && c < ncols) {
+        float t = sm[0][lane];
+#pragma unroll
+        for (int w = 1; w < SLICES; ++w) t += sm[w][lane];
+        if (c < hidden) dgamma[c] = t; else dbeta[c - hidden] = t;
+    }
+}
+
+// ---- generic path: any hidden; one wave per row, element-strided, rows re-read from cache
+template <typename T>
+__global__ __launch_bounds__(256) void ln_fwd_generic(T* __restrict__ y, float* __restrict__ mean,
+                                                      float* __restrict__ rstd, const T* __restrict__ x,
+                                                      const T* __restrict__ gamma, const T* __restrict__ beta,
+                                                      int64_t rows, int hidden, float eps)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t r = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (r >= rows) return;                     // whole waves leave together
+    const T* xr = x + r * hidden;
+    const float inv_h = 1.0f / static_cast<float>(hidden);
+    float s = 0.0f;
+    for (int i = lane; i < hidden; i += 64) s += to_f32<T>(xr[i]);
+    const float mu = group_sum<64>(s) * inv_h;
+    float q = 0.0f;
+    for (int i = lane; i < hidden; i += 64) { const float d = to_f32<T>(xr[i]) - mu; q = fmaf(d, d, q); }
+    const float rs = 1.0f / sqrtf(fmaf(group_sum<64>(q), inv_h, eps));
+    if (lane == 0) { mean[r] = mu; rstd[r] = rs; }
+    T* yr = y + r * hidden;
+    for (int i = lane; i < hidden; i += 64)
+        yr[i] = from_f32<T>(fmaf((to_f32<T>(xr[i]) - mu) * rs, to_f32<T>(gamma[i]), to_f32<T>(beta[i])));
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void ln_bwd_generic(T* dx, const T* dy, const T* __restrict__ x,
+                                                      const T* __restrict__ gamma, const float* __restrict__ mean,
+                                                      const float* __restrict__ rstd, const T* dres,
+                                                      int64_t rows, int hidden)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t r = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    const int64_t ro = r * hidden;
+    const float mu = mean[r], rs = rstd[r];
+    const float inv_h = 1.0f / static_cast<float>(hidden);
+    float s1 = 0.0f, s2 = 0.0f;
+    for (int i = lane; i < hidden; i += 64) {
+        const float gg = to_f32<T>(dy[ro + i]) * to_f32<T>(gamma[i]);
+        s1 += gg;
+        s2 = fmaf(gg, (to_f32<T>(x[ro + i]) - mu) * rs, s2);
+    }
+    const float a = group_sum<64>(s1) * inv_h, b = group_sum<64>(s2) * inv_h;
+    for (int i = lane; i < hidden; i += 64) {
+        const float gg = to_f32<T>(dy[ro + i]) * to_f32<T>(gamma[i]);
+        const float xhat = (to_f32<T>(x[ro + i]) - mu) * rs;
+        float v = rs * (gg - fmaf(xhat, b, a));
+        if (dres) v += to_f32<T>(dres[ro + i]);
+        dx[ro + i] = from_f32<T>(v);
+    }
+}
+
+// dgamma/dbeta for the generic path: one thread per column walks down the rows.
+// Runs BEFORE ln_bwd_generic so that dx may alias dy.
+template <typename T>
+__global__ __launch_bounds__(256) void ln_dparams_generic(float* __restrict__ dgamma, float* __restrict__ dbeta,
+                                                          const T* __restrict__ dy, const T* __restrict__ x,
+                                                          const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                          int64_t rows, int hidden)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= hidden) return;
+    float sg = 0.0f, sb = 0.0f;
+    for (int64_t r = 0; r < rows; ++r) {
+        const float gy = to_f32<T>(dy[r * hidden + c]);
+        sg = fmaf(gy, (to_f32<T>(x[r * hidden + c]) - mean[r]) * rstd[r], sg);
+        sb += gy;
+    }
+    dgamma[c] = sg;
+    dbeta[c] = sb;
+}
+
+// ------------------------------------------------------------------ dispatch
+// Shape buckets: lanes per row and packs per lane for a row of nv packs.
+struct LnShape { int lpr, vpl; };
+
+inline LnShape ln_shape(int hidden)
+{
+    if (hidden % kPack != 0) return {0, 0};
+    const int nv = hidden / kPack;
+    if (nv <= 8) return {8, 1};
+    if (nv <= 16) return {16, 1};
+    if (nv <= 32) return {32, 1};
+    if (nv <= 64) return {64, 1};
+    if (nv <= 128) return {64, 2};
+    if (nv <= 192) return {64, 3};
+    if (nv <= 256) return {64, 4};
+    if (nv <= 512) return {256, 2};
+    if (nv <= 1024) return {256, 4};
+    return {0, 0};
+}
+
+inline int ln_fwd_blocks(int64_t rows, int lpr)
+{
+    const int rpb = 256 / lpr;
+    int64_t b = ceil_div(rows, static_cast<int64_t>(rpb) * 2);   // about two row groups per workgroup
+    if (b > 4096) b = 4096;
+    if (b < 1) b = 1;
+    return static_cast<int>(b);
+}
+
+#define LSQ_LN_CASES(X) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 3) X(64, 4) X(256, 2) X(256, 4)
+
+template <typename T>
+static lsq_status ln_fwd_dispatch(void* y, float* mean, float* rstd, const void* x, const void* gamma, const void* beta,
+                                  int64_t rows, int32_t hidden, float eps, hipStream_t s)
+{
+    T* yp = static_cast<T*>(y);
+    const T* xp = static_cast<const T*>(x);
+    const T* gp = static_cast<const T*>(gamma);
+    const T* bp = static_cast<const T*>(beta);
+    const LnShape sh = ln_shape(hidden);
+    if (sh.lpr == 0) {
+        hipLaunchKernelGGL((ln_fwd_generic<T>), dim3(static_cast<unsigned>(ceil_div(rows, 4))), dim3(256), 0, s,
+                           yp, mean, rstd, xp, gp, bp, rows, hidden, eps);
+        return launch_status();
+    }
+    const dim3 grid(ln_fwd_blocks(rows, sh.lpr)), block(256);
+#define X(L, V)                                                                                              \
+    if (sh.lpr == L && sh.vpl == V)                                                                          \
+        hipLaunchKernelGGL((ln_fwd_kernel<T, L, V>), grid, block, 0, s, yp, mean, rstd, xp, gp, bp, rows, hidden, eps);
+    LSQ_LN_CASES(X)
+#undef X
+    return launch_status();
+}
+
+template <typename T>
+static lsq_status ln_bwd_dispatch(void* dx, float* dgamma, float* dbeta, const void* dy, const void* x,
+                                  const void* gamma, const float* mean, const float* rstd, const void* dres,
+                                  void* workspace, int64_t rows, int32_t hidden, hipStream_t s)
+{
+    T* dxp = static_cast<T*>(dx);
+    const T* dyp = static_cast<const T*>(dy);
+    const T* xp = static_cast<const T*>(x);
+    const T* gp = static_cast<const T*>(gamma);
+    const T* rp = static_cast<const T*>(dres);
+    const LnShape sh = ln_shape(hidden);
+    if (sh.lpr == 0) {
+        hipLaunchKernelGGL((ln_dparams_generic<T>), dim3(static_cast<unsigned>(ceil_div(hidden, 256))), dim3(256), 0, s,
+                           dgamma, dbeta, dyp, xp, mean, rstd, rows, hidden);
+        hipLaunchKernelGGL((ln_bwd_generic<T>), dim3(static_cast<unsigned>(ceil_div(rows, 4))), dim3(256), 0, s,
+                           dxp, dyp, xp, gp, mean, rstd, rp, rows, hidden);
+        return launch_status();
+    }
+    const int P = ln_bwd_blocks(rows, hidden);
+    float* partial = static_cast<float*>(workspace);
+    const dim3 grid(P), block(256);
+    const size_t shmem = sh.lpr == 256 ? 0 : sizeof(float) * 2 * hidden;
+#define X(L, V)                                                                                              \
+    if (sh.lpr == L && sh.vpl == V) {                                                                        \
+        if (rp) hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, true>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden); \
+        else hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, false>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden);   \
+    }
+    LSQ_LN_CASES(X)
+#undef X
+    hipLaunchKernelGGL((ln_bwd_finalize<8>), dim3(static_cast<unsigned>(ceil_div(2 * hidden, 64))), dim3(512), 0, s,
+                       dgamma, dbeta, partial, P, hidden);
+    return launch_status();
+}
+
+}  // namespace lsq
+
+extern "C" lsq_status lsq_layernorm_fwd(void* y, float* mean, float* rstd, const void* x, const void* gamma,
+                                        const void* beta, int64_t rows, int32_t hidden, float eps, lsq_dtype dt,
+                                        void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(rows >= 0 && hidden > 0 && eps >= 0.0f);
+    if (!valid_dtype(dt)) return LSQ_UNSUPPORTED_DTYPE;
+    if (rows == 0) return LSQ_OK;
+    LSQ_REQUIRE(y && mean && rstd && x && gamma && beta);
+    LSQ_ALIGNED(y); LSQ_ALIGNED(x); LSQ_ALIGNED(gamma); LSQ_ALIGNED(beta);
+    LSQ_REQUIRE(ceil_div(rows, 4) <= 0x7FFFFFFF);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (dt) {
+        case LSQ_F16: return ln_fwd_dispatch<f16>(y, mean, rstd, x, gamma, beta, rows, hidden, eps, s);
+        case LSQ_BF16: return ln_fwd_dispatch<bf16>(y, mean, rstd, x, gamma, beta, rows, hidden, eps, s);
+        default: return ln_fwd_dispatch<float>(y, mean, rstd, x, gamma, beta, rows, hidden, eps, s);
+    }
+}
+
+extern "C" lsq_status lsq_layernorm_bwd(void* dx, float* dgamma, float* dbeta, const void* dy, const void* x,
+                                        const void* gamma, const float* mean, const float* rstd, const void* dres_in,
+                                        void* workspace, size_t workspace_bytes, int64_t rows, int32_t hidden,
+                                        lsq_dtype dt, void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(rows >= 0 && hidden > 0);
+    if (!valid_dtype(dt)) return LSQ_UNSUPPORTED_DTYPE;
+    LSQ_REQUIRE(dgamma && dbeta);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (rows == 0) {
+        lsq_status st = zero_fill(dgamma, hidden, s);
+        return st != LSQ_OK ? st : zero_fill(dbeta, hidden, s);
+    }
+    LSQ_REQUIRE(dx && dy && x && gamma && mean && rstd);
+    LSQ_ALIGNED(dx); LSQ_ALIGNED(dy); LSQ_ALIGNED(x); LSQ_ALIGNED(gamma); LSQ_ALIGNED(dres_in); LSQ_ALIGNED(workspace);
+    LSQ_REQUIRE(ceil_div(rows, 4) <= 0x7FFFFFFF);
+    const size_t need = lsq_workspace_bytes(LSQ_OP_LAYERNORM_BWD, rows, hidden);
+    if (need && (!workspace || workspace_bytes < need)) return LSQ_WORKSPACE_TOO_SMALL;
+    switch (dt) {
+        case LSQ_F16: return ln_bwd_dispatch<f16>(dx, dgamma, dbeta, dy, x, gamma, mean, rstd, dres_in, workspace, rows, hidden, s);
+        case LSQ_BF16: return ln_bwd_dispatch<bf16>(dx, dgamma, dbeta, dy, x, gamma, mean, rstd, dres_in, workspace, rows, hidden, s);
+        default: return ln_bwd_dispatch<float>(dx, dgamma, dbeta, dy, x, gamma, mean, rstd, dres_in, workspace, rows, hidden, s);
+    }
+}

@@ -1,0 +1,252 @@
+// Label-smoothed cross-entropy, forward and backward (Sec. IV-A of the paper,
+// criterion layer).  The loss is evaluated through log-softmax, as the paper
+// does: loss = lse - (1-alpha)*h_k - (alpha/V)*sum_i h_i, and the gradient is the
+// element-wise expression q_i - alpha/V - (1-alpha)[i == k] with q_i rebuilt as
+// exp(h_i - lse) from the saved lse, so neither direction ever materialises the
+// softmax.
+//
+// One workgroup per token.  The vocabulary row is read ONCE in forward: every
+// thread keeps a running (max, sum) pair in the base-2 domain and rescales its
+// sum when the maximum moves (9 exponentials per 8 logits), and the pairs are
+// merged across the workgroup at the end.  Rows of odd vocabularies (50257,
+// 30522) do not start on 16-byte boundaries: a row is split into a scalar head up
+// to the next pack boundary of the flat tensor, a body of aligned 128-bit packs,
+// and a scalar tail, so the body keeps full-width accesses for any vocab.
+#include "host.hpp"
+
+namespace lsq {
+
+constexpr float kLog2eX = 1.4426950408889634f;
+constexpr float kLn2X = 0.6931471805599453f;
+constexpr int kXentThreads = 256;
+
+struct RowSplit {
+    int64_t begin, head_end, pack_begin, pack_end, tail_begin, end;
+};
+
+// [begin, head_end) scalar, packs [pack_begin, pack_end) aligned, [tail_begin, end) scalar.
+__device__ __forceinline__ RowSplit split_row(int64_t t, int vocab)
+{
+    RowSplit r;
+    r.begin = t * vocab;
+    r.end = r.begin + vocab;
+    r.pack_begin = (r.begin + kPack - 1) / kPack;
+    r.pack_end = r.end / kPack;
+    if (r.pack_begin > r.pack_end) {          // the row lies inside one pack
+        r.pack_end = r.pack_begin;
+        r.head_end = r.end;
+        r.tail_begin = r.end;
+    } else {
+        r.head_end = r.pack_begin * kPack;
+        r.tail_begin = r.pack_end * kPack;
+    }
+    return r;
+}
+
+__device__ __forceinline__ bool is_ignored(int k, int vocab, int ignore_index)
+{
+    return k == ignore_index || k < 0 || k >= vocab;
+}
+
+struct OnlineLse {
+    float m = -INFINITY;   // running maximum of h*log2(e)
+    float s = 0.0f;        // sum of exp2(h*log2e - m)
+    float sh = 0.0f;       // sum of h
+    __device__ __forceinline__ void add1(float h)
+    {
+        const float hs = h * kLog2eX;
+        const float mn = fmaxf(m, hs);
+        s = fmaf(s, __builtin_amdgcn_exp2f(m - mn), __builtin_amdgcn_exp2f(hs - mn));
+        m = mn;
+        sh += h;
+    }
+    __device__ __forceinline__ void add8(const float (&h)[8])
+    {
+        float hs[8];
+        float vm = h[0] * kLog2eX;
+        hs[0] = vm;
+#pragma unroll
+        for (int j = 1; j < 8; ++j) { hs[j] = h[j] * kLog2eX; vm = fmaxf(vm, hs[j]); }
+        const float mn = fmaxf(m, vm);
+        float acc = s * __builtin_amdgcn_exp2f(m - mn);
+        float hsum = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { acc += __builtin_amdgcn_exp2f(hs[j] - mn); hsum += h[j]; }
+        s = acc;
+        m = mn;
+        sh += hsum;
+    }
+};
+
+template <typename T>
+__global__ __launch_bounds__(kXentThreads) void xent_fwd_kernel(float* __restrict__ loss, float* __restrict__ lse,
+                                                               const T* __restrict__ logits,
+                                                               const int32_t* __restrict__ target, int vocab,
+                                                               float alpha, int ignore_index)
+{
+    __shared__ float lds[kXentThreads / 64];
+    const int64_t t = blockIdx.x;
+    const RowSplit r = split_row(t, vocab);
+    const int tid = threadIdx.x;
+    OnlineLse st;
+    if (r.begin + tid < r.head_end) st.add1(to_f32<T>(logits[r.begin + tid]));
+    if (r.tail_begin + tid < r.end) st.add1(to_f32<T>(logits[r.tail_begin + tid]));
+    for (int64_t p = r.pack_begin + tid; p < r.pack_end; p += kXentThreads) {
+        float h[8];
+        load8<T>(logits + p * kPack, h);
+        st.add8(h);
+    }
+    const float M = block_allreduce<kXentThreads / 64, OpMax>(st.m, lds);
+    const float S = block_allreduce<kXentThreads / 64, OpSum>(st.s * __builtin_amdgcn_exp2f(st.m - M), lds);
+    const float SH = block_allreduce<kXentThreads / 64, OpSum>(st.sh, lds);
+    if (tid == 0) {
+        const float l = (M + __builtin_amdgcn_logf(S)) * kLn2X;     // v_log_f32 is log2
+        lse[t] = l;
+        const int k = target[t];
+        float out = 0.0f;
+        if (!is_ignored(k, vocab, ignore_index)) {
+            const float hk = to_f32<T>(logits[r.begin + k]);
+            out = l - (1.0f - alpha) * hk - (alpha / static_cast<float>(vocab)) * SH;
+        }
+        loss[t] = out;
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kXentThreads) void xent_bwd_kernel(T* dlogits, const T* logits,
+                                                               const float* __restrict__ lse,
+                                                               const int32_t* __restrict__ target, int vocab,
+                                                               float alpha, int ignore_index, float grad_scale)
+{
+    const int64_t t = blockIdx.x;
+    const RowSplit r = split_row(t, vocab);
+    const int tid = threadIdx.x;
+    const int k = target[t];
+    if (is_ignored(k, vocab, ignore_index)) {           // uniform over the workgroup
+        if (r.begin + tid < r.head_end) dlogits[r.begin + tid] = from_f32<T>(0.0f);
+        if (r.tail_begin + tid < r.end) dlogits[r.tail_begin + tid] = from_f32<T>(0.0f);
+        const float z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int64_t p = r.pack_begin + tid; p < r.pack_end; p += kXentThreads) store8<T>(dlogits + p * kPack, z);
+        return;
+    }
+    const float ls = lse[t] * kLog2eX;
+    const float smooth = alpha / static_cast<float>(vocab);
+    const float hit = grad_scale * (1.0f - alpha);
+    const int64_t kpos = r.begin + k;
+    auto one = [&](int64_t e) {
+        float gq = grad_scale * (__builtin_amdgcn_exp2f(fmaf(to_f32<T>(logits[e]), kLog2eX, -ls)) - smooth);
+        if (e == kpos) gq -= hit;
+        dlogits[e] = from_f32<T>(gq);
+    };
+    if (r.begin + tid < r.head_end) one(r.begin + tid);
+    if (r.tail_begin + tid < r.end) one(r.tail_begin + tid);
+    const int64_t kpack = kpos >> 3;
+    for (int64_t p = r.pack_begin + tid; p < r.pack_end; p += kXentThreads) {
+        float h[8];
+        load8<T>(logits + p * kPack, h);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) h[j] = grad_scale * (__builtin_amdgcn_exp2f(fmaf(h[j], kLog2eX, -ls)) - smooth);
+        if (p == kpack) {
+            const int jj = static_cast<int>(kpos & 7);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) h[j] -= (j == jj) ? hit : 0.0f;
+        }
+        store8<T>(dlogits + p * kPack, h);
+    }
+}
+
+// sums = { sum loss, sum (lse - h_k), count } over non-ignored tokens: one workgroup,
+// double accumulators, fixed strided order and a fixed LDS tree.
+template <typename T>
+__global__ __launch_bounds__(1024) void xent_sums_kernel(float* __restrict__ sums, const float* __restrict__ loss,
+                                                         const float* __restrict__ lse, const T* __restrict__ logits,
+                                                         const int32_t* __restrict__ target, int64_t tokens, int vocab,
+                                                         int ignore_index)
+{
+    __shared__ double sm[3][1024];
+    const int tid = threadIdx.x;
+    double a = 0.0, b = 0.0, c = 0.0;
+    for (int64_t t = tid; t < tokens; t += 1024) {
+        const int k = target[t];
+        if (!is_ignored(k, vocab, ignore_index)) {
+            a += static_cast<double>(loss[t]);
+            b += static_cast<double>(lse[t]) - static_cast<double>(to_f32<T>(logits[t * vocab + k]));
+            c += 1.0;
+        }
+    }
+    sm[0][tid] = a; sm[1][tid] = b; sm[2][tid] = c;
+    __syncthreads();
+    for (int w = 512; w > 0; w >>= 1) {
+        if (tid < w) {
+            sm[0][tid] += sm[0][tid + w];
+            sm[1][tid] += sm[1][tid + w];
+            sm[2][tid] += sm[2][tid + w];
+        }
+        __syncthreads();
+    }
+    if (tid < 3) sums[tid] = static_cast<float>(sm[tid][0]);
+}
+
+template <typename T>
+static lsq_status xent_fwd_dispatch(float* loss, float* lse, float* sums, const void* logits, const int32_t* target,
+                                    int64_t tokens, int32_t vocab, float alpha, int32_t ignore_index, hipStream_t s)
+{
+    const T* lp = static_cast<const T*>(logits);
+    hipLaunchKernelGGL((xent_fwd_kernel<T>), dim3(static_cast<unsigned>(tokens)), dim3(kXentThreads), 0, s,
+                       loss, lse, lp, target, vocab, alpha, ignore_index);
+    if (sums)
+        hipLaunchKernelGGL((xent_sums_kernel<T>), dim3(1), dim3(1024), 0, s, sums, loss, lse, lp, target, tokens, vocab,
+                           ignore_index);
+    return launch_status();
+}
+
+template <typename T>
+static lsq_status xent_bwd_dispatch(void* dlogits, const void* logits, const float* lse, const int32_t* target,
+                                    int64_t tokens, int32_t vocab, float alpha, int32_t ignore_index, float grad_scale,
+                                    hipStream_t s)
+{
+    hipLaunchKernelGGL((xent_bwd_kernel<T>), dim3(static_cast<unsigned>(tokens)), dim3(kXentThreads), 0, s,
+                       static_cast<T*>(dlogits), static_cast<const T*>(logits), lse, target, vocab, alpha, ignore_index,
+                       grad_scale);
+    return launch_status();
+}
+
+}  // namespace lsq
+
+extern "C" lsq_status lsq_ls_xent_fwd(float* loss, float* lse, float* sums, const void* logits, const int32_t* target,
+                                      int64_t tokens, int32_t vocab, float alpha, int32_t ignore_index, lsq_dtype dt,
+                                      void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(tokens >= 0 && tokens <= 0x7FFFFFFF && vocab > 0);
+    LSQ_REQUIRE(alpha >= 0.0f && alpha <= 1.0f);
+    if (!valid_dtype(dt)) return LSQ_UNSUPPORTED_DTYPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (tokens == 0) return sums ? zero_fill(sums, 3, s) : LSQ_OK;
+    LSQ_REQUIRE(loss && lse && logits && target);
+    LSQ_ALIGNED(logits);
+    switch (dt) {
+        case LSQ_F16: return xent_fwd_dispatch<f16>(loss, lse, sums, logits, target, tokens, vocab, alpha, ignore_index, s);
+        case LSQ_BF16: return xent_fwd_dispatch<bf16>(loss, lse, sums, logits, target, tokens, vocab, alpha, ignore_index, s);
+        default: return xent_fwd_dispatch<float>(loss, lse, sums, logits, target, tokens, vocab, alpha, ignore_index, s);
+    }
+}
+
+extern "C" lsq_status lsq_ls_xent_bwd(void* dlogits, const void* logits, const float* lse, const int32_t* target,
+                                      int64_t tokens, int32_t vocab, float alpha, int32_t ignore_index,
+                                      float grad_scale, lsq_dtype dt, void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(tokens >= 0 && tokens <= 0x7FFFFFFF && vocab > 0);
+    LSQ_REQUIRE(alpha >= 0.0f && alpha <= 1.0f);
+    if (!valid_dtype(dt)) return LSQ_UNSUPPORTED_DTYPE;
+    if (tokens == 0) return LSQ_OK;
+    LSQ_REQUIRE(dlogits && logits && lse && target);
+    LSQ_ALIGNED(dlogits); LSQ_ALIGNED(logits);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (dt) {
+        case LSQ_F16: return xent_bwd_dispatch<f16>(dlogits, logits, lse, target, tokens, vocab, alpha, ignore_index, grad_scale, s);
+        case LSQ_BF16: return xent_bwd_dispatch<bf16>(dlogits, logits, lse, target, tokens, vocab, alpha, ignore_index, grad_scale, s);
+        default: return xent_bwd_dispatch<float>(dlogits, logits, lse, target, tokens, vocab, alpha, ignore_index, grad_scale, s);
+    }
+}

@@ -1,0 +1,352 @@
+// Masked, variable-length attention softmax, forward and backward (Sec. IV-B of
+// the paper, Softmax: maximum, partition function, normalisation; backward is
+// the softmax Jacobian of Sec. IV-A contracted with the upstream gradient).
+//
+// The paper copes with the spread of shapes ("a few to thousands" of columns,
+// "thousands to millions" of rows) by tuning templates at run time.  Here the
+// shape picks a compile-time bucket instead: LPR lanes share a row (1..64 lanes
+// of a wave64), each lane keeps VPL packs of 8 scores in registers, so a row is
+// read from HBM once, both reductions run on DPP inside the wave, and nothing
+// goes through LDS.  Short rows put many rows in one wave (k_len 32 -> 16 rows per
+// wave) so lanes are never idle.
+//
+// Masks restrict the SET the softmax runs over: packs that lie wholly beyond the
+// row's limit (key padding, or the causal diagonal) are not even loaded, and
+// their outputs are written as exact zeros.  Attention-probability dropout is
+// fused (Philox per pack, mask regenerated in backward).
+#include "host.hpp"
+
+namespace lsq {
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct SoftmaxGeom {
+    int64_t nrows;        // batch * heads * q_len
+    int rows_per_batch;   // heads * q_len
+    int q_len, k_len;
+    int causal;           // 0 / 1
+    int shift;            // k_len - q_len (end-aligned causal mask)
+    float scale;
+};
+
+// number of allowed keys (a prefix of the row) for query row `row`
+__device__ __forceinline__ int row_limit(const SoftmaxGeom& g, const int32_t* __restrict__ key_len, int64_t row)
+{
+    int limit = g.k_len;
+    if (key_len) {
+        const int b = static_cast<int>(row / g.rows_per_batch);
+        limit = min(max(key_len[b], 0), g.k_len);
+    }
+    if (g.causal) {
+        const int i = static_cast<int>(row % g.q_len);
+        limit = min(limit, max(i + 1 + g.shift, 0));
+    }
+    return limit;
+}
+
+template <typename T, int LPR, int VPL, bool DROP>
+__global__ __launch_bounds__(256) void softmax_fwd_kernel(T* y, T* __restrict__ yd, const T* x,
+                                                          const int32_t* __restrict__ key_len, SoftmaxGeom g,
+                                                          DropoutParams d)
+{
+    constexpr int RPB = 256 / LPR;
+    const int sub = threadIdx.x % LPR;
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * RPB + threadIdx.x / LPR;
+    const bool rv = row < g.nrows;
+    const int nv = g.k_len / kPack;
+    const int limit = rv ? row_limit(g, key_len, row) : 0;
+    const int64_t ro = row * g.k_len;
+
+    float v[VPL][8];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        const int j0 = (sub + k * LPR) * kPack;
+        if (j0 < limit) {                     // implies rv and idx < nv
+            load8<T>(x + ro + j0, v[k]);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                v[k][j] = (j0 + j < limit) ? v[k][j] * g.scale : -INFINITY;
+                mx = fmaxf(mx, v[k][j]);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[k][j] = -INFINITY;
+        }
+    }
+    mx = group_max<LPR>(mx);
+    const float mxs = (limit > 0 ? mx : 0.0f) * kLog2e;
+    float z = 0.0f;
+#pragma unroll
+    for (int k = 0; k < VPL; ++k)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float e = __builtin_amdgcn_exp2f(fmaf(v[k][j], kLog2e, -mxs));   // exp2(-inf) = 0 on masked lanes
+            v[k][j] = e;
+            z += e;
+        }
+    z = group_sum<LPR>(z);
+    const float inv = limit > 0 ? 1.0f / z : 0.0f;
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        const int idx = sub + k * LPR;
+        if (rv && idx < nv) {
+            float o[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o[j] = v[k][j] * inv;
+            store8<T>(y + ro + idx * kPack, o);
+            if constexpr (DROP) {
+                float kf[8];
+                dropout_factors8(d, static_cast<uint64_t>(row) * nv + idx, kf);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) o[j] *= kf[j];
+                store8<T>(yd + ro + idx * kPack, o);
+            }
+        }
+    }
+}
+
+template <typename T, int LPR, int VPL, bool DROP>
+__global__ __launch_bounds__(256) void softmax_bwd_kernel(T* dx, const T* dy, const T* __restrict__ y,
+                                                          const int32_t* __restrict__ key_len, SoftmaxGeom g,
+                                                          DropoutParams d)
+{
+    constexpr int RPB = 256 / LPR;
+    const int sub = threadIdx.x % LPR;
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * RPB + threadIdx.x / LPR;
+    const bool rv = row < g.nrows;
+    const int nv = g.k_len / kPack;
+    const int limit = rv ? row_limit(g, key_len, row) : 0;
+    const int64_t ro = row * g.k_len;
+
+    float yv[VPL][8], gv[VPL][8];
+    float dot = 0.0f;
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        const int idx = sub + k * LPR;
+        const int j0 = idx * kPack;
+        if (j0 < limit) {
+            load8<T>(y + ro + j0, yv[k]);
+            load8<T>(dy + ro + j0, gv[k]);
+            if constexpr (DROP) {
+                float kf[8];
+                dropout_factors8(d, static_cast<uint64_t>(row) * nv + idx, kf);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) gv[k][j] *= kf[j];
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (j0 + j >= limit) yv[k][j] = 0.0f;
+                dot = fmaf(gv[k][j], yv[k][j], dot);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { yv[k][j] = 0.0f; gv[k][j] = 0.0f; }
+        }
+    }
+    dot = group_sum<LPR>(dot);
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        const int idx = sub + k * LPR;
+        if (rv && idx < nv) {
+            float o[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)      // outside the allowed set: +0, not the -0 a product could give
+                o[j] = (idx * kPack + j < limit) ? g.scale * yv[k][j] * (gv[k][j] - dot) : 0.0f;
+            store8<T>(dx + ro + idx * kPack, o);
+        }
+    }
+}
+
+// ---- generic path: any k_len; one wave per row, element-strided, row re-read from cache
+template <typename T>
+__global__ __launch_bounds__(256) void softmax_fwd_generic(T* y, T* __restrict__ yd, const T* x,
+                                                           const int32_t* __restrict__ key_len, SoftmaxGeom g,
+                                                           DropoutParams d)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (row >= g.nrows) return;               // whole waves leave together
+    const int limit = row_limit(g, key_len, row);
+    const int64_t ro = row * g.k_len;
+    float mx = -INFINITY;
+    for (int j = lane; j < limit; j += 64) mx = fmaxf(mx, to_f32<T>(x[ro + j]) * g.scale);
+    mx = group_max<64>(mx);
+    const float mxs = (limit > 0 ? mx : 0.0f) * kLog2e;
+    float z = 0.0f;
+    for (int j = lane; j < limit; j += 64) z += __builtin_amdgcn_exp2f(fmaf(to_f32<T>(x[ro + j]) * g.scale, kLog2e, -mxs));
+    z = group_sum<64>(z);
+    const float inv = limit > 0 ? 1.0f / z : 0.0f;
+    for (int j = lane; j < g.k_len; j += 64) {
+        float o = 0.0f;
+        if (j < limit) o = __builtin_amdgcn_exp2f(fmaf(to_f32<T>(x[ro + j]) * g.scale, kLog2e, -mxs)) * inv;
+        y[ro + j] = from_f32<T>(o);
+        if (yd) yd[ro + j] = from_f32<T>(o * dropout_factor1(d, static_cast<uint64_t>(ro + j)));
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void softmax_bwd_generic(T* dx, const T* dy, const T* __restrict__ y,
+                                                           const int32_t* __restrict__ key_len, SoftmaxGeom g,
+                                                           DropoutParams d)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (row >= g.nrows) return;
+    const int limit = row_limit(g, key_len, row);
+    const int64_t ro = row * g.k_len;
+    float dot = 0.0f;
+    for (int j = lane; j < limit; j += 64) {
+        float gg = to_f32<T>(dy[ro + j]);
+        if (d.t16) gg *= dropout_factor1(d, static_cast<uint64_t>(ro + j));
+        dot = fmaf(gg, to_f32<T>(y[ro + j]), dot);
+    }
+    dot = group_sum<64>(dot);
+    for (int j = lane; j < g.k_len; j += 64) {
+        float o = 0.0f;
+        if (j < limit) {
+            float gg = to_f32<T>(dy[ro + j]);
+            if (d.t16) gg *= dropout_factor1(d, static_cast<uint64_t>(ro + j));
+            o = g.scale * to_f32<T>(y[ro + j]) * (gg - dot);
+        }
+        dx[ro + j] = from_f32<T>(o);
+    }
+}
+
+// ------------------------------------------------------------------ dispatch
+struct SmShape { int lpr, vpl; };
+
+inline SmShape softmax_shape(int k_len)
+{
+    if (k_len % kPack != 0) return {0, 0};
+    const int nv = k_len / kPack;
+    if (nv <= 1) return {1, 1};
+    if (nv <= 2) return {2, 1};
+    if (nv <= 4) return {4, 1};
+    if (nv <= 8) return {8, 1};
+    if (nv <= 16) return {16, 1};
+    if (nv <= 32) return {32, 1};
+    if (nv <= 64) return {64, 1};
+    if (nv <= 128) return {64, 2};
+    if (nv <= 192) return {64, 3};
+    if (nv <= 256) return {64, 4};
+    return {0, 0};
+}
+
+#define LSQ_SM_CASES(X) X(1, 1) X(2, 1) X(4, 1) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 3) X(64, 4)
+
+template <typename T>
+static lsq_status softmax_fwd_dispatch(void* y, void* yd, const void* x, const int32_t* key_len, const SoftmaxGeom& g,
+                                       const DropoutParams& d, hipStream_t s)
+{
+    T* yp = static_cast<T*>(y);
+    T* ydp = static_cast<T*>(yd);
+    const T* xp = static_cast<const T*>(x);
+    const SmShape sh = softmax_shape(g.k_len);
+    const bool drop = d.t16 != 0;
+    if (sh.lpr == 0) {
+        hipLaunchKernelGGL((softmax_fwd_generic<T>), dim3(static_cast<unsigned>(ceil_div(g.nrows, 4))), dim3(256), 0, s,
+                           yp, ydp, xp, key_len, g, d);
+        return launch_status();
+    }
+    const dim3 grid(static_cast<unsigned>(ceil_div(g.nrows, 256 / sh.lpr))), block(256);
+#define X(L, V)                                                                                              \
+    if (sh.lpr == L && sh.vpl == V) {                                                                        \
+        if (drop) hipLaunchKernelGGL((softmax_fwd_kernel<T, L, V, true>), grid, block, 0, s, yp, ydp, xp, key_len, g, d); \
+        else hipLaunchKernelGGL((softmax_fwd_kernel<T, L, V, false>), grid, block, 0, s, yp, ydp, xp, key_len, g, d);    \
+    }
+    LSQ_SM_CASES(X)
+#undef X
+    return launch_status();
+}
+
+template <typename T>
+static lsq_status softmax_bwd_dispatch(void* dx, const void* dy, const void* y, const int32_t* key_len,
+                                       const SoftmaxGeom& g, const DropoutParams& d, hipStream_t s)
+{
+    T* dxp = static_cast<T*>(dx);
+    const T* dyp = static_cast<const T*>(dy);
+    const T* yp = static_cast<const T*>(y);
+    const SmShape sh = softmax_shape(g.k_len);
+    const bool drop = d.t16 != 0;
+    if (sh.lpr == 0) {
+        hipLaunchKernelGGL((softmax_bwd_generic<T>), dim3(static_cast<unsigned>(ceil_div(g.nrows, 4))), dim3(256), 0, s,
+                           dxp, dyp, yp, key_len, g, d);
+        return launch_status();
+    }
+    const dim3 grid(static_cast<unsigned>(ceil_div(g.nrows, 256 / sh.lpr))), block(256);
+#define X(L, V)                                                                                              \
+    if (sh.lpr == L && sh.vpl == V) {                                                                        \
+        if (drop) hipLaunchKernelGGL((softmax_bwd_kernel<T, L, V, true>), grid, block, 0, s, dxp, dyp, yp, key_len, g, d); \
+        else hipLaunchKernelGGL((softmax_bwd_kernel<T, L, V, false>), grid, block, 0, s, dxp, dyp, yp, key_len, g, d);    \
+    }
+    LSQ_SM_CASES(X)
+#undef X
+    return launch_status();
+}
+
+static lsq_status softmax_check(const void* a, const void* b, int32_t batch, int32_t heads, int32_t q_len,
+                                int32_t k_len, float scale, int dt, SoftmaxGeom* g)
+{
+    (void)a; (void)b;
+    if (batch < 0 || heads < 0 || q_len < 0 || k_len < 0) return LSQ_INVALID_ARG;
+    if (!(scale == scale) || isinf(scale)) return LSQ_INVALID_ARG;
+    if (!valid_dtype(dt)) return LSQ_UNSUPPORTED_DTYPE;
+    const int64_t rpb = static_cast<int64_t>(heads) * q_len;
+    if (rpb > 0x7FFFFFFF) return LSQ_INVALID_ARG;
+    g->nrows = static_cast<int64_t>(batch) * rpb;
+    g->rows_per_batch = static_cast<int>(rpb);
+    g->q_len = q_len;
+    g->k_len = k_len;
+    g->shift = k_len - q_len;
+    g->scale = scale;
+    if (ceil_div(g->nrows, 4) > 0x7FFFFFFF) return LSQ_INVALID_ARG;
+    return LSQ_OK;
+}
+
+}  // namespace lsq
+
+extern "C" lsq_status lsq_softmax_fwd(void* y, void* y_drop, const void* x, const int32_t* key_len, int32_t batch,
+                                      int32_t heads, int32_t q_len, int32_t k_len, int32_t causal, float scale,
+                                      float p_attn, uint64_t seed, uint64_t offset, lsq_dtype dt, void* stream)
+{
+    using namespace lsq;
+    SoftmaxGeom g;
+    lsq_status st = softmax_check(y, x, batch, heads, q_len, k_len, scale, dt, &g);
+    if (st != LSQ_OK) return st;
+    g.causal = causal != 0;
+    DropoutParams d;
+    LSQ_REQUIRE(make_dropout(p_attn, seed, offset, &d));
+    LSQ_REQUIRE((d.t16 != 0) == (y_drop != nullptr));
+    if (g.nrows == 0 || k_len == 0) return LSQ_OK;
+    LSQ_REQUIRE(y && x);
+    LSQ_ALIGNED(y); LSQ_ALIGNED(y_drop); LSQ_ALIGNED(x);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (dt) {
+        case LSQ_F16: return softmax_fwd_dispatch<f16>(y, y_drop, x, key_len, g, d, s);
+        case LSQ_BF16: return softmax_fwd_dispatch<bf16>(y, y_drop, x, key_len, g, d, s);
+        default: return softmax_fwd_dispatch<float>(y, y_drop, x, key_len, g, d, s);
+    }
+}
+
+extern "C" lsq_status lsq_softmax_bwd(void* dx, const void* dy, const void* y, const int32_t* key_len, int32_t batch,
+                                      int32_t heads, int32_t q_len, int32_t k_len, int32_t causal, float scale,
+                                      float p_attn, uint64_t seed, uint64_t offset, lsq_dtype dt, void* stream)
+{
+    using namespace lsq;
+    SoftmaxGeom g;
+    lsq_status st = softmax_check(dx, dy, batch, heads, q_len, k_len, scale, dt, &g);
+    if (st != LSQ_OK) return st;
+    g.causal = causal != 0;
+    DropoutParams d;
+    LSQ_REQUIRE(make_dropout(p_attn, seed, offset, &d));
+    if (g.nrows == 0 || k_len == 0) return LSQ_OK;
+    LSQ_REQUIRE(dx && dy && y);
+    LSQ_ALIGNED(dx); LSQ_ALIGNED(dy); LSQ_ALIGNED(y);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (dt) {
+        case LSQ_F16: return softmax_bwd_dispatch<f16>(dx, dy, y, key_len, g, d, s);
+        case LSQ_BF16: return softmax_bwd_dispatch<bf16>(dx, dy, y, key_len, g, d, s);
+        default: return softmax_bwd_dispatch<float>(dx, dy, y, key_len, g, d, s);
+    }
+}

@@ -1,0 +1,103 @@
+"""CPU-side checks of the boundary: the shared library loads, exports every symbol
+the header declares, and rejects bad arguments on the host before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2110_05722_amd as L
+from paper_2110_05722_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(L.lib_path()):
+        from paper_2110_05722_amd.build import build
+        build(verbose=False)
+    return L.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    hdr = open(os.path.join(ROOT, "include", "lsq.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(lsq_[a-z0-9_]+)\s*\(", hdr))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings_and_workspace(lib):
+    names = [L.lsq_status_string(i) for i in range(6)]
+    assert names == ["LSQ_OK", "LSQ_INVALID_ARG", "LSQ_UNSUPPORTED_DTYPE", "LSQ_MISALIGNED",
+                     "LSQ_WORKSPACE_TOO_SMALL", "LSQ_LAUNCH_FAILED"]
+    assert L.lsq_workspace_bytes(0, 0, 1024) == 0
+    w = L.lsq_workspace_bytes(0, 8192, 1024)
+    assert w > 0 and w % (2 * 1024 * 4) == 0
+    w = L.lsq_workspace_bytes(1, 8192, 1024)
+    assert w > 0 and w % (1024 * 4) == 0
+    assert L.lsq_workspace_bytes(99, 8192, 1024) == 0
+
+
+A = C.c_void_p(4096)      # aligned, never dereferenced: every call below fails before a launch
+U = C.c_void_p(4096 + 2)  # misaligned
+
+
+def test_host_side_argument_errors(lib):
+    INVALID, DTYPE, MISALIGNED, WS = 1, 2, 3, 4
+    # adam: step < 1, beta out of range, bad dtype, misaligned, null
+    f = lib.lsq_adam_step
+    assert f(A, A, A, A, None, 8, 1e-3, .9, .98, 1e-8, 0., 0, 0, 1, 1., 0, 0, None) == INVALID
+    assert f(A, A, A, A, None, 8, 1e-3, 1.0, .98, 1e-8, 0., 1, 0, 1, 1., 0, 0, None) == INVALID
+    assert f(A, A, A, A, None, -1, 1e-3, .9, .98, 1e-8, 0., 1, 0, 1, 1., 0, 0, None) == INVALID
+    assert f(A, A, A, A, None, 8, 1e-3, .9, .98, 1e-8, 0., 1, 0, 1, 1., 7, 0, None) == DTYPE
+    assert f(A, A, A, A, A, 8, 1e-3, .9, .98, 1e-8, 0., 1, 0, 1, 1., 0, 2, None) == DTYPE
+    assert f(U, A, A, A, None, 8, 1e-3, .9, .98, 1e-8, 0., 1, 0, 1, 1., 0, 0, None) == MISALIGNED
+    assert f(None, A, A, A, None, 8, 1e-3, .9, .98, 1e-8, 0., 1, 0, 1, 1., 0, 0, None) == INVALID
+    assert f(None, None, None, None, None, 0, 1e-3, .9, .98, 1e-8, 0., 1, 0, 1, 1., 0, 0, None) == 0
+    # layernorm
+    f = lib.lsq_layernorm_fwd
+    assert f(A, A, A, A, A, A, 4, 0, 1e-5, 0, None) == INVALID
+    assert f(A, A, A, A, A, A, 4, 8, -1.0, 0, None) == INVALID
+    assert f(A, A, A, U, A, A, 4, 8, 1e-5, 0, None) == MISALIGNED
+    assert f(A, A, A, A, A, A, 4, 8, 1e-5, 5, None) == DTYPE
+    assert f(None, None, None, None, None, None, 0, 8, 1e-5, 0, None) == 0
+    f = lib.lsq_layernorm_bwd
+    assert f(A, A, A, A, A, A, A, A, None, A, 16, 64, 512, 0, None) == WS
+    assert f(A, A, A, A, A, A, A, A, None, None, 0, 64, 512, 0, None) == WS
+    assert f(A, None, A, A, A, A, A, A, None, A, 1 << 30, 64, 512, 0, None) == INVALID
+    # bias + dropout + residual: p outside [0, 1)
+    f = lib.lsq_bias_dropout_residual_fwd
+    assert f(A, A, A, A, 4, 8, 1.0, 1, 0, 0, None) == INVALID
+    assert f(A, A, A, A, 4, 8, -0.1, 1, 0, 0, None) == INVALID
+    assert f(A, A, A, A, 4, 8, float("nan"), 1, 0, 0, None) == INVALID
+    assert f(A, U, A, A, 4, 8, 0.1, 1, 0, 0, None) == MISALIGNED
+    f = lib.lsq_bias_dropout_residual_bwd
+    assert f(A, A, A, 64, 512, 0.1, 1, 0, A, 8, 0, None) == WS
+    assert f(A, None, A, 64, 512, 1.5, 1, 0, None, 0, 0, None) == INVALID
+    # softmax: y_drop must be given iff p_attn > 0
+    f = lib.lsq_softmax_fwd
+    assert f(A, None, A, None, 2, 2, 8, 8, 0, 1.0, 0.1, 1, 0, 0, None) == INVALID
+    assert f(A, A, A, None, 2, 2, 8, 8, 0, 1.0, 0.0, 1, 0, 0, None) == INVALID
+    assert f(A, None, A, None, -1, 2, 8, 8, 0, 1.0, 0.0, 1, 0, 0, None) == INVALID
+    assert f(A, None, U, None, 2, 2, 8, 8, 0, 1.0, 0.0, 1, 0, 0, None) == MISALIGNED
+    assert f(None, None, None, None, 0, 2, 8, 8, 0, 1.0, 0.0, 1, 0, 0, None) == 0
+    f = lib.lsq_softmax_bwd
+    assert f(A, A, None, None, 2, 2, 8, 8, 0, 1.0, 0.0, 1, 0, 0, None) == INVALID
+    # criterion
+    f = lib.lsq_ls_xent_fwd
+    assert f(A, A, None, A, A, 4, 0, 0.1, -100, 0, None) == INVALID
+    assert f(A, A, None, A, A, 4, 8, 1.5, -100, 0, None) == INVALID
+    assert f(A, A, None, U, A, 4, 8, 0.1, -100, 0, None) == MISALIGNED
+    f = lib.lsq_ls_xent_bwd
+    assert f(A, A, None, A, 4, 8, 0.1, -100, 1.0, 0, None) == INVALID
+    assert f(A, A, A, A, 4, 8, 0.1, -100, 1.0, 9, None) == DTYPE
+
+
+def test_binding_refuses_cpu_tensors(lib):
+    import torch
+    x = torch.zeros(4, 8, dtype=torch.float16)
+    with pytest.raises(L.LsqError):
+        L.lsq_layernorm_fwd(x, x[0], x[0])

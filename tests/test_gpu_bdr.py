@@ -1,0 +1,90 @@
+"""GPU parity: fused bias + dropout + residual through the C-ABI against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2110_05722_amd as L
+from tests._util import assert_close_f32, assert_close_store, dev, say
+from workloads import CONFIGS, layer_tensors, to_torch
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [
+    (512, 512, 0.1), (4096, 512, 0.1), (8192, 1024, 0.3), (8192, 1280, 0.1),
+    (4096, 256, 0.1), (1000, 768, 0.5), (37, 64, 0.1), (5, 8, 0.25), (3, 1536, 0.1), (2, 8192, 0.1),
+    (1, 1024, 0.1), (7, 257, 0.2), (33, 50, 0.1), (9, 1, 0.5), (131, 520, 0.0),
+]
+
+
+def _case(rows, hidden, dt):
+    return layer_tensors(CONFIGS[0], dt, rows=rows, hidden=hidden, stream=200 + rows % 89 + hidden)
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("rows,hidden,p", SHAPES)
+def test_bdr_fwd_bwd(rows, hidden, p, dt):
+    if dt == "f32" and rows * hidden > 1 << 21:
+        pytest.skip("fp32 storage is exercised on the small shapes only")
+    say(f"[bias_dropout_residual] rows={rows} hidden={hidden} p={p} dt={dt}")
+    seed, offset = 1234, rows  # a different Philox offset per case
+    t = _case(rows, hidden, dt)
+    d = dev()
+    x, bias, res, dy = (to_torch(t[k], dt, d) for k in ("x", "bias", "residual", "dy"))
+    out = L.lsq_bias_dropout_residual_fwd(x, bias, res, p, seed, offset)
+    ref = oracle.bias_dropout_residual_fwd(t["x"], t["bias"], t["residual"], p, seed, offset, dt)
+    assert_close_store(out, ref, dt, "out")
+    out_nb = L.lsq_bias_dropout_residual_fwd(x, None, res, p, seed, offset)
+    ref_nb = oracle.bias_dropout_residual_fwd(t["x"], None, t["residual"], p, seed, offset, dt)
+    assert_close_store(out_nb, ref_nb, dt, "out(no bias)")
+
+    dx, dbias = L.lsq_bias_dropout_residual_bwd(dy, p, seed, offset)
+    rdx, rdb = oracle.bias_dropout_residual_bwd(t["dy"], p, seed, offset, dt)
+    assert_close_store(dx, rdx, dt, "dx")
+    assert_close_f32(dbias, rdb, "dbias", floor=1e-6 * np.sqrt(rows) * 4)
+    dx2, none = L.lsq_bias_dropout_residual_bwd(dy, p, seed, offset, want_dbias=False)
+    assert none is None and torch.equal(dx, dx2)
+
+
+@pytest.mark.parametrize("rows,hidden", [(8192, 1024), (513, 520), (64, 257)])
+@pytest.mark.parametrize("p", [0.1, 0.3])
+def test_dropout_mask_is_bit_exact_and_shared_by_fwd_and_bwd(rows, hidden, p):
+    say(f"[bias_dropout_residual] mask rows={rows} hidden={hidden} p={p}")
+    d = dev()
+    seed, offset = 0xDEADBEEF12345678, (1 << 33) + 5
+    ones = torch.ones((rows, hidden), dtype=torch.float16, device=d)
+    zeros = torch.zeros_like(ones)
+    keep = oracle.dropout_mask(rows * hidden, p, seed, offset).reshape(rows, hidden)
+    fwd = L.lsq_bias_dropout_residual_fwd(ones, None, zeros, p, seed, offset)
+    dx, _ = L.lsq_bias_dropout_residual_bwd(ones, p, seed, offset)
+    m_fwd = (fwd != 0).cpu().numpy().astype(np.uint8)
+    m_bwd = (dx != 0).cpu().numpy().astype(np.uint8)
+    assert np.array_equal(m_fwd, keep)
+    assert np.array_equal(m_bwd, keep)
+    # kept values carry exactly the nominal 1/(1-p)
+    scale = torch.tensor(1.0 / (1.0 - float(np.float32(p))), dtype=torch.float32).to(torch.float16).item()
+    assert torch.all((fwd == 0) | (fwd == scale))
+
+
+def test_bdr_in_place_and_reproducible():
+    say("[bias_dropout_residual] in place / reproducible")
+    dt, d = "f16", dev()
+    t = _case(1024, 1024, dt)
+    x, bias, res, dy = (to_torch(t[k], dt, d) for k in ("x", "bias", "residual", "dy"))
+    a = L.lsq_bias_dropout_residual_fwd(x, bias, res, 0.1, 7, 0)
+    xc = x.clone()
+    b = L.lsq_bias_dropout_residual_fwd(xc, bias, res, 0.1, 7, 0, out=xc)
+    assert torch.equal(a, b)
+    dx1, db1 = L.lsq_bias_dropout_residual_bwd(dy, 0.1, 7, 0)
+    dyc = dy.clone()
+    dx2, db2 = L.lsq_bias_dropout_residual_bwd(dyc, 0.1, 7, 0, dx=dyc)
+    assert torch.equal(dx1, dx2) and torch.equal(db1, db2)
+
+
+def test_bdr_empty():
+    d = dev()
+    x = torch.empty((0, 64), dtype=torch.float16, device=d)
+    out = L.lsq_bias_dropout_residual_fwd(x, None, x, 0.1, 1, 0)
+    dx, dbias = L.lsq_bias_dropout_residual_bwd(x, 0.1, 1, 0)
+    torch.cuda.synchronize()
+    assert out.numel() == 0 and dbias.abs().sum().item() == 0
