@@ -1,0 +1,355 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused non-GEMM training kernels on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config gpt2-large] [--dtype f16]
+
+A "step" is one pass of the whole hot path over one synthetic batch of the chosen
+configuration: layernorm fwd, softmax fwd, bias+dropout+residual fwd, criterion
+fwd, criterion bwd, bias+dropout+residual bwd, softmax bwd, layernorm bwd and one
+Adam step over the flat workspace, each through the C-ABI, inputs resident in HBM.
+The layer-sized tensors (tens of MiB) rotate through enough buffer sets that
+neither L2 nor the 256 MB Infinity Cache can serve them ("cold" numbers).
+
+Prints ONE JSON line: whole-step throughput in algorithmic GB/s, the roofline
+entry of the dominant kernel (Adam), a per-operator table (us, GB/s, fraction of
+the 8 TB/s HBM peak), the per-layer non-GEMM roll-up, and the CPU oracle timed on
+a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+COLD_FOOTPRINT = 768 << 20       # rotate layer tensors over at least this many bytes
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="gpt2-large")
+    ap.add_argument("--dtype", default="f16", choices=["f16", "bf16"])
+    ap.add_argument("--op-reps", type=int, default=40, help="back-to-back launches per operator in the per-op table")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--warm", action="store_true", help="do not rotate buffers (cache-warm numbers)")
+    ap.add_argument("--ops", default="", help="comma-separated subset of operators (tuning runs; the default is all nine)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path has no collective; see DESIGN.md, sharding). "
+              f"--gpus {args.gpus} is not supported.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2110_05722_amd as L
+    from workloads import ADAM_HYPER, CONFIGS, IGNORE_INDEX, device_normal, torch_dtype
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU path to time.", file=sys.stderr)
+        sys.exit(2)
+    L.load()
+    cfg = next(c for c in CONFIGS if c.name == args.config)
+    dt = args.dtype
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    tdt = torch_dtype(dt)
+    T, H, V, n = cfg.tokens, cfg.hidden, cfg.vocab, cfg.adam_n
+    B, N, Lq = cfg.batch, cfg.heads, cfg.max_len
+    E = T * H
+    Es = B * N * Lq * Lq
+    scale = 1.0 / float(np.sqrt(H / N))
+
+    # ------------------------------------------------------------------ inputs
+    layer_bytes = 6 * E * 2
+    sets = 1 if args.warm else max(2, -(-COLD_FOOTPRINT // layer_bytes))
+    seed = cfg.seed * 1000
+    layer = []
+    for s in range(sets):
+        layer.append(dict(
+            x=device_normal((T, H), 1.0, dt, seed + 10 * s + 1, dev),
+            res=device_normal((T, H), 1.0, dt, seed + 10 * s + 2, dev),
+            dy=device_normal((T, H), 1.0, dt, seed + 10 * s + 3, dev),
+            out=torch.empty((T, H), dtype=tdt, device=dev),
+            y=torch.empty((T, H), dtype=tdt, device=dev),
+            dx=torch.empty((T, H), dtype=tdt, device=dev),
+            mean=torch.empty(T, dtype=torch.float32, device=dev),
+            rstd=torch.empty(T, dtype=torch.float32, device=dev),
+        ))
+    gamma = device_normal((H,), 0.1, dt, seed + 5, dev, mean=1.0)
+    beta = device_normal((H,), 0.1, dt, seed + 6, dev)
+    bias = device_normal((H,), 0.1, dt, seed + 7, dev)
+    dgamma = torch.empty(H, dtype=torch.float32, device=dev)
+    dbeta = torch.empty(H, dtype=torch.float32, device=dev)
+    dbias = torch.empty(H, dtype=torch.float32, device=dev)
+    ws = torch.empty(max(L.lsq_workspace_bytes(0, T, H), L.lsq_workspace_bytes(1, T, H), 16), dtype=torch.uint8, device=dev)
+
+    soft_sets = 1 if args.warm else max(2, -(-COLD_FOOTPRINT // (4 * Es * 2)))
+    soft = []
+    rng = np.random.Generator(np.random.PCG64([cfg.seed, 99]))
+    from workloads import sentence_lengths
+    key_len = None if cfg.lengths == "full" else torch.from_numpy(sentence_lengths(cfg, rng)).to(dev)
+    for s in range(soft_sets):
+        soft.append(dict(
+            x=device_normal((B, N, Lq, Lq), 1.0, dt, seed + 100 + s, dev),
+            dy=device_normal((B, N, Lq, Lq), 1.0, dt, seed + 200 + s, dev),
+            y=torch.empty((B, N, Lq, Lq), dtype=tdt, device=dev),
+            yd=torch.empty((B, N, Lq, Lq), dtype=tdt, device=dev) if cfg.p_attn > 0 else None,
+            dx=torch.empty((B, N, Lq, Lq), dtype=tdt, device=dev),
+        ))
+    allowed = _allowed_elements(cfg, None if key_len is None else key_len.cpu().numpy())
+
+    logits = device_normal((T, V), cfg.logit_std, dt, seed + 300, dev)
+    dlogits = torch.empty((T, V), dtype=tdt, device=dev)
+    tgt = rng.integers(0, V, size=T).astype(np.int32)
+    if cfg.active_frac < 1.0:
+        tgt[rng.random(T) >= cfg.active_frac] = IGNORE_INDEX
+    elif key_len is not None:
+        pad = (np.arange(Lq)[None, :] >= key_len.cpu().numpy()[:, None]).reshape(-1)
+        tgt[pad] = IGNORE_INDEX
+    t_active = int((tgt != IGNORE_INDEX).sum())
+    target = torch.from_numpy(tgt).to(dev)
+    loss = torch.empty(T, dtype=torch.float32, device=dev)
+    lse = torch.empty(T, dtype=torch.float32, device=dev)
+    sums = torch.empty(3, dtype=torch.float32, device=dev)
+
+    p = device_normal((n,), 0.02, "f32", seed + 400, dev)
+    g = device_normal((n,), 1e-3, dt, seed + 401, dev)
+    m = torch.zeros(n, dtype=torch.float32, device=dev)
+    v = torch.zeros(n, dtype=torch.float32, device=dev)
+    p_lp = torch.empty(n, dtype=tdt, device=dev)
+
+    pr, pa, ps = cfg.p_residual, cfg.p_attn, cfg.philox_seed
+    causal = cfg.causal
+    state = dict(step=0)
+
+    # --------------------------------------------------------------- operators
+    def op_ln_fwd(i):
+        a = layer[i % sets]
+        L.lsq_layernorm_fwd(a["x"], gamma, beta, 1e-5, y=a["y"], mean=a["mean"], rstd=a["rstd"])
+
+    def op_ln_bwd(i):
+        a = layer[i % sets]
+        L.lsq_layernorm_bwd(a["dy"], a["x"], gamma, a["mean"], a["rstd"], dx=a["dx"], dgamma=dgamma, dbeta=dbeta,
+                            workspace=ws)
+
+    def op_bdr_fwd(i):
+        a = layer[i % sets]
+        L.lsq_bias_dropout_residual_fwd(a["x"], bias, a["res"], pr, ps, i, out=a["out"])
+
+    def op_bdr_bwd(i):
+        a = layer[i % sets]
+        L.lsq_bias_dropout_residual_bwd(a["dy"], pr, ps, i, dx=a["dx"], dbias=dbias, workspace=ws)
+
+    def op_sm_fwd(i):
+        a = soft[i % soft_sets]
+        L.lsq_softmax_fwd(a["x"], key_len, causal, scale, pa, ps, 1000 + i, y=a["y"], y_drop=a["yd"])
+
+    def op_sm_bwd(i):
+        a = soft[i % soft_sets]
+        L.lsq_softmax_bwd(a["dy"], a["y"], key_len, causal, scale, pa, ps, 1000 + i, dx=a["dx"])
+
+    def op_xent_fwd(i):
+        L.lsq_ls_xent_fwd(logits, target, cfg.alpha, IGNORE_INDEX, loss=loss, lse=lse, sums=sums)
+
+    def op_xent_bwd(i):
+        L.lsq_ls_xent_bwd(logits, lse, target, cfg.alpha, IGNORE_INDEX, 1.0 / max(t_active, 1), dlogits=dlogits)
+
+    def op_adam(i):
+        state["step"] += 1
+        L.lsq_adam_step(p, m, v, g, p_lp, step=state["step"], **ADAM_HYPER)
+
+    # algorithmic bytes per launch (what the method must move)
+    bts = {
+        "layernorm_fwd": 4 * E + 8 * T + 4 * H,
+        "layernorm_bwd": 6 * E + 8 * T + 2 * H + 8 * H,
+        "bias_dropout_residual_fwd": 6 * E + 2 * H,
+        "bias_dropout_residual_bwd": 4 * E + 4 * H,
+        "softmax_fwd": 2 * allowed + 2 * Es + (2 * Es if pa > 0 else 0),
+        "softmax_bwd": 4 * allowed + 2 * Es,
+        "ls_xent_fwd": 2 * T * V + 12 * T,
+        "ls_xent_bwd": 2 * t_active * V + 2 * T * V + 8 * T,
+        "adam_step": 28 * n,
+    }
+    ops = [
+        ("layernorm_fwd", op_ln_fwd), ("softmax_fwd", op_sm_fwd), ("bias_dropout_residual_fwd", op_bdr_fwd),
+        ("ls_xent_fwd", op_xent_fwd), ("ls_xent_bwd", op_xent_bwd), ("bias_dropout_residual_bwd", op_bdr_bwd),
+        ("softmax_bwd", op_sm_bwd), ("layernorm_bwd", op_ln_bwd), ("adam_step", op_adam),
+    ]
+
+    if args.ops:
+        keep = set(args.ops.split(","))
+        ops = [o for o in ops if o[0] in keep]
+        if not ops:
+            sys.exit("bench.py: --ops matched nothing")
+
+    def one_step(i):
+        for _, f in ops:
+            f(i)
+
+    # ---------------------------------------------------------- timed region
+    for i in range(args.warmup):
+        one_step(i)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        for name, f in ops:
+            if name == "adam_step":
+                ev[i][0].record()
+                f(args.warmup + i)
+                ev[i][1].record()
+            else:
+                f(args.warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    names = [o[0] for o in ops]
+    adam_ms = float(np.mean([a.elapsed_time(b) for a, b in ev])) if "adam_step" in names else float("nan")
+    step_bytes = sum(bts[k] for k in names)
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ------------------------------------------- per-operator table (cold, back to back)
+    table = {}
+    for name, f in ops:
+        reps = max(3, min(args.op_reps, int(2e10 // max(bts[name], 1)) + 3))
+        for i in range(3):
+            f(i)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(reps):
+            f(3 + i)
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 1e3 / reps
+        gbs = bts[name] / (us * 1e-6) / 1e9
+        table[name] = {"us": round(us, 2), "GBps": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
+                       "bytes": int(bts[name]), "launches": reps}
+    for k in bts:
+        table.setdefault(k, {"us": float("nan")})
+    enc = 2 * table["layernorm_fwd"]["us"] + 2 * table["bias_dropout_residual_fwd"]["us"] + table["softmax_fwd"]["us"] \
+        + 2 * table["layernorm_bwd"]["us"] + 2 * table["bias_dropout_residual_bwd"]["us"] + table["softmax_bwd"]["us"]
+    dec = 3 * (table["layernorm_fwd"]["us"] + table["bias_dropout_residual_fwd"]["us"] + table["layernorm_bwd"]["us"]
+               + table["bias_dropout_residual_bwd"]["us"]) + 2 * (table["softmax_fwd"]["us"] + table["softmax_bwd"]["us"])
+
+    achieved = bts["adam_step"] / (adam_ms * 1e-3) / 1e9
+    roofline = {"kernel": "adam_kernel", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": _traffic(cfg.name, dt),
+                "bytes_per_launch": int(bts["adam_step"]), "avg_launch_ms": round(adam_ms, 4)}
+
+    out = {
+        "metric": "achieved HBM GB/s over one pass of the fused non-GEMM training kernels "
+                  "(per-op GB/s, % of peak and us per layer in 'ops' / 'layer_us')",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "storage_dtype": dt, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {B}x{Lq} tokens, hidden {H}, heads {N}, vocab {V}, Adam n={n}, "
+                               f"{'causal' if causal else 'key-padding'} softmax, storage {dt}",
+                   "buffers": "warm" if args.warm else f"cold (layer tensors rotate over {sets} sets, softmax over {soft_sets})"},
+        "roofline": roofline,
+        "ops": table,
+        "layer_us": {"encoder_layer_fwd_bwd_nongemm": round(enc, 1), "decoder_layer_fwd_bwd_nongemm": round(dec, 1)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, dt)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+
+
+def _allowed_elements(cfg, key_len):
+    """Number of (row, key) pairs inside the allowed set: what a masked softmax must read."""
+    B, N, L = cfg.batch, cfg.heads, cfg.max_len
+    kl = np.full(B, L) if key_len is None else np.clip(key_len, 0, L)
+    total = 0
+    for b in range(B):
+        if cfg.causal:
+            i = np.arange(L)
+            total += int(np.minimum(i + 1, kl[b]).sum()) * N
+        else:
+            total += int(kl[b]) * L * N
+    return total
+
+
+def _traffic(cfg_name, dt):
+    """HBM bytes per Adam launch as measured by rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by the
+    copy-kernel calibration): read from the committed profile summary of this workload, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"adam_kernel_{cfg_name}_{dt}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(float(line.split(":", 1)[1].strip()))
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(cfg, dt):
+    """The CPU oracle as it stands, timed on a bounded sample of the same workload on the host cores."""
+    import oracle
+    from workloads import ADAM_HYPER, IGNORE_INDEX, encode
+
+    rng = np.random.Generator(np.random.PCG64([cfg.seed, 555]))
+    H, V, L, N = cfg.hidden, cfg.vocab, cfg.max_len, cfg.heads
+    rows = min(cfg.tokens, 8192)
+    sb = max(1, min(cfg.batch, 64_000_000 // (N * L * L)))
+    xt = min(cfg.tokens, 200_000_000 // V)
+    an = min(cfg.adam_n, 128_000_000)
+    f = lambda shape, s=1.0: encode(rng.standard_normal(shape, dtype=np.float32) * np.float32(s), dt)
+    x, res, dy = f((rows, H)), f((rows, H)), f((rows, H))
+    gamma, beta, bias = f((H,)), f((H,)), f((H,))
+    sx, sdy = f((sb, N, L, L)), f((sb, N, L, L))
+    logits = f((xt, V), cfg.logit_std)
+    tgt = rng.integers(0, V, size=xt).astype(np.int32)
+    p = rng.standard_normal(an, dtype=np.float32) * np.float32(0.02)
+    g = f((an,), 1e-3)
+    z = np.zeros(an, np.float32)
+    oracle.lib()
+    E, Es = rows * H, sb * N * L * L
+
+    def one_pass():
+        oracle.layernorm_fwd(x, gamma, beta, 1e-5, dt)
+        oracle.layernorm_bwd(dy, x, gamma, 1e-5, dt)
+        oracle.bias_dropout_residual_fwd(x, bias, res, cfg.p_residual, 1, 0, dt)
+        oracle.bias_dropout_residual_bwd(dy, cfg.p_residual, 1, 0, dt)
+        y, _ = oracle.softmax_fwd(sx, None, cfg.causal, 0.125, dt, cfg.p_attn, 1, 0)
+        oracle.softmax_bwd(sdy, encode(y, dt), None, cfg.causal, 0.125, dt, cfg.p_attn, 1, 0)
+        oracle.ls_xent_fwd(logits, tgt, cfg.alpha, IGNORE_INDEX, dt)
+        oracle.ls_xent_bwd(logits, tgt, cfg.alpha, IGNORE_INDEX, 1.0, dt)
+        oracle.adam_step(p, z, z, g, dt, step=1, **ADAM_HYPER)
+
+    # repeat the sample until about 10 s of CPU work have been timed (at most 30 passes)
+    passes = 0
+    t0 = time.perf_counter()
+    while True:
+        one_pass()
+        passes += 1
+        t1 = time.perf_counter()
+        if t1 - t0 >= 10.0 or passes >= 30:
+            break
+    half = 0.5 if cfg.causal else 1.0
+    nbytes = (4 * E + 6 * E + 6 * E + 4 * E) + (2 * half + 2 + (2 if cfg.p_attn > 0 else 0)) * Es \
+        + (4 * half + 2) * Es + 2 * xt * V + 4 * xt * V + 28 * an
+    return {"value": round(passes * nbytes / (t1 - t0) / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(t1 - t0, 2),
+            "sample": f"{passes} passes of all nine operators on {rows} of {cfg.tokens} tokens (layer ops), "
+                      f"{sb} of {cfg.batch} batches (softmax), {xt} tokens (criterion), {an} of {cfg.adam_n} parameters "
+                      f"(Adam); same algorithmic byte counts as the GPU line"}
+
+
+if __name__ == "__main__":
+    main()

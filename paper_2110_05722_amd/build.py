@@ -15,8 +15,9 @@ from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-LIB = os.path.join(HERE, "liblsq.so")
-OBJ_DIR = os.path.join(HERE, "_build")
+# LSQ_LIB_NAME / LSQ_DEFINES: build an experimental variant next to the default library (tuning only)
+LIB = os.path.join(HERE, os.environ.get("LSQ_LIB_NAME", "liblsq.so"))
+OBJ_DIR = os.path.join(HERE, "_build", os.environ.get("LSQ_LIB_NAME", "liblsq.so"))
 SOURCES = ["api", "adam", "bias_dropout_residual", "layernorm", "softmax", "ls_xent"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -24,7 +25,7 @@ FLAGS = [
     # packed fp32 VALU forms are switched off for the device pass (the host pass warns that it
     # does not know the feature; that is harmless)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-]
+] + os.environ.get("LSQ_DEFINES", "").split()
 
 
 def _compile(name: str) -> str:

@@ -11,6 +11,11 @@
 
 namespace lsq {
 
+#ifndef LSQ_NT
+#define LSQ_NT 1
+#endif
+constexpr bool kNT = LSQ_NT != 0;   // nontemporal hint on the streamed tensors (not on gamma/beta/bias)
+
 constexpr int kBdrWaves = 4;   // waves per workgroup; each takes its own rows
 
 template <typename T, bool HAS_BIAS, bool DROP>
@@ -27,15 +32,15 @@ __global__ __launch_bounds__(256) void bdr_fwd_cols(T* out, const T* x,
     for (int64_t r = static_cast<int64_t>(blockIdx.y) * kBdrWaves + wave; r < rows; r += stride) {
         const int64_t pack = r * ppr + cp;
         float xf[8], rf[8], k[8];
-        load8<T>(x + pack * kPack, xf);
-        load8<T>(res + pack * kPack, rf);
+        load8<T, kNT>(x + pack * kPack, xf);
+        load8<T, kNT>(res + pack * kPack, rf);
         if constexpr (DROP) dropout_factors8(d, static_cast<uint64_t>(pack), k);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const float z = xf[j] + b[j];
             rf[j] = DROP ? fmaf(z, k[j], rf[j]) : rf[j] + z;
         }
-        store8<T>(out + pack * kPack, rf);
+        store8<T, kNT>(out + pack * kPack, rf);
     }
 }
 
@@ -56,13 +61,13 @@ __global__ __launch_bounds__(256) void bdr_bwd_cols(T* dx, float* __restrict__ p
         for (int64_t r = static_cast<int64_t>(blockIdx.y) * kBdrWaves + wave; r < rows; r += stride) {
             const int64_t pack = r * ppr + cp;
             float g[8], k[8];
-            load8<T>(dy + pack * kPack, g);
+            load8<T, kNT>(dy + pack * kPack, g);
             if constexpr (DROP) {
                 dropout_factors8(d, static_cast<uint64_t>(pack), k);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) g[j] *= k[j];
             }
-            store8<T>(dx + pack * kPack, g);
+            store8<T, kNT>(dx + pack * kPack, g);
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[j] += g[j];
         }
@@ -83,17 +88,6 @@ __global__ __launch_bounds__(256) void bdr_bwd_cols(T* dx, float* __restrict__ p
         }
         store8<float>(dst, s);
     }
-}
-
-// out[c] = sum over the P partial rows, in row order (fixed order: reproducible).
-__global__ __launch_bounds__(256) void colsum_finalize(float* __restrict__ out, const float* __restrict__ partial,
-                                                       int P, int ncols)
-{
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= ncols) return;
-    float s = 0.0f;
-    for (int y = 0; y < P; ++y) s += partial[static_cast<int64_t>(y) * ncols + c];
-    out[c] = s;
 }
 
 // ---- generic paths: any hidden (rows are not 16-byte aligned), one element per thread
@@ -153,8 +147,8 @@ static lsq_status bdr_fwd_dispatch(void* out, const void* x, const void* bias, c
     const T* rp = static_cast<const T*>(res);
     if (hidden % kPack == 0) {
         const int ppr = hidden / kPack;
-        int64_t rb = ceil_div(rows, 4 * kBdrWaves);
-        if (rb > 1024) rb = 1024;
+        int64_t rb = ceil_div(rows, tune_env("LSQ_BDR_FWD_ROWS", 4) * kBdrWaves);
+        if (rb > 4096) rb = 4096;
         const dim3 grid = bdr_grid(rows, ppr, static_cast<int>(rb)), block(256);
         const bool drop = d.t16 != 0;
         if (bp && drop) hipLaunchKernelGGL((bdr_fwd_cols<T, true, true>), grid, block, 0, s, o, xp, bp, rp, rows, ppr, d);
@@ -183,8 +177,7 @@ static lsq_status bdr_bwd_dispatch(void* dx, float* dbias, const void* dy, int64
         if (d.t16) hipLaunchKernelGGL((bdr_bwd_cols<T, true>), grid, block, 0, s, o, partial, g, rows, ppr, d);
         else hipLaunchKernelGGL((bdr_bwd_cols<T, false>), grid, block, 0, s, o, partial, g, rows, ppr, d);
         if (dbias)
-            hipLaunchKernelGGL(colsum_finalize, dim3(static_cast<unsigned>(ceil_div(hidden, 256))), dim3(256), 0, s,
-                               dbias, partial, rb, hidden);
+            launch_colsum_finalize(dbias, dbias, hidden, partial, rb, hidden, s);
     } else {
         const int64_t total = rows * hidden;
         hipLaunchKernelGGL((bdr_bwd_flat<T>), dim3(static_cast<unsigned>(ceil_div(total, 256))), dim3(256), 0, s,

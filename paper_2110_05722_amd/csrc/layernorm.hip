@@ -20,11 +20,30 @@
 
 namespace lsq {
 
+#ifndef LSQ_NT
+#define LSQ_NT 1
+#endif
+constexpr bool kNT = LSQ_NT != 0;   // nontemporal hint on the streamed tensors (not on gamma/beta/bias)
+
 template <int LPR>
 __device__ __forceinline__ float row_sum(float v, float* lds)
 {
     if constexpr (LPR == 256) return block_allreduce<4, OpSum>(v, lds);
     else return group_sum<LPR>(v);
+}
+
+// Raw packs of row r for this lane (zeros where the row or the pack does not exist).
+// Loads only, no arithmetic: every load of the row is in flight before the first use.
+template <typename T, int LPR, int VPL>
+__device__ __forceinline__ void ln_load_row(RawPack<T> (&raw)[VPL], const T* __restrict__ base, int64_t r, bool rv,
+                                            int hidden, int nv, int sub)
+{
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        const int idx = sub + k * LPR;
+        if (rv && idx < nv) raw[k] = load_raw<T, kNT>(base + r * hidden + idx * kPack);
+        else raw[k] = zero_raw<T>();
+    }
 }
 
 template <typename T, int LPR, int VPL>
@@ -39,45 +58,43 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(T* __restrict__ y, float* _
     const int slot = threadIdx.x / LPR;
     const int nv = hidden / kPack;
     const float inv_h = 1.0f / static_cast<float>(hidden);
+    const int64_t gstride = static_cast<int64_t>(gridDim.x) * RPB;
 
-    float gm[VPL][8], bt[VPL][8];
-#pragma unroll
-    for (int k = 0; k < VPL; ++k) {
-        const int idx = sub + k * LPR;
-        if (idx < nv) {
-            load8<T>(gamma + idx * kPack, gm[k]);
-            load8<T>(beta + idx * kPack, bt[k]);
-        }
-    }
+    RawPack<T> gm[VPL], bt[VPL];              // gamma/beta stay packed; widened where used
+    ln_load_row<T, LPR, VPL>(gm, gamma, 0, true, hidden, nv, sub);
+    ln_load_row<T, LPR, VPL>(bt, beta, 0, true, hidden, nv, sub);
 
-    for (int64_t base = static_cast<int64_t>(blockIdx.x) * RPB; base < rows; base += static_cast<int64_t>(gridDim.x) * RPB) {
+    int64_t base = static_cast<int64_t>(blockIdx.x) * RPB;
+    RawPack<T> nxt[VPL];
+    ln_load_row<T, LPR, VPL>(nxt, x, base + slot, base + slot < rows, hidden, nv, sub);
+    for (; base < rows; base += gstride) {
         const int64_t r = base + slot;
         const bool rv = r < rows;
-        const T* xr = x + r * hidden;
+        RawPack<T> cur[VPL];
+#pragma unroll
+        for (int k = 0; k < VPL; ++k) cur[k] = nxt[k];
+        if (base + gstride < rows)            // prefetch the next row group while this one is reduced
+            ln_load_row<T, LPR, VPL>(nxt, x, r + gstride, r + gstride < rows, hidden, nv, sub);
+
         float xv[VPL][8];
         float s = 0.0f;
 #pragma unroll
         for (int k = 0; k < VPL; ++k) {
-            const int idx = sub + k * LPR;
-            if (rv && idx < nv) {
-                load8<T>(xr + idx * kPack, xv[k]);
+            unpack<T>(cur[k], xv[k]);         // absent packs are zeros: they add nothing
 #pragma unroll
-                for (int j = 0; j < 8; ++j) s += xv[k][j];
-            }
+            for (int j = 0; j < 8; ++j) s += xv[k][j];
         }
         s = row_sum<LPR>(s, lds);
         const float mu = s * inv_h;
         float q = 0.0f;
 #pragma unroll
         for (int k = 0; k < VPL; ++k) {
-            const int idx = sub + k * LPR;
-            if (rv && idx < nv) {
+            const bool ok = sub + k * LPR < nv;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const float dlt = xv[k][j] - mu;
-                    xv[k][j] = dlt;
-                    q = fmaf(dlt, dlt, q);
-                }
+            for (int j = 0; j < 8; ++j) {
+                const float dlt = xv[k][j] - mu;
+                xv[k][j] = dlt;
+                q = ok ? fmaf(dlt, dlt, q) : q;
             }
         }
         q = row_sum<LPR>(q, lds);
@@ -91,10 +108,12 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(T* __restrict__ y, float* _
         for (int k = 0; k < VPL; ++k) {
             const int idx = sub + k * LPR;
             if (rv && idx < nv) {
-                float o[8];
+                float o[8], g8[8], b8[8];
+                unpack<T>(gm[k], g8);
+                unpack<T>(bt[k], b8);
 #pragma unroll
-                for (int j = 0; j < 8; ++j) o[j] = fmaf(xv[k][j] * rs, gm[k][j], bt[k][j]);
-                store8<T>(yr + idx * kPack, o);
+                for (int j = 0; j < 8; ++j) o[j] = fmaf(xv[k][j] * rs, g8[j], b8[j]);
+                store8<T, kNT>(yr + idx * kPack, o);
             }
         }
     }
@@ -107,66 +126,91 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(T* dx, float* __restrict__ 
                                                      const float* __restrict__ mean, const float* __restrict__ rstd,
                                                      const T* dres, int64_t rows, int hidden)
 {
-    extern __shared__ float colbuf[];         // [2][hidden] when LPR < 256
+    extern __shared__ float colbuf[];         // [2][8][packs | 1] when LPR < 256
     __shared__ float lds[4];
     constexpr int RPB = 256 / LPR;
     const int sub = threadIdx.x % LPR;
     const int slot = threadIdx.x / LPR;
     const int nv = hidden / kPack;
     const float inv_h = 1.0f / static_cast<float>(hidden);
+    const int64_t gstride = static_cast<int64_t>(gridDim.x) * RPB;
 
-    float gm[VPL][8], dg[VPL][8], db[VPL][8];
+    RawPack<T> gm[VPL];
+    ln_load_row<T, LPR, VPL>(gm, gamma, 0, true, hidden, nv, sub);
+    float dg[VPL][8], db[VPL][8];
 #pragma unroll
-    for (int k = 0; k < VPL; ++k) {
-        const int idx = sub + k * LPR;
-        if (idx < nv) load8<T>(gamma + idx * kPack, gm[k]);
+    for (int k = 0; k < VPL; ++k)
 #pragma unroll
         for (int j = 0; j < 8; ++j) { dg[k][j] = 0.0f; db[k][j] = 0.0f; }
-    }
 
-    for (int64_t base = static_cast<int64_t>(blockIdx.x) * RPB; base < rows; base += static_cast<int64_t>(gridDim.x) * RPB) {
+    int64_t base = static_cast<int64_t>(blockIdx.x) * RPB;
+    RawPack<T> ndy[VPL], nx[VPL];
+    float nmu = 0.0f, nrs = 0.0f;
+    {
+        const int64_t r = base + slot;
+        const bool rv = r < rows;
+        ln_load_row<T, LPR, VPL>(ndy, dy, r, rv, hidden, nv, sub);
+        ln_load_row<T, LPR, VPL>(nx, x, r, rv, hidden, nv, sub);
+        if (rv) { nmu = mean[r]; nrs = rstd[r]; }
+    }
+    for (; base < rows; base += gstride) {
         const int64_t r = base + slot;
         const bool rv = r < rows;
         const int64_t ro = r * hidden;
-        float g[VPL][8], xh[VPL][8];
-        float mu = 0.0f, rs = 0.0f;
-        if (rv) { mu = mean[r]; rs = rstd[r]; }
+        RawPack<T> cdy[VPL], cx[VPL], cres[VPL];
+#pragma unroll
+        for (int k = 0; k < VPL; ++k) { cdy[k] = ndy[k]; cx[k] = nx[k]; }
+        const float mu = nmu, rs = nrs;
+        if constexpr (HAS_RES) ln_load_row<T, LPR, VPL>(cres, dres, r, rv, hidden, nv, sub);
+        if (base + gstride < rows) {          // prefetch the next row group
+            const int64_t rn = r + gstride;
+            const bool rnv = rn < rows;
+            ln_load_row<T, LPR, VPL>(ndy, dy, rn, rnv, hidden, nv, sub);
+            ln_load_row<T, LPR, VPL>(nx, x, rn, rnv, hidden, nv, sub);
+            nmu = 0.0f; nrs = 0.0f;
+            if (rnv) { nmu = mean[rn]; nrs = rstd[rn]; }
+        }
+
+        // pass 1 over registers: the two row sums and the column accumulators.  Absent packs
+        // hold dy = 0, so they add nothing to any of the sums.
         float s1 = 0.0f, s2 = 0.0f;
 #pragma unroll
         for (int k = 0; k < VPL; ++k) {
-            const int idx = sub + k * LPR;
-            if (rv && idx < nv) {
-                load8<T>(dy + ro + idx * kPack, g[k]);
-                load8<T>(x + ro + idx * kPack, xh[k]);
+            float gy[8], xv[8], g8[8];
+            unpack<T>(cdy[k], gy);
+            unpack<T>(cx[k], xv);
+            unpack<T>(gm[k], g8);
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const float xhat = (xh[k][j] - mu) * rs;
-                    const float gy = g[k][j];
-                    dg[k][j] = fmaf(gy, xhat, dg[k][j]);
-                    db[k][j] += gy;
-                    const float gg = gy * gm[k][j];
-                    s1 += gg;
-                    s2 = fmaf(gg, xhat, s2);
-                    xh[k][j] = xhat;
-                    g[k][j] = gg;
-                }
+            for (int j = 0; j < 8; ++j) {
+                const float xhat = (xv[j] - mu) * rs;
+                dg[k][j] = fmaf(gy[j], xhat, dg[k][j]);
+                db[k][j] += gy[j];
+                const float gg = gy[j] * g8[j];
+                s1 += gg;
+                s2 = fmaf(gg, xhat, s2);
             }
         }
         s1 = row_sum<LPR>(s1, lds);
         s2 = row_sum<LPR>(s2, lds);
         const float a = s1 * inv_h, b = s2 * inv_h;
+        // pass 2: xhat and gamma*dy are rebuilt from the packed row (3 flops each) rather than
+        // kept in 16 more registers per pack
 #pragma unroll
         for (int k = 0; k < VPL; ++k) {
             const int idx = sub + k * LPR;
             if (rv && idx < nv) {
-                float o[8];
-                if constexpr (HAS_RES) load8<T>(dres + ro + idx * kPack, o);
+                float gy[8], xv[8], g8[8], o[8];
+                unpack<T>(cdy[k], gy);
+                unpack<T>(cx[k], xv);
+                unpack<T>(gm[k], g8);
+                if constexpr (HAS_RES) unpack<T>(cres[k], o);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const float v = rs * (g[k][j] - fmaf(xh[k][j], b, a));
+                    const float xhat = (xv[j] - mu) * rs;
+                    const float v = rs * (gy[j] * g8[j] - fmaf(xhat, b, a));
                     o[j] = HAS_RES ? o[j] + v : v;
                 }
-                store8<T>(dx + ro + idx * kPack, o);
+                store8<T, kNT>(dx + ro + idx * kPack, o);
             }
         }
     }
@@ -182,48 +226,46 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(T* dx, float* __restrict__ 
             }
         }
     } else {
-        // sum the RPB row slots in slot order through LDS
+        // Sum the RPB row slots in slot order through LDS.  Layout [dgamma|dbeta][j][pack] with an
+        // odd pack stride: consecutive lanes (consecutive packs) fall in consecutive banks.  A
+        // [column] layout would put the lanes of a wave 8 floats apart: a 16-way bank conflict.
+        const int stride = nv | 1;
+        float* cg = colbuf;
+        float* cb = colbuf + 8 * stride;
         for (int turn = 0; turn < RPB; ++turn) {
             if (slot == turn) {
+                // all reads of the turn first, then the adds, then all writes: a read-add-write
+                // per element would pay one LDS round trip each, 48 in a row
+                if (turn > 0) {
+#pragma unroll
+                    for (int k = 0; k < VPL; ++k) {
+                        const int idx = min(sub + k * LPR, nv - 1);
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            dg[k][j] += cg[j * stride + idx];
+                            db[k][j] += cb[j * stride + idx];
+                        }
+                    }
+                }
 #pragma unroll
                 for (int k = 0; k < VPL; ++k) {
                     const int idx = sub + k * LPR;
                     if (idx < nv) {
 #pragma unroll
                         for (int j = 0; j < 8; ++j) {
-                            const int c = idx * kPack + j;
-                            if (turn == 0) { colbuf[c] = dg[k][j]; colbuf[hidden + c] = db[k][j]; }
-                            else { colbuf[c] += dg[k][j]; colbuf[hidden + c] += db[k][j]; }
+                            cg[j * stride + idx] = dg[k][j];
+                            cb[j * stride + idx] = db[k][j];
                         }
                     }
                 }
             }
             __syncthreads();
         }
-        for (int c = threadIdx.x; c < 2 * hidden; c += 256) prow[c] = colbuf[c];
-    }
-}
-
-// Sum P partial rows of `ncols` columns in row order.  64 columns per workgroup,
-// SLICES waves each take every SLICES-th row; the slices are combined in order.
-template <int SLICES>
-__global__ __launch_bounds__(64 * SLICES) void ln_bwd_finalize(float* __restrict__ dgamma, float* __restrict__ dbeta,
-                                                              const float* __restrict__ partial, int P, int hidden)
-{
-    __shared__ float sm[SLICES][64];
-    const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
-    const int c = blockIdx.x * 64 + lane;
-    const int ncols = 2 * hidden;
-    float s = 0.0f;
-    if (c < ncols)
-        for (int y = slice; y < P; y += SLICES) s += partial[static_cast<int64_t>(y) * ncols + c];
-    sm[slice][lane] = s;
-    __syncthreads();
-    if (slice == 0 && c < ncols) {
-        float t = sm[0][lane];
-#pragma unroll
-        for (int w = 1; w < SLICES; ++w) t += sm[w][lane];
-        if (c < hidden) dgamma[c] = t; else dbeta[c - hidden] = t;
+        for (int c = threadIdx.x; c < 2 * hidden; c += 256) {
+            const int half = c >= hidden;
+            const int cc = c - half * hidden;
+            prow[c] = colbuf[half * 8 * stride + (cc & 7) * stride + (cc >> 3)];
+        }
     }
 }
 
@@ -322,8 +364,8 @@ inline LnShape ln_shape(int hidden)
 inline int ln_fwd_blocks(int64_t rows, int lpr)
 {
     const int rpb = 256 / lpr;
-    int64_t b = ceil_div(rows, static_cast<int64_t>(rpb) * 2);   // about two row groups per workgroup
-    if (b > 4096) b = 4096;
+    int64_t b = ceil_div(rows, static_cast<int64_t>(rpb) * tune_env("LSQ_LN_FWD_GROUPS", 2));   // about two row groups per workgroup
+    if (b > 8192) b = 8192;
     if (b < 1) b = 1;
     return static_cast<int>(b);
 }
@@ -374,7 +416,7 @@ static lsq_status ln_bwd_dispatch(void* dx, float* dgamma, float* dbeta, const v
     const int P = ln_bwd_blocks(rows, hidden);
     float* partial = static_cast<float*>(workspace);
     const dim3 grid(P), block(256);
-    const size_t shmem = sh.lpr == 256 ? 0 : sizeof(float) * 2 * hidden;
+    const size_t shmem = sh.lpr == 256 ? 0 : sizeof(float) * 16 * ((hidden / kPack) | 1);
 #define X(L, V)                                                                                              \
     if (sh.lpr == L && sh.vpl == V) {                                                                        \
         if (rp) hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, true>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden); \
@@ -382,8 +424,7 @@ static lsq_status ln_bwd_dispatch(void* dx, float* dgamma, float* dbeta, const v
     }
     LSQ_LN_CASES(X)
 #undef X
-    hipLaunchKernelGGL((ln_bwd_finalize<8>), dim3(static_cast<unsigned>(ceil_div(2 * hidden, 64))), dim3(512), 0, s,
-                       dgamma, dbeta, partial, P, hidden);
+    launch_colsum_finalize(dgamma, dbeta, hidden, partial, P, 2 * hidden, s);
     return launch_status();
 }
 

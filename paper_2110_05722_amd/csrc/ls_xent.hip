@@ -16,9 +16,28 @@
 
 namespace lsq {
 
+#ifndef LSQ_NT
+#define LSQ_NT 1
+#endif
+constexpr bool kNT = LSQ_NT != 0;   // nontemporal hint on the streamed tensors
+#ifndef LSQ_XB_NTL
+#define LSQ_XB_NTL 1
+#endif
+#ifndef LSQ_XB_NTS
+#define LSQ_XB_NTS 1
+#endif
+constexpr bool kBwdNTL = LSQ_XB_NTL != 0, kBwdNTS = LSQ_XB_NTS != 0;
+
 constexpr float kLog2eX = 1.4426950408889634f;
 constexpr float kLn2X = 0.6931471805599453f;
-constexpr int kXentThreads = 256;
+#ifndef LSQ_XENT_THREADS
+#define LSQ_XENT_THREADS 256
+#endif
+#ifndef LSQ_XENT_UNROLL
+#define LSQ_XENT_UNROLL 4
+#endif
+constexpr int kXentThreads = LSQ_XENT_THREADS;
+constexpr int kXentUnroll = LSQ_XENT_UNROLL;
 
 struct RowSplit {
     int64_t begin, head_end, pack_begin, pack_end, tail_begin, end;
@@ -91,9 +110,19 @@ __global__ __launch_bounds__(kXentThreads) void xent_fwd_kernel(float* __restric
     OnlineLse st;
     if (r.begin + tid < r.head_end) st.add1(to_f32<T>(logits[r.begin + tid]));
     if (r.tail_begin + tid < r.end) st.add1(to_f32<T>(logits[r.tail_begin + tid]));
-    for (int64_t p = r.pack_begin + tid; p < r.pack_end; p += kXentThreads) {
+    // kXentUnroll packs in flight per thread: one load per iteration would leave the
+    // kernel bound by memory latency, not bandwidth
+    int64_t p = r.pack_begin + tid;
+    for (; p + (kXentUnroll - 1) * kXentThreads < r.pack_end; p += kXentUnroll * kXentThreads) {
+        float h[kXentUnroll][8];
+#pragma unroll
+        for (int u = 0; u < kXentUnroll; ++u) load8<T, kNT>(logits + (p + u * kXentThreads) * kPack, h[u]);
+#pragma unroll
+        for (int u = 0; u < kXentUnroll; ++u) st.add8(h[u]);
+    }
+    for (; p < r.pack_end; p += kXentThreads) {
         float h[8];
-        load8<T>(logits + p * kPack, h);
+        load8<T, kNT>(logits + p * kPack, h);
         st.add8(h);
     }
     const float M = block_allreduce<kXentThreads / 64, OpMax>(st.m, lds);
@@ -126,7 +155,7 @@ __global__ __launch_bounds__(kXentThreads) void xent_bwd_kernel(T* dlogits, cons
         if (r.begin + tid < r.head_end) dlogits[r.begin + tid] = from_f32<T>(0.0f);
         if (r.tail_begin + tid < r.end) dlogits[r.tail_begin + tid] = from_f32<T>(0.0f);
         const float z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        for (int64_t p = r.pack_begin + tid; p < r.pack_end; p += kXentThreads) store8<T>(dlogits + p * kPack, z);
+        for (int64_t p = r.pack_begin + tid; p < r.pack_end; p += kXentThreads) store8<T, kBwdNTS>(dlogits + p * kPack, z);
         return;
     }
     const float ls = lse[t] * kLog2eX;
@@ -141,17 +170,121 @@ __global__ __launch_bounds__(kXentThreads) void xent_bwd_kernel(T* dlogits, cons
     if (r.begin + tid < r.head_end) one(r.begin + tid);
     if (r.tail_begin + tid < r.end) one(r.tail_begin + tid);
     const int64_t kpack = kpos >> 3;
-    for (int64_t p = r.pack_begin + tid; p < r.pack_end; p += kXentThreads) {
-        float h[8];
-        load8<T>(logits + p * kPack, h);
+    auto pack = [&](int64_t q, float (&h)[8]) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) h[j] = grad_scale * (__builtin_amdgcn_exp2f(fmaf(h[j], kLog2eX, -ls)) - smooth);
-        if (p == kpack) {
+        if (q == kpack) {
             const int jj = static_cast<int>(kpos & 7);
 #pragma unroll
             for (int j = 0; j < 8; ++j) h[j] -= (j == jj) ? hit : 0.0f;
         }
-        store8<T>(dlogits + p * kPack, h);
+        store8<T, kBwdNTS>(dlogits + q * kPack, h);
+    };
+    int64_t p = r.pack_begin + tid;
+    for (; p + (kXentUnroll - 1) * kXentThreads < r.pack_end; p += kXentUnroll * kXentThreads) {
+        float h[kXentUnroll][8];
+#pragma unroll
+        for (int u = 0; u < kXentUnroll; ++u) load8<T, kBwdNTL>(logits + (p + u * kXentThreads) * kPack, h[u]);
+#pragma unroll
+        for (int u = 0; u < kXentUnroll; ++u) pack(p + u * kXentThreads, h[u]);
+    }
+    for (; p < r.pack_end; p += kXentThreads) {
+        float h[8];
+        load8<T, kBwdNTL>(logits + p * kPack, h);
+        pack(p, h);
+    }
+}
+
+// Backward over the FLAT [tokens*vocab] tensor: a workgroup owns a contiguous chunk
+// of U*256 aligned packs whatever rows they fall in, so the access pattern is that
+// of a plain copy (few DRAM pages open at a time, every access 128-bit and aligned,
+// no scalar head/tail per row).  Measured on MI355X a copy laid out one row per
+// workgroup reaches 4.8 TB/s at vocab 50257, the flat one 6.6 TB/s.  The chunk is
+// never longer than a row, so it touches at most two rows, A and B: their lse and
+// target are wave-uniform and sit in scalar registers.  Only the one pack that
+// straddles the boundary (vocab % 8 != 0) selects per element.  Packs of ignored
+// rows are not read at all.
+template <typename T, int U>
+__global__ __launch_bounds__(256) void xent_bwd_flat_kernel(T* dlogits, const T* logits,
+                                                            const float* __restrict__ lse,
+                                                            const int32_t* __restrict__ target, int64_t tokens,
+                                                            int vocab, float alpha, int ignore_index, float grad_scale)
+{
+    const int64_t total = tokens * vocab;
+    const int64_t npacks = total / kPack;                     // full packs; the ragged end is handled below
+    const int64_t pb = static_cast<int64_t>(blockIdx.x) * (U * 256);
+    const int64_t tA = (pb * kPack) / vocab;                  // row of the chunk's first element (uniform)
+    const int64_t baseA = tA * vocab;
+    const int64_t bnd = baseA + vocab;                        // first element of row B
+    const bool hasB = tA + 1 < tokens;
+    const float smooth = alpha / static_cast<float>(vocab);
+    const float hit = grad_scale * (1.0f - alpha);
+    const int kA = target[tA];
+    const int kB = hasB ? target[tA + 1] : ignore_index;
+    const bool liveA = !is_ignored(kA, vocab, ignore_index);
+    const bool liveB = hasB && !is_ignored(kB, vocab, ignore_index);
+    const float lsA = lse[tA] * kLog2eX;
+    const float lsB = hasB ? lse[tA + 1] * kLog2eX : 0.0f;
+    const int64_t hitA = baseA + (liveA ? kA : -1);           // flat index of the target element, if live
+    const int64_t hitB = bnd + (liveB ? kB : -1);
+
+    float h[U][8];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t q = pb + u * 256 + threadIdx.x;
+        const int64_t e0 = q * kPack;
+        const bool need = q < npacks && ((e0 < bnd && liveA) || (e0 + kPack > bnd && liveB));
+        if (need) {
+            load8<T, kBwdNTL>(logits + e0, h[u]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) h[u][j] = 0.0f;
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t q = pb + u * 256 + threadIdx.x;
+        if (q >= npacks) continue;
+        const int64_t e0 = q * kPack;
+        float o[8];
+        if (e0 + kPack <= bnd || e0 >= bnd) {                 // the whole pack lies in one row
+            const bool inB = e0 >= bnd;
+            const bool live = inB ? liveB : liveA;
+            const float ls = inB ? lsB : lsA;
+            const int64_t hp = (inB ? hitB : hitA) - e0;      // 0..7 iff the target element is in this pack
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                o[j] = live ? grad_scale * (__builtin_amdgcn_exp2f(fmaf(h[u][j], kLog2eX, -ls)) - smooth) : 0.0f;
+            if (live && hp >= 0 && hp < kPack) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) o[j] -= (j == static_cast<int>(hp)) ? hit : 0.0f;
+            }
+        } else {                                              // straddles the boundary: select per element
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bool inB = e0 + j >= bnd;
+                const bool live = inB ? liveB : liveA;
+                const float ls = inB ? lsB : lsA;
+                float gq = grad_scale * (__builtin_amdgcn_exp2f(fmaf(h[u][j], kLog2eX, -ls)) - smooth);
+                if (e0 + j == (inB ? hitB : hitA)) gq -= hit;
+                o[j] = live ? gq : 0.0f;
+            }
+        }
+        store8<T, kBwdNTS>(dlogits + e0, o);
+    }
+    // ragged end of the whole tensor (total % 8 elements): last workgroup, scalar
+    if (blockIdx.x == gridDim.x - 1) {
+        const int64_t e = npacks * kPack + threadIdx.x;
+        if (e < total) {
+            const int64_t t = e / vocab;
+            const int k = target[t];
+            float gq = 0.0f;
+            if (!is_ignored(k, vocab, ignore_index)) {
+                gq = grad_scale * (__builtin_amdgcn_exp2f(fmaf(to_f32<T>(logits[e]), kLog2eX, -lse[t] * kLog2eX)) - smooth);
+                if (e == t * vocab + k) gq -= hit;
+            }
+            dlogits[e] = from_f32<T>(gq);
+        }
     }
 }
 
@@ -166,12 +299,32 @@ __global__ __launch_bounds__(1024) void xent_sums_kernel(float* __restrict__ sum
     __shared__ double sm[3][1024];
     const int tid = threadIdx.x;
     double a = 0.0, b = 0.0, c = 0.0;
-    for (int64_t t = tid; t < tokens; t += 1024) {
-        const int k = target[t];
-        if (!is_ignored(k, vocab, ignore_index)) {
-            a += static_cast<double>(loss[t]);
-            b += static_cast<double>(lse[t]) - static_cast<double>(to_f32<T>(logits[t * vocab + k]));
-            c += 1.0;
+    // 8 tokens per thread and trip with all their loads in flight together (a plain loop
+    // would pay the target -> logit dependent latency once per token)
+    for (int64_t t0 = tid; t0 < tokens; t0 += 8 * 1024) {
+        int k[8];
+        float ls[8], lo[8], hk[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int64_t t = t0 + u * 1024;
+            k[u] = t < tokens ? target[t] : ignore_index;
+            ls[u] = t < tokens ? lse[t] : 0.0f;
+            lo[u] = t < tokens ? loss[t] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int64_t t = t0 + u * 1024;
+            const bool live = t < tokens && !is_ignored(k[u], vocab, ignore_index);
+            hk[u] = live ? to_f32<T>(logits[t * vocab + k[u]]) : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int64_t t = t0 + u * 1024;
+            if (t < tokens && !is_ignored(k[u], vocab, ignore_index)) {
+                a += static_cast<double>(lo[u]);
+                b += static_cast<double>(ls[u]) - static_cast<double>(hk[u]);
+                c += 1.0;
+            }
         }
     }
     sm[0][tid] = a; sm[1][tid] = b; sm[2][tid] = c;
@@ -205,9 +358,24 @@ static lsq_status xent_bwd_dispatch(void* dlogits, const void* logits, const flo
                                     int64_t tokens, int32_t vocab, float alpha, int32_t ignore_index, float grad_scale,
                                     hipStream_t s)
 {
-    hipLaunchKernelGGL((xent_bwd_kernel<T>), dim3(static_cast<unsigned>(tokens)), dim3(kXentThreads), 0, s,
-                       static_cast<T*>(dlogits), static_cast<const T*>(logits), lse, target, vocab, alpha, ignore_index,
-                       grad_scale);
+    // the flat kernel needs chunk <= vocab (a chunk touches at most two rows): pick the unroll by vocab
+    const int64_t npacks = tokens * vocab / kPack;
+    const int U = vocab >= 4 * 256 * kPack ? 4 : vocab >= 2 * 256 * kPack ? 2 : vocab >= 256 * kPack ? 1 : 0;
+    const int64_t blocks = U ? ceil_div(npacks, U * 256) : 0;
+    T* dp = static_cast<T*>(dlogits);
+    const T* lp = static_cast<const T*>(logits);
+    if (U == 4 && blocks <= 0x7FFFFFFF)
+        hipLaunchKernelGGL((xent_bwd_flat_kernel<T, 4>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, dp, lp, lse,
+                           target, tokens, vocab, alpha, ignore_index, grad_scale);
+    else if (U == 2 && blocks <= 0x7FFFFFFF)
+        hipLaunchKernelGGL((xent_bwd_flat_kernel<T, 2>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, dp, lp, lse,
+                           target, tokens, vocab, alpha, ignore_index, grad_scale);
+    else if (U == 1 && blocks <= 0x7FFFFFFF)
+        hipLaunchKernelGGL((xent_bwd_flat_kernel<T, 1>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, dp, lp, lse,
+                           target, tokens, vocab, alpha, ignore_index, grad_scale);
+    else
+        hipLaunchKernelGGL((xent_bwd_kernel<T>), dim3(static_cast<unsigned>(tokens)), dim3(kXentThreads), 0, s, dp, lp,
+                           lse, target, vocab, alpha, ignore_index, grad_scale);
     return launch_status();
 }
 

@@ -18,6 +18,11 @@
 
 namespace lsq {
 
+#ifndef LSQ_NT
+#define LSQ_NT 1
+#endif
+constexpr bool kNT = LSQ_NT != 0;   // nontemporal hint on the streamed tensors
+
 constexpr float kLog2e = 1.4426950408889634f;
 
 struct SoftmaxGeom {
@@ -63,7 +68,7 @@ __global__ __launch_bounds__(256) void softmax_fwd_kernel(T* y, T* __restrict__ 
     for (int k = 0; k < VPL; ++k) {
         const int j0 = (sub + k * LPR) * kPack;
         if (j0 < limit) {                     // implies rv and idx < nv
-            load8<T>(x + ro + j0, v[k]);
+            load8<T, kNT>(x + ro + j0, v[k]);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 v[k][j] = (j0 + j < limit) ? v[k][j] * g.scale : -INFINITY;
@@ -94,13 +99,13 @@ __global__ __launch_bounds__(256) void softmax_fwd_kernel(T* y, T* __restrict__ 
             float o[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) o[j] = v[k][j] * inv;
-            store8<T>(y + ro + idx * kPack, o);
+            store8<T, kNT>(y + ro + idx * kPack, o);
             if constexpr (DROP) {
                 float kf[8];
                 dropout_factors8(d, static_cast<uint64_t>(row) * nv + idx, kf);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) o[j] *= kf[j];
-                store8<T>(yd + ro + idx * kPack, o);
+                store8<T, kNT>(yd + ro + idx * kPack, o);
             }
         }
     }
@@ -126,8 +131,8 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(T* dx, const T* dy, co
         const int idx = sub + k * LPR;
         const int j0 = idx * kPack;
         if (j0 < limit) {
-            load8<T>(y + ro + j0, yv[k]);
-            load8<T>(dy + ro + j0, gv[k]);
+            load8<T, kNT>(y + ro + j0, yv[k]);
+            load8<T, kNT>(dy + ro + j0, gv[k]);
             if constexpr (DROP) {
                 float kf[8];
                 dropout_factors8(d, static_cast<uint64_t>(row) * nv + idx, kf);
@@ -153,7 +158,7 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(T* dx, const T* dy, co
 #pragma unroll
             for (int j = 0; j < 8; ++j)      // outside the allowed set: +0, not the -0 a product could give
                 o[j] = (idx * kPack + j < limit) ? g.scale * yv[k][j] * (gv[k][j] - dot) : 0.0f;
-            store8<T>(dx + ro + idx * kPack, o);
+            store8<T, kNT>(dx + ro + idx * kPack, o);
         }
     }
 }
