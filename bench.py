@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--op-reps", type=int, default=40, help="back-to-back launches per operator in the per-op table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--warm", action="store_true", help="do not rotate buffers (cache-warm numbers)")
+    ap.add_argument("--no-graph", action="store_true", help="time the per-op table with eager launches")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a plain 1 GiB -> 1 GiB elementwise copy three times (counter calibration under rocprofv3 --pmc)")
     ap.add_argument("--ops", default="", help="comma-separated subset of operators (tuning runs; the default is all nine)")
     return ap.parse_args()
 
@@ -124,6 +127,7 @@ def main():
     target = torch.from_numpy(tgt).to(dev)
     loss = torch.empty(T, dtype=torch.float32, device=dev)
     lse = torch.empty(T, dtype=torch.float32, device=dev)
+    nll = torch.empty(T, dtype=torch.float32, device=dev)
     sums = torch.empty(3, dtype=torch.float32, device=dev)
 
     p = device_normal((n,), 0.02, "f32", seed + 400, dev)
@@ -163,7 +167,7 @@ def main():
         L.lsq_softmax_bwd(a["dy"], a["y"], key_len, causal, scale, pa, ps, 1000 + i, dx=a["dx"])
 
     def op_xent_fwd(i):
-        L.lsq_ls_xent_fwd(logits, target, cfg.alpha, IGNORE_INDEX, loss=loss, lse=lse, sums=sums)
+        L.lsq_ls_xent_fwd(logits, target, cfg.alpha, IGNORE_INDEX, loss=loss, nll=nll, lse=lse, sums=sums)
 
     def op_xent_bwd(i):
         L.lsq_ls_xent_bwd(logits, lse, target, cfg.alpha, IGNORE_INDEX, 1.0 / max(t_active, 1), dlogits=dlogits)
@@ -180,7 +184,7 @@ def main():
         "bias_dropout_residual_bwd": 4 * E + 4 * H,
         "softmax_fwd": 2 * allowed + 2 * Es + (2 * Es if pa > 0 else 0),
         "softmax_bwd": 4 * allowed + 2 * Es,
-        "ls_xent_fwd": 2 * T * V + 12 * T,
+        "ls_xent_fwd": 2 * T * V + 16 * T,
         "ls_xent_bwd": 2 * t_active * V + 2 * T * V + 8 * T,
         "adam_step": 28 * n,
     }
@@ -223,16 +227,35 @@ def main():
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
     # ------------------------------------------- per-operator table (cold, back to back)
+    # `reps` launches of one operator are captured into a HIP graph and the graph is replayed
+    # between two events: what is timed is the GPU running the kernels back to back, not the
+    # Python interpreter issuing them (a ctypes call costs more than a 10 us kernel).
     table = {}
+    timing = "eager" if args.no_graph else "hipgraph"
     for name, f in ops:
         reps = max(3, min(args.op_reps, int(2e10 // max(bts[name], 1)) + 3))
         for i in range(3):
             f(i)
         torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        graph = None
+        if not args.no_graph:
+            try:
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    for i in range(reps):
+                        f(3 + i)
+                graph.replay()
+                torch.cuda.synchronize()
+            except Exception as e:  # capture is an optimisation of the measurement, not of the product
+                print(f"bench.py: graph capture failed for {name} ({e}); timing eagerly", file=sys.stderr)
+                graph, timing = None, "eager"
         a.record()
-        for i in range(reps):
-            f(3 + i)
+        if graph is not None:
+            graph.replay()
+        else:
+            for i in range(reps):
+                f(3 + i)
         b.record()
         torch.cuda.synchronize()
         us = a.elapsed_time(b) * 1e3 / reps
@@ -245,6 +268,15 @@ def main():
         + 2 * table["layernorm_bwd"]["us"] + 2 * table["bias_dropout_residual_bwd"]["us"] + table["softmax_bwd"]["us"]
     dec = 3 * (table["layernorm_fwd"]["us"] + table["bias_dropout_residual_fwd"]["us"] + table["layernorm_bwd"]["us"]
                + table["bias_dropout_residual_bwd"]["us"]) + 2 * (table["softmax_fwd"]["us"] + table["softmax_bwd"]["us"])
+
+    if args.calibrate:
+        # known traffic for scaling FETCH_SIZE / WRITE_SIZE: reads 2^30 bytes, writes 2^30 bytes per launch
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     achieved = bts["adam_step"] / (adam_ms * 1e-3) / 1e9
     roofline = {"kernel": "adam_kernel", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
@@ -261,7 +293,7 @@ def main():
                                f"{'causal' if causal else 'key-padding'} softmax, storage {dt}",
                    "buffers": "warm" if args.warm else f"cold (layer tensors rotate over {sets} sets, softmax over {soft_sets})"},
         "roofline": roofline,
-        "ops": table,
+        "ops": table, "ops_timing": timing,
         "layer_us": {"encoder_layer_fwd_bwd_nongemm": round(enc, 1), "decoder_layer_fwd_bwd_nongemm": round(dec, 1)},
     }
     if not args.no_cpu_baseline:

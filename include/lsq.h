@@ -149,12 +149,14 @@ lsq_status lsq_softmax_bwd(void* dx, const void* dy, const void* y, const int32_
 /* Label-smoothed cross-entropy forward (Sec. IV-A, criterion layer): per token,
  * with q = softmax(h) over the whole vocabulary and p = (1-alpha)*onehot(k) + alpha/V,
  *   loss = -sum_i p_i log q_i = lse - (1-alpha)*h_k - (alpha/V) * sum_i h_i,
- *   lse  = log sum_i exp(h_i).
- * logits: [tokens, vocab] dt;  target: int32[tokens];  loss, lse: fp32[tokens].
- * A token whose target equals ignore_index or lies outside [0, vocab) is ignored:
- * loss = 0 (lse is still written).  sums: nullable fp32[3] = { sum loss,
- * sum of -log q_k, number of non-ignored tokens }, reduced in a fixed order. */
-lsq_status lsq_ls_xent_fwd(float* loss, float* lse, float* sums,
+ *   nll  = -log q_k = lse - h_k,        lse = log sum_i exp(h_i).
+ * logits: [tokens, vocab] dt;  target: int32[tokens];  loss, lse: fp32[tokens];
+ * nll: nullable fp32[tokens].  A token whose target equals ignore_index or lies
+ * outside [0, vocab) is ignored: loss = nll = 0 (lse is still written).
+ * sums: nullable fp32[3] = { sum loss, sum nll, number of non-ignored tokens },
+ * reduced in a fixed order (bit-reproducible); it is cheapest when nll is given
+ * (without it the target logits are gathered a second time). */
+lsq_status lsq_ls_xent_fwd(float* loss, float* nll, float* lse, float* sums,
                            const void* logits, const int32_t* target,
                            int64_t tokens, int32_t vocab, float alpha, int32_t ignore_index,
                            lsq_dtype dt, void* stream);

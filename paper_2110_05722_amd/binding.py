@@ -54,7 +54,7 @@ def load():
         "lsq_bias_dropout_residual_bwd": (C.c_int, [vp, vp, vp, i64, i32, f32, u64, u64, vp, sz, C.c_int, vp]),
         "lsq_softmax_fwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64, C.c_int, vp]),
         "lsq_softmax_bwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64, C.c_int, vp]),
-        "lsq_ls_xent_fwd": (C.c_int, [vp, vp, vp, vp, vp, i64, i32, f32, i32, C.c_int, vp]),
+        "lsq_ls_xent_fwd": (C.c_int, [vp, vp, vp, vp, vp, vp, i64, i32, f32, i32, C.c_int, vp]),
         "lsq_ls_xent_bwd": (C.c_int, [vp, vp, vp, vp, i64, i32, f32, i32, f32, C.c_int, vp]),
         "lsq_adam_step": (C.c_int, [vp, vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, i32, i32, i32, f32,
                                     C.c_int, C.c_int, vp]),
@@ -175,19 +175,23 @@ def lsq_softmax_bwd(dy, y, key_len=None, causal: bool = False, scale: float = 1.
     return dx
 
 
-def lsq_ls_xent_fwd(logits, target, alpha: float, ignore_index: int = -100, want_sums: bool = True, loss=None,
-                    lse=None, sums=None):
-    """logits: [tokens, vocab]; target: int32[tokens] -> (loss[tokens], lse[tokens], sums[3] or None), fp32."""
+def lsq_ls_xent_fwd(logits, target, alpha: float, ignore_index: int = -100, want_sums: bool = True,
+                    want_nll: bool = True, loss=None, nll=None, lse=None, sums=None):
+    """logits: [tokens, vocab]; target: int32[tokens] -> (loss[tokens], nll[tokens] or None, lse[tokens],
+    sums[3] or None), all fp32."""
     T, V = logits.shape
     loss = torch.empty(T, dtype=torch.float32, device=logits.device) if loss is None else loss
     lse = torch.empty(T, dtype=torch.float32, device=logits.device) if lse is None else lse
+    if want_nll and nll is None:
+        nll = torch.empty(T, dtype=torch.float32, device=logits.device)
     if want_sums and sums is None:
         sums = torch.empty(3, dtype=torch.float32, device=logits.device)
     if target.dtype != torch.int32:
         raise LsqError("target must be int32")
-    _check(load().lsq_ls_xent_fwd(_ptr(loss), _ptr(lse), _ptr(sums) if want_sums else None, _ptr(logits), _ptr(target),
-                                  T, V, alpha, ignore_index, _dt(logits), _stream()), "lsq_ls_xent_fwd")
-    return loss, lse, (sums if want_sums else None)
+    _check(load().lsq_ls_xent_fwd(_ptr(loss), _ptr(nll) if want_nll else None, _ptr(lse),
+                                  _ptr(sums) if want_sums else None, _ptr(logits), _ptr(target), T, V, alpha,
+                                  ignore_index, _dt(logits), _stream()), "lsq_ls_xent_fwd")
+    return loss, (nll if want_nll else None), lse, (sums if want_sums else None)
 
 
 def lsq_ls_xent_bwd(logits, lse, target, alpha: float, ignore_index: int = -100, grad_scale: float = 1.0,

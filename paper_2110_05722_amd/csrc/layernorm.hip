@@ -119,16 +119,40 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(T* __restrict__ y, float* _
     }
 }
 
+// Hide a value from the optimiser (the packed row is re-widened in pass 2 instead of
+// keeping 16 fp32 registers per pack alive across the row reduction).
+template <typename T>
+__device__ __forceinline__ void opaque(RawPack<T>& r)
+{
+    if constexpr (sizeof(T) == 2) asm volatile("" : "+v"(r.u));
+    else asm volatile("" : "+v"(r.a), "+v"(r.b));
+}
+
+#ifndef LSQ_LN_BWD_THREADS
+#define LSQ_LN_BWD_THREADS 256
+#endif
+#ifndef LSQ_LN_BWD_RECOMPUTE
+#define LSQ_LN_BWD_RECOMPUTE 1
+#endif
+#ifndef LSQ_LN_BWD_PREFETCH
+#define LSQ_LN_BWD_PREFETCH 1
+#endif
+constexpr int kLnBwdThreads = LSQ_LN_BWD_THREADS;
+
 // partial: [gridDim.x][2][hidden] fp32 (dgamma row, then dbeta row).
-template <typename T, int LPR, int VPL, bool HAS_RES>
-__global__ __launch_bounds__(256) void ln_bwd_kernel(T* dx, float* __restrict__ partial, const T* dy,
-                                                     const T* __restrict__ x, const T* __restrict__ gamma,
-                                                     const float* __restrict__ mean, const float* __restrict__ rstd,
-                                                     const T* dres, int64_t rows, int hidden)
+// THREADS lanes per workgroup: THREADS/LPR rows in flight per workgroup (plus their
+// prefetched successors).  With one wave per SIMD the kernel is bound by memory latency,
+// not bandwidth: the bytes in flight per compute unit are what THREADS buys.
+template <typename T, int LPR, int VPL, bool HAS_RES, int THREADS>
+__global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restrict__ partial, const T* dy,
+                                                         const T* __restrict__ x, const T* __restrict__ gamma,
+                                                         const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                         const T* dres, int64_t rows, int hidden)
 {
     extern __shared__ float colbuf[];         // [2][8][packs | 1] when LPR < 256
     __shared__ float lds[4];
-    constexpr int RPB = 256 / LPR;
+    static_assert(LPR != 256 || THREADS == 256, "a whole-workgroup row needs 256 threads");
+    constexpr int RPB = THREADS / LPR;
     const int sub = threadIdx.x % LPR;
     const int slot = threadIdx.x / LPR;
     const int nv = hidden / kPack;
@@ -162,6 +186,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(T* dx, float* __restrict__ 
         for (int k = 0; k < VPL; ++k) { cdy[k] = ndy[k]; cx[k] = nx[k]; }
         const float mu = nmu, rs = nrs;
         if constexpr (HAS_RES) ln_load_row<T, LPR, VPL>(cres, dres, r, rv, hidden, nv, sub);
+#if LSQ_LN_BWD_PREFETCH
         if (base + gstride < rows) {          // prefetch the next row group
             const int64_t rn = r + gstride;
             const bool rnv = rn < rows;
@@ -170,10 +195,15 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(T* dx, float* __restrict__ 
             nmu = 0.0f; nrs = 0.0f;
             if (rnv) { nmu = mean[rn]; nrs = rstd[rn]; }
         }
+#endif
 
         // pass 1 over registers: the two row sums and the column accumulators.  Absent packs
-        // hold dy = 0, so they add nothing to any of the sums.
+        // hold dy = 0, so they add nothing to any of the sums.  xhat = x*rstd - mean*rstd.
+        const float nmr = -mu * rs;
         float s1 = 0.0f, s2 = 0.0f;
+#if !LSQ_LN_BWD_RECOMPUTE
+        float gk[VPL][8], xk[VPL][8];
+#endif
 #pragma unroll
         for (int k = 0; k < VPL; ++k) {
             float gy[8], xv[8], g8[8];
@@ -182,37 +212,61 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(T* dx, float* __restrict__ 
             unpack<T>(gm[k], g8);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const float xhat = (xv[j] - mu) * rs;
+                const float xhat = fmaf(xv[j], rs, nmr);
                 dg[k][j] = fmaf(gy[j], xhat, dg[k][j]);
                 db[k][j] += gy[j];
                 const float gg = gy[j] * g8[j];
                 s1 += gg;
                 s2 = fmaf(gg, xhat, s2);
+#if !LSQ_LN_BWD_RECOMPUTE
+                gk[k][j] = gg; xk[k][j] = xhat;
+#endif
             }
         }
         s1 = row_sum<LPR>(s1, lds);
         s2 = row_sum<LPR>(s2, lds);
-        const float a = s1 * inv_h, b = s2 * inv_h;
-        // pass 2: xhat and gamma*dy are rebuilt from the packed row (3 flops each) rather than
-        // kept in 16 more registers per pack
+        // dx = rstd*(g - (s1 + xhat*s2)/hidden) = g*rstd + xhat*c1 + c0
+        const float c0 = -rs * s1 * inv_h, c1 = -rs * s2 * inv_h;
 #pragma unroll
         for (int k = 0; k < VPL; ++k) {
             const int idx = sub + k * LPR;
             if (rv && idx < nv) {
-                float gy[8], xv[8], g8[8], o[8];
+                float o[8];
+                if constexpr (HAS_RES) unpack<T>(cres[k], o);
+#if LSQ_LN_BWD_RECOMPUTE
+                // xhat and gamma*dy are rebuilt from the packed row (a few flops) rather than kept
+                // in 16 more registers per pack across the reduction
+                opaque<T>(cdy[k]);
+                opaque<T>(cx[k]);
+                float gy[8], xv[8], g8[8];
                 unpack<T>(cdy[k], gy);
                 unpack<T>(cx[k], xv);
                 unpack<T>(gm[k], g8);
-                if constexpr (HAS_RES) unpack<T>(cres[k], o);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const float xhat = (xv[j] - mu) * rs;
-                    const float v = rs * (gy[j] * g8[j] - fmaf(xhat, b, a));
+                    const float v = fmaf(gy[j] * g8[j], rs, fmaf(fmaf(xv[j], rs, nmr), c1, c0));
                     o[j] = HAS_RES ? o[j] + v : v;
                 }
+#else
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float v = fmaf(gk[k][j], rs, fmaf(xk[k][j], c1, c0));
+                    o[j] = HAS_RES ? o[j] + v : v;
+                }
+#endif
                 store8<T, kNT>(dx + ro + idx * kPack, o);
             }
         }
+#if !LSQ_LN_BWD_PREFETCH
+        if (base + gstride < rows) {          // no prefetch: occupancy hides the latency instead
+            const int64_t rn = r + gstride;
+            const bool rnv = rn < rows;
+            ln_load_row<T, LPR, VPL>(ndy, dy, rn, rnv, hidden, nv, sub);
+            ln_load_row<T, LPR, VPL>(nx, x, rn, rnv, hidden, nv, sub);
+            nmu = 0.0f; nrs = 0.0f;
+            if (rnv) { nmu = mean[rn]; nrs = rstd[rn]; }
+        }
+#endif
     }
 
     float* prow = partial + static_cast<int64_t>(blockIdx.x) * 2 * hidden;
@@ -261,7 +315,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(T* dx, float* __restrict__ 
             }
             __syncthreads();
         }
-        for (int c = threadIdx.x; c < 2 * hidden; c += 256) {
+        for (int c = threadIdx.x; c < 2 * hidden; c += THREADS) {
             const int half = c >= hidden;
             const int cc = c - half * hidden;
             prow[c] = colbuf[half * 8 * stride + (cc & 7) * stride + (cc >> 3)];
@@ -415,12 +469,13 @@ static lsq_status ln_bwd_dispatch(void* dx, float* dgamma, float* dbeta, const v
     }
     const int P = ln_bwd_blocks(rows, hidden);
     float* partial = static_cast<float*>(workspace);
-    const dim3 grid(P), block(256);
     const size_t shmem = sh.lpr == 256 ? 0 : sizeof(float) * 16 * ((hidden / kPack) | 1);
 #define X(L, V)                                                                                              \
     if (sh.lpr == L && sh.vpl == V) {                                                                        \
-        if (rp) hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, true>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden); \
-        else hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, false>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden);   \
+        constexpr int TH = L == 256 ? 256 : kLnBwdThreads;                                                   \
+        const dim3 grid(P), block(TH);                                                                       \
+        if (rp) hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, true, TH>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden); \
+        else hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, false, TH>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden);   \
     }
     LSQ_LN_CASES(X)
 #undef X

@@ -98,7 +98,8 @@ struct OnlineLse {
 };
 
 template <typename T>
-__global__ __launch_bounds__(kXentThreads) void xent_fwd_kernel(float* __restrict__ loss, float* __restrict__ lse,
+__global__ __launch_bounds__(kXentThreads) void xent_fwd_kernel(float* __restrict__ loss, float* __restrict__ nll,
+                                                               float* __restrict__ lse,
                                                                const T* __restrict__ logits,
                                                                const int32_t* __restrict__ target, int vocab,
                                                                float alpha, int ignore_index)
@@ -132,12 +133,14 @@ __global__ __launch_bounds__(kXentThreads) void xent_fwd_kernel(float* __restric
         const float l = (M + __builtin_amdgcn_logf(S)) * kLn2X;     // v_log_f32 is log2
         lse[t] = l;
         const int k = target[t];
-        float out = 0.0f;
+        float out = 0.0f, nl = 0.0f;
         if (!is_ignored(k, vocab, ignore_index)) {
             const float hk = to_f32<T>(logits[r.begin + k]);
             out = l - (1.0f - alpha) * hk - (alpha / static_cast<float>(vocab)) * SH;
+            nl = l - hk;
         }
         loss[t] = out;
+        if (nll) nll[t] = nl;
     }
 }
 
@@ -288,19 +291,20 @@ __global__ __launch_bounds__(256) void xent_bwd_flat_kernel(T* dlogits, const T*
     }
 }
 
-// sums = { sum loss, sum (lse - h_k), count } over non-ignored tokens: one workgroup,
-// double accumulators, fixed strided order and a fixed LDS tree.
+// sums = { sum loss, sum nll, count } over non-ignored tokens: one workgroup, double
+// accumulators, fixed strided order and a fixed LDS tree.  With the per-token nll at
+// hand every input is a contiguous array; without it the target logits are gathered
+// (one DRAM page each), 8 per thread in flight.
 template <typename T>
 __global__ __launch_bounds__(1024) void xent_sums_kernel(float* __restrict__ sums, const float* __restrict__ loss,
-                                                         const float* __restrict__ lse, const T* __restrict__ logits,
+                                                         const float* __restrict__ nll, const float* __restrict__ lse,
+                                                         const T* __restrict__ logits,
                                                          const int32_t* __restrict__ target, int64_t tokens, int vocab,
                                                          int ignore_index)
 {
     __shared__ double sm[3][1024];
     const int tid = threadIdx.x;
     double a = 0.0, b = 0.0, c = 0.0;
-    // 8 tokens per thread and trip with all their loads in flight together (a plain loop
-    // would pay the target -> logit dependent latency once per token)
     for (int64_t t0 = tid; t0 < tokens; t0 += 8 * 1024) {
         int k[8];
         float ls[8], lo[8], hk[8];
@@ -308,14 +312,17 @@ __global__ __launch_bounds__(1024) void xent_sums_kernel(float* __restrict__ sum
         for (int u = 0; u < 8; ++u) {
             const int64_t t = t0 + u * 1024;
             k[u] = t < tokens ? target[t] : ignore_index;
-            ls[u] = t < tokens ? lse[t] : 0.0f;
             lo[u] = t < tokens ? loss[t] : 0.0f;
+            if (nll) { ls[u] = t < tokens ? nll[t] : 0.0f; hk[u] = 0.0f; }
+            else ls[u] = t < tokens ? lse[t] : 0.0f;
         }
+        if (!nll) {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int64_t t = t0 + u * 1024;
-            const bool live = t < tokens && !is_ignored(k[u], vocab, ignore_index);
-            hk[u] = live ? to_f32<T>(logits[t * vocab + k[u]]) : 0.0f;
+            for (int u = 0; u < 8; ++u) {
+                const int64_t t = t0 + u * 1024;
+                const bool live = t < tokens && !is_ignored(k[u], vocab, ignore_index);
+                hk[u] = live ? to_f32<T>(logits[t * vocab + k[u]]) : 0.0f;
+            }
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -341,15 +348,15 @@ __global__ __launch_bounds__(1024) void xent_sums_kernel(float* __restrict__ sum
 }
 
 template <typename T>
-static lsq_status xent_fwd_dispatch(float* loss, float* lse, float* sums, const void* logits, const int32_t* target,
+static lsq_status xent_fwd_dispatch(float* loss, float* nll, float* lse, float* sums, const void* logits, const int32_t* target,
                                     int64_t tokens, int32_t vocab, float alpha, int32_t ignore_index, hipStream_t s)
 {
     const T* lp = static_cast<const T*>(logits);
     hipLaunchKernelGGL((xent_fwd_kernel<T>), dim3(static_cast<unsigned>(tokens)), dim3(kXentThreads), 0, s,
-                       loss, lse, lp, target, vocab, alpha, ignore_index);
+                       loss, nll, lse, lp, target, vocab, alpha, ignore_index);
     if (sums)
-        hipLaunchKernelGGL((xent_sums_kernel<T>), dim3(1), dim3(1024), 0, s, sums, loss, lse, lp, target, tokens, vocab,
-                           ignore_index);
+        hipLaunchKernelGGL((xent_sums_kernel<T>), dim3(1), dim3(1024), 0, s, sums, loss, nll, lse, lp, target, tokens,
+                           vocab, ignore_index);
     return launch_status();
 }
 
@@ -381,7 +388,7 @@ static lsq_status xent_bwd_dispatch(void* dlogits, const void* logits, const flo
 
 }  // namespace lsq
 
-extern "C" lsq_status lsq_ls_xent_fwd(float* loss, float* lse, float* sums, const void* logits, const int32_t* target,
+extern "C" lsq_status lsq_ls_xent_fwd(float* loss, float* nll, float* lse, float* sums, const void* logits, const int32_t* target,
                                       int64_t tokens, int32_t vocab, float alpha, int32_t ignore_index, lsq_dtype dt,
                                       void* stream)
 {
@@ -394,9 +401,9 @@ extern "C" lsq_status lsq_ls_xent_fwd(float* loss, float* lse, float* sums, cons
     LSQ_REQUIRE(loss && lse && logits && target);
     LSQ_ALIGNED(logits);
     switch (dt) {
-        case LSQ_F16: return xent_fwd_dispatch<f16>(loss, lse, sums, logits, target, tokens, vocab, alpha, ignore_index, s);
-        case LSQ_BF16: return xent_fwd_dispatch<bf16>(loss, lse, sums, logits, target, tokens, vocab, alpha, ignore_index, s);
-        default: return xent_fwd_dispatch<float>(loss, lse, sums, logits, target, tokens, vocab, alpha, ignore_index, s);
+        case LSQ_F16: return xent_fwd_dispatch<f16>(loss, nll, lse, sums, logits, target, tokens, vocab, alpha, ignore_index, s);
+        case LSQ_BF16: return xent_fwd_dispatch<bf16>(loss, nll, lse, sums, logits, target, tokens, vocab, alpha, ignore_index, s);
+        default: return xent_fwd_dispatch<float>(loss, nll, lse, sums, logits, target, tokens, vocab, alpha, ignore_index, s);
     }
 }
 

@@ -62,21 +62,25 @@ __global__ __launch_bounds__(256) void softmax_fwd_kernel(T* y, T* __restrict__ 
     const int limit = rv ? row_limit(g, key_len, row) : 0;
     const int64_t ro = row * g.k_len;
 
+    // loads first (only the packs that reach into the allowed prefix), arithmetic after:
+    // all loads of the row are in flight together
+    RawPack<T> raw[VPL];
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        const int j0 = (sub + k * LPR) * kPack;
+        if (j0 < limit) raw[k] = load_raw<T, kNT>(x + ro + j0);     // implies rv and idx < nv
+        else raw[k] = zero_raw<T>();
+    }
     float v[VPL][8];
     float mx = -INFINITY;
 #pragma unroll
     for (int k = 0; k < VPL; ++k) {
         const int j0 = (sub + k * LPR) * kPack;
-        if (j0 < limit) {                     // implies rv and idx < nv
-            load8<T, kNT>(x + ro + j0, v[k]);
+        unpack<T>(raw[k], v[k]);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                v[k][j] = (j0 + j < limit) ? v[k][j] * g.scale : -INFINITY;
-                mx = fmaxf(mx, v[k][j]);
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[k][j] = -INFINITY;
+        for (int j = 0; j < 8; ++j) {
+            v[k][j] = (j0 + j < limit) ? v[k][j] * g.scale : -INFINITY;
+            mx = fmaxf(mx, v[k][j]);
         }
     }
     mx = group_max<LPR>(mx);
@@ -101,10 +105,12 @@ __global__ __launch_bounds__(256) void softmax_fwd_kernel(T* y, T* __restrict__ 
             for (int j = 0; j < 8; ++j) o[j] = v[k][j] * inv;
             store8<T, kNT>(y + ro + idx * kPack, o);
             if constexpr (DROP) {
-                float kf[8];
-                dropout_factors8(d, static_cast<uint64_t>(row) * nv + idx, kf);
+                if (idx * kPack < limit) {    // packs beyond the mask are zeros whatever the draw
+                    float kf[8];
+                    dropout_factors8(d, static_cast<uint64_t>(row) * nv + idx, kf);
 #pragma unroll
-                for (int j = 0; j < 8; ++j) o[j] *= kf[j];
+                    for (int j = 0; j < 8; ++j) o[j] *= kf[j];
+                }
                 store8<T, kNT>(yd + ro + idx * kPack, o);
             }
         }
@@ -124,29 +130,38 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(T* dx, const T* dy, co
     const int limit = rv ? row_limit(g, key_len, row) : 0;
     const int64_t ro = row * g.k_len;
 
+    RawPack<T> ry[VPL], rg[VPL];
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        const int j0 = (sub + k * LPR) * kPack;
+        if (j0 < limit) {
+            ry[k] = load_raw<T, kNT>(y + ro + j0);
+            rg[k] = load_raw<T, kNT>(dy + ro + j0);
+        } else {
+            ry[k] = zero_raw<T>();
+            rg[k] = zero_raw<T>();
+        }
+    }
     float yv[VPL][8], gv[VPL][8];
     float dot = 0.0f;
 #pragma unroll
     for (int k = 0; k < VPL; ++k) {
         const int idx = sub + k * LPR;
         const int j0 = idx * kPack;
-        if (j0 < limit) {
-            load8<T, kNT>(y + ro + j0, yv[k]);
-            load8<T, kNT>(dy + ro + j0, gv[k]);
-            if constexpr (DROP) {
+        unpack<T>(ry[k], yv[k]);
+        unpack<T>(rg[k], gv[k]);
+        if constexpr (DROP) {
+            if (j0 < limit) {
                 float kf[8];
                 dropout_factors8(d, static_cast<uint64_t>(row) * nv + idx, kf);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) gv[k][j] *= kf[j];
             }
+        }
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                if (j0 + j >= limit) yv[k][j] = 0.0f;
-                dot = fmaf(gv[k][j], yv[k][j], dot);
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) { yv[k][j] = 0.0f; gv[k][j] = 0.0f; }
+        for (int j = 0; j < 8; ++j) {
+            if (j0 + j >= limit) yv[k][j] = 0.0f;
+            dot = fmaf(gv[k][j], yv[k][j], dot);
         }
     }
     dot = group_sum<LPR>(dot);

@@ -88,9 +88,10 @@ def test_host_side_argument_errors(lib):
     assert f(A, A, None, None, 2, 2, 8, 8, 0, 1.0, 0.0, 1, 0, 0, None) == INVALID
     # criterion
     f = lib.lsq_ls_xent_fwd
-    assert f(A, A, None, A, A, 4, 0, 0.1, -100, 0, None) == INVALID
-    assert f(A, A, None, A, A, 4, 8, 1.5, -100, 0, None) == INVALID
-    assert f(A, A, None, U, A, 4, 8, 0.1, -100, 0, None) == MISALIGNED
+    assert f(A, None, A, None, A, A, 4, 0, 0.1, -100, 0, None) == INVALID
+    assert f(A, None, A, None, A, A, 4, 8, 1.5, -100, 0, None) == INVALID
+    assert f(A, A, A, None, U, A, 4, 8, 0.1, -100, 0, None) == MISALIGNED
+    assert f(None, None, A, None, A, A, 4, 8, 0.1, -100, 0, None) == INVALID
     f = lib.lsq_ls_xent_bwd
     assert f(A, A, None, A, 4, 8, 0.1, -100, 1.0, 0, None) == INVALID
     assert f(A, A, A, A, 4, 8, 0.1, -100, 1.0, 9, None) == DTYPE

@@ -21,12 +21,17 @@ def _run(t, T, V, alpha, dt, grad_scale=1.0):
     d = dev()
     logits = to_torch(t["logits"], dt, d)
     target = torch.from_numpy(t["target"]).to(d)
-    loss, lse, sums = L.lsq_ls_xent_fwd(logits, target, alpha, IGNORE_INDEX)
+    loss, nll, lse, sums = L.lsq_ls_xent_fwd(logits, target, alpha, IGNORE_INDEX)
     rloss, rnll, rlse, rsums = oracle.ls_xent_fwd(t["logits"], t["target"], alpha, IGNORE_INDEX, dt)
     # lse and loss are O(log V): relative tolerance plus the rounding floor of a V-term fp32 sum
     assert_close_f32(lse, rlse, "lse", floor=1e-6)
     assert_close_f32(loss, rloss, "loss", floor=2e-6)
+    assert_close_f32(nll, rnll, "nll", floor=2e-6)
     assert_close_f32(sums, rsums, "sums", floor=1e-5)
+    # without the nll output the sums come from a second gather of the target logits: same numbers
+    loss_b, none, lse_b, sums_b = L.lsq_ls_xent_fwd(logits, target, alpha, IGNORE_INDEX, want_nll=False)
+    assert none is None and torch.equal(loss, loss_b) and torch.equal(lse, lse_b)
+    assert_close_f32(sums_b, rsums, "sums (gathered)", floor=1e-5)
     ign = (t["target"] == IGNORE_INDEX) | (t["target"] < 0) | (t["target"] >= V)
     assert (loss.cpu().numpy()[ign] == 0).all()
     dl = L.lsq_ls_xent_bwd(logits, lse, target, alpha, IGNORE_INDEX, grad_scale)
@@ -62,9 +67,10 @@ def test_ls_xent_alpha_zero_equals_nll_and_sums_reproducible():
     t = criterion_tensors(CONFIGS[0], dt)
     logits = to_torch(t["logits"], dt, d)
     target = torch.from_numpy(t["target"]).to(d)
-    loss, lse, sums = L.lsq_ls_xent_fwd(logits, target, 0.0, IGNORE_INDEX)
-    loss2, lse2, sums2 = L.lsq_ls_xent_fwd(logits, target, 0.0, IGNORE_INDEX)
-    assert torch.equal(loss, loss2) and torch.equal(lse, lse2) and torch.equal(sums, sums2)
+    loss, nll, lse, sums = L.lsq_ls_xent_fwd(logits, target, 0.0, IGNORE_INDEX)
+    loss2, nll2, lse2, sums2 = L.lsq_ls_xent_fwd(logits, target, 0.0, IGNORE_INDEX)
+    assert torch.equal(loss, loss2) and torch.equal(lse, lse2) and torch.equal(sums, sums2) and torch.equal(nll, nll2)
+    assert_close_f32(loss, nll.cpu().numpy(), "loss == nll at alpha 0", floor=1e-6)
     assert abs(sums[0].item() - sums[1].item()) <= 1e-5 * abs(sums[1].item())
     assert sums[2].item() == int((t["target"] != IGNORE_INDEX).sum())
 
@@ -86,7 +92,7 @@ def test_ls_xent_full_size(ci, dt):
         tgt[rng.random(T) < 0.2] = IGNORE_INDEX      # padded positions
     target = torch.from_numpy(tgt).to(d)
     gs = 1.0      # fp16 gradients of size alpha/V * 1/64 would sit below half the smallest subnormal
-    loss, lse, sums = L.lsq_ls_xent_fwd(logits, target, cfg.alpha, IGNORE_INDEX)
+    loss, nll, lse, sums = L.lsq_ls_xent_fwd(logits, target, cfg.alpha, IGNORE_INDEX)
     dl = L.lsq_ls_xent_bwd(logits, lse, target, cfg.alpha, IGNORE_INDEX, gs)
     rows = np.sort(rng.choice(T, size=96, replace=False))
     rows[:4] = [0, 1, T - 2, T - 1]
@@ -96,6 +102,7 @@ def test_ls_xent_full_size(ci, dt):
     rloss, rnll, rlse, _ = oracle.ls_xent_fwd(sub, tgt[rows], cfg.alpha, IGNORE_INDEX, dt)
     assert_close_f32(lse[idx], rlse, "lse", floor=1e-6)
     assert_close_f32(loss[idx], rloss, "loss", floor=2e-6)
+    assert_close_f32(nll[idx], rnll, "nll", floor=2e-6)
     rdl = oracle.ls_xent_bwd(sub, tgt[rows], cfg.alpha, IGNORE_INDEX, gs, dt)
     assert_close_store(dl[idx], rdl, dt, "dlogits")
     # properties at any size: ignored rows are all-zero; gradient rows sum to ~0; sums == sum of the vector
@@ -105,4 +112,5 @@ def test_ls_xent_full_size(ci, dt):
     rs = dl[~ign].float().sum(-1).abs().max().item()
     assert rs < gs * (3e-2 if dt == "bf16" else 4e-3) + 1e-4   # + the fp16 subnormal rounding floor over V terms
     assert abs(sums[0].item() - loss.double().sum().item()) <= 1e-5 * loss.double().sum().item()
+    assert abs(sums[1].item() - nll.double().sum().item()) <= 1e-5 * nll.double().sum().item()
     assert sums[2].item() == int((tgt != IGNORE_INDEX).sum())
