@@ -147,7 +147,7 @@ static lsq_status bdr_fwd_dispatch(void* out, const void* x, const void* bias, c
     const T* rp = static_cast<const T*>(res);
     if (hidden % kPack == 0) {
         const int ppr = hidden / kPack;
-        int64_t rb = ceil_div(rows, tune_env("LSQ_BDR_FWD_ROWS", 4) * kBdrWaves);
+        int64_t rb = ceil_div(rows, 4 * kBdrWaves);
         if (rb > 4096) rb = 4096;
         const dim3 grid = bdr_grid(rows, ppr, static_cast<int>(rb)), block(256);
         const bool drop = d.t16 != 0;

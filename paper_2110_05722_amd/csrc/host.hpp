@@ -4,7 +4,6 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
-#include <stdlib.h>
 
 #include "../../include/lsq.h"
 #include "device.hpp"
@@ -58,18 +57,22 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Second stage of the column reductions: out[c] = sum over the P partial rows of
 // partial[y][c], C columns, in a fixed order (reproducible).  Columns below `split`
-// go to out0, the rest to out1.  A workgroup owns 32 columns; its 8 row slices each
+// go to out0, the rest to out1.  A workgroup owns 32 columns; its 32 row slices each
 // sum a contiguous chunk of rows with the loads of 8 rows in flight at a time (a
 // plain loop would pay one memory latency per row), then the slices are combined in
 // slice order through LDS.
+constexpr int kFinalizeSlices = 32;
+
 template <int = 0>
-__global__ __launch_bounds__(256) void colsum_finalize_kernel(float* __restrict__ out0, float* __restrict__ out1,
-                                                              int split, const float* __restrict__ partial, int P, int C)
+__global__ __launch_bounds__(32 * kFinalizeSlices) void colsum_finalize_kernel(float* __restrict__ out0,
+                                                                               float* __restrict__ out1, int split,
+                                                                               const float* __restrict__ partial,
+                                                                               int P, int C)
 {
-    __shared__ float sm[8][32];
+    __shared__ float sm[kFinalizeSlices][33];
     const int lane = threadIdx.x & 31, slice = threadIdx.x >> 5;
     const int c = blockIdx.x * 32 + lane;
-    const int chunk = (P + 7) / 8;
+    const int chunk = (P + kFinalizeSlices - 1) / kFinalizeSlices;
     const int y0 = slice * chunk, y1 = min(P, y0 + chunk);
     float s = 0.0f;
     if (c < C) {
@@ -88,31 +91,24 @@ __global__ __launch_bounds__(256) void colsum_finalize_kernel(float* __restrict_
     if (slice == 0 && c < C) {
         float t = sm[0][lane];
 #pragma unroll
-        for (int w = 1; w < 8; ++w) t += sm[w][lane];
+        for (int w = 1; w < kFinalizeSlices; ++w) t += sm[w][lane];
         if (c < split) out0[c] = t; else out1[c - split] = t;
     }
 }
 
 inline void launch_colsum_finalize(float* out0, float* out1, int split, const float* partial, int P, int C, hipStream_t s)
 {
-    hipLaunchKernelGGL((colsum_finalize_kernel<0>), dim3(static_cast<unsigned>((C + 31) / 32)), dim3(256), 0, s,
+    hipLaunchKernelGGL((colsum_finalize_kernel<0>), dim3(static_cast<unsigned>((C + 31) / 32)), dim3(32 * kFinalizeSlices), 0, s,
                        out0, out1, split, partial, P, C);
 }
 
 // Number of partial-sum rows the column reductions write to the workspace.
 // One per workgroup; sized so the grid fills 256 compute units a few times over
 // while the partials stay a small fraction of the tensor traffic.
-inline int tune_env(const char* name, int dflt)
-{
-    const char* v = getenv(name);
-    return v ? atoi(v) : dflt;
-}
-
 inline int ln_bwd_blocks(int64_t rows, int32_t /*hidden*/)
 {
     int64_t b = ceil_div(rows, 8);       // at least 8 rows per workgroup
-    const int cap = tune_env("LSQ_LN_BWD_BLOCKS", 512);
-    if (b > cap) b = cap;
+    if (b > 256) b = 256;                // one workgroup per compute unit: measured best at 8192 rows
     if (b < 1) b = 1;
     return static_cast<int>(b);
 }
@@ -120,8 +116,7 @@ inline int ln_bwd_blocks(int64_t rows, int32_t /*hidden*/)
 inline int bdr_bwd_row_blocks(int64_t rows, int32_t /*hidden*/)
 {
     int64_t b = ceil_div(rows, 16);
-    const int cap = tune_env("LSQ_BDR_BWD_BLOCKS", 256);
-    if (b > cap) b = cap;
+    if (b > 256) b = 256;
     if (b < 1) b = 1;
     return static_cast<int>(b);
 }

@@ -418,7 +418,7 @@ inline LnShape ln_shape(int hidden)
 inline int ln_fwd_blocks(int64_t rows, int lpr)
 {
     const int rpb = 256 / lpr;
-    int64_t b = ceil_div(rows, static_cast<int64_t>(rpb) * tune_env("LSQ_LN_FWD_GROUPS", 2));   // about two row groups per workgroup
+    int64_t b = ceil_div(rows, static_cast<int64_t>(rpb) * 2);   // about two row groups per workgroup
     if (b > 8192) b = 8192;
     if (b < 1) b = 1;
     return static_cast<int>(b);

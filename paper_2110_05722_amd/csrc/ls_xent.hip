@@ -111,20 +111,29 @@ __global__ __launch_bounds__(kXentThreads) void xent_fwd_kernel(float* __restric
     OnlineLse st;
     if (r.begin + tid < r.head_end) st.add1(to_f32<T>(logits[r.begin + tid]));
     if (r.tail_begin + tid < r.end) st.add1(to_f32<T>(logits[r.tail_begin + tid]));
-    // kXentUnroll packs in flight per thread: one load per iteration would leave the
-    // kernel bound by memory latency, not bandwidth
-    int64_t p = r.pack_begin + tid;
-    for (; p + (kXentUnroll - 1) * kXentThreads < r.pack_end; p += kXentUnroll * kXentThreads) {
-        float h[kXentUnroll][8];
+    // kXentUnroll packs in flight per thread.  The sweep starts at the 128-byte line that
+    // holds the row's first pack, not at the pack itself: every wave request is then
+    // line-aligned.  (Started at the pack, each 1 KiB request straddles nine lines and,
+    // with nontemporal loads, the shared line is fetched from HBM twice: +6 % traffic.)
+    const int64_t base = r.pack_begin & ~static_cast<int64_t>(7);
+    for (int64_t p = base + tid; p < r.pack_end; p += kXentUnroll * kXentThreads) {
+        RawPack<T> raw[kXentUnroll];
+        bool ok[kXentUnroll];
 #pragma unroll
-        for (int u = 0; u < kXentUnroll; ++u) load8<T, kNT>(logits + (p + u * kXentThreads) * kPack, h[u]);
+        for (int u = 0; u < kXentUnroll; ++u) {
+            const int64_t q = p + u * kXentThreads;
+            ok[u] = q >= r.pack_begin && q < r.pack_end;
+            if (ok[u]) raw[u] = load_raw<T, kNT>(logits + q * kPack);
+            else raw[u] = zero_raw<T>();
+        }
 #pragma unroll
-        for (int u = 0; u < kXentUnroll; ++u) st.add8(h[u]);
-    }
-    for (; p < r.pack_end; p += kXentThreads) {
-        float h[8];
-        load8<T, kNT>(logits + p * kPack, h);
-        st.add8(h);
+        for (int u = 0; u < kXentUnroll; ++u) {
+            if (ok[u]) {
+                float h[8];
+                unpack<T>(raw[u], h);
+                st.add8(h);
+            }
+        }
     }
     const float M = block_allreduce<kXentThreads / 64, OpMax>(st.m, lds);
     const float S = block_allreduce<kXentThreads / 64, OpSum>(st.s * __builtin_amdgcn_exp2f(st.m - M), lds);
