@@ -200,3 +200,61 @@ def adam_step(p, m, v, g, g_dt: str, lr, beta1, beta2, eps, step: int, weight_de
                          f(beta2), f(eps), f(weight_decay), C.c_int32(step), C.c_int32(int(adamw)),
                          C.c_int32(int(bias_correction)), f(inv_grad_scale), C.c_int(_DT[g_dt]))
     return po, mo, vo
+
+
+# ------------------------------------------------ bias + activation + dropout
+ACT = {"relu": 0, "gelu": 1, "gelu_tanh": 2}
+
+
+def bias_act_dropout_fwd(x, bias, act: str, p: float, seed: int, offset: int, dt: str, e0: int = 0):
+    x = _stored(x, dt)
+    if bias is not None:
+        bias = _stored(bias, dt)
+    rows, hidden = x.shape
+    out = np.empty((rows, hidden))
+    lib().lsqo_bias_act_dropout_fwd(_p(out), _p(x), _p(bias), C.c_int64(rows), C.c_int32(hidden), C.c_int32(ACT[act]),
+                                    C.c_double(float(np.float32(p))), C.c_uint64(seed), C.c_uint64(offset),
+                                    C.c_uint64(e0), C.c_int(_DT[dt]))
+    return out
+
+
+def bias_act_dropout_bwd(dy, x, bias, act: str, p: float, seed: int, offset: int, dt: str, e0: int = 0):
+    dy, x = _stored(dy, dt), _stored(x, dt)
+    if bias is not None:
+        bias = _stored(bias, dt)
+    rows, hidden = x.shape
+    dx = np.empty((rows, hidden)); dbias = np.empty(hidden)
+    lib().lsqo_bias_act_dropout_bwd(_p(dx), _p(dbias), _p(dy), _p(x), _p(bias), C.c_int64(rows), C.c_int32(hidden),
+                                    C.c_int32(ACT[act]), C.c_double(float(np.float32(p))), C.c_uint64(seed),
+                                    C.c_uint64(offset), C.c_uint64(e0), C.c_int(_DT[dt]))
+    return dx, dbias
+
+
+# ------------------------------------------------------------ trainer variants
+def adam_step_lp(p_lp, m, v, g, dt: str, lr, beta1, beta2, eps, step: int, weight_decay=0.0, adamw=False,
+                 bias_correction=True, inv_grad_scale=1.0):
+    p_lp = _stored(p_lp, dt)
+    g = _stored(g, dt)
+    m = np.ascontiguousarray(m, dtype=np.float32)
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    n = p_lp.size
+    po = np.empty(n); mo = np.empty(n); vo = np.empty(n)
+    f = lambda s: C.c_double(float(np.float32(s)))
+    lib().lsqo_adam_step_lp(_p(po), _p(mo), _p(vo), _p(p_lp), _p(m), _p(v), _p(g), C.c_int64(n), f(lr), f(beta1),
+                            f(beta2), f(eps), f(weight_decay), C.c_int32(step), C.c_int32(int(adamw)),
+                            C.c_int32(int(bias_correction)), f(inv_grad_scale), C.c_int(_DT[dt]))
+    return po, mo, vo
+
+
+def sgd_step(p, buf, g, g_dt: str, lr, momentum=0.0, weight_decay=0.0, nesterov=False, inv_grad_scale=1.0):
+    p = np.ascontiguousarray(p, dtype=np.float32)
+    g = _stored(g, g_dt)
+    n = p.size
+    po = np.empty(n)
+    bo = np.empty(n) if momentum != 0.0 else None
+    if momentum != 0.0:
+        buf = np.ascontiguousarray(buf, dtype=np.float32)
+    f = lambda s: C.c_double(float(np.float32(s)))
+    lib().lsqo_sgd_step(_p(po), _p(bo), _p(p), _p(buf) if momentum != 0.0 else None, _p(g), C.c_int64(n), f(lr),
+                        f(momentum), f(weight_decay), C.c_int32(int(nesterov)), f(inv_grad_scale), C.c_int(_DT[g_dt]))
+    return po, bo

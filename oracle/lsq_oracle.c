@@ -26,6 +26,8 @@
 #include <stdint.h>
 #include <string.h>
 
+static const double PI = 3.14159265358979323846;
+
 /* ------------------------------------------------------------------ storage */
 static double half_to_double(uint16_t h)
 {
@@ -261,6 +263,66 @@ void lsqo_bias_dropout_residual_bwd(double* dx, double* dbias, const void* dy, i
     }
 }
 
+/* ------------------------------------------------- bias + activation + dropout */
+/* The feed-forward half of Sec. IV-A's fused element-wise kernels: bias adding,
+ * activation, dropout.  The paper names ReLU; BERT and GPT-2 (Sec. VI) use GELU,
+ * in its erf form and its tanh approximation respectively.
+ * act: 0 = ReLU, 1 = GELU (erf), 2 = GELU (tanh approximation). */
+static double act_value(double z, int act)
+{
+    if (act == 0) return z > 0.0 ? z : 0.0;
+    if (act == 1) return 0.5 * z * erfc(-z / sqrt(2.0));   /* = z*Phi(z); erfc keeps the negative tail exact */
+    double u = sqrt(2.0 / PI) * (z + 0.044715 * z * z * z);
+    return 0.5 * z * (1.0 + tanh(u));
+}
+
+static double act_slope(double z, int act)
+{
+    if (act == 0) return z > 0.0 ? 1.0 : 0.0;
+    if (act == 1) return 0.5 * erfc(-z / sqrt(2.0)) + z * exp(-0.5 * z * z) / sqrt(2.0 * PI);
+    double c = sqrt(2.0 / PI);
+    double u = c * (z + 0.044715 * z * z * z);
+    double t = tanh(u);
+    return 0.5 * (1.0 + t) + 0.5 * z * (1.0 - t * t) * c * (1.0 + 3.0 * 0.044715 * z * z);
+}
+
+void lsqo_bias_act_dropout_fwd(double* out, const void* x, const void* bias, int64_t rows, int32_t hidden,
+                               int32_t act, double p, uint64_t seed, uint64_t offset, uint64_t e0, int dt)
+{
+    const uint32_t t16 = threshold16(p);
+    const double scale = 1.0 / (1.0 - p);
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int i = 0; i < hidden; ++i) {
+            int64_t e = r * hidden + i;
+            double z = load(x, e, dt) + (bias ? load(bias, i, dt) : 0.0);
+            double a = act_value(z, act);
+            out[e] = keep_element(e0 + (uint64_t)e, p, t16, seed, offset) ? a * scale : 0.0;
+        }
+}
+
+/* dx = act'(x + bias) * keep * dy / (1-p);  dbias = column sums of dx. */
+void lsqo_bias_act_dropout_bwd(double* dx, double* dbias, const void* dy, const void* x, const void* bias,
+                               int64_t rows, int32_t hidden, int32_t act, double p, uint64_t seed,
+                               uint64_t offset, uint64_t e0, int dt)
+{
+    const uint32_t t16 = threshold16(p);
+    const double scale = 1.0 / (1.0 - p);
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int i = 0; i < hidden; ++i) {
+            int64_t e = r * hidden + i;
+            double z = load(x, e, dt) + (bias ? load(bias, i, dt) : 0.0);
+            double g = keep_element(e0 + (uint64_t)e, p, t16, seed, offset) ? load(dy, e, dt) * scale : 0.0;
+            dx[e] = g * act_slope(z, act);
+        }
+    if (dbias) {
+        for (int i = 0; i < hidden; ++i) dbias[i] = 0.0;
+        for (int64_t r = 0; r < rows; ++r)
+            for (int i = 0; i < hidden; ++i) dbias[i] += dx[r * hidden + i];
+    }
+}
+
 /* ------------------------------------------------------------------ softmax */
 static int allowed(int j, int i, int klen_b, int causal, int q_len, int k_len)
 {
@@ -445,5 +507,56 @@ void lsqo_adam_step(double* p_out, double* m_out, double* v_out, const float* p,
         p_out[i] = pi - lr * upd;
         m_out[i] = mi;
         v_out[i] = vi;
+    }
+}
+
+/* The paper's own trainer layout (Sec. IV-C, Fig. "Mixed-precision trainer"): the
+ * workspace holds the parameter in LOW precision; it is widened, updated in
+ * higher precision and narrowed again in place.  Same update rule as above; p
+ * arrives in storage type `dt` (as does g). */
+void lsqo_adam_step_lp(double* p_out, double* m_out, double* v_out, const void* p_lp, const float* m,
+                       const float* v, const void* g, int64_t n, double lr, double beta1, double beta2,
+                       double eps, double weight_decay, int32_t step, int32_t adamw, int32_t bias_correction,
+                       double inv_grad_scale, int dt)
+{
+    double c1 = 1.0, c2 = 1.0;
+    if (bias_correction) {
+        c1 = 1.0 - pow(beta1, (double)step);
+        c2 = 1.0 - pow(beta2, (double)step);
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        double pi = load(p_lp, i, dt);
+        double gh = load(g, i, dt) * inv_grad_scale;
+        if (!adamw) gh += weight_decay * pi;
+        double mi = beta1 * (double)m[i] + (1.0 - beta1) * gh;
+        double vi = beta2 * (double)v[i] + (1.0 - beta2) * gh * gh;
+        double upd = (mi / c1) / (sqrt(vi / c2) + eps);
+        if (adamw) upd += weight_decay * pi;
+        p_out[i] = pi - lr * upd;
+        m_out[i] = mi;
+        v_out[i] = vi;
+    }
+}
+
+/* SGD trainer over the same flat workspace (Sec. VI-C names an SGD trainer next to
+ * Adam; the rule is the textbook one): g' = g*inv_grad_scale + wd*p;
+ * buf = momentum*buf + g' (momentum > 0; buf starts at 0); step direction
+ * d = g' + momentum*buf if nesterov, buf if momentum > 0, else g';  p -= lr*d. */
+void lsqo_sgd_step(double* p_out, double* buf_out, const float* p, const float* buf, const void* g,
+                   int64_t n, double lr, double momentum, double weight_decay, int32_t nesterov,
+                   double inv_grad_scale, int g_dt)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        double pi = (double)p[i];
+        double gh = load(g, i, g_dt) * inv_grad_scale + weight_decay * pi;
+        double d = gh;
+        if (momentum != 0.0) {
+            double b = momentum * (double)buf[i] + gh;
+            buf_out[i] = b;
+            d = nesterov ? gh + momentum * b : b;
+        }
+        p_out[i] = pi - lr * d;
     }
 }
