@@ -176,6 +176,36 @@ def main():
         state["step"] += 1
         L.lsq_adam_step(p, m, v, g, p_lp, step=state["step"], **ADAM_HYPER)
 
+    # ---- rows beyond the nine (bias+activation+dropout of the FFN, trainer variants): per-op table only
+    F = 4 * H
+    EF = T * F
+    act = "relu" if cfg.name.startswith("transformer") or cfg.name == "tiny" else ("gelu" if cfg.name == "bert-large" else "gelu_tanh")
+    ffn_sets = 1 if args.warm else max(2, -(-COLD_FOOTPRINT // (4 * EF * 2)))
+    ffn = []
+    if not args.ops or any(o.startswith("bias_act") for o in args.ops.split(",")):
+        for s_ in range(ffn_sets):
+            ffn.append(dict(x=device_normal((T, F), 1.0, dt, seed + 500 + s_, dev),
+                            dy=device_normal((T, F), 1.0, dt, seed + 600 + s_, dev),
+                            out=torch.empty((T, F), dtype=tdt, device=dev), dx=torch.empty((T, F), dtype=tdt, device=dev)))
+    fbias = device_normal((F,), 0.1, dt, seed + 8, dev)
+    fdbias = torch.empty(F, dtype=torch.float32, device=dev)
+    fws = torch.empty(max(L.lsq_workspace_bytes(2, T, F), 16), dtype=torch.uint8, device=dev)
+
+    def op_bad_fwd(i):
+        a = ffn[i % ffn_sets]
+        L.lsq_bias_act_dropout_fwd(a["x"], fbias, act, pa, ps, 2000 + i, out=a["out"])
+
+    def op_bad_bwd(i):
+        a = ffn[i % ffn_sets]
+        L.lsq_bias_act_dropout_bwd(a["dy"], a["x"], fbias, act, pa, ps, 2000 + i, dx=a["dx"], dbias=fdbias, workspace=fws)
+
+    def op_adam_lp(i):
+        state["step"] += 1
+        L.lsq_adam_step_lp(p_lp, m, v, g, step=state["step"], **ADAM_HYPER)
+
+    def op_sgd(i):
+        L.lsq_sgd_step(p, m, g, p_lp, lr=1e-3, momentum=0.9)      # m doubles as the momentum buffer here
+
     # algorithmic bytes per launch (what the method must move)
     bts = {
         "layernorm_fwd": 4 * E + 8 * T + 4 * H,
@@ -187,6 +217,8 @@ def main():
         "ls_xent_fwd": 2 * T * V + 16 * T,
         "ls_xent_bwd": 2 * t_active * V + 2 * T * V + 8 * T,
         "adam_step": 28 * n,
+        "bias_act_dropout_fwd": 4 * EF + 2 * F, "bias_act_dropout_bwd": 6 * EF + 6 * F,
+        "adam_step_lp": 22 * n, "sgd_step": 20 * n,
     }
     ops = [
         ("layernorm_fwd", op_ln_fwd), ("softmax_fwd", op_sm_fwd), ("bias_dropout_residual_fwd", op_bdr_fwd),
@@ -194,10 +226,13 @@ def main():
         ("softmax_bwd", op_sm_bwd), ("layernorm_bwd", op_ln_bwd), ("adam_step", op_adam),
     ]
 
+    extra = [("bias_act_dropout_fwd", op_bad_fwd), ("bias_act_dropout_bwd", op_bad_bwd),
+             ("adam_step_lp", op_adam_lp), ("sgd_step", op_sgd)]
     if args.ops:
         keep = set(args.ops.split(","))
         ops = [o for o in ops if o[0] in keep]
-        if not ops:
+        extra = [o for o in extra if o[0] in keep]
+        if not ops and not extra:
             sys.exit("bench.py: --ops matched nothing")
 
     def one_step(i):
@@ -224,6 +259,8 @@ def main():
     names = [o[0] for o in ops]
     adam_ms = float(np.mean([a.elapsed_time(b) for a, b in ev])) if "adam_step" in names else float("nan")
     step_bytes = sum(bts[k] for k in names)
+    if not names:
+        ms_per_step, step_bytes = float("nan"), 0
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
     # ------------------------------------------- per-operator table (cold, back to back)
@@ -232,7 +269,7 @@ def main():
     # Python interpreter issuing them (a ctypes call costs more than a 10 us kernel).
     table = {}
     timing = "eager" if args.no_graph else "hipgraph"
-    for name, f in ops:
+    for name, f in ops + extra:
         reps = max(3, min(args.op_reps, int(2e10 // max(bts[name], 1)) + 3))
         for i in range(3):
             f(i)
@@ -262,6 +299,7 @@ def main():
         gbs = bts[name] / (us * 1e-6) / 1e9
         table[name] = {"us": round(us, 2), "GBps": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
                        "bytes": int(bts[name]), "launches": reps}
+    next_table = {k: table.pop(k) for k, _ in extra if k in table}
     for k in bts:
         table.setdefault(k, {"us": float("nan")})
     enc = 2 * table["layernorm_fwd"]["us"] + 2 * table["bias_dropout_residual_fwd"]["us"] + table["softmax_fwd"]["us"] \
@@ -294,6 +332,8 @@ def main():
                    "buffers": "warm" if args.warm else f"cold (layer tensors rotate over {sets} sets, softmax over {soft_sets})"},
         "roofline": roofline,
         "ops": table, "ops_timing": timing,
+        "ops_next": dict(next_table, note=f"rows beyond the nine: FFN bias+{act}+dropout(p={pa}) on [{T}, {F}], the paper's "
+                                          "low-precision-parameter Adam (22 B/param), SGD with momentum (20 B/param)"),
         "layer_us": {"encoder_layer_fwd_bwd_nongemm": round(enc, 1), "decoder_layer_fwd_bwd_nongemm": round(dec, 1)},
     }
     if not args.no_cpu_baseline:

@@ -59,7 +59,14 @@ typedef enum {
 typedef enum { LSQ_F16 = 0, LSQ_BF16 = 1, LSQ_F32 = 2 } lsq_dtype;
 
 /* Operators that need a caller-supplied device workspace (column reductions). */
-typedef enum { LSQ_OP_LAYERNORM_BWD = 0, LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD = 1 } lsq_op;
+typedef enum {
+    LSQ_OP_LAYERNORM_BWD = 0,
+    LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD = 1,
+    LSQ_OP_BIAS_ACT_DROPOUT_BWD = 2
+} lsq_op;
+
+/* Activations of the feed-forward block. */
+typedef enum { LSQ_ACT_RELU = 0, LSQ_ACT_GELU = 1 /* erf form */, LSQ_ACT_GELU_TANH = 2 /* tanh approximation */ } lsq_act;
 
 /* Bytes of device workspace `op` needs for a [rows, cols] problem (0 if none).
  * Contents on entry are ignored; contents on exit are unspecified. */
@@ -186,6 +193,48 @@ lsq_status lsq_adam_step(float* p, float* m, float* v, const void* g, void* p_lp
                          float weight_decay, int32_t step, int32_t adamw,
                          int32_t bias_correction, float inv_grad_scale,
                          lsq_dtype g_dt, lsq_dtype p_lp_dt, void* stream);
+
+/* Fused bias + activation + dropout of the feed-forward block, forward (Sec. IV-A:
+ * adjacent element-wise kernels fused; the paper names ReLU, the BERT / GPT-2
+ * models of Sec. VI use GELU):
+ *   out[r,i] = keep[r,i] * act(x[r,i] + bias[i]) / (1 - p)
+ * x, out: [rows, hidden] dt;  bias: nullable [hidden] dt;  act: an lsq_act.
+ * out may alias x (but backward needs x: keep it if you train). */
+lsq_status lsq_bias_act_dropout_fwd(void* out, const void* x, const void* bias,
+                                    int64_t rows, int32_t hidden, int32_t act,
+                                    float p, uint64_t seed, uint64_t offset,
+                                    lsq_dtype dt, void* stream);
+
+/* Backward of the above: dx = act'(x + bias) * keep * dy / (1-p), mask regenerated,
+ * slope recomputed from the saved pre-activation x (ReLU slope at 0 is 0);
+ * dbias[i] = sum_rows dx[r,i] (nullable; fp32 [hidden], overwritten).  dx may
+ * alias dy.  workspace: >= lsq_workspace_bytes(LSQ_OP_BIAS_ACT_DROPOUT_BWD, rows,
+ * hidden) bytes, only used when dbias != NULL. */
+lsq_status lsq_bias_act_dropout_bwd(void* dx, float* dbias, const void* dy, const void* x,
+                                    const void* bias, int64_t rows, int32_t hidden, int32_t act,
+                                    float p, uint64_t seed, uint64_t offset,
+                                    void* workspace, size_t workspace_bytes,
+                                    lsq_dtype dt, void* stream);
+
+/* The paper's own trainer layout (Sec. IV-C): the workspace holds the parameter in
+ * LOW precision; it is widened in registers, updated with the rule of
+ * lsq_adam_step, narrowed (round to nearest even) and stored in place.
+ * p_lp, g: [n] dt (LSQ_F16 or LSQ_BF16);  m, v: fp32[n] in place.  22 bytes/param. */
+lsq_status lsq_adam_step_lp(void* p_lp, float* m, float* v, const void* g, int64_t n,
+                            float lr, float beta1, float beta2, float eps, float weight_decay,
+                            int32_t step, int32_t adamw, int32_t bias_correction,
+                            float inv_grad_scale, lsq_dtype dt, void* stream);
+
+/* SGD over the flat workspace, one launch (the paper's second trainer, Sec. VI-C):
+ *   ghat = g * inv_grad_scale + weight_decay * p
+ *   buf  = momentum * buf + ghat                    (momentum > 0; buf starts at 0)
+ *   d    = nesterov ? ghat + momentum * buf : (momentum > 0 ? buf : ghat)
+ *   p    = p - lr * d;   p_lp = round-to-nearest-even(p)  (nullable)
+ * p: fp32[n] in place;  momentum_buf: fp32[n] in place, may be NULL iff momentum == 0;
+ * g: [n] g_dt.  Errors: momentum < 0, nesterov without momentum. */
+lsq_status lsq_sgd_step(float* p, float* momentum_buf, const void* g, void* p_lp, int64_t n,
+                        float lr, float momentum, float weight_decay, int32_t nesterov,
+                        float inv_grad_scale, lsq_dtype g_dt, lsq_dtype p_lp_dt, void* stream);
 
 #ifdef __cplusplus
 }

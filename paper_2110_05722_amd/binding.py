@@ -17,13 +17,15 @@ _LIB_PATH = os.path.join(_HERE, os.environ.get("LSQ_LIB_NAME", "liblsq.so"))
 _lib = None
 
 LSQ_F16, LSQ_BF16, LSQ_F32 = 0, 1, 2
-LSQ_OP_LAYERNORM_BWD, LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD = 0, 1
+LSQ_OP_LAYERNORM_BWD, LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD, LSQ_OP_BIAS_ACT_DROPOUT_BWD = 0, 1, 2
+LSQ_ACT = {"relu": 0, "gelu": 1, "gelu_tanh": 2}
 _DT = {torch.float16: LSQ_F16, torch.bfloat16: LSQ_BF16, torch.float32: LSQ_F32}
 
 EXPORTS = [
     "lsq_workspace_bytes", "lsq_status_string", "lsq_layernorm_fwd", "lsq_layernorm_bwd",
     "lsq_bias_dropout_residual_fwd", "lsq_bias_dropout_residual_bwd", "lsq_softmax_fwd", "lsq_softmax_bwd",
     "lsq_ls_xent_fwd", "lsq_ls_xent_bwd", "lsq_adam_step",
+    "lsq_bias_act_dropout_fwd", "lsq_bias_act_dropout_bwd", "lsq_adam_step_lp", "lsq_sgd_step",
 ]
 
 
@@ -58,6 +60,10 @@ def load():
         "lsq_ls_xent_bwd": (C.c_int, [vp, vp, vp, vp, i64, i32, f32, i32, f32, C.c_int, vp]),
         "lsq_adam_step": (C.c_int, [vp, vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, i32, i32, i32, f32,
                                     C.c_int, C.c_int, vp]),
+        "lsq_bias_act_dropout_fwd": (C.c_int, [vp, vp, vp, i64, i32, i32, f32, u64, u64, C.c_int, vp]),
+        "lsq_bias_act_dropout_bwd": (C.c_int, [vp, vp, vp, vp, vp, i64, i32, i32, f32, u64, u64, vp, sz, C.c_int, vp]),
+        "lsq_adam_step_lp": (C.c_int, [vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, i32, i32, i32, f32, C.c_int, vp]),
+        "lsq_sgd_step": (C.c_int, [vp, vp, vp, vp, i64, f32, f32, f32, i32, f32, C.c_int, C.c_int, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -217,3 +223,49 @@ def lsq_adam_step(p, m, v, g, p_lp=None, *, lr: float, beta1: float, beta2: floa
                                 step, int(adamw), int(bias_correction), inv_grad_scale, _dt(g),
                                 _dt(p_lp) if p_lp is not None else LSQ_F16, _stream()), "lsq_adam_step")
     return p, m, v, p_lp
+
+
+def lsq_bias_act_dropout_fwd(x, bias, act: str, p: float, seed: int, offset: int, out=None):
+    """out = Dropout_p(act(x + bias)); act in {"relu", "gelu", "gelu_tanh"}."""
+    rows, hidden = x.shape
+    out = torch.empty_like(x) if out is None else out
+    _check(load().lsq_bias_act_dropout_fwd(_ptr(out), _ptr(x), _ptr(bias), rows, hidden, LSQ_ACT[act], p, seed, offset,
+                                           _dt(x), _stream()), "lsq_bias_act_dropout_fwd")
+    return out
+
+
+def lsq_bias_act_dropout_bwd(dy, x, bias, act: str, p: float, seed: int, offset: int, want_dbias: bool = True, dx=None,
+                             dbias=None, workspace=None):
+    """-> (dx, dbias[hidden] fp32 or None)."""
+    rows, hidden = x.shape
+    dx = torch.empty_like(x) if dx is None else dx
+    if want_dbias and dbias is None:
+        dbias = torch.empty(hidden, dtype=torch.float32, device=x.device)
+    ws = _workspace(lsq_workspace_bytes(LSQ_OP_BIAS_ACT_DROPOUT_BWD, rows, hidden), x, workspace)
+    _check(load().lsq_bias_act_dropout_bwd(_ptr(dx), _ptr(dbias) if want_dbias else None, _ptr(dy), _ptr(x), _ptr(bias),
+                                           rows, hidden, LSQ_ACT[act], p, seed, offset, _ptr(ws),
+                                           ws.numel() * ws.element_size(), _dt(x), _stream()), "lsq_bias_act_dropout_bwd")
+    return dx, (dbias if want_dbias else None)
+
+
+def lsq_adam_step_lp(p_lp, m, v, g, *, lr: float, beta1: float, beta2: float, eps: float, step: int,
+                     weight_decay: float = 0.0, adamw: bool = False, bias_correction: bool = True,
+                     inv_grad_scale: float = 1.0):
+    """In place on the low-precision p_lp and fp32 m, v (flat); g in the same low precision."""
+    if g.dtype != p_lp.dtype:
+        raise LsqError("g and p_lp must share one low-precision dtype")
+    _check(load().lsq_adam_step_lp(_ptr(p_lp), _ptr(m), _ptr(v), _ptr(g), p_lp.numel(), lr, beta1, beta2, eps,
+                                   weight_decay, step, int(adamw), int(bias_correction), inv_grad_scale, _dt(p_lp),
+                                   _stream()), "lsq_adam_step_lp")
+    return p_lp, m, v
+
+
+def lsq_sgd_step(p, momentum_buf, g, p_lp=None, *, lr: float, momentum: float = 0.0, weight_decay: float = 0.0,
+                 nesterov: bool = False, inv_grad_scale: float = 1.0):
+    """In place on fp32 p (and momentum_buf if momentum > 0); p_lp optional low-precision copy out."""
+    if p.dtype != torch.float32:
+        raise LsqError("p must be fp32")
+    _check(load().lsq_sgd_step(_ptr(p), _ptr(momentum_buf), _ptr(g), _ptr(p_lp), p.numel(), lr, momentum, weight_decay,
+                               int(nesterov), inv_grad_scale, _dt(g), _dt(p_lp) if p_lp is not None else LSQ_F16,
+                               _stream()), "lsq_sgd_step")
+    return p, momentum_buf, p_lp

@@ -83,6 +83,112 @@ static lsq_status adam_dispatch(float* p, float* m, float* v, const void* g, voi
     return launch_status();
 }
 
+// ---- the paper's own layout: the workspace holds the parameter in low precision and
+// it is updated in place (Sec. IV-C, "on-the-fly conversion"): 22 bytes per parameter.
+template <typename T>
+__global__ __launch_bounds__(256) void adam_lp_kernel(T* __restrict__ p, float* __restrict__ m, float* __restrict__ v,
+                                                      const T* __restrict__ g, int64_t n, AdamParams a)
+{
+    const int64_t e = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * kAdamPack;
+    if (e + kAdamPack <= n) {
+        float pf[4], mf[4], vf[4], gf[4];
+        load4<T, true>(p + e, pf);
+        load4<float, true>(m + e, mf);
+        load4<float, true>(v + e, vf);
+        load4<T, true>(g + e, gf);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) adam_update(pf[j], mf[j], vf[j], gf[j], a);
+        store4<T, true>(p + e, pf);
+        store4<float, true>(m + e, mf);
+        store4<float, true>(v + e, vf);
+    } else {
+        for (int64_t i = e; i < n; ++i) {
+            float pf = to_f32<T>(p[i]), mf = m[i], vf = v[i];
+            adam_update(pf, mf, vf, to_f32<T>(g[i]), a);
+            p[i] = from_f32<T>(pf); m[i] = mf; v[i] = vf;
+        }
+    }
+}
+
+// ---- SGD over the same flat workspace (the paper's second trainer): fp32 master p,
+// optional fp32 momentum buffer, low-precision gradient in, low-precision copy out.
+struct SgdParams { float lr, momentum, wd, inv_scale; int nesterov; };
+
+template <bool MOM>
+__device__ __forceinline__ void sgd_update(float& p, float& b, float g, const SgdParams& a)
+{
+    const float gh = fmaf(a.wd, p, g * a.inv_scale);
+    float d = gh;
+    if constexpr (MOM) {
+        b = fmaf(a.momentum, b, gh);
+        d = a.nesterov ? fmaf(a.momentum, b, gh) : b;
+    }
+    p = fmaf(-a.lr, d, p);
+}
+
+template <typename G, typename PL, bool HAS_PL, bool MOM>
+__global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ p, float* __restrict__ buf,
+                                                  const G* __restrict__ g, PL* __restrict__ plp, int64_t n, SgdParams a)
+{
+    const int64_t e = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * kAdamPack;
+    if (e + kAdamPack <= n) {
+        float pf[4], bf[4] = {0, 0, 0, 0}, gf[4];
+        load4<float, true>(p + e, pf);
+        if constexpr (MOM) load4<float, true>(buf + e, bf);
+        load4<G, true>(g + e, gf);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            sgd_update<MOM>(pf[j], bf[j], gf[j], a);
+            asm volatile("" : "+v"(pf[j]));     // the low-precision copy is the image of the STORED fp32 value
+        }
+        store4<float, true>(p + e, pf);
+        if constexpr (MOM) store4<float, true>(buf + e, bf);
+        if constexpr (HAS_PL) store4<PL, true>(plp + e, pf);
+    } else {
+        for (int64_t i = e; i < n; ++i) {
+            float pf = p[i], bf = MOM ? buf[i] : 0.0f;
+            sgd_update<MOM>(pf, bf, to_f32<G>(g[i]), a);
+            asm volatile("" : "+v"(pf));
+            p[i] = pf;
+            if constexpr (MOM) buf[i] = bf;
+            if constexpr (HAS_PL) plp[i] = from_f32<PL>(pf);
+        }
+    }
+}
+
+template <typename G, bool MOM>
+static lsq_status sgd_dispatch(float* p, float* buf, const void* g, void* plp, int64_t n, const SgdParams& a,
+                               int p_lp_dt, hipStream_t s)
+{
+    const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(n, kAdamPack), 256))), block(256);
+    const G* gp = static_cast<const G*>(g);
+    if (!plp)
+        hipLaunchKernelGGL((sgd_kernel<G, f16, false, MOM>), grid, block, 0, s, p, buf, gp, static_cast<f16*>(nullptr), n, a);
+    else if (p_lp_dt == LSQ_F16)
+        hipLaunchKernelGGL((sgd_kernel<G, f16, true, MOM>), grid, block, 0, s, p, buf, gp, static_cast<f16*>(plp), n, a);
+    else
+        hipLaunchKernelGGL((sgd_kernel<G, bf16, true, MOM>), grid, block, 0, s, p, buf, gp, static_cast<bf16*>(plp), n, a);
+    return launch_status();
+}
+
+static bool make_adam_params(AdamParams* a, float lr, float beta1, float beta2, float eps, float weight_decay,
+                             int32_t step, int32_t adamw, int32_t bias_correction, float inv_grad_scale)
+{
+    if (step < 1 || !(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f) || !(eps >= 0.0f)) return false;
+    a->lr = lr; a->beta1 = beta1; a->beta2 = beta2;
+    a->omb1 = 1.0f - beta1; a->omb2 = 1.0f - beta2;
+    a->eps = eps; a->wd = weight_decay; a->inv_scale = inv_grad_scale; a->adamw = adamw != 0;
+    // bias corrections in double on the host; the kernel multiplies by their reciprocals
+    double c1 = 1.0, c2 = 1.0;
+    if (bias_correction) {
+        c1 = 1.0 - pow(static_cast<double>(beta1), static_cast<double>(step));
+        c2 = 1.0 - pow(static_cast<double>(beta2), static_cast<double>(step));
+    }
+    a->rc1 = static_cast<float>(1.0 / c1);
+    a->rc2 = static_cast<float>(1.0 / c2);
+    return true;
+}
+
 }  // namespace lsq
 
 extern "C" lsq_status lsq_adam_step(float* p, float* m, float* v, const void* g, void* p_lp, int64_t n,
@@ -102,22 +208,60 @@ extern "C" lsq_status lsq_adam_step(float* p, float* m, float* v, const void* g,
     LSQ_REQUIRE(ceil_div(ceil_div(n, kAdamPack), 256) <= 0x7FFFFFFF);
 
     AdamParams a;
-    a.lr = lr; a.beta1 = beta1; a.beta2 = beta2;
-    a.omb1 = 1.0f - beta1; a.omb2 = 1.0f - beta2;
-    a.eps = eps; a.wd = weight_decay; a.inv_scale = inv_grad_scale; a.adamw = adamw != 0;
-    // bias corrections in double on the host; the kernel multiplies by their reciprocals
-    double c1 = 1.0, c2 = 1.0;
-    if (bias_correction) {
-        c1 = 1.0 - pow(static_cast<double>(beta1), static_cast<double>(step));
-        c2 = 1.0 - pow(static_cast<double>(beta2), static_cast<double>(step));
-    }
-    a.rc1 = static_cast<float>(1.0 / c1);
-    a.rc2 = static_cast<float>(1.0 / c2);
+    LSQ_REQUIRE(make_adam_params(&a, lr, beta1, beta2, eps, weight_decay, step, adamw, bias_correction, inv_grad_scale));
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (g_dt) {
         case LSQ_F16: return adam_dispatch<f16>(p, m, v, g, p_lp, n, a, p_lp_dt, s);
         case LSQ_BF16: return adam_dispatch<bf16>(p, m, v, g, p_lp, n, a, p_lp_dt, s);
         default: return adam_dispatch<float>(p, m, v, g, p_lp, n, a, p_lp_dt, s);
+    }
+}
+
+extern "C" lsq_status lsq_adam_step_lp(void* p_lp, float* m, float* v, const void* g, int64_t n, float lr, float beta1,
+                                       float beta2, float eps, float weight_decay, int32_t step, int32_t adamw,
+                                       int32_t bias_correction, float inv_grad_scale, lsq_dtype dt, void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(n >= 0);
+    AdamParams a;
+    LSQ_REQUIRE(make_adam_params(&a, lr, beta1, beta2, eps, weight_decay, step, adamw, bias_correction, inv_grad_scale));
+    if (dt != LSQ_F16 && dt != LSQ_BF16) return LSQ_UNSUPPORTED_DTYPE;
+    if (n == 0) return LSQ_OK;
+    LSQ_REQUIRE(p_lp && m && v && g);
+    LSQ_ALIGNED(p_lp); LSQ_ALIGNED(m); LSQ_ALIGNED(v); LSQ_ALIGNED(g);
+    LSQ_REQUIRE(ceil_div(ceil_div(n, kAdamPack), 256) <= 0x7FFFFFFF);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(n, kAdamPack), 256))), block(256);
+    if (dt == LSQ_F16)
+        hipLaunchKernelGGL((adam_lp_kernel<f16>), grid, block, 0, s, static_cast<f16*>(p_lp), m, v, static_cast<const f16*>(g), n, a);
+    else
+        hipLaunchKernelGGL((adam_lp_kernel<bf16>), grid, block, 0, s, static_cast<bf16*>(p_lp), m, v, static_cast<const bf16*>(g), n, a);
+    return launch_status();
+}
+
+extern "C" lsq_status lsq_sgd_step(float* p, float* momentum_buf, const void* g, void* p_lp, int64_t n, float lr,
+                                   float momentum, float weight_decay, int32_t nesterov, float inv_grad_scale,
+                                   lsq_dtype g_dt, lsq_dtype p_lp_dt, void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(n >= 0 && momentum >= 0.0f);
+    LSQ_REQUIRE(!(nesterov && momentum == 0.0f));
+    if (!valid_dtype(g_dt)) return LSQ_UNSUPPORTED_DTYPE;
+    if (p_lp && p_lp_dt != LSQ_F16 && p_lp_dt != LSQ_BF16) return LSQ_UNSUPPORTED_DTYPE;
+    if (n == 0) return LSQ_OK;
+    LSQ_REQUIRE(p && g && (momentum == 0.0f || momentum_buf));
+    LSQ_ALIGNED(p); LSQ_ALIGNED(momentum_buf); LSQ_ALIGNED(g); LSQ_ALIGNED(p_lp);
+    LSQ_REQUIRE(ceil_div(ceil_div(n, kAdamPack), 256) <= 0x7FFFFFFF);
+    SgdParams a{lr, momentum, weight_decay, inv_grad_scale, nesterov != 0};
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool mom = momentum != 0.0f;
+    switch (g_dt) {
+        case LSQ_F16: return mom ? sgd_dispatch<f16, true>(p, momentum_buf, g, p_lp, n, a, p_lp_dt, s)
+                                 : sgd_dispatch<f16, false>(p, momentum_buf, g, p_lp, n, a, p_lp_dt, s);
+        case LSQ_BF16: return mom ? sgd_dispatch<bf16, true>(p, momentum_buf, g, p_lp, n, a, p_lp_dt, s)
+                                  : sgd_dispatch<bf16, false>(p, momentum_buf, g, p_lp, n, a, p_lp_dt, s);
+        default: return mom ? sgd_dispatch<float, true>(p, momentum_buf, g, p_lp, n, a, p_lp_dt, s)
+                            : sgd_dispatch<float, false>(p, momentum_buf, g, p_lp, n, a, p_lp_dt, s);
     }
 }

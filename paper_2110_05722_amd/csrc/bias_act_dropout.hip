@@ -1,0 +1,298 @@
+// Fused bias + activation + dropout of the feed-forward block, forward and backward
+// (Sec. IV-A of the paper: adjacent element-wise kernels — bias adding, activation,
+// dropout — fused into one launch).  The paper names ReLU; the BERT and GPT-2
+// models of its Sec. VI use GELU (erf form and tanh approximation).
+//
+// Same layout as the bias+dropout+residual kernels: a wave owns 64 consecutive
+// packs of one row and walks down the rows with the bias pack in registers; the
+// dropout mask is rebuilt from the Philox counter of the pack in both directions;
+// backward recomputes the activation slope from the saved pre-activation input
+// and accumulates dbias per lane (no atomics; partial rows + ordered second stage).
+// HBM traffic: forward 2 tensors, backward 3.
+#include "host.hpp"
+
+namespace lsq {
+
+#ifndef LSQ_NT
+#define LSQ_NT 1
+#endif
+constexpr bool kNT = LSQ_NT != 0;
+
+constexpr int kBadWaves = 4;
+enum { ACT_RELU = 0, ACT_GELU = 1, ACT_GELU_TANH = 2 };
+
+// sigmoid(t) = 1/(1 + 2^(-t*log2 e)): one v_exp_f32 and one v_rcp_f32 (1 ulp; an IEEE
+// division costs ten instructions and this kernel is close to ALU-bound)
+__device__ __forceinline__ float sigmoidf_fast(float t)
+{
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * t));
+}
+
+template <int ACT> __device__ __forceinline__ float act_value(float z)
+{
+    if constexpr (ACT == ACT_RELU) return fmaxf(z, 0.0f);
+    else if constexpr (ACT == ACT_GELU) return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
+    else {
+        // 0.5*(1 + tanh(u)) == sigmoid(2u): no cancellation in the negative tail, no tanh call
+        const float u2 = 1.5957691216057308f * fmaf(0.044715f * z * z, z, z);
+        return z * sigmoidf_fast(u2);
+    }
+}
+
+template <int ACT> __device__ __forceinline__ float act_slope(float z)
+{
+    if constexpr (ACT == ACT_RELU) return z > 0.0f ? 1.0f : 0.0f;
+    else if constexpr (ACT == ACT_GELU)
+        return fmaf(z * 0.3989422804014327f, __expf(-0.5f * z * z), 0.5f * (1.0f + erff(z * 0.70710678118654752f)));
+    else {
+        // d/dz [z*sigmoid(2u)] = s + z*s*(1-s)*d(2u)/dz
+        const float z2 = z * z;
+        const float s = sigmoidf_fast(1.5957691216057308f * fmaf(0.044715f * z2, z, z));
+        const float du2 = 1.5957691216057308f * fmaf(3.0f * 0.044715f, z2, 1.0f);
+        return fmaf(z * s * (1.0f - s), du2, s);
+    }
+}
+
+template <typename T, int ACT, bool HAS_BIAS, bool DROP>
+__global__ __launch_bounds__(256) void bad_fwd_cols(T* out, const T* x, const T* __restrict__ bias, int64_t rows,
+                                                    int ppr, DropoutParams d)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int cp = blockIdx.x * 64 + lane;
+    if (cp >= ppr) return;
+    float b[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if constexpr (HAS_BIAS) load8<T>(bias + static_cast<int64_t>(cp) * kPack, b);
+    const int64_t stride = static_cast<int64_t>(gridDim.y) * kBadWaves;
+    for (int64_t r = static_cast<int64_t>(blockIdx.y) * kBadWaves + wave; r < rows; r += stride) {
+        const int64_t pack = r * ppr + cp;
+        float xf[8], k[8];
+        load8<T, kNT>(x + pack * kPack, xf);
+        if constexpr (DROP) dropout_factors8(d, static_cast<uint64_t>(pack), k);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float a = act_value<ACT>(xf[j] + b[j]);
+            xf[j] = DROP ? a * k[j] : a;
+        }
+        store8<T, kNT>(out + pack * kPack, xf);
+    }
+}
+
+template <typename T, int ACT, bool HAS_BIAS, bool DROP>
+__global__ __launch_bounds__(256) void bad_bwd_cols(T* dx, float* __restrict__ partial, const T* dy, const T* x,
+                                                    const T* __restrict__ bias, int64_t rows, int ppr, DropoutParams d)
+{
+    __shared__ float sm[kBadWaves][8][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int cp = blockIdx.x * 64 + lane;
+    const bool active = cp < ppr;
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const int64_t stride = static_cast<int64_t>(gridDim.y) * kBadWaves;
+    if (active) {
+        float b[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if constexpr (HAS_BIAS) load8<T>(bias + static_cast<int64_t>(cp) * kPack, b);
+        for (int64_t r = static_cast<int64_t>(blockIdx.y) * kBadWaves + wave; r < rows; r += stride) {
+            const int64_t pack = r * ppr + cp;
+            float g[8], xf[8], k[8];
+            load8<T, kNT>(dy + pack * kPack, g);
+            load8<T, kNT>(x + pack * kPack, xf);
+            if constexpr (DROP) dropout_factors8(d, static_cast<uint64_t>(pack), k);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float s = act_slope<ACT>(xf[j] + b[j]);
+                g[j] = DROP ? g[j] * k[j] * s : g[j] * s;
+                acc[j] += g[j];
+            }
+            store8<T, kNT>(dx + pack * kPack, g);
+        }
+    }
+    if (partial == nullptr) return;        // uniform over the grid
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sm[wave][j][lane] = acc[j];
+    __syncthreads();
+    if (wave == 0 && active) {
+        float* dst = partial + static_cast<int64_t>(blockIdx.y) * ppr * kPack + static_cast<int64_t>(cp) * kPack;
+        float s[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            float t = sm[0][j][lane];
+#pragma unroll
+            for (int w = 1; w < kBadWaves; ++w) t += sm[w][j][lane];
+            s[j] = t;
+        }
+        store8<float>(dst, s);
+    }
+}
+
+// ---- generic paths: any hidden, one element per thread
+template <typename T, int ACT>
+__global__ __launch_bounds__(256) void bad_fwd_flat(T* out, const T* x, const T* __restrict__ bias, int64_t total,
+                                                    int hidden, DropoutParams d)
+{
+    const int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (e >= total) return;
+    float z = to_f32<T>(x[e]);
+    if (bias) z += to_f32<T>(bias[e % hidden]);
+    float a = act_value<ACT>(z);
+    if (d.t16) a *= dropout_factor1(d, static_cast<uint64_t>(e));
+    out[e] = from_f32<T>(a);
+}
+
+template <typename T, int ACT>
+__global__ __launch_bounds__(256) void bad_bwd_flat(T* dx, const T* dy, const T* x, const T* __restrict__ bias,
+                                                    int64_t total, int hidden, DropoutParams d)
+{
+    const int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (e >= total) return;
+    float z = to_f32<T>(x[e]);
+    if (bias) z += to_f32<T>(bias[e % hidden]);
+    float g = to_f32<T>(dy[e]) * act_slope<ACT>(z);
+    if (d.t16) g *= dropout_factor1(d, static_cast<uint64_t>(e));
+    dx[e] = from_f32<T>(g);
+}
+
+// dbias for the generic path; runs BEFORE bad_bwd_flat so that dx may alias dy
+template <typename T, int ACT>
+__global__ __launch_bounds__(256) void bad_dbias_flat(float* __restrict__ dbias, const T* __restrict__ dy,
+                                                      const T* __restrict__ x, const T* __restrict__ bias, int64_t rows,
+                                                      int hidden, DropoutParams d)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= hidden) return;
+    const float b = bias ? to_f32<T>(bias[c]) : 0.0f;
+    float s = 0.0f;
+    for (int64_t r = 0; r < rows; ++r) {
+        const int64_t e = r * hidden + c;
+        float g = to_f32<T>(dy[e]) * act_slope<ACT>(to_f32<T>(x[e]) + b);
+        if (d.t16) g *= dropout_factor1(d, static_cast<uint64_t>(e));
+        s += g;
+    }
+    dbias[c] = s;
+}
+
+template <typename T, int ACT>
+static lsq_status bad_fwd_dispatch(void* out, const void* x, const void* bias, int64_t rows, int32_t hidden,
+                                   const DropoutParams& d, hipStream_t s)
+{
+    T* o = static_cast<T*>(out);
+    const T* xp = static_cast<const T*>(x);
+    const T* bp = static_cast<const T*>(bias);
+    if (hidden % kPack == 0) {
+        const int ppr = hidden / kPack;
+        int64_t rb = ceil_div(rows, 4 * kBadWaves);
+        if (rb > 4096) rb = 4096;
+        const dim3 grid(static_cast<unsigned>(ceil_div(ppr, 64)), static_cast<unsigned>(rb)), block(256);
+        const bool drop = d.t16 != 0;
+        if (bp && drop) hipLaunchKernelGGL((bad_fwd_cols<T, ACT, true, true>), grid, block, 0, s, o, xp, bp, rows, ppr, d);
+        else if (bp) hipLaunchKernelGGL((bad_fwd_cols<T, ACT, true, false>), grid, block, 0, s, o, xp, bp, rows, ppr, d);
+        else if (drop) hipLaunchKernelGGL((bad_fwd_cols<T, ACT, false, true>), grid, block, 0, s, o, xp, bp, rows, ppr, d);
+        else hipLaunchKernelGGL((bad_fwd_cols<T, ACT, false, false>), grid, block, 0, s, o, xp, bp, rows, ppr, d);
+    } else {
+        const int64_t total = rows * hidden;
+        hipLaunchKernelGGL((bad_fwd_flat<T, ACT>), dim3(static_cast<unsigned>(ceil_div(total, 256))), dim3(256), 0, s,
+                           o, xp, bp, total, hidden, d);
+    }
+    return launch_status();
+}
+
+template <typename T, int ACT>
+static lsq_status bad_bwd_dispatch(void* dx, float* dbias, const void* dy, const void* x, const void* bias, int64_t rows,
+                                   int32_t hidden, const DropoutParams& d, void* workspace, hipStream_t s)
+{
+    T* o = static_cast<T*>(dx);
+    const T* g = static_cast<const T*>(dy);
+    const T* xp = static_cast<const T*>(x);
+    const T* bp = static_cast<const T*>(bias);
+    if (hidden % kPack == 0) {
+        const int ppr = hidden / kPack;
+        const int rb = bdr_bwd_row_blocks(rows, hidden);
+        const dim3 grid(static_cast<unsigned>(ceil_div(ppr, 64)), static_cast<unsigned>(rb)), block(256);
+        float* partial = dbias ? static_cast<float*>(workspace) : nullptr;
+        const bool drop = d.t16 != 0;
+        if (bp && drop) hipLaunchKernelGGL((bad_bwd_cols<T, ACT, true, true>), grid, block, 0, s, o, partial, g, xp, bp, rows, ppr, d);
+        else if (bp) hipLaunchKernelGGL((bad_bwd_cols<T, ACT, true, false>), grid, block, 0, s, o, partial, g, xp, bp, rows, ppr, d);
+        else if (drop) hipLaunchKernelGGL((bad_bwd_cols<T, ACT, false, true>), grid, block, 0, s, o, partial, g, xp, bp, rows, ppr, d);
+        else hipLaunchKernelGGL((bad_bwd_cols<T, ACT, false, false>), grid, block, 0, s, o, partial, g, xp, bp, rows, ppr, d);
+        if (dbias) launch_colsum_finalize(dbias, dbias, hidden, partial, rb, hidden, s);
+    } else {
+        const int64_t total = rows * hidden;
+        if (dbias)
+            hipLaunchKernelGGL((bad_dbias_flat<T, ACT>), dim3(static_cast<unsigned>(ceil_div(hidden, 256))), dim3(256), 0, s,
+                               dbias, g, xp, bp, rows, hidden, d);
+        hipLaunchKernelGGL((bad_bwd_flat<T, ACT>), dim3(static_cast<unsigned>(ceil_div(total, 256))), dim3(256), 0, s,
+                           o, g, xp, bp, total, hidden, d);
+    }
+    return launch_status();
+}
+
+template <typename T>
+static lsq_status bad_fwd_act(int act, void* out, const void* x, const void* bias, int64_t rows, int32_t hidden,
+                              const DropoutParams& d, hipStream_t s)
+{
+    switch (act) {
+        case ACT_RELU: return bad_fwd_dispatch<T, ACT_RELU>(out, x, bias, rows, hidden, d, s);
+        case ACT_GELU: return bad_fwd_dispatch<T, ACT_GELU>(out, x, bias, rows, hidden, d, s);
+        default: return bad_fwd_dispatch<T, ACT_GELU_TANH>(out, x, bias, rows, hidden, d, s);
+    }
+}
+
+template <typename T>
+static lsq_status bad_bwd_act(int act, void* dx, float* dbias, const void* dy, const void* x, const void* bias,
+                              int64_t rows, int32_t hidden, const DropoutParams& d, void* ws, hipStream_t s)
+{
+    switch (act) {
+        case ACT_RELU: return bad_bwd_dispatch<T, ACT_RELU>(dx, dbias, dy, x, bias, rows, hidden, d, ws, s);
+        case ACT_GELU: return bad_bwd_dispatch<T, ACT_GELU>(dx, dbias, dy, x, bias, rows, hidden, d, ws, s);
+        default: return bad_bwd_dispatch<T, ACT_GELU_TANH>(dx, dbias, dy, x, bias, rows, hidden, d, ws, s);
+    }
+}
+
+}  // namespace lsq
+
+extern "C" lsq_status lsq_bias_act_dropout_fwd(void* out, const void* x, const void* bias, int64_t rows, int32_t hidden,
+                                               int32_t act, float p, uint64_t seed, uint64_t offset, lsq_dtype dt,
+                                               void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(rows >= 0 && hidden > 0);
+    LSQ_REQUIRE(act == LSQ_ACT_RELU || act == LSQ_ACT_GELU || act == LSQ_ACT_GELU_TANH);
+    if (!valid_dtype(dt)) return LSQ_UNSUPPORTED_DTYPE;
+    DropoutParams d;
+    LSQ_REQUIRE(make_dropout(p, seed, offset, &d));
+    if (rows == 0) return LSQ_OK;
+    LSQ_REQUIRE(out && x);
+    LSQ_ALIGNED(out); LSQ_ALIGNED(x); LSQ_ALIGNED(bias);
+    LSQ_REQUIRE(ceil_div(rows * hidden, 256) <= 0x7FFFFFFF);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (dt) {
+        case LSQ_F16: return bad_fwd_act<f16>(act, out, x, bias, rows, hidden, d, s);
+        case LSQ_BF16: return bad_fwd_act<bf16>(act, out, x, bias, rows, hidden, d, s);
+        default: return bad_fwd_act<float>(act, out, x, bias, rows, hidden, d, s);
+    }
+}
+
+extern "C" lsq_status lsq_bias_act_dropout_bwd(void* dx, float* dbias, const void* dy, const void* x, const void* bias,
+                                               int64_t rows, int32_t hidden, int32_t act, float p, uint64_t seed,
+                                               uint64_t offset, void* workspace, size_t workspace_bytes, lsq_dtype dt,
+                                               void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(rows >= 0 && hidden > 0);
+    LSQ_REQUIRE(act == LSQ_ACT_RELU || act == LSQ_ACT_GELU || act == LSQ_ACT_GELU_TANH);
+    if (!valid_dtype(dt)) return LSQ_UNSUPPORTED_DTYPE;
+    DropoutParams d;
+    LSQ_REQUIRE(make_dropout(p, seed, offset, &d));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (rows == 0) return dbias ? zero_fill(dbias, hidden, s) : LSQ_OK;
+    LSQ_REQUIRE(dx && dy && x);
+    LSQ_ALIGNED(dx); LSQ_ALIGNED(dy); LSQ_ALIGNED(x); LSQ_ALIGNED(bias); LSQ_ALIGNED(dbias); LSQ_ALIGNED(workspace);
+    LSQ_REQUIRE(ceil_div(rows * hidden, 256) <= 0x7FFFFFFF);
+    if (dbias) {
+        const size_t need = lsq_workspace_bytes(LSQ_OP_BIAS_ACT_DROPOUT_BWD, rows, hidden);
+        if (need && (!workspace || workspace_bytes < need)) return LSQ_WORKSPACE_TOO_SMALL;
+    }
+    switch (dt) {
+        case LSQ_F16: return bad_bwd_act<f16>(act, dx, dbias, dy, x, bias, rows, hidden, d, workspace, s);
+        case LSQ_BF16: return bad_bwd_act<bf16>(act, dx, dbias, dy, x, bias, rows, hidden, d, workspace, s);
+        default: return bad_bwd_act<float>(act, dx, dbias, dy, x, bias, rows, hidden, d, workspace, s);
+    }
+}

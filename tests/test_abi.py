@@ -38,6 +38,7 @@ def test_status_strings_and_workspace(lib):
     assert w > 0 and w % (2 * 1024 * 4) == 0
     w = L.lsq_workspace_bytes(1, 8192, 1024)
     assert w > 0 and w % (1024 * 4) == 0
+    assert L.lsq_workspace_bytes(2, 8192, 4096) == L.lsq_workspace_bytes(1, 8192, 4096) > 0
     assert L.lsq_workspace_bytes(99, 8192, 1024) == 0
 
 
@@ -95,6 +96,28 @@ def test_host_side_argument_errors(lib):
     f = lib.lsq_ls_xent_bwd
     assert f(A, A, None, A, 4, 8, 0.1, -100, 1.0, 0, None) == INVALID
     assert f(A, A, A, A, 4, 8, 0.1, -100, 1.0, 9, None) == DTYPE
+
+
+def test_host_side_argument_errors_of_the_next_rows(lib):
+    INVALID, DTYPE, MISALIGNED, WS = 1, 2, 3, 4
+    f = lib.lsq_bias_act_dropout_fwd
+    assert f(A, A, A, 4, 8, 3, 0.1, 1, 0, 0, None) == INVALID          # unknown activation
+    assert f(A, A, A, 4, 8, 0, 1.0, 1, 0, 0, None) == INVALID
+    assert f(A, U, A, 4, 8, 0, 0.1, 1, 0, 0, None) == MISALIGNED
+    assert f(None, None, None, 0, 8, 1, 0.1, 1, 0, 0, None) == 0
+    f = lib.lsq_bias_act_dropout_bwd
+    assert f(A, A, A, A, A, 64, 512, 1, 0.1, 1, 0, A, 8, 0, None) == WS
+    assert f(A, None, A, None, A, 64, 512, 1, 0.1, 1, 0, None, 0, 0, None) == INVALID
+    f = lib.lsq_adam_step_lp
+    assert f(A, A, A, A, 8, 1e-3, .9, .98, 1e-8, 0., 0, 0, 1, 1., 0, None) == INVALID
+    assert f(A, A, A, A, 8, 1e-3, .9, .98, 1e-8, 0., 1, 0, 1, 1., 2, None) == DTYPE   # fp32 is not "low precision"
+    assert f(A, U, A, A, 8, 1e-3, .9, .98, 1e-8, 0., 1, 0, 1, 1., 0, None) == MISALIGNED
+    f = lib.lsq_sgd_step
+    assert f(A, None, A, None, 8, 0.1, 0.9, 0., 0, 1., 0, 0, None) == INVALID         # momentum without a buffer
+    assert f(A, None, A, None, 8, 0.1, 0.0, 0., 1, 1., 0, 0, None) == INVALID         # nesterov without momentum
+    assert f(A, A, A, None, 8, 0.1, -0.5, 0., 0, 1., 0, 0, None) == INVALID
+    assert f(A, A, A, A, 8, 0.1, 0.9, 0., 0, 1., 0, 2, None) == DTYPE
+    assert f(None, None, None, None, 0, 0.1, 0.0, 0., 0, 1., 0, 0, None) == 0
 
 
 def test_binding_refuses_cpu_tensors(lib):
