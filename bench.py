@@ -199,6 +199,31 @@ def main():
         a = ffn[i % ffn_sets]
         L.lsq_bias_act_dropout_bwd(a["dy"], a["x"], fbias, act, pa, ps, 2000 + i, dx=a["dx"], dbias=fdbias, workspace=fws)
 
+    D = H // N
+    head_sets = 1 if args.warm else max(2, -(-COLD_FOOTPRINT // (12 * E * 2)))
+    heads_buf = []
+    if not args.ops or any("heads" in o for o in args.ops.split(",")):
+        for s_ in range(head_sets):
+            heads_buf.append(dict(qkv=device_normal((T, 3 * H), 1.0, dt, seed + 700 + s_, dev),
+                                  q=[torch.empty((B, N, Lq, D), dtype=tdt, device=dev) for _ in range(3)],
+                                  dqkv=torch.empty((T, 3 * H), dtype=tdt, device=dev),
+                                  merged=torch.empty((T, H), dtype=tdt, device=dev)))
+    qkv_bias = device_normal((3 * H,), 0.1, dt, seed + 9, dev)
+    qkv_dbias = torch.empty(3 * H, dtype=torch.float32, device=dev)
+    hws = torch.empty(max(L.lsq_workspace_bytes(3, T, 3 * H), 16), dtype=torch.uint8, device=dev)
+
+    def op_split_fwd(i):
+        a = heads_buf[i % head_sets]
+        L.lsq_split_heads_fwd(a["qkv"], qkv_bias, B, Lq, N, D, 3, outs=a["q"])
+
+    def op_split_bwd(i):
+        a = heads_buf[i % head_sets]
+        L.lsq_split_heads_bwd(a["q"], B, Lq, N, D, din=a["dqkv"], dbias=qkv_dbias, workspace=hws)
+
+    def op_merge_fwd(i):
+        a = heads_buf[i % head_sets]
+        L.lsq_merge_heads_fwd(a["q"][0], out=a["merged"])
+
     def op_adam_lp(i):
         state["step"] += 1
         L.lsq_adam_step_lp(p_lp, m, v, g, step=state["step"], **ADAM_HYPER)
@@ -219,6 +244,7 @@ def main():
         "adam_step": 28 * n,
         "bias_act_dropout_fwd": 4 * EF + 2 * F, "bias_act_dropout_bwd": 6 * EF + 6 * F,
         "adam_step_lp": 22 * n, "sgd_step": 20 * n,
+        "split_heads_fwd": 12 * E + 6 * H, "split_heads_bwd": 12 * E + 12 * H, "merge_heads_fwd": 4 * E,
     }
     ops = [
         ("layernorm_fwd", op_ln_fwd), ("softmax_fwd", op_sm_fwd), ("bias_dropout_residual_fwd", op_bdr_fwd),
@@ -227,6 +253,7 @@ def main():
     ]
 
     extra = [("bias_act_dropout_fwd", op_bad_fwd), ("bias_act_dropout_bwd", op_bad_bwd),
+             ("split_heads_fwd", op_split_fwd), ("split_heads_bwd", op_split_bwd), ("merge_heads_fwd", op_merge_fwd),
              ("adam_step_lp", op_adam_lp), ("sgd_step", op_sgd)]
     if args.ops:
         keep = set(args.ops.split(","))
@@ -333,7 +360,8 @@ def main():
         "roofline": roofline,
         "ops": table, "ops_timing": timing,
         "ops_next": dict(next_table, note=f"rows beyond the nine: FFN bias+{act}+dropout(p={pa}) on [{T}, {F}], the paper's "
-                                          "low-precision-parameter Adam (22 B/param), SGD with momentum (20 B/param)"),
+                                          "low-precision-parameter Adam (22 B/param), SGD with momentum (20 B/param), "
+                                          f"QKV bias + head split on [{T}, {3 * H}] and its backward, head merge"),
         "layer_us": {"encoder_layer_fwd_bwd_nongemm": round(enc, 1), "decoder_layer_fwd_bwd_nongemm": round(dec, 1)},
     }
     if not args.no_cpu_baseline:

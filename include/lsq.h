@@ -62,7 +62,8 @@ typedef enum { LSQ_F16 = 0, LSQ_BF16 = 1, LSQ_F32 = 2 } lsq_dtype;
 typedef enum {
     LSQ_OP_LAYERNORM_BWD = 0,
     LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD = 1,
-    LSQ_OP_BIAS_ACT_DROPOUT_BWD = 2
+    LSQ_OP_BIAS_ACT_DROPOUT_BWD = 2,
+    LSQ_OP_SPLIT_HEADS_BWD = 3          /* cols = parts * heads * head_dim */
 } lsq_op;
 
 /* Activations of the feed-forward block. */
@@ -235,6 +236,33 @@ lsq_status lsq_adam_step_lp(void* p_lp, float* m, float* v, const void* g, int64
 lsq_status lsq_sgd_step(float* p, float* momentum_buf, const void* g, void* p_lp, int64_t n,
                         float lr, float momentum, float weight_decay, int32_t nesterov,
                         float inv_grad_scale, lsq_dtype g_dt, lsq_dtype p_lp_dt, void* stream);
+
+/* Head split (the "Reshape" of Sec. IV-A's element-wise operations): the projection
+ * output `in` [batch*len, parts*hidden], columns ordered (part, head, head_dim), plus
+ * an optional bias [parts*hidden], is written as `parts` tensors
+ * out_k[batch, heads, len, head_dim] (k < parts; parts in 1..3: 3 for a fused QKV
+ * projection).  hidden = heads*head_dim.  Unused out pointers may be NULL.
+ * Without a bias the move is bit-exact. */
+lsq_status lsq_split_heads_fwd(void* out0, void* out1, void* out2, const void* in, const void* bias,
+                               int32_t batch, int32_t len, int32_t heads, int32_t head_dim,
+                               int32_t parts, lsq_dtype dt, void* stream);
+
+/* Backward of the split: din[batch*len, parts*hidden] gathers d_k[batch, heads, len,
+ * head_dim] (bit-exact), and dbias[parts*hidden] (nullable, fp32, overwritten) is
+ * the column sum of din.  workspace: >= lsq_workspace_bytes(LSQ_OP_SPLIT_HEADS_BWD,
+ * batch*len, parts*hidden) bytes, only used when dbias != NULL. */
+lsq_status lsq_split_heads_bwd(void* din, float* dbias, const void* d0, const void* d1, const void* d2,
+                               int32_t batch, int32_t len, int32_t heads, int32_t head_dim,
+                               int32_t parts, void* workspace, size_t workspace_bytes,
+                               lsq_dtype dt, void* stream);
+
+/* Head merge of the attention output: x[batch, heads, len, head_dim] ->
+ * out[batch*len, hidden]; and its backward, dy[batch*len, hidden] ->
+ * dx[batch, heads, len, head_dim].  Both are bit-exact moves. */
+lsq_status lsq_merge_heads_fwd(void* out, const void* x, int32_t batch, int32_t len, int32_t heads,
+                               int32_t head_dim, lsq_dtype dt, void* stream);
+lsq_status lsq_merge_heads_bwd(void* dx, const void* dy, int32_t batch, int32_t len, int32_t heads,
+                               int32_t head_dim, lsq_dtype dt, void* stream);
 
 #ifdef __cplusplus
 }

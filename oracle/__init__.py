@@ -258,3 +258,29 @@ def sgd_step(p, buf, g, g_dt: str, lr, momentum=0.0, weight_decay=0.0, nesterov=
     lib().lsqo_sgd_step(_p(po), _p(bo), _p(p), _p(buf) if momentum != 0.0 else None, _p(g), C.c_int64(n), f(lr),
                         f(momentum), f(weight_decay), C.c_int32(int(nesterov)), f(inv_grad_scale), C.c_int(_DT[g_dt]))
     return po, bo
+
+
+# ---------------------------------------------------------- head split / merge
+def split_heads_fwd(x, bias, batch: int, length: int, heads: int, head_dim: int, parts: int, dt: str):
+    """x: [batch*len, parts*heads*head_dim] (+bias) -> `parts` arrays [batch, heads, len, head_dim]."""
+    x = _stored(x, dt)
+    if bias is not None:
+        bias = _stored(bias, dt)
+    outs = [np.empty((batch, heads, length, head_dim)) for _ in range(parts)]
+    ptrs = [_p(o) for o in outs] + [None] * (3 - parts)
+    lib().lsqo_split_heads_fwd(ptrs[0], ptrs[1], ptrs[2], _p(x), _p(bias), C.c_int32(batch), C.c_int32(length),
+                               C.c_int32(heads), C.c_int32(head_dim), C.c_int32(parts), C.c_int(_DT[dt]))
+    return outs
+
+
+def split_heads_bwd(grads, batch: int, length: int, heads: int, head_dim: int, dt: str, want_dbias: bool = True):
+    """grads: list of `parts` arrays [batch, heads, len, head_dim] -> (din [batch*len, parts*hidden], dbias)."""
+    parts = len(grads)
+    grads = [_stored(g, dt) for g in grads]
+    hidden = heads * head_dim
+    din = np.empty((batch * length, parts * hidden))
+    dbias = np.empty(parts * hidden) if want_dbias else None
+    ptrs = [_p(g) for g in grads] + [None] * (3 - parts)
+    lib().lsqo_split_heads_bwd(_p(din), _p(dbias), ptrs[0], ptrs[1], ptrs[2], C.c_int32(batch), C.c_int32(length),
+                               C.c_int32(heads), C.c_int32(head_dim), C.c_int32(parts), C.c_int(_DT[dt]))
+    return din, dbias

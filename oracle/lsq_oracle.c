@@ -560,3 +560,46 @@ void lsqo_sgd_step(double* p_out, double* buf_out, const float* p, const float* 
         p_out[i] = pi - lr * d;
     }
 }
+
+/* --------------------------------------------------------- head split / merge */
+/* The "Reshape" of Sec. IV-A's element-wise list: the projection output [batch*len,
+ * parts*hidden] (columns ordered part, head, head_dim) plus its bias is laid out as
+ * `parts` tensors [batch, heads, len, head_dim] for the batched attention GEMMs, and
+ * the attention output is laid back.  Pure index permutations (+ the bias). */
+void lsqo_split_heads_fwd(double* out0, double* out1, double* out2, const void* in, const void* bias,
+                          int32_t batch, int32_t len, int32_t heads, int32_t head_dim, int32_t parts, int dt)
+{
+    double* outs[3] = { out0, out1, out2 };
+    const int64_t hidden = (int64_t)heads * head_dim;
+    for (int b = 0; b < batch; ++b)
+        for (int l = 0; l < len; ++l)
+            for (int part = 0; part < parts; ++part)
+                for (int n = 0; n < heads; ++n)
+                    for (int d = 0; d < head_dim; ++d) {
+                        int64_t col = part * hidden + (int64_t)n * head_dim + d;
+                        int64_t src = ((int64_t)b * len + l) * parts * hidden + col;
+                        int64_t dst = (((int64_t)b * heads + n) * len + l) * head_dim + d;
+                        outs[part][dst] = load(in, src, dt) + (bias ? load(bias, col, dt) : 0.0);
+                    }
+}
+
+/* The inverse layout change, with the bias gradient (column sums) as a by-product. */
+void lsqo_split_heads_bwd(double* din, double* dbias, const void* d0, const void* d1, const void* d2,
+                          int32_t batch, int32_t len, int32_t heads, int32_t head_dim, int32_t parts, int dt)
+{
+    const void* ds[3] = { d0, d1, d2 };
+    const int64_t hidden = (int64_t)heads * head_dim;
+    if (dbias) for (int64_t c = 0; c < parts * hidden; ++c) dbias[c] = 0.0;
+    for (int b = 0; b < batch; ++b)
+        for (int l = 0; l < len; ++l)
+            for (int part = 0; part < parts; ++part)
+                for (int n = 0; n < heads; ++n)
+                    for (int d = 0; d < head_dim; ++d) {
+                        int64_t col = part * hidden + (int64_t)n * head_dim + d;
+                        int64_t dst = ((int64_t)b * len + l) * parts * hidden + col;
+                        int64_t src = (((int64_t)b * heads + n) * len + l) * head_dim + d;
+                        double g = load(ds[part], src, dt);
+                        din[dst] = g;
+                        if (dbias) dbias[col] += g;
+                    }
+}

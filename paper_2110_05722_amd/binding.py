@@ -18,6 +18,7 @@ _lib = None
 
 LSQ_F16, LSQ_BF16, LSQ_F32 = 0, 1, 2
 LSQ_OP_LAYERNORM_BWD, LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD, LSQ_OP_BIAS_ACT_DROPOUT_BWD = 0, 1, 2
+LSQ_OP_SPLIT_HEADS_BWD = 3
 LSQ_ACT = {"relu": 0, "gelu": 1, "gelu_tanh": 2}
 _DT = {torch.float16: LSQ_F16, torch.bfloat16: LSQ_BF16, torch.float32: LSQ_F32}
 
@@ -26,6 +27,7 @@ EXPORTS = [
     "lsq_bias_dropout_residual_fwd", "lsq_bias_dropout_residual_bwd", "lsq_softmax_fwd", "lsq_softmax_bwd",
     "lsq_ls_xent_fwd", "lsq_ls_xent_bwd", "lsq_adam_step",
     "lsq_bias_act_dropout_fwd", "lsq_bias_act_dropout_bwd", "lsq_adam_step_lp", "lsq_sgd_step",
+    "lsq_split_heads_fwd", "lsq_split_heads_bwd", "lsq_merge_heads_fwd", "lsq_merge_heads_bwd",
 ]
 
 
@@ -64,6 +66,10 @@ def load():
         "lsq_bias_act_dropout_bwd": (C.c_int, [vp, vp, vp, vp, vp, i64, i32, i32, f32, u64, u64, vp, sz, C.c_int, vp]),
         "lsq_adam_step_lp": (C.c_int, [vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, i32, i32, i32, f32, C.c_int, vp]),
         "lsq_sgd_step": (C.c_int, [vp, vp, vp, vp, i64, f32, f32, f32, i32, f32, C.c_int, C.c_int, vp]),
+        "lsq_split_heads_fwd": (C.c_int, [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, C.c_int, vp]),
+        "lsq_split_heads_bwd": (C.c_int, [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, sz, C.c_int, vp]),
+        "lsq_merge_heads_fwd": (C.c_int, [vp, vp, i32, i32, i32, i32, C.c_int, vp]),
+        "lsq_merge_heads_bwd": (C.c_int, [vp, vp, i32, i32, i32, i32, C.c_int, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -269,3 +275,46 @@ def lsq_sgd_step(p, momentum_buf, g, p_lp=None, *, lr: float, momentum: float = 
                                int(nesterov), inv_grad_scale, _dt(g), _dt(p_lp) if p_lp is not None else LSQ_F16,
                                _stream()), "lsq_sgd_step")
     return p, momentum_buf, p_lp
+
+
+def lsq_split_heads_fwd(x, bias, batch: int, length: int, heads: int, head_dim: int, parts: int, outs=None):
+    """x: [batch*len, parts*heads*head_dim] (+ bias) -> list of `parts` tensors [batch, heads, len, head_dim]."""
+    if outs is None:
+        outs = [torch.empty((batch, heads, length, head_dim), dtype=x.dtype, device=x.device) for _ in range(parts)]
+    ptrs = [_ptr(o) for o in outs] + [None] * (3 - parts)
+    _check(load().lsq_split_heads_fwd(ptrs[0], ptrs[1], ptrs[2], _ptr(x), _ptr(bias), batch, length, heads, head_dim,
+                                      parts, _dt(x), _stream()), "lsq_split_heads_fwd")
+    return outs
+
+
+def lsq_split_heads_bwd(grads, batch: int, length: int, heads: int, head_dim: int, want_dbias: bool = True, din=None,
+                        dbias=None, workspace=None):
+    """grads: list of `parts` tensors [batch, heads, len, head_dim] -> (din [batch*len, parts*hidden], dbias or None)."""
+    parts = len(grads)
+    cols = parts * heads * head_dim
+    g0 = grads[0]
+    din = torch.empty((batch * length, cols), dtype=g0.dtype, device=g0.device) if din is None else din
+    if want_dbias and dbias is None:
+        dbias = torch.empty(cols, dtype=torch.float32, device=g0.device)
+    ws = _workspace(lsq_workspace_bytes(LSQ_OP_SPLIT_HEADS_BWD, batch * length, cols), g0, workspace)
+    ptrs = [_ptr(g) for g in grads] + [None] * (3 - parts)
+    _check(load().lsq_split_heads_bwd(_ptr(din), _ptr(dbias) if want_dbias else None, ptrs[0], ptrs[1], ptrs[2], batch,
+                                      length, heads, head_dim, parts, _ptr(ws), ws.numel() * ws.element_size(), _dt(g0),
+                                      _stream()), "lsq_split_heads_bwd")
+    return din, (dbias if want_dbias else None)
+
+
+def lsq_merge_heads_fwd(x, out=None):
+    """x: [batch, heads, len, head_dim] -> [batch*len, heads*head_dim]."""
+    B, N, Ln, D = x.shape
+    out = torch.empty((B * Ln, N * D), dtype=x.dtype, device=x.device) if out is None else out
+    _check(load().lsq_merge_heads_fwd(_ptr(out), _ptr(x), B, Ln, N, D, _dt(x), _stream()), "lsq_merge_heads_fwd")
+    return out
+
+
+def lsq_merge_heads_bwd(dy, batch: int, length: int, heads: int, head_dim: int, dx=None):
+    """dy: [batch*len, heads*head_dim] -> [batch, heads, len, head_dim]."""
+    dx = torch.empty((batch, heads, length, head_dim), dtype=dy.dtype, device=dy.device) if dx is None else dx
+    _check(load().lsq_merge_heads_bwd(_ptr(dx), _ptr(dy), batch, length, heads, head_dim, _dt(dy), _stream()),
+           "lsq_merge_heads_bwd")
+    return dx

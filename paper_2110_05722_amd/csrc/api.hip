@@ -11,6 +11,7 @@ extern "C" size_t lsq_workspace_bytes(int32_t op, int64_t rows, int32_t cols)
             return static_cast<size_t>(ln_bwd_blocks(rows, cols)) * 2u * static_cast<size_t>(cols) * sizeof(float);
         case LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD:
         case LSQ_OP_BIAS_ACT_DROPOUT_BWD:
+        case LSQ_OP_SPLIT_HEADS_BWD:
             // one [cols] fp32 partial row (dbias) per row block
             return static_cast<size_t>(bdr_bwd_row_blocks(rows, cols)) * static_cast<size_t>(cols) * sizeof(float);
         default:
