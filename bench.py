@@ -224,6 +224,27 @@ def main():
         a = heads_buf[i % head_sets]
         L.lsq_merge_heads_fwd(a["q"][0], out=a["merged"])
 
+    zipf = np.minimum((rng.pareto(1.1, size=(B, Lq)) * 3).astype(np.int64) + 2, V - 1).astype(np.int32)
+    if key_len is not None:
+        zipf[np.arange(Lq)[None, :] >= key_len.cpu().numpy()[:, None]] = 1
+    emb_tokens = torch.from_numpy(zipf).to(dev)
+    n_unique = int(np.unique(zipf[zipf != 1]).size)
+    emb_tab = demb_tab = None
+    if not args.ops or any("embedding" in o for o in args.ops.split(",")):
+        emb_tab = device_normal((V, H), 1.0, dt, seed + 800, dev)
+        demb_tab = torch.zeros((V, H), dtype=tdt, device=dev)
+    pos_tab = device_normal((Lq, H), 0.5, dt, seed + 801, dev)
+    dpos_tab = torch.zeros((Lq, H), dtype=tdt, device=dev)
+    ews = torch.empty(max(L.lsq_workspace_bytes(4, T, H), 16), dtype=torch.uint8, device=dev)
+
+    def op_emb_fwd(i):
+        a = layer[i % sets]
+        L.lsq_embedding_fwd(emb_tokens, emb_tab, pos_tab, 1, float(np.sqrt(H)), pr, ps, 3000 + i, out=a["out"])
+
+    def op_emb_bwd(i):
+        a = layer[i % sets]
+        L.lsq_embedding_bwd(demb_tab, dpos_tab, a["dy"], emb_tokens, 1, float(np.sqrt(H)), pr, ps, 3000 + i, workspace=ews)
+
     def op_adam_lp(i):
         state["step"] += 1
         L.lsq_adam_step_lp(p_lp, m, v, g, step=state["step"], **ADAM_HYPER)
@@ -244,6 +265,7 @@ def main():
         "adam_step": 28 * n,
         "bias_act_dropout_fwd": 4 * EF + 2 * F, "bias_act_dropout_bwd": 6 * EF + 6 * F,
         "adam_step_lp": 22 * n, "sgd_step": 20 * n,
+        "embedding_fwd": 4 * E + 4 * T, "embedding_bwd": 2 * E + 4 * n_unique * H + 4 * Lq * H + 4 * T,
         "split_heads_fwd": 12 * E + 6 * H, "split_heads_bwd": 12 * E + 12 * H, "merge_heads_fwd": 4 * E,
     }
     ops = [
@@ -253,6 +275,7 @@ def main():
     ]
 
     extra = [("bias_act_dropout_fwd", op_bad_fwd), ("bias_act_dropout_bwd", op_bad_bwd),
+             ("embedding_fwd", op_emb_fwd), ("embedding_bwd", op_emb_bwd),
              ("split_heads_fwd", op_split_fwd), ("split_heads_bwd", op_split_bwd), ("merge_heads_fwd", op_merge_fwd),
              ("adam_step_lp", op_adam_lp), ("sgd_step", op_sgd)]
     if args.ops:
@@ -361,7 +384,8 @@ def main():
         "ops": table, "ops_timing": timing,
         "ops_next": dict(next_table, note=f"rows beyond the nine: FFN bias+{act}+dropout(p={pa}) on [{T}, {F}], the paper's "
                                           "low-precision-parameter Adam (22 B/param), SGD with momentum (20 B/param), "
-                                          f"QKV bias + head split on [{T}, {3 * H}] and its backward, head merge"),
+                                          f"QKV bias + head split on [{T}, {3 * H}] and its backward, head merge, embedding of {T} Zipf-"
+                                          f"distributed tokens ({n_unique} distinct ids) into [{T}, {H}] and its backward"),
         "layer_us": {"encoder_layer_fwd_bwd_nongemm": round(enc, 1), "decoder_layer_fwd_bwd_nongemm": round(dec, 1)},
     }
     if not args.no_cpu_baseline:

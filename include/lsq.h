@@ -63,7 +63,8 @@ typedef enum {
     LSQ_OP_LAYERNORM_BWD = 0,
     LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD = 1,
     LSQ_OP_BIAS_ACT_DROPOUT_BWD = 2,
-    LSQ_OP_SPLIT_HEADS_BWD = 3          /* cols = parts * heads * head_dim */
+    LSQ_OP_SPLIT_HEADS_BWD = 3,         /* cols = parts * heads * head_dim */
+    LSQ_OP_EMBEDDING_BWD = 4            /* rows = batch * len tokens */
 } lsq_op;
 
 /* Activations of the feed-forward block. */
@@ -263,6 +264,30 @@ lsq_status lsq_merge_heads_fwd(void* out, const void* x, int32_t batch, int32_t 
                                int32_t head_dim, lsq_dtype dt, void* stream);
 lsq_status lsq_merge_heads_bwd(void* dx, const void* dy, int32_t batch, int32_t len, int32_t heads,
                                int32_t head_dim, lsq_dtype dt, void* stream);
+
+/* Embedding forward (Sec. IV-A, embedding layer):
+ *   out[t,:] = keep[t,:] * (scale * emb[tokens[t],:] + pos[t mod len,:]) / (1 - p)
+ * tokens: int32[batch*len];  emb: [vocab, hidden] dt;  pos: [>= len, hidden] dt;
+ * out: [batch*len, hidden] dt.  A token equal to pad_idx or outside [0, vocab)
+ * gives a zero row.  Dropout contract as everywhere, flat index over out. */
+lsq_status lsq_embedding_fwd(void* out, const int32_t* tokens, const void* emb, const void* pos,
+                             int32_t batch, int32_t len, int32_t hidden, int32_t vocab, int32_t pad_idx,
+                             float scale, float p, uint64_t seed, uint64_t offset,
+                             lsq_dtype dt, void* stream);
+
+/* Embedding backward (Sec. IV-A): the gradient rows of a repeated token are summed
+ * (the paper uses atomicAdd; here the order is fixed, ascending position, so the
+ * result is bit-reproducible):
+ *   demb[w,:] += scale * sum_{t: tokens[t] == w} keep[t,:] * dy[t,:] / (1-p)
+ *   dpos[l,:] += sum_b keep * dy[b*len + l,:] / (1-p)            (dpos nullable)
+ * demb [vocab, hidden] and dpos [len, hidden] are dt and are ACCUMULATED INTO (one
+ * rounding per row and call; rows of tokens that do not occur are not touched).
+ * Padding tokens receive nothing.  workspace: >= lsq_workspace_bytes(
+ * LSQ_OP_EMBEDDING_BWD, batch*len, hidden) bytes. */
+lsq_status lsq_embedding_bwd(void* demb, void* dpos, const void* dy, const int32_t* tokens,
+                             int32_t batch, int32_t len, int32_t hidden, int32_t vocab, int32_t pad_idx,
+                             float scale, float p, uint64_t seed, uint64_t offset,
+                             void* workspace, size_t workspace_bytes, lsq_dtype dt, void* stream);
 
 #ifdef __cplusplus
 }

@@ -284,3 +284,34 @@ def split_heads_bwd(grads, batch: int, length: int, heads: int, head_dim: int, d
     lib().lsqo_split_heads_bwd(_p(din), _p(dbias), ptrs[0], ptrs[1], ptrs[2], C.c_int32(batch), C.c_int32(length),
                                C.c_int32(heads), C.c_int32(head_dim), C.c_int32(parts), C.c_int(_DT[dt]))
     return din, dbias
+
+
+# ------------------------------------------------------------------ embedding
+def embedding_fwd(tokens, emb, pos, pad_idx: int, scale: float, p: float, seed: int, offset: int, dt: str, e0: int = 0):
+    """tokens: int32 [batch, len]; emb: [vocab, hidden]; pos: [>=len, hidden] -> out [batch*len, hidden]."""
+    tokens = _i32(tokens)
+    emb, pos = _stored(emb, dt), _stored(pos, dt)
+    B, Ln = tokens.shape
+    V, H = emb.shape
+    out = np.empty((B * Ln, H))
+    lib().lsqo_embedding_fwd(_p(out), _p(tokens), _p(emb), _p(pos), C.c_int32(B), C.c_int32(Ln), C.c_int32(H),
+                             C.c_int32(V), C.c_int32(pad_idx), C.c_double(float(np.float32(scale))),
+                             C.c_double(float(np.float32(p))), C.c_uint64(seed), C.c_uint64(offset), C.c_uint64(e0),
+                             C.c_int(_DT[dt]))
+    return out
+
+
+def embedding_bwd(dy, tokens, vocab: int, pad_idx: int, scale: float, p: float, seed: int, offset: int, dt: str,
+                  want_dpos: bool = True, e0: int = 0):
+    """-> (increment of dE [vocab, hidden], increment of dP [len, hidden] or None), float64."""
+    tokens = _i32(tokens)
+    dy = _stored(dy, dt)
+    B, Ln = tokens.shape
+    H = dy.shape[-1]
+    demb = np.empty((vocab, H))
+    dpos = np.empty((Ln, H)) if want_dpos else None
+    lib().lsqo_embedding_bwd(_p(demb), _p(dpos), _p(dy), _p(tokens), C.c_int32(B), C.c_int32(Ln), C.c_int32(H),
+                             C.c_int32(vocab), C.c_int32(pad_idx), C.c_double(float(np.float32(scale))),
+                             C.c_double(float(np.float32(p))), C.c_uint64(seed), C.c_uint64(offset), C.c_uint64(e0),
+                             C.c_int(_DT[dt]))
+    return demb, dpos

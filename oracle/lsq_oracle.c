@@ -603,3 +603,57 @@ void lsqo_split_heads_bwd(double* din, double* dbias, const void* d0, const void
                         if (dbias) dbias[col] += g;
                     }
 }
+
+/* ------------------------------------------------------------------ embedding */
+/* Sec. IV-A, embedding layer: y^(w,p) = Dropout(s * E_w + P_p) for the token w at
+ * position p of its sentence.  tokens: [batch, len]; a token equal to pad_idx or
+ * outside [0, vocab) produces a zero row (and receives no gradient). */
+static int is_pad(int32_t w, int32_t vocab, int32_t pad_idx) { return w == pad_idx || w < 0 || w >= vocab; }
+
+void lsqo_embedding_fwd(double* out, const int32_t* tokens, const void* emb, const void* pos, int32_t batch,
+                        int32_t len, int32_t hidden, int32_t vocab, int32_t pad_idx, double scale, double p,
+                        uint64_t seed, uint64_t offset, uint64_t e0, int dt)
+{
+    const uint32_t t16 = threshold16(p);
+    const double dscale = 1.0 / (1.0 - p);
+    const int64_t T = (int64_t)batch * len;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        const int32_t w = tokens[t];
+        const int l = (int)(t % len);
+        for (int i = 0; i < hidden; ++i) {
+            const int64_t e = t * hidden + i;
+            double v = 0.0;
+            if (!is_pad(w, vocab, pad_idx)) {
+                v = scale * load(emb, (int64_t)w * hidden + i, dt) + load(pos, (int64_t)l * hidden + i, dt);
+                v = keep_element(e0 + (uint64_t)e, p, t16, seed, offset) ? v * dscale : 0.0;
+            }
+            out[e] = v;
+        }
+    }
+}
+
+/* Sec. IV-A: grad E_w = s * sum over the positions that hold token w of m (.) grad y, summed here in
+ * ascending position order; grad P_l = the same sum over the batch for position l.  demb [vocab, hidden]
+ * and dpos [len, hidden] receive the INCREMENTS (they are zeroed first); dpos may be NULL. */
+void lsqo_embedding_bwd(double* demb, double* dpos, const void* dy, const int32_t* tokens, int32_t batch,
+                        int32_t len, int32_t hidden, int32_t vocab, int32_t pad_idx, double scale, double p,
+                        uint64_t seed, uint64_t offset, uint64_t e0, int dt)
+{
+    const uint32_t t16 = threshold16(p);
+    const double dscale = 1.0 / (1.0 - p);
+    const int64_t T = (int64_t)batch * len;
+    for (int64_t i = 0; i < (int64_t)vocab * hidden; ++i) demb[i] = 0.0;
+    if (dpos) for (int64_t i = 0; i < (int64_t)len * hidden; ++i) dpos[i] = 0.0;
+    for (int64_t t = 0; t < T; ++t) {
+        const int32_t w = tokens[t];
+        if (is_pad(w, vocab, pad_idx)) continue;
+        const int l = (int)(t % len);
+        for (int i = 0; i < hidden; ++i) {
+            const int64_t e = t * hidden + i;
+            double g = keep_element(e0 + (uint64_t)e, p, t16, seed, offset) ? load(dy, e, dt) * dscale : 0.0;
+            demb[(int64_t)w * hidden + i] += scale * g;
+            if (dpos) dpos[(int64_t)l * hidden + i] += g;
+        }
+    }
+}

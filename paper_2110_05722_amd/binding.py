@@ -19,6 +19,7 @@ _lib = None
 LSQ_F16, LSQ_BF16, LSQ_F32 = 0, 1, 2
 LSQ_OP_LAYERNORM_BWD, LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD, LSQ_OP_BIAS_ACT_DROPOUT_BWD = 0, 1, 2
 LSQ_OP_SPLIT_HEADS_BWD = 3
+LSQ_OP_EMBEDDING_BWD = 4
 LSQ_ACT = {"relu": 0, "gelu": 1, "gelu_tanh": 2}
 _DT = {torch.float16: LSQ_F16, torch.bfloat16: LSQ_BF16, torch.float32: LSQ_F32}
 
@@ -28,6 +29,7 @@ EXPORTS = [
     "lsq_ls_xent_fwd", "lsq_ls_xent_bwd", "lsq_adam_step",
     "lsq_bias_act_dropout_fwd", "lsq_bias_act_dropout_bwd", "lsq_adam_step_lp", "lsq_sgd_step",
     "lsq_split_heads_fwd", "lsq_split_heads_bwd", "lsq_merge_heads_fwd", "lsq_merge_heads_bwd",
+    "lsq_embedding_fwd", "lsq_embedding_bwd",
 ]
 
 
@@ -70,6 +72,8 @@ def load():
         "lsq_split_heads_bwd": (C.c_int, [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, sz, C.c_int, vp]),
         "lsq_merge_heads_fwd": (C.c_int, [vp, vp, i32, i32, i32, i32, C.c_int, vp]),
         "lsq_merge_heads_bwd": (C.c_int, [vp, vp, i32, i32, i32, i32, C.c_int, vp]),
+        "lsq_embedding_fwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64, C.c_int, vp]),
+        "lsq_embedding_bwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64, vp, sz, C.c_int, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -318,3 +322,29 @@ def lsq_merge_heads_bwd(dy, batch: int, length: int, heads: int, head_dim: int, 
     _check(load().lsq_merge_heads_bwd(_ptr(dx), _ptr(dy), batch, length, heads, head_dim, _dt(dy), _stream()),
            "lsq_merge_heads_bwd")
     return dx
+
+
+def lsq_embedding_fwd(tokens, emb, pos, pad_idx: int, scale: float, p: float, seed: int, offset: int, out=None):
+    """tokens: int32 [batch, len]; emb: [vocab, hidden]; pos: [>= len, hidden] -> out [batch*len, hidden]."""
+    if tokens.dtype != torch.int32:
+        raise LsqError("tokens must be int32")
+    B, Ln = tokens.shape
+    V, H = emb.shape
+    out = torch.empty((B * Ln, H), dtype=emb.dtype, device=emb.device) if out is None else out
+    _check(load().lsq_embedding_fwd(_ptr(out), _ptr(tokens), _ptr(emb), _ptr(pos), B, Ln, H, V, pad_idx, scale, p, seed,
+                                    offset, _dt(emb), _stream()), "lsq_embedding_fwd")
+    return out
+
+
+def lsq_embedding_bwd(demb, dpos, dy, tokens, pad_idx: int, scale: float, p: float, seed: int, offset: int,
+                      workspace=None):
+    """Accumulates into demb [vocab, hidden] and (if not None) dpos [len, hidden]."""
+    if tokens.dtype != torch.int32:
+        raise LsqError("tokens must be int32")
+    B, Ln = tokens.shape
+    V, H = demb.shape
+    ws = _workspace(lsq_workspace_bytes(LSQ_OP_EMBEDDING_BWD, B * Ln, H), dy, workspace)
+    _check(load().lsq_embedding_bwd(_ptr(demb), _ptr(dpos), _ptr(dy), _ptr(tokens), B, Ln, H, V, pad_idx, scale, p, seed,
+                                    offset, _ptr(ws), ws.numel() * ws.element_size(), _dt(demb), _stream()),
+           "lsq_embedding_bwd")
+    return demb, dpos

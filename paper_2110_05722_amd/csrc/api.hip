@@ -14,6 +14,11 @@ extern "C" size_t lsq_workspace_bytes(int32_t op, int64_t rows, int32_t cols)
         case LSQ_OP_SPLIT_HEADS_BWD:
             // one [cols] fp32 partial row (dbias) per row block
             return static_cast<size_t>(bdr_bwd_row_blocks(rows, cols)) * static_cast<size_t>(cols) * sizeof(float);
+        case LSQ_OP_EMBEDDING_BWD: {
+            // per-tile rank counts [tiles][rows] + the sorted order and its keys, all int32
+            const size_t tiles = static_cast<size_t>(ceil_div(rows, 256));
+            return (tiles + 2u) * static_cast<size_t>(rows) * sizeof(int32_t);
+        }
         default:
             return 0;
     }
