@@ -224,7 +224,9 @@ def main():
         a = heads_buf[i % head_sets]
         L.lsq_merge_heads_fwd(a["q"][0], out=a["merged"])
 
-    zipf = np.minimum((rng.pareto(1.1, size=(B, Lq)) * 3).astype(np.int64) + 2, V - 1).astype(np.int32)
+    # token ids with a 1/rank frequency law over the vocabulary (the most frequent id takes ~9 % of the positions)
+    w_ = 1.0 / np.arange(1, V - 1, dtype=np.float64)
+    zipf = (rng.choice(V - 2, size=(B, Lq), p=w_ / w_.sum()) + 2).astype(np.int32)
     if key_len is not None:
         zipf[np.arange(Lq)[None, :] >= key_len.cpu().numpy()[:, None]] = 1
     emb_tokens = torch.from_numpy(zipf).to(dev)

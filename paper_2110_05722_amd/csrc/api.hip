@@ -15,9 +15,12 @@ extern "C" size_t lsq_workspace_bytes(int32_t op, int64_t rows, int32_t cols)
             // one [cols] fp32 partial row (dbias) per row block
             return static_cast<size_t>(bdr_bwd_row_blocks(rows, cols)) * static_cast<size_t>(cols) * sizeof(float);
         case LSQ_OP_EMBEDDING_BWD: {
-            // per-tile rank counts [tiles][rows] + the sorted order and its keys, all int32
+            // sorted order (int4 per token) + fp32 chunk rows [2*ceil(rows/32)][cols] + rank counts [3][tiles][rows]
+            const size_t r = static_cast<size_t>(rows);
             const size_t tiles = static_cast<size_t>(ceil_div(rows, 256));
-            return (tiles + 2u) * static_cast<size_t>(rows) * sizeof(int32_t);
+            const size_t colsp = (static_cast<size_t>(cols) + 7u) / 8u * 8u;
+            return r * 16u + 2u * static_cast<size_t>(ceil_div(rows, 32)) * colsp * sizeof(float)
+                   + 3u * tiles * r * sizeof(int32_t);
         }
         default:
             return 0;

@@ -7,11 +7,13 @@
 // instead, with no atomics at all:
 //   1. rank: every token's position in the order sorted by (token id, position) is
 //      COUNTED — tile against tile, 256 x 256 comparisons per workgroup out of LDS —
-//      rather than sorted: counting is order-free, so the result is deterministic;
-//   2. scatter: sorted[rank[t]] = t, sorted_id[rank[t]] = w_t;
-//   3. accumulate: the workgroup of the first entry of each id segment walks the segment
-//      (64 entries per read, in ascending position), sums m (.) dy rows in fp32 and adds
-//      the total to dE[w,:] once (one rounding per call).
+//      rather than sorted: counting is order-free, so the result is deterministic; the
+//      same counts give the start and the length of each id segment;
+//   2. scatter: order[rank[t]] = (t, id, segment start, segment length);
+//   3. accumulate: a segment is cut into chunks of 32 rows; one workgroup per chunk sums
+//      m (.) dy rows in ascending position in fp32 (eight rows in flight).  A segment of one
+//      chunk is added to dE[w,:] at once; a longer one (a frequent token) leaves fp32 chunk
+//      rows that a last kernel adds in chunk order: one rounding of dE per call either way.
 // Tokens equal to pad_idx (or outside the vocabulary) produce zero rows and no gradient.
 #include <limits.h>
 
@@ -63,9 +65,12 @@ __global__ __launch_bounds__(256) void emb_fwd_cols(T* __restrict__ out, const i
 // sort key of a token: its id, with padding last
 __device__ __forceinline__ int emb_key(int w, int vocab, int pad_idx) { return emb_is_pad(w, vocab, pad_idx) ? INT_MAX : w; }
 
-// partial[jt][i] = number of tokens j in tile jt with (key_j, j) < (key_i, i)
+// Three counts per (token i, tile jt), tile against tile out of LDS:
+//   less[jt][i]   tokens j of the tile with key_j <  key_i          -> start of i's id segment
+//   before[jt][i] tokens j of the tile with key_j == key_i, j < i   -> i's place inside the segment
+//   equal[jt][i]  tokens j of the tile with key_j == key_i          -> length of the segment
 __global__ __launch_bounds__(kTile) void emb_rank_partial(int32_t* __restrict__ partial, const int32_t* __restrict__ tokens,
-                                                          int64_t rows, int vocab, int pad_idx)
+                                                          int64_t rows, int ntiles, int vocab, int pad_idx)
 {
     __shared__ int keys[kTile];
     const int64_t i = static_cast<int64_t>(blockIdx.x) * kTile + threadIdx.x;
@@ -76,59 +81,97 @@ __global__ __launch_bounds__(kTile) void emb_rank_partial(int32_t* __restrict__ 
     if (i >= rows) return;
     const int ki = emb_key(tokens[i], vocab, pad_idx);
     const int nj = static_cast<int>(min(static_cast<int64_t>(kTile), rows - j0));
-    int count = 0;
+    int less = 0, before = 0, equal = 0;
     for (int jj = 0; jj < nj; ++jj) {
         const int kj = keys[jj];                       // LDS broadcast
-        count += (kj < ki || (kj == ki && j0 + jj < i)) ? 1 : 0;
+        less += kj < ki ? 1 : 0;
+        equal += kj == ki ? 1 : 0;
+        before += (kj == ki && j0 + jj < i) ? 1 : 0;
     }
-    partial[static_cast<int64_t>(blockIdx.y) * rows + i] = count;
+    const int64_t plane = static_cast<int64_t>(ntiles) * rows;
+    const int64_t o = static_cast<int64_t>(blockIdx.y) * rows + i;
+    partial[o] = less;
+    partial[plane + o] = before;
+    partial[2 * plane + o] = equal;
 }
 
-__global__ __launch_bounds__(256) void emb_scatter(int32_t* __restrict__ sorted, int32_t* __restrict__ sorted_key,
-                                                   const int32_t* __restrict__ partial, const int32_t* __restrict__ tokens,
-                                                   int64_t rows, int ntiles, int vocab, int pad_idx)
+// order[q] = { token position, key, segment start, segment length } for sorted position q
+__global__ __launch_bounds__(256) void emb_scatter(int4* __restrict__ order, const int32_t* __restrict__ partial,
+                                                   const int32_t* __restrict__ tokens, int64_t rows, int ntiles,
+                                                   int vocab, int pad_idx)
 {
     const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     if (t >= rows) return;
-    int rank = 0;
-    for (int jt = 0; jt < ntiles; ++jt) rank += partial[static_cast<int64_t>(jt) * rows + t];
-    sorted[rank] = static_cast<int32_t>(t);
-    sorted_key[rank] = emb_key(tokens[t], vocab, pad_idx);
+    const int64_t plane = static_cast<int64_t>(ntiles) * rows;
+    int less = 0, before = 0, equal = 0;
+    int jt = 0;
+    for (; jt + 4 <= ntiles; jt += 4) {               // twelve loads in flight per trip (integer sums: any order)
+        int a[4], b[4], c[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int64_t o = static_cast<int64_t>(jt + k) * rows + t;
+            a[k] = partial[o]; b[k] = partial[plane + o]; c[k] = partial[2 * plane + o];
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { less += a[k]; before += b[k]; equal += c[k]; }
+    }
+    for (; jt < ntiles; ++jt) {
+        const int64_t o = static_cast<int64_t>(jt) * rows + t;
+        less += partial[o];
+        before += partial[plane + o];
+        equal += partial[2 * plane + o];
+    }
+    order[less + before] = make_int4(static_cast<int>(t), emb_key(tokens[t], vocab, pad_idx), less, equal);
 }
 
-// one workgroup per sorted entry; only the first entry of an id segment works
+constexpr int kEmbChunk = 32;    // rows of one id summed by one workgroup
+
+// slot of the partial row written by the chunk that starts at sorted position q (segment start s):
+// a window of kEmbChunk sorted positions holds at most one chunk head that is not a segment start
+// and at most one start of a segment longer than a chunk
+__device__ __forceinline__ int64_t emb_slot(int64_t q, int64_t s) { return 2 * (q / kEmbChunk) + (q == s ? 1 : 0); }
+
+// One workgroup per sorted entry; only chunk heads work.  A chunk sums up to kEmbChunk rows of one id
+// in ascending position.  Segments of one chunk are added to dE at once; longer ones leave fp32
+// partial rows that emb_combine sums in chunk order.
 template <typename T, bool DROP>
-__global__ __launch_bounds__(256) void emb_accumulate(T* __restrict__ demb, const T* __restrict__ dy,
-                                                      const int32_t* __restrict__ sorted,
-                                                      const int32_t* __restrict__ sorted_key, int64_t rows, int ppr,
-                                                      float scale, DropoutParams d)
+__global__ __launch_bounds__(256) void emb_accumulate(T* __restrict__ demb, float* __restrict__ chunk_rows,
+                                                      const T* __restrict__ dy, const int4* __restrict__ order,
+                                                      int ppr, float scale, DropoutParams d)
 {
     const int64_t q = blockIdx.x;
-    const int key = sorted_key[q];
+    const int4 me = order[q];                                    // uniform
+    const int key = me.y;
+    const int64_t s = me.z;
+    const int len = me.w;
     if (key == INT_MAX) return;                                  // padding
-    if (q > 0 && sorted_key[q - 1] == key) return;               // not the head of its segment
+    if ((q - s) % kEmbChunk != 0) return;                        // not a chunk head
+    const int cnt = static_cast<int>(min(static_cast<int64_t>(kEmbChunk), s + len - q));
     const int lane = threadIdx.x & 63;
-    // the trip count is uniform over the wave: the ballot below needs all 64 lanes
-    for (int cp0 = (threadIdx.x & ~63); cp0 < ppr; cp0 += 256) {
-        const int cp = cp0 + lane;
-        const bool active = cp < ppr;
+    const int tt = lane < cnt ? order[q + lane].x : 0;           // the chunk's token positions, one per lane
+    for (int cp = threadIdx.x; cp < ppr; cp += 256) {
         float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        for (int64_t c = q; c < rows; c += 64) {
-            // 64 entries of the sorted order per read; the segment ends at the first other key
-            const int64_t qq = c + lane;
-            const int k = qq < rows ? sorted_key[qq] : INT_MAX;
-            const int tt = qq < rows ? sorted[qq] : 0;
-            const unsigned long long same = __ballot(k == key);
-            const int run = same == ~0ull ? 64 : __builtin_ctzll(~same);   // leading entries of this id
-            if (active) {
-                for (int u = 0; u < run; ++u) {
-                    const int64_t t = __builtin_amdgcn_readlane(tt, u);
-                    const int64_t pack = t * ppr + cp;
+        for (int u0 = 0; u0 < cnt; u0 += 8) {
+            // eight rows in flight, then added in order
+            RawPack<T> raw[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                if (u0 + k < cnt) {
+                    const int64_t t = __builtin_amdgcn_readlane(tt, u0 + k);
+                    raw[k] = load_raw<T, kNT>(dy + (t * ppr + cp) * kPack);
+                } else {
+                    raw[k] = zero_raw<T>();
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                if (u0 + k < cnt) {
                     float g[8];
-                    load8<T, kNT>(dy + pack * kPack, g);
+                    unpack<T>(raw[k], g);
                     if constexpr (DROP) {
+                        const int64_t t = __builtin_amdgcn_readlane(tt, u0 + k);
                         float kf[8];
-                        dropout_factors8(d, static_cast<uint64_t>(pack), kf);
+                        dropout_factors8(d, static_cast<uint64_t>(t * ppr + cp), kf);
 #pragma unroll
                         for (int j = 0; j < 8; ++j) acc[j] = fmaf(g[j], kf[j], acc[j]);
                     } else {
@@ -137,16 +180,43 @@ __global__ __launch_bounds__(256) void emb_accumulate(T* __restrict__ demb, cons
                     }
                 }
             }
-            if (run < 64) break;
         }
-        if (active) {
+        if (len <= kEmbChunk) {
             T* dst = demb + (static_cast<int64_t>(key) * ppr + cp) * kPack;
             float o[8];
             load8<T>(dst, o);
 #pragma unroll
             for (int j = 0; j < 8; ++j) o[j] = fmaf(scale, acc[j], o[j]);
             store8<T>(dst, o);
+        } else {
+            store8<float>(chunk_rows + (emb_slot(q, s) * ppr + cp) * kPack, acc);
         }
+    }
+}
+
+// segments longer than a chunk: the workgroup of the segment start adds the chunk rows in chunk order
+template <typename T>
+__global__ __launch_bounds__(256) void emb_combine(T* __restrict__ demb, const float* __restrict__ chunk_rows,
+                                                   const int4* __restrict__ order, int ppr, float scale)
+{
+    const int64_t q = blockIdx.x;
+    const int4 me = order[q];
+    if (me.y == INT_MAX || me.z != q || me.w <= kEmbChunk) return;
+    const int nchunks = (me.w + kEmbChunk - 1) / kEmbChunk;
+    for (int cp = threadIdx.x; cp < ppr; cp += 256) {
+        float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int c = 0; c < nchunks; ++c) {
+            float r[8];
+            load8<float>(chunk_rows + (emb_slot(q + static_cast<int64_t>(c) * kEmbChunk, q) * ppr + cp) * kPack, r);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] += r[j];
+        }
+        T* dst = demb + (static_cast<int64_t>(me.y) * ppr + cp) * kPack;
+        float o[8];
+        load8<T>(dst, o);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] = fmaf(scale, acc[j], o[j]);
+        store8<T>(dst, o);
     }
 }
 
@@ -207,23 +277,21 @@ __global__ __launch_bounds__(256) void emb_fwd_flat(T* __restrict__ out, const i
 // one thread per (id segment head, column): walks the segment sequentially
 template <typename T>
 __global__ __launch_bounds__(256) void emb_accumulate_flat(T* __restrict__ demb, const T* __restrict__ dy,
-                                                           const int32_t* __restrict__ sorted,
-                                                           const int32_t* __restrict__ sorted_key, int64_t rows,
-                                                           int hidden, float scale, DropoutParams d)
+                                                           const int4* __restrict__ order, int hidden, float scale,
+                                                           DropoutParams d)
 {
     const int64_t q = blockIdx.x;
-    const int key = sorted_key[q];
-    if (key == INT_MAX) return;
-    if (q > 0 && sorted_key[q - 1] == key) return;
+    const int4 me = order[q];
+    if (me.y == INT_MAX || me.z != q) return;
     for (int i = threadIdx.x; i < hidden; i += 256) {
         float acc = 0.0f;
-        for (int64_t c = q; c < rows && sorted_key[c] == key; ++c) {
-            const int64_t e = static_cast<int64_t>(sorted[c]) * hidden + i;
+        for (int c = 0; c < me.w; ++c) {
+            const int64_t e = static_cast<int64_t>(order[q + c].x) * hidden + i;
             float g = to_f32<T>(dy[e]);
             if (d.t16) g *= dropout_factor1(d, static_cast<uint64_t>(e));
             acc += g;
         }
-        T* dst = demb + static_cast<int64_t>(key) * hidden + i;
+        T* dst = demb + static_cast<int64_t>(me.y) * hidden + i;
         *dst = from_f32<T>(fmaf(scale, acc, to_f32<T>(*dst)));
     }
 }
@@ -272,33 +340,35 @@ static lsq_status emb_fwd_dispatch(void* out, const int32_t* tokens, const void*
 }
 
 template <typename T>
-static lsq_status emb_bwd_dispatch(void* demb, void* dpos, const void* dy, const int32_t* tokens, int32_t* ws,
+static lsq_status emb_bwd_dispatch(void* demb, void* dpos, const void* dy, const int32_t* tokens, void* ws,
                                    int batch, int len, int hidden, int vocab, int pad_idx, float scale,
                                    const DropoutParams& d, hipStream_t s)
 {
     const int64_t rows = static_cast<int64_t>(batch) * len;
     const int ntiles = static_cast<int>(ceil_div(rows, kTile));
-    int32_t* partial = ws;
-    int32_t* sorted = ws + static_cast<int64_t>(ntiles) * rows;
-    int32_t* sorted_key = sorted + rows;
+    // workspace: order[rows] (int4) | chunk rows [2*ceil(rows/chunk)][hidden] fp32 | rank counts [3][ntiles][rows] int32
+    int4* order = reinterpret_cast<int4*>(ws);
+    float* chunk_rows = reinterpret_cast<float*>(order + rows);
+    int32_t* partial = reinterpret_cast<int32_t*>(chunk_rows + 2 * ceil_div(rows, kEmbChunk) * ((hidden + 7) / 8 * 8));
     T* de = static_cast<T*>(demb);
     T* dp = static_cast<T*>(dpos);
     const T* g = static_cast<const T*>(dy);
     // the dropout scale 1/(1-p) is carried by the per-element factors; `scale` is the embedding scale
-    hipLaunchKernelGGL(emb_rank_partial, dim3(ntiles, ntiles), dim3(kTile), 0, s, partial, tokens, rows, vocab, pad_idx);
-    hipLaunchKernelGGL(emb_scatter, dim3(static_cast<unsigned>(ceil_div(rows, 256))), dim3(256), 0, s, sorted, sorted_key,
-                       partial, tokens, rows, ntiles, vocab, pad_idx);
+    hipLaunchKernelGGL(emb_rank_partial, dim3(ntiles, ntiles), dim3(kTile), 0, s, partial, tokens, rows, ntiles, vocab, pad_idx);
+    hipLaunchKernelGGL(emb_scatter, dim3(static_cast<unsigned>(ceil_div(rows, 256))), dim3(256), 0, s, order, partial,
+                       tokens, rows, ntiles, vocab, pad_idx);
+    const dim3 grid(static_cast<unsigned>(rows)), block(256);
     if (hidden % kPack == 0) {
         const int ppr = hidden / kPack;
-        if (d.t16) hipLaunchKernelGGL((emb_accumulate<T, true>), dim3(static_cast<unsigned>(rows)), dim3(256), 0, s, de, g, sorted, sorted_key, rows, ppr, scale, d);
-        else hipLaunchKernelGGL((emb_accumulate<T, false>), dim3(static_cast<unsigned>(rows)), dim3(256), 0, s, de, g, sorted, sorted_key, rows, ppr, scale, d);
+        if (d.t16) hipLaunchKernelGGL((emb_accumulate<T, true>), grid, block, 0, s, de, chunk_rows, g, order, ppr, scale, d);
+        else hipLaunchKernelGGL((emb_accumulate<T, false>), grid, block, 0, s, de, chunk_rows, g, order, ppr, scale, d);
+        hipLaunchKernelGGL((emb_combine<T>), grid, block, 0, s, de, chunk_rows, order, ppr, scale);
         if (dp) {
             if (d.t16) hipLaunchKernelGGL((emb_dpos<T, true>), dim3(len), dim3(256), 0, s, dp, g, tokens, batch, len, ppr, vocab, pad_idx, d);
             else hipLaunchKernelGGL((emb_dpos<T, false>), dim3(len), dim3(256), 0, s, dp, g, tokens, batch, len, ppr, vocab, pad_idx, d);
         }
     } else {
-        hipLaunchKernelGGL((emb_accumulate_flat<T>), dim3(static_cast<unsigned>(rows)), dim3(256), 0, s, de, g, sorted,
-                           sorted_key, rows, hidden, scale, d);
+        hipLaunchKernelGGL((emb_accumulate_flat<T>), grid, block, 0, s, de, g, order, hidden, scale, d);
         if (dp)
             hipLaunchKernelGGL((emb_dpos_flat<T>), dim3(len), dim3(256), 0, s, dp, g, tokens, batch, len, hidden, vocab,
                                pad_idx, d);
@@ -348,7 +418,7 @@ extern "C" lsq_status lsq_embedding_bwd(void* demb, void* dpos, const void* dy, 
     const size_t need = lsq_workspace_bytes(LSQ_OP_EMBEDDING_BWD, rows, hidden);
     if (!workspace || workspace_bytes < need) return LSQ_WORKSPACE_TOO_SMALL;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    int32_t* ws = static_cast<int32_t*>(workspace);
+    void* ws = workspace;
     switch (dt) {
         case LSQ_F16: return emb_bwd_dispatch<f16>(demb, dpos, dy, tokens, ws, batch, len, hidden, vocab, pad_idx, scale, d, s);
         case LSQ_BF16: return emb_bwd_dispatch<bf16>(demb, dpos, dy, tokens, ws, batch, len, hidden, vocab, pad_idx, scale, d, s);
