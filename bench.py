@@ -276,6 +276,7 @@ def main():
         ("softmax_bwd", op_sm_bwd), ("layernorm_bwd", op_ln_bwd), ("adam_step", op_adam),
     ]
 
+    all_nine = list(ops)
     extra = [("bias_act_dropout_fwd", op_bad_fwd), ("bias_act_dropout_bwd", op_bad_bwd),
              ("embedding_fwd", op_emb_fwd), ("embedding_bwd", op_emb_bwd),
              ("split_heads_fwd", op_split_fwd), ("split_heads_bwd", op_split_bwd), ("merge_heads_fwd", op_merge_fwd),
@@ -352,7 +353,7 @@ def main():
         table[name] = {"us": round(us, 2), "GBps": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
                        "bytes": int(bts[name]), "launches": reps}
     next_table = {k: table.pop(k) for k, _ in extra if k in table}
-    for k in bts:
+    for k, _ in all_nine:
         table.setdefault(k, {"us": float("nan")})
     enc = 2 * table["layernorm_fwd"]["us"] + 2 * table["bias_dropout_residual_fwd"]["us"] + table["softmax_fwd"]["us"] \
         + 2 * table["layernorm_bwd"]["us"] + 2 * table["bias_dropout_residual_bwd"]["us"] + table["softmax_bwd"]["us"]
