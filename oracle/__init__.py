@@ -137,13 +137,14 @@ def bias_dropout_residual_bwd(dy, p: float, seed: int, offset: int, dt: str, e0:
 
 # ------------------------------------------------------------------ softmax
 def softmax_fwd(x, key_len, causal: bool, scale: float, dt: str, p: float = 0.0, seed: int = 0,
-                offset: int = 0, e0: int = 0):
+                offset: int = 0, e0: int = 0, query_len=None):
     x = _stored(x, dt)
     B, N, Lq, Lk = x.shape
     key_len = _i32(key_len)
+    query_len = _i32(query_len)
     y = np.empty(x.shape)
     yd = np.empty(x.shape) if p > 0 else None
-    lib().lsqo_softmax_fwd(_p(y), _p(yd), _p(x), _p(key_len), C.c_int32(B), C.c_int32(N), C.c_int32(Lq),
+    lib().lsqo_softmax_varlen_fwd(_p(y), _p(yd), _p(x), _p(key_len), _p(query_len), C.c_int32(B), C.c_int32(N), C.c_int32(Lq),
                            C.c_int32(Lk), C.c_int32(int(causal)), C.c_double(float(np.float32(scale))),
                            C.c_double(float(np.float32(p))), C.c_uint64(seed), C.c_uint64(offset),
                            C.c_uint64(e0), C.c_int(_DT[dt]))
@@ -151,12 +152,13 @@ def softmax_fwd(x, key_len, causal: bool, scale: float, dt: str, p: float = 0.0,
 
 
 def softmax_bwd(dy, y, key_len, causal: bool, scale: float, dt: str, p: float = 0.0, seed: int = 0,
-                offset: int = 0, e0: int = 0):
+                offset: int = 0, e0: int = 0, query_len=None):
     dy, y = _stored(dy, dt), _stored(y, dt)
     B, N, Lq, Lk = y.shape
     key_len = _i32(key_len)
+    query_len = _i32(query_len)
     dx = np.empty(y.shape)
-    lib().lsqo_softmax_bwd(_p(dx), _p(dy), _p(y), _p(key_len), C.c_int32(B), C.c_int32(N), C.c_int32(Lq),
+    lib().lsqo_softmax_varlen_bwd(_p(dx), _p(dy), _p(y), _p(key_len), _p(query_len), C.c_int32(B), C.c_int32(N), C.c_int32(Lq),
                            C.c_int32(Lk), C.c_int32(int(causal)), C.c_double(float(np.float32(scale))),
                            C.c_double(float(np.float32(p))), C.c_uint64(seed), C.c_uint64(offset),
                            C.c_uint64(e0), C.c_int(_DT[dt]))
@@ -315,3 +317,35 @@ def embedding_bwd(dy, tokens, vocab: int, pad_idx: int, scale: float, p: float, 
                              C.c_double(float(np.float32(p))), C.c_uint64(seed), C.c_uint64(offset), C.c_uint64(e0),
                              C.c_int(_DT[dt]))
     return demb, dpos
+
+
+# ------------------------------------------------------------ padding removal
+def pad_offsets(key_len, max_len: int) -> np.ndarray:
+    """int32[batch+1]: first packed row of every sentence, then the total."""
+    key_len = _i32(key_len)
+    off = np.empty(len(key_len) + 1, dtype=np.int32)
+    lib().lsqo_pad_offsets(_p(off), _p(key_len), C.c_int32(len(key_len)), C.c_int32(max_len))
+    return off
+
+
+def pad_remove(padded, key_len, dt: str) -> np.ndarray:
+    """padded [batch, max_len, hidden] -> packed [sum(len), hidden]."""
+    padded = _stored(padded, dt)
+    B, L, H = padded.shape
+    key_len = _i32(key_len)
+    total = int(pad_offsets(key_len, L)[-1])
+    packed = np.empty((total, H))
+    lib().lsqo_pad_remove(_p(packed), _p(padded), _p(key_len), C.c_int32(B), C.c_int32(L), C.c_int32(H),
+                          C.c_int(_DT[dt]))
+    return packed
+
+
+def pad_restore(packed, key_len, max_len: int, dt: str) -> np.ndarray:
+    """packed [sum(len), hidden] -> padded [batch, max_len, hidden], zeros on the padding."""
+    packed = _stored(packed, dt)
+    key_len = _i32(key_len)
+    H = packed.shape[1]
+    padded = np.empty((len(key_len), max_len, H))
+    lib().lsqo_pad_restore(_p(padded), _p(packed), _p(key_len), C.c_int32(len(key_len)), C.c_int32(max_len),
+                           C.c_int32(H), C.c_int(_DT[dt]))
+    return padded

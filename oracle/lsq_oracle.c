@@ -341,10 +341,12 @@ static int clamp_len(const int32_t* key_len, int b, int k_len)
 }
 
 /* Sec. IV-B Softmax, the three steps in order, over the allowed set only;
- * positions outside it are exactly 0.  y_drop may be NULL. */
-void lsqo_softmax_fwd(double* y, double* y_drop, const void* x, const int32_t* key_len,
-                      int32_t batch, int32_t heads, int32_t q_len, int32_t k_len, int32_t causal,
-                      double scale, double p, uint64_t seed, uint64_t offset, uint64_t e0, int dt)
+ * positions outside it are exactly 0.  y_drop may be NULL.  query_len (nullable):
+ * query rows at or beyond query_len[b] are padding, their allowed set is empty. */
+void lsqo_softmax_varlen_fwd(double* y, double* y_drop, const void* x, const int32_t* key_len,
+                             const int32_t* query_len, int32_t batch, int32_t heads, int32_t q_len,
+                             int32_t k_len, int32_t causal, double scale, double p, uint64_t seed,
+                             uint64_t offset, uint64_t e0, int dt)
 {
     const uint32_t t16 = threshold16(p);
     const double dscale = 1.0 / (1.0 - p);
@@ -354,6 +356,7 @@ void lsqo_softmax_fwd(double* y, double* y_drop, const void* x, const int32_t* k
         int b = (int)(row / ((int64_t)heads * q_len));
         int i = (int)(row % q_len);
         int kl = clamp_len(key_len, b, k_len);
+        if (query_len && i >= query_len[b]) kl = 0;
         const int64_t o = row * k_len;
         /* step 1: the maximum */
         int any = 0;
@@ -379,11 +382,20 @@ void lsqo_softmax_fwd(double* y, double* y_drop, const void* x, const int32_t* k
     }
 }
 
-/* Contraction of the softmax Jacobian (Sec. IV-A, criterion layer: dq_i/dh_j)
- * with the upstream gradient; y is the STORED forward output. */
-void lsqo_softmax_bwd(double* dx, const void* dy, const void* y, const int32_t* key_len,
+void lsqo_softmax_fwd(double* y, double* y_drop, const void* x, const int32_t* key_len,
                       int32_t batch, int32_t heads, int32_t q_len, int32_t k_len, int32_t causal,
                       double scale, double p, uint64_t seed, uint64_t offset, uint64_t e0, int dt)
+{
+    lsqo_softmax_varlen_fwd(y, y_drop, x, key_len, NULL, batch, heads, q_len, k_len, causal, scale, p, seed,
+                            offset, e0, dt);
+}
+
+/* Contraction of the softmax Jacobian (Sec. IV-A, criterion layer: dq_i/dh_j)
+ * with the upstream gradient; y is the STORED forward output. */
+void lsqo_softmax_varlen_bwd(double* dx, const void* dy, const void* y, const int32_t* key_len,
+                             const int32_t* query_len, int32_t batch, int32_t heads, int32_t q_len,
+                             int32_t k_len, int32_t causal, double scale, double p, uint64_t seed,
+                             uint64_t offset, uint64_t e0, int dt)
 {
     const uint32_t t16 = threshold16(p);
     const double dscale = 1.0 / (1.0 - p);
@@ -393,6 +405,7 @@ void lsqo_softmax_bwd(double* dx, const void* dy, const void* y, const int32_t* 
         int b = (int)(row / ((int64_t)heads * q_len));
         int i = (int)(row % q_len);
         int kl = clamp_len(key_len, b, k_len);
+        if (query_len && i >= query_len[b]) kl = 0;
         const int64_t o = row * k_len;
         double dot = 0.0;
         for (int j = 0; j < k_len; ++j)
@@ -411,6 +424,14 @@ void lsqo_softmax_bwd(double* dx, const void* dy, const void* y, const int32_t* 
             dx[o + j] = v;
         }
     }
+}
+
+void lsqo_softmax_bwd(double* dx, const void* dy, const void* y, const int32_t* key_len,
+                      int32_t batch, int32_t heads, int32_t q_len, int32_t k_len, int32_t causal,
+                      double scale, double p, uint64_t seed, uint64_t offset, uint64_t e0, int dt)
+{
+    lsqo_softmax_varlen_bwd(dx, dy, y, key_len, NULL, batch, heads, q_len, k_len, causal, scale, p, seed,
+                            offset, e0, dt);
 }
 
 /* ---------------------------------------------------------------- criterion */
@@ -654,6 +675,46 @@ void lsqo_embedding_bwd(double* demb, double* dpos, const void* dy, const int32_
             double g = keep_element(e0 + (uint64_t)e, p, t16, seed, offset) ? load(dy, e, dt) * dscale : 0.0;
             demb[(int64_t)w * hidden + i] += scale * g;
             if (dpos) dpos[(int64_t)l * hidden + i] += g;
+        }
+    }
+}
+
+/* ---------------------------------------------------------- padding removal */
+/* Padding removal (the paper's conclusion names it as the next optimisation): the
+ * len_b = clamp(key_len[b], 0, max_len) real rows of every sentence are stored
+ * back to back.  offsets[b] = first packed row of sentence b, offsets[batch] = total. */
+void lsqo_pad_offsets(int32_t* offsets, const int32_t* key_len, int32_t batch, int32_t max_len)
+{
+    int32_t run = 0;
+    for (int b = 0; b < batch; ++b) {
+        offsets[b] = run;
+        run += clamp_len(key_len, b, max_len);
+    }
+    offsets[batch] = run;
+}
+
+/* packed[offsets[b] + i, :] = padded[b, i, :] for i < len_b */
+void lsqo_pad_remove(double* packed, const void* padded, const int32_t* key_len, int32_t batch,
+                     int32_t max_len, int32_t hidden, int dt)
+{
+    int64_t r = 0;
+    for (int b = 0; b < batch; ++b)
+        for (int i = 0; i < clamp_len(key_len, b, max_len); ++i, ++r)
+            for (int c = 0; c < hidden; ++c)
+                packed[r * hidden + c] = load(padded, ((int64_t)b * max_len + i) * hidden + c, dt);
+}
+
+/* padded[b, i, :] = packed[offsets[b] + i, :] for i < len_b, 0 on the padding */
+void lsqo_pad_restore(double* padded, const void* packed, const int32_t* key_len, int32_t batch,
+                      int32_t max_len, int32_t hidden, int dt)
+{
+    int64_t r = 0;
+    for (int b = 0; b < batch; ++b) {
+        const int lb = clamp_len(key_len, b, max_len);
+        for (int i = 0; i < max_len; ++i) {
+            for (int c = 0; c < hidden; ++c)
+                padded[((int64_t)b * max_len + i) * hidden + c] = i < lb ? load(packed, r * hidden + c, dt) : 0.0;
+            if (i < lb) ++r;
         }
     }
 }
