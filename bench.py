@@ -247,6 +247,34 @@ def main():
         a = layer[i % sets]
         L.lsq_embedding_bwd(demb_tab, dpos_tab, a["dy"], emb_tokens, 1, float(np.sqrt(H)), pr, ps, 3000 + i, workspace=ews)
 
+    # padding removal: the layer tensors of the batch packed to sum(len) rows and back; the softmax with
+    # query lengths (self-attention: query_len == key_len); LayerNorm on the packed rows
+    lens_np = np.full(B, Lq, dtype=np.int64) if key_len is None else np.clip(key_len.cpu().numpy(), 0, Lq).astype(np.int64)
+    T_real = int(lens_np.sum())
+    pad_off = L.lsq_pad_offsets(key_len, B, Lq)
+    allowed_q = _allowed_elements(cfg, lens_np, lens_np)
+
+    def op_pad_remove(i):
+        a = layer[i % sets]
+        L.lsq_pad_remove(a["x"].view(B, Lq, H), pad_off, T, packed=a["out"])
+
+    def op_pad_restore(i):
+        a = layer[i % sets]
+        L.lsq_pad_restore(a["x"][:T_real], pad_off, B, Lq, padded=a["out"].view(B, Lq, H))
+
+    def op_ln_fwd_packed(i):
+        a = layer[i % sets]
+        L.lsq_layernorm_fwd(a["x"][:T_real], gamma, beta, 1e-5, y=a["y"][:T_real], mean=a["mean"][:T_real],
+                            rstd=a["rstd"][:T_real])
+
+    def op_smv_fwd(i):
+        a = soft[i % soft_sets]
+        L.lsq_softmax_varlen_fwd(a["x"], key_len, key_len, causal, scale, pa, ps, 1000 + i, y=a["y"], y_drop=a["yd"])
+
+    def op_smv_bwd(i):
+        a = soft[i % soft_sets]
+        L.lsq_softmax_varlen_bwd(a["dy"], a["y"], key_len, key_len, causal, scale, pa, ps, 1000 + i, dx=a["dx"])
+
     def op_adam_lp(i):
         state["step"] += 1
         L.lsq_adam_step_lp(p_lp, m, v, g, step=state["step"], **ADAM_HYPER)
@@ -269,6 +297,10 @@ def main():
         "adam_step_lp": 22 * n, "sgd_step": 20 * n,
         "embedding_fwd": 4 * E + 4 * T, "embedding_bwd": 2 * E + 4 * n_unique * H + 4 * Lq * H + 4 * T,
         "split_heads_fwd": 12 * E + 6 * H, "split_heads_bwd": 12 * E + 12 * H, "merge_heads_fwd": 4 * E,
+        "pad_remove": 4 * T_real * H + 4 * B, "pad_restore": 2 * T_real * H + 2 * E + 4 * B,
+        "layernorm_fwd_packed": 4 * T_real * H + 8 * T_real + 4 * H,
+        "softmax_varlen_fwd": 2 * allowed_q + 2 * Es + (2 * Es if pa > 0 else 0),
+        "softmax_varlen_bwd": 4 * allowed_q + 2 * Es,
     }
     ops = [
         ("layernorm_fwd", op_ln_fwd), ("softmax_fwd", op_sm_fwd), ("bias_dropout_residual_fwd", op_bdr_fwd),
@@ -280,6 +312,8 @@ def main():
     extra = [("bias_act_dropout_fwd", op_bad_fwd), ("bias_act_dropout_bwd", op_bad_bwd),
              ("embedding_fwd", op_emb_fwd), ("embedding_bwd", op_emb_bwd),
              ("split_heads_fwd", op_split_fwd), ("split_heads_bwd", op_split_bwd), ("merge_heads_fwd", op_merge_fwd),
+             ("pad_remove", op_pad_remove), ("pad_restore", op_pad_restore), ("layernorm_fwd_packed", op_ln_fwd_packed),
+             ("softmax_varlen_fwd", op_smv_fwd), ("softmax_varlen_bwd", op_smv_bwd),
              ("adam_step_lp", op_adam_lp), ("sgd_step", op_sgd)]
     if args.ops:
         keep = set(args.ops.split(","))
@@ -388,7 +422,9 @@ def main():
         "ops_next": dict(next_table, note=f"rows beyond the nine: FFN bias+{act}+dropout(p={pa}) on [{T}, {F}], the paper's "
                                           "low-precision-parameter Adam (22 B/param), SGD with momentum (20 B/param), "
                                           f"QKV bias + head split on [{T}, {3 * H}] and its backward, head merge, embedding of {T} Zipf-"
-                                          f"distributed tokens ({n_unique} distinct ids) into [{T}, {H}] and its backward"),
+                                          f"distributed tokens ({n_unique} distinct ids) into [{T}, {H}] and its backward; padding removal "
+                                          f"({T_real} real rows of {T}): pack, unpack, LayerNorm on the packed rows, softmax "
+                                          "with query lengths (rows of padded queries neither read nor computed)"),
         "layer_us": {"encoder_layer_fwd_bwd_nongemm": round(enc, 1), "decoder_layer_fwd_bwd_nongemm": round(dec, 1)},
     }
     if not args.no_cpu_baseline:
@@ -398,17 +434,18 @@ def main():
     print(json.dumps(out))
 
 
-def _allowed_elements(cfg, key_len):
+def _allowed_elements(cfg, key_len, query_len=None):
     """Number of (row, key) pairs inside the allowed set: what a masked softmax must read."""
     B, N, L = cfg.batch, cfg.heads, cfg.max_len
     kl = np.full(B, L) if key_len is None else np.clip(key_len, 0, L)
+    ql = np.full(B, L) if query_len is None else np.clip(query_len, 0, L)
     total = 0
     for b in range(B):
+        i = np.arange(int(ql[b]))
         if cfg.causal:
-            i = np.arange(L)
             total += int(np.minimum(i + 1, kl[b]).sum()) * N
         else:
-            total += int(kl[b]) * L * N
+            total += int(kl[b]) * len(i) * N
     return total
 
 

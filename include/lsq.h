@@ -289,6 +289,44 @@ lsq_status lsq_embedding_bwd(void* demb, void* dpos, const void* dy, const int32
                              float scale, float p, uint64_t seed, uint64_t offset,
                              void* workspace, size_t workspace_bytes, lsq_dtype dt, void* stream);
 
+/* Padding removal (named in the paper's conclusion as the optimisation to do next):
+ * the real rows of a padded [batch, max_len, hidden] tensor are stored back to back
+ * as [sum(len), hidden], so the row-wise operators above run on sum(len) rows.
+ *
+ * lsq_pad_offsets writes offsets[b] = sum_{b' < b} len_b', offsets[batch] = sum(len),
+ * with len_b = clamp(key_len[b], 0, max_len) (key_len NULL: every sentence is full).
+ * offsets: int32[batch + 1], device.  batch * max_len must fit in int32. */
+lsq_status lsq_pad_offsets(int32_t* offsets, const int32_t* key_len, int32_t batch, int32_t max_len,
+                           void* stream);
+
+/* packed[offsets[b] + i, :] = padded[b, i, :] for i < len_b (len_b = offsets[b+1] -
+ * offsets[b]); a bit-exact move.  packed_rows is the capacity of `packed` in rows
+ * (>= sum(len), which the caller's batching knows; the padded row count is always
+ * enough): rows that would fall outside it are skipped, nothing is written beyond.
+ * Rows of `packed` from sum(len) on are not touched.  Its backward is
+ * lsq_pad_restore (the gradient of a dropped row is 0). */
+lsq_status lsq_pad_remove(void* packed, const void* padded, const int32_t* offsets, int32_t batch,
+                          int32_t max_len, int32_t hidden, int64_t packed_rows, lsq_dtype dt, void* stream);
+
+/* padded[b, i, :] = packed[offsets[b] + i, :] for i < len_b, and +0 on the padding;
+ * every element of `padded` is written.  Its backward is lsq_pad_remove. */
+lsq_status lsq_pad_restore(void* padded, const void* packed, const int32_t* offsets, int32_t batch,
+                           int32_t max_len, int32_t hidden, int64_t packed_rows, lsq_dtype dt, void* stream);
+
+/* lsq_softmax_fwd / lsq_softmax_bwd with query lengths as well: query rows
+ * i >= query_len[b] are padding, their allowed set is empty, so they are not read and
+ * their outputs are exact zeros (finite, so that the batched products around the
+ * softmax stay finite).  query_len: int32[batch], device, nullable (NULL gives
+ * lsq_softmax_fwd / lsq_softmax_bwd exactly).  Everything else as documented there. */
+lsq_status lsq_softmax_varlen_fwd(void* y, void* y_drop, const void* x, const int32_t* key_len,
+                                  const int32_t* query_len, int32_t batch, int32_t heads, int32_t q_len,
+                                  int32_t k_len, int32_t causal, float scale, float p_attn,
+                                  uint64_t seed, uint64_t offset, lsq_dtype dt, void* stream);
+lsq_status lsq_softmax_varlen_bwd(void* dx, const void* dy, const void* y, const int32_t* key_len,
+                                  const int32_t* query_len, int32_t batch, int32_t heads, int32_t q_len,
+                                  int32_t k_len, int32_t causal, float scale, float p_attn,
+                                  uint64_t seed, uint64_t offset, lsq_dtype dt, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

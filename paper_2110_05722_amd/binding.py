@@ -30,6 +30,7 @@ EXPORTS = [
     "lsq_bias_act_dropout_fwd", "lsq_bias_act_dropout_bwd", "lsq_adam_step_lp", "lsq_sgd_step",
     "lsq_split_heads_fwd", "lsq_split_heads_bwd", "lsq_merge_heads_fwd", "lsq_merge_heads_bwd",
     "lsq_embedding_fwd", "lsq_embedding_bwd",
+    "lsq_pad_offsets", "lsq_pad_remove", "lsq_pad_restore", "lsq_softmax_varlen_fwd", "lsq_softmax_varlen_bwd",
 ]
 
 
@@ -74,6 +75,11 @@ def load():
         "lsq_merge_heads_bwd": (C.c_int, [vp, vp, i32, i32, i32, i32, C.c_int, vp]),
         "lsq_embedding_fwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64, C.c_int, vp]),
         "lsq_embedding_bwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64, vp, sz, C.c_int, vp]),
+        "lsq_pad_offsets": (C.c_int, [vp, vp, i32, i32, vp]),
+        "lsq_pad_remove": (C.c_int, [vp, vp, vp, i32, i32, i32, i64, C.c_int, vp]),
+        "lsq_pad_restore": (C.c_int, [vp, vp, vp, i32, i32, i32, i64, C.c_int, vp]),
+        "lsq_softmax_varlen_fwd": (C.c_int, [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64, C.c_int, vp]),
+        "lsq_softmax_varlen_bwd": (C.c_int, [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64, C.c_int, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -348,3 +354,54 @@ def lsq_embedding_bwd(demb, dpos, dy, tokens, pad_idx: int, scale: float, p: flo
                                     offset, _ptr(ws), ws.numel() * ws.element_size(), _dt(demb), _stream()),
            "lsq_embedding_bwd")
     return demb, dpos
+
+
+def lsq_pad_offsets(key_len, batch: int, max_len: int, offsets=None):
+    """key_len: int32[batch] (or None: all full) -> offsets int32[batch+1] on the device."""
+    if offsets is None:
+        dev = key_len.device if key_len is not None else torch.device("cuda", torch.cuda.current_device())
+        offsets = torch.empty(batch + 1, dtype=torch.int32, device=dev)
+    _check(load().lsq_pad_offsets(_ptr(offsets), _ptr(key_len), batch, max_len, _stream()), "lsq_pad_offsets")
+    return offsets
+
+
+def lsq_pad_remove(padded, offsets, packed_rows: int, packed=None):
+    """padded: [batch, max_len, hidden] -> packed [packed_rows, hidden] (rows from sum(len) on are not written)."""
+    B, L, H = padded.shape
+    packed = torch.empty((packed_rows, H), dtype=padded.dtype, device=padded.device) if packed is None else packed
+    _check(load().lsq_pad_remove(_ptr(packed) if packed.numel() else None, _ptr(padded) if padded.numel() else None,
+                                 _ptr(offsets), B, L, H, packed.shape[0], _dt(padded), _stream()), "lsq_pad_remove")
+    return packed
+
+
+def lsq_pad_restore(packed, offsets, batch: int, max_len: int, padded=None):
+    """packed: [rows, hidden] -> padded [batch, max_len, hidden], zeros on the padding."""
+    H = packed.shape[1]
+    padded = torch.empty((batch, max_len, H), dtype=packed.dtype, device=packed.device) if padded is None else padded
+    _check(load().lsq_pad_restore(_ptr(padded) if padded.numel() else None, _ptr(packed) if packed.numel() else None,
+                                  _ptr(offsets), batch, max_len, H, packed.shape[0], _dt(packed), _stream()),
+           "lsq_pad_restore")
+    return padded
+
+
+def lsq_softmax_varlen_fwd(x, key_len=None, query_len=None, causal: bool = False, scale: float = 1.0,
+                           p_attn: float = 0.0, seed: int = 0, offset: int = 0, y=None, y_drop=None):
+    """lsq_softmax_fwd with query_len: int32[batch]; rows of padded queries are not read and come out as zeros."""
+    B, N, Lq, Lk = x.shape
+    y = torch.empty_like(x) if y is None else y
+    if p_attn > 0 and y_drop is None:
+        y_drop = torch.empty_like(x)
+    _check(load().lsq_softmax_varlen_fwd(_ptr(y), _ptr(y_drop) if p_attn > 0 else None, _ptr(x), _ptr(key_len),
+                                         _ptr(query_len), B, N, Lq, Lk, int(causal), scale, p_attn, seed, offset,
+                                         _dt(x), _stream()), "lsq_softmax_varlen_fwd")
+    return y, (y_drop if p_attn > 0 else None)
+
+
+def lsq_softmax_varlen_bwd(dy, y, key_len=None, query_len=None, causal: bool = False, scale: float = 1.0,
+                           p_attn: float = 0.0, seed: int = 0, offset: int = 0, dx=None):
+    B, N, Lq, Lk = y.shape
+    dx = torch.empty_like(y) if dx is None else dx
+    _check(load().lsq_softmax_varlen_bwd(_ptr(dx), _ptr(dy), _ptr(y), _ptr(key_len), _ptr(query_len), B, N, Lq, Lk,
+                                         int(causal), scale, p_attn, seed, offset, _dt(y), _stream()),
+           "lsq_softmax_varlen_bwd")
+    return dx

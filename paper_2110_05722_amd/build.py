@@ -18,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 # LSQ_LIB_NAME / LSQ_DEFINES: build an experimental variant next to the default library (tuning only)
 LIB = os.path.join(HERE, os.environ.get("LSQ_LIB_NAME", "liblsq.so"))
 OBJ_DIR = os.path.join(HERE, "_build", os.environ.get("LSQ_LIB_NAME", "liblsq.so"))
-SOURCES = ["api", "adam", "bias_dropout_residual", "bias_act_dropout", "heads", "embedding", "layernorm", "softmax", "ls_xent"]
+SOURCES = ["api", "adam", "bias_dropout_residual", "bias_act_dropout", "heads", "embedding", "pad", "layernorm", "softmax", "ls_xent"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument",

@@ -110,6 +110,17 @@ __device__ __forceinline__ RawPack<T> load_raw(const T* __restrict__ p)
     return r;
 }
 
+template <typename T, bool NT = false>
+__device__ __forceinline__ void store_raw(T* __restrict__ p, const RawPack<T>& r)
+{
+    if constexpr (sizeof(T) == 2) {
+        st_u4<NT>(p, r.u);
+    } else {
+        st_f4<NT>(reinterpret_cast<float*>(p), r.a);
+        st_f4<NT>(reinterpret_cast<float*>(p) + 4, r.b);
+    }
+}
+
 template <typename T>
 __device__ __forceinline__ RawPack<T> zero_raw()
 {

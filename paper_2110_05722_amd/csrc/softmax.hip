@@ -34,24 +34,29 @@ struct SoftmaxGeom {
     float scale;
 };
 
-// number of allowed keys (a prefix of the row) for query row `row`
-__device__ __forceinline__ int row_limit(const SoftmaxGeom& g, const int32_t* __restrict__ key_len, int64_t row)
+// key and query lengths of the batch (either may be absent)
+struct SoftmaxLens {
+    const int32_t* __restrict__ key;
+    const int32_t* __restrict__ query;
+};
+
+// number of allowed keys (a prefix of the row) for query row `row`; 0 for a padded query
+__device__ __forceinline__ int row_limit(const SoftmaxGeom& g, const SoftmaxLens& len, int64_t row)
 {
     int limit = g.k_len;
-    if (key_len) {
+    const int i = static_cast<int>(row % g.q_len);
+    if (len.key || len.query) {
         const int b = static_cast<int>(row / g.rows_per_batch);
-        limit = min(max(key_len[b], 0), g.k_len);
+        if (len.key) limit = min(max(len.key[b], 0), g.k_len);
+        if (len.query && i >= len.query[b]) limit = 0;
     }
-    if (g.causal) {
-        const int i = static_cast<int>(row % g.q_len);
-        limit = min(limit, max(i + 1 + g.shift, 0));
-    }
+    if (g.causal) limit = min(limit, max(i + 1 + g.shift, 0));
     return limit;
 }
 
 template <typename T, int LPR, int VPL, bool DROP>
 __global__ __launch_bounds__(256) void softmax_fwd_kernel(T* y, T* __restrict__ yd, const T* x,
-                                                          const int32_t* __restrict__ key_len, SoftmaxGeom g,
+                                                          SoftmaxLens key_len, SoftmaxGeom g,
                                                           DropoutParams d)
 {
     constexpr int RPB = 256 / LPR;
@@ -119,7 +124,7 @@ __global__ __launch_bounds__(256) void softmax_fwd_kernel(T* y, T* __restrict__ 
 
 template <typename T, int LPR, int VPL, bool DROP>
 __global__ __launch_bounds__(256) void softmax_bwd_kernel(T* dx, const T* dy, const T* __restrict__ y,
-                                                          const int32_t* __restrict__ key_len, SoftmaxGeom g,
+                                                          SoftmaxLens key_len, SoftmaxGeom g,
                                                           DropoutParams d)
 {
     constexpr int RPB = 256 / LPR;
@@ -181,7 +186,7 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(T* dx, const T* dy, co
 // ---- generic path: any k_len; one wave per row, element-strided, row re-read from cache
 template <typename T>
 __global__ __launch_bounds__(256) void softmax_fwd_generic(T* y, T* __restrict__ yd, const T* x,
-                                                           const int32_t* __restrict__ key_len, SoftmaxGeom g,
+                                                           SoftmaxLens key_len, SoftmaxGeom g,
                                                            DropoutParams d)
 {
     const int lane = threadIdx.x & 63;
@@ -207,7 +212,7 @@ __global__ __launch_bounds__(256) void softmax_fwd_generic(T* y, T* __restrict__
 
 template <typename T>
 __global__ __launch_bounds__(256) void softmax_bwd_generic(T* dx, const T* dy, const T* __restrict__ y,
-                                                           const int32_t* __restrict__ key_len, SoftmaxGeom g,
+                                                           SoftmaxLens key_len, SoftmaxGeom g,
                                                            DropoutParams d)
 {
     const int lane = threadIdx.x & 63;
@@ -256,7 +261,7 @@ inline SmShape softmax_shape(int k_len)
 #define LSQ_SM_CASES(X) X(1, 1) X(2, 1) X(4, 1) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 3) X(64, 4)
 
 template <typename T>
-static lsq_status softmax_fwd_dispatch(void* y, void* yd, const void* x, const int32_t* key_len, const SoftmaxGeom& g,
+static lsq_status softmax_fwd_dispatch(void* y, void* yd, const void* x, SoftmaxLens key_len, const SoftmaxGeom& g,
                                        const DropoutParams& d, hipStream_t s)
 {
     T* yp = static_cast<T*>(y);
@@ -281,7 +286,7 @@ static lsq_status softmax_fwd_dispatch(void* y, void* yd, const void* x, const i
 }
 
 template <typename T>
-static lsq_status softmax_bwd_dispatch(void* dx, const void* dy, const void* y, const int32_t* key_len,
+static lsq_status softmax_bwd_dispatch(void* dx, const void* dy, const void* y, SoftmaxLens key_len,
                                        const SoftmaxGeom& g, const DropoutParams& d, hipStream_t s)
 {
     T* dxp = static_cast<T*>(dx);
@@ -326,11 +331,13 @@ static lsq_status softmax_check(const void* a, const void* b, int32_t batch, int
 
 }  // namespace lsq
 
-extern "C" lsq_status lsq_softmax_fwd(void* y, void* y_drop, const void* x, const int32_t* key_len, int32_t batch,
-                                      int32_t heads, int32_t q_len, int32_t k_len, int32_t causal, float scale,
-                                      float p_attn, uint64_t seed, uint64_t offset, lsq_dtype dt, void* stream)
+extern "C" lsq_status lsq_softmax_varlen_fwd(void* y, void* y_drop, const void* x, const int32_t* key_len,
+                                             const int32_t* query_len, int32_t batch, int32_t heads, int32_t q_len,
+                                             int32_t k_len, int32_t causal, float scale, float p_attn, uint64_t seed,
+                                             uint64_t offset, lsq_dtype dt, void* stream)
 {
     using namespace lsq;
+    const SoftmaxLens len{key_len, query_len};
     SoftmaxGeom g;
     lsq_status st = softmax_check(y, x, batch, heads, q_len, k_len, scale, dt, &g);
     if (st != LSQ_OK) return st;
@@ -343,17 +350,27 @@ extern "C" lsq_status lsq_softmax_fwd(void* y, void* y_drop, const void* x, cons
     LSQ_ALIGNED(y); LSQ_ALIGNED(y_drop); LSQ_ALIGNED(x);
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (dt) {
-        case LSQ_F16: return softmax_fwd_dispatch<f16>(y, y_drop, x, key_len, g, d, s);
-        case LSQ_BF16: return softmax_fwd_dispatch<bf16>(y, y_drop, x, key_len, g, d, s);
-        default: return softmax_fwd_dispatch<float>(y, y_drop, x, key_len, g, d, s);
+        case LSQ_F16: return softmax_fwd_dispatch<f16>(y, y_drop, x, len, g, d, s);
+        case LSQ_BF16: return softmax_fwd_dispatch<bf16>(y, y_drop, x, len, g, d, s);
+        default: return softmax_fwd_dispatch<float>(y, y_drop, x, len, g, d, s);
     }
 }
 
-extern "C" lsq_status lsq_softmax_bwd(void* dx, const void* dy, const void* y, const int32_t* key_len, int32_t batch,
+extern "C" lsq_status lsq_softmax_fwd(void* y, void* y_drop, const void* x, const int32_t* key_len, int32_t batch,
                                       int32_t heads, int32_t q_len, int32_t k_len, int32_t causal, float scale,
                                       float p_attn, uint64_t seed, uint64_t offset, lsq_dtype dt, void* stream)
 {
+    return lsq_softmax_varlen_fwd(y, y_drop, x, key_len, nullptr, batch, heads, q_len, k_len, causal, scale, p_attn,
+                                  seed, offset, dt, stream);
+}
+
+extern "C" lsq_status lsq_softmax_varlen_bwd(void* dx, const void* dy, const void* y, const int32_t* key_len,
+                                             const int32_t* query_len, int32_t batch, int32_t heads, int32_t q_len,
+                                             int32_t k_len, int32_t causal, float scale, float p_attn, uint64_t seed,
+                                             uint64_t offset, lsq_dtype dt, void* stream)
+{
     using namespace lsq;
+    const SoftmaxLens len{key_len, query_len};
     SoftmaxGeom g;
     lsq_status st = softmax_check(dx, dy, batch, heads, q_len, k_len, scale, dt, &g);
     if (st != LSQ_OK) return st;
@@ -365,8 +382,16 @@ extern "C" lsq_status lsq_softmax_bwd(void* dx, const void* dy, const void* y, c
     LSQ_ALIGNED(dx); LSQ_ALIGNED(dy); LSQ_ALIGNED(y);
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (dt) {
-        case LSQ_F16: return softmax_bwd_dispatch<f16>(dx, dy, y, key_len, g, d, s);
-        case LSQ_BF16: return softmax_bwd_dispatch<bf16>(dx, dy, y, key_len, g, d, s);
-        default: return softmax_bwd_dispatch<float>(dx, dy, y, key_len, g, d, s);
+        case LSQ_F16: return softmax_bwd_dispatch<f16>(dx, dy, y, len, g, d, s);
+        case LSQ_BF16: return softmax_bwd_dispatch<bf16>(dx, dy, y, len, g, d, s);
+        default: return softmax_bwd_dispatch<float>(dx, dy, y, len, g, d, s);
     }
+}
+
+extern "C" lsq_status lsq_softmax_bwd(void* dx, const void* dy, const void* y, const int32_t* key_len, int32_t batch,
+                                      int32_t heads, int32_t q_len, int32_t k_len, int32_t causal, float scale,
+                                      float p_attn, uint64_t seed, uint64_t offset, lsq_dtype dt, void* stream)
+{
+    return lsq_softmax_varlen_bwd(dx, dy, y, key_len, nullptr, batch, heads, q_len, k_len, causal, scale, p_attn, seed,
+                                  offset, dt, stream);
 }

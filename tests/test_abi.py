@@ -120,6 +120,23 @@ def test_host_side_argument_errors_of_the_next_rows(lib):
     assert f(None, None, None, None, 0, 0.1, 0.0, 0., 0, 1., 0, 0, None) == 0
 
 
+def test_host_side_argument_errors_of_padding_removal(lib):
+    INVALID, DTYPE = 1, 2
+    f = lib.lsq_pad_offsets
+    assert f(None, A, 4, 8, None) == INVALID
+    assert f(A, A, -1, 8, None) == INVALID
+    assert f(A, A, 1 << 20, 1 << 20, None) == INVALID                  # batch * max_len beyond int32
+    for f in (lib.lsq_pad_remove, lib.lsq_pad_restore):
+        assert f(A, A, None, 4, 8, 16, 32, 0, None) == INVALID         # no offsets
+        assert f(A, A, A, 4, 8, 16, -1, 0, None) == INVALID
+        assert f(A, A, A, 4, 8, 16, 32, 7, None) == DTYPE
+        assert f(None, None, None, 0, 8, 16, 0, 0, None) == 0          # empty batch: nothing to do
+    f = lib.lsq_softmax_varlen_fwd
+    assert f(A, None, A, A, A, 2, 2, 8, 8, 0, float("nan"), 0.0, 1, 0, 0, None) == INVALID
+    assert f(A, None, A, A, A, 2, 2, 8, 8, 0, 1.0, 0.1, 1, 0, 0, None) == INVALID   # dropout without y_drop
+    assert f(None, None, None, None, None, 0, 2, 8, 8, 0, 1.0, 0.0, 1, 0, 0, None) == 0
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     x = torch.zeros(4, 8, dtype=torch.float16)
