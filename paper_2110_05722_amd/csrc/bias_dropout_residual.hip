@@ -17,6 +17,10 @@ namespace lsq {
 constexpr bool kNT = LSQ_NT != 0;   // nontemporal hint on the streamed tensors (not on gamma/beta/bias)
 
 constexpr int kBdrWaves = 4;   // waves per workgroup; each takes its own rows
+#ifndef LSQ_BDR_UNROLL
+#define LSQ_BDR_UNROLL 4
+#endif
+constexpr int kBdrUnroll = LSQ_BDR_UNROLL;   // rows a wave has in flight in backward
 
 template <typename T, bool HAS_BIAS, bool DROP>
 __global__ __launch_bounds__(256) void bdr_fwd_cols(T* out, const T* x,
@@ -58,18 +62,32 @@ __global__ __launch_bounds__(256) void bdr_bwd_cols(T* dx, float* __restrict__ p
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     const int64_t stride = static_cast<int64_t>(gridDim.y) * kBdrWaves;
     if (active) {
-        for (int64_t r = static_cast<int64_t>(blockIdx.y) * kBdrWaves + wave; r < rows; r += stride) {
-            const int64_t pack = r * ppr + cp;
-            float g[8], k[8];
-            load8<T, kNT>(dy + pack * kPack, g);
-            if constexpr (DROP) {
-                dropout_factors8(d, static_cast<uint64_t>(pack), k);
+        // kBdrUnroll rows per trip: their loads are issued before the first Philox call
+        for (int64_t r0 = static_cast<int64_t>(blockIdx.y) * kBdrWaves + wave; r0 < rows; r0 += stride * kBdrUnroll) {
+            RawPack<T> raw[kBdrUnroll];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) g[j] *= k[j];
+            for (int u = 0; u < kBdrUnroll; ++u) {
+                const int64_t r = r0 + u * stride;
+                if (r < rows) raw[u] = load_raw<T, kNT>(dy + (r * ppr + cp) * kPack);
+                else raw[u] = zero_raw<T>();
             }
-            store8<T, kNT>(dx + pack * kPack, g);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j] += g[j];
+            for (int u = 0; u < kBdrUnroll; ++u) {
+                const int64_t r = r0 + u * stride;
+                if (r < rows) {
+                    const int64_t pack = r * ppr + cp;
+                    float g[8], k[8];
+                    unpack<T>(raw[u], g);
+                    if constexpr (DROP) {
+                        dropout_factors8(d, static_cast<uint64_t>(pack), k);
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) g[j] *= k[j];
+                    }
+                    store8<T, kNT>(dx + pack * kPack, g);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[j] += g[j];
+                }
+            }
         }
     }
     if (partial == nullptr) return;        // uniform over the grid

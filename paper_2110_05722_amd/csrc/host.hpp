@@ -115,8 +115,11 @@ inline int ln_bwd_blocks(int64_t rows, int32_t /*hidden*/)
 
 inline int bdr_bwd_row_blocks(int64_t rows, int32_t /*hidden*/)
 {
+#ifndef LSQ_BDR_BWD_BLOCKS
+#define LSQ_BDR_BWD_BLOCKS 256
+#endif
     int64_t b = ceil_div(rows, 16);
-    if (b > 256) b = 256;
+    if (b > LSQ_BDR_BWD_BLOCKS) b = LSQ_BDR_BWD_BLOCKS;
     if (b < 1) b = 1;
     return static_cast<int>(b);
 }

@@ -46,139 +46,168 @@ __device__ __forceinline__ int row_limit(const SoftmaxGeom& g, const SoftmaxLens
     int limit = g.k_len;
     const int i = static_cast<int>(row % g.q_len);
     if (len.key || len.query) {
+        // the rows of a wave almost always belong to one sentence: its lengths come through
+        // the scalar path (one cached load per wave), the vector path serves a straddling wave
         const int b = static_cast<int>(row / g.rows_per_batch);
-        if (len.key) limit = min(max(len.key[b], 0), g.k_len);
-        if (len.query && i >= len.query[b]) limit = 0;
+        const int b0 = __builtin_amdgcn_readfirstlane(b);
+        if (len.key) {
+            int kl = len.key[b0];
+            if (b != b0) kl = len.key[b];
+            limit = min(max(kl, 0), g.k_len);
+        }
+        if (len.query) {
+            int ql = len.query[b0];
+            if (b != b0) ql = len.query[b];
+            if (i >= ql) limit = 0;
+        }
     }
     if (g.causal) limit = min(limit, max(i + 1 + g.shift, 0));
     return limit;
 }
 
-template <typename T, int LPR, int VPL, bool DROP>
+// RPT rows per lane group: the loads of all RPT rows are issued before the first
+// reduction, so a wave has RPT*VPL packs per lane in flight and the two dependent
+// round trips (lengths, then scores) are paid once per RPT rows.
+template <typename T, int LPR, int VPL, int RPT, bool DROP>
 __global__ __launch_bounds__(256) void softmax_fwd_kernel(T* y, T* __restrict__ yd, const T* x,
-                                                          SoftmaxLens key_len, SoftmaxGeom g,
-                                                          DropoutParams d)
+                                                          SoftmaxLens len, SoftmaxGeom g, DropoutParams d)
 {
     constexpr int RPB = 256 / LPR;
     const int sub = threadIdx.x % LPR;
-    const int64_t row = static_cast<int64_t>(blockIdx.x) * RPB + threadIdx.x / LPR;
-    const bool rv = row < g.nrows;
     const int nv = g.k_len / kPack;
-    const int limit = rv ? row_limit(g, key_len, row) : 0;
-    const int64_t ro = row * g.k_len;
-
-    // loads first (only the packs that reach into the allowed prefix), arithmetic after:
-    // all loads of the row are in flight together
-    RawPack<T> raw[VPL];
+    int64_t row[RPT];
+    int limit[RPT];
 #pragma unroll
-    for (int k = 0; k < VPL; ++k) {
-        const int j0 = (sub + k * LPR) * kPack;
-        if (j0 < limit) raw[k] = load_raw<T, kNT>(x + ro + j0);     // implies rv and idx < nv
-        else raw[k] = zero_raw<T>();
+    for (int r = 0; r < RPT; ++r) {
+        row[r] = (static_cast<int64_t>(blockIdx.x) * RPT + r) * RPB + threadIdx.x / LPR;
+        limit[r] = row[r] < g.nrows ? row_limit(g, len, row[r]) : 0;
     }
-    float v[VPL][8];
-    float mx = -INFINITY;
+    // loads first (only the packs that reach into the allowed prefix), arithmetic after
+    RawPack<T> raw[RPT][VPL];
 #pragma unroll
-    for (int k = 0; k < VPL; ++k) {
-        const int j0 = (sub + k * LPR) * kPack;
-        unpack<T>(raw[k], v[k]);
+    for (int r = 0; r < RPT; ++r)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            v[k][j] = (j0 + j < limit) ? v[k][j] * g.scale : -INFINITY;
-            mx = fmaxf(mx, v[k][j]);
+        for (int k = 0; k < VPL; ++k) {
+            const int j0 = (sub + k * LPR) * kPack;
+            if (j0 < limit[r]) raw[r][k] = load_raw<T, kNT>(x + row[r] * g.k_len + j0);   // implies a valid row and pack
+            else raw[r][k] = zero_raw<T>();
         }
-    }
-    mx = group_max<LPR>(mx);
-    const float mxs = (limit > 0 ? mx : 0.0f) * kLog2e;
-    float z = 0.0f;
 #pragma unroll
-    for (int k = 0; k < VPL; ++k)
+    for (int r = 0; r < RPT; ++r) {
+        const int64_t ro = row[r] * g.k_len;
+        const int lim = limit[r];
+        float v[VPL][8];
+        float mx = -INFINITY;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float e = __builtin_amdgcn_exp2f(fmaf(v[k][j], kLog2e, -mxs));   // exp2(-inf) = 0 on masked lanes
-            v[k][j] = e;
-            z += e;
+        for (int k = 0; k < VPL; ++k) {
+            const int j0 = (sub + k * LPR) * kPack;
+            unpack<T>(raw[r][k], v[k]);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                v[k][j] = (j0 + j < lim) ? v[k][j] * g.scale : -INFINITY;
+                mx = fmaxf(mx, v[k][j]);
+            }
         }
-    z = group_sum<LPR>(z);
-    const float inv = limit > 0 ? 1.0f / z : 0.0f;
+        mx = group_max<LPR>(mx);
+        const float mxs = (lim > 0 ? mx : 0.0f) * kLog2e;
+        float z = 0.0f;
 #pragma unroll
-    for (int k = 0; k < VPL; ++k) {
-        const int idx = sub + k * LPR;
-        if (rv && idx < nv) {
-            float o[8];
+        for (int k = 0; k < VPL; ++k)
 #pragma unroll
-            for (int j = 0; j < 8; ++j) o[j] = v[k][j] * inv;
-            store8<T, kNT>(y + ro + idx * kPack, o);
-            if constexpr (DROP) {
-                if (idx * kPack < limit) {    // packs beyond the mask are zeros whatever the draw
-                    float kf[8];
-                    dropout_factors8(d, static_cast<uint64_t>(row) * nv + idx, kf);
+            for (int j = 0; j < 8; ++j) {
+                const float e = __builtin_amdgcn_exp2f(fmaf(v[k][j], kLog2e, -mxs));   // exp2(-inf) = 0 on masked lanes
+                v[k][j] = e;
+                z += e;
+            }
+        z = group_sum<LPR>(z);
+        const float inv = lim > 0 ? 1.0f / z : 0.0f;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) o[j] *= kf[j];
+        for (int k = 0; k < VPL; ++k) {
+            const int idx = sub + k * LPR;
+            if (row[r] < g.nrows && idx < nv) {
+                float o[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) o[j] = v[k][j] * inv;
+                store8<T, kNT>(y + ro + idx * kPack, o);
+                if constexpr (DROP) {
+                    if (idx * kPack < lim) {    // packs beyond the mask are zeros whatever the draw
+                        float kf[8];
+                        dropout_factors8(d, static_cast<uint64_t>(row[r]) * nv + idx, kf);
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) o[j] *= kf[j];
+                    }
+                    store8<T, kNT>(yd + ro + idx * kPack, o);
                 }
-                store8<T, kNT>(yd + ro + idx * kPack, o);
             }
         }
     }
 }
 
-template <typename T, int LPR, int VPL, bool DROP>
+template <typename T, int LPR, int VPL, int RPT, bool DROP>
 __global__ __launch_bounds__(256) void softmax_bwd_kernel(T* dx, const T* dy, const T* __restrict__ y,
-                                                          SoftmaxLens key_len, SoftmaxGeom g,
-                                                          DropoutParams d)
+                                                          SoftmaxLens len, SoftmaxGeom g, DropoutParams d)
 {
     constexpr int RPB = 256 / LPR;
     const int sub = threadIdx.x % LPR;
-    const int64_t row = static_cast<int64_t>(blockIdx.x) * RPB + threadIdx.x / LPR;
-    const bool rv = row < g.nrows;
     const int nv = g.k_len / kPack;
-    const int limit = rv ? row_limit(g, key_len, row) : 0;
-    const int64_t ro = row * g.k_len;
-
-    RawPack<T> ry[VPL], rg[VPL];
+    int64_t row[RPT];
+    int limit[RPT];
 #pragma unroll
-    for (int k = 0; k < VPL; ++k) {
-        const int j0 = (sub + k * LPR) * kPack;
-        if (j0 < limit) {
-            ry[k] = load_raw<T, kNT>(y + ro + j0);
-            rg[k] = load_raw<T, kNT>(dy + ro + j0);
-        } else {
-            ry[k] = zero_raw<T>();
-            rg[k] = zero_raw<T>();
-        }
+    for (int r = 0; r < RPT; ++r) {
+        row[r] = (static_cast<int64_t>(blockIdx.x) * RPT + r) * RPB + threadIdx.x / LPR;
+        limit[r] = row[r] < g.nrows ? row_limit(g, len, row[r]) : 0;
     }
-    float yv[VPL][8], gv[VPL][8];
-    float dot = 0.0f;
+    RawPack<T> ry[RPT][VPL], rg[RPT][VPL];
 #pragma unroll
-    for (int k = 0; k < VPL; ++k) {
-        const int idx = sub + k * LPR;
-        const int j0 = idx * kPack;
-        unpack<T>(ry[k], yv[k]);
-        unpack<T>(rg[k], gv[k]);
-        if constexpr (DROP) {
-            if (j0 < limit) {
-                float kf[8];
-                dropout_factors8(d, static_cast<uint64_t>(row) * nv + idx, kf);
+    for (int r = 0; r < RPT; ++r)
 #pragma unroll
-                for (int j = 0; j < 8; ++j) gv[k][j] *= kf[j];
+        for (int k = 0; k < VPL; ++k) {
+            const int j0 = (sub + k * LPR) * kPack;
+            if (j0 < limit[r]) {
+                ry[r][k] = load_raw<T, kNT>(y + row[r] * g.k_len + j0);
+                rg[r][k] = load_raw<T, kNT>(dy + row[r] * g.k_len + j0);
+            } else {
+                ry[r][k] = zero_raw<T>();
+                rg[r][k] = zero_raw<T>();
             }
         }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            if (j0 + j >= limit) yv[k][j] = 0.0f;
-            dot = fmaf(gv[k][j], yv[k][j], dot);
+    for (int r = 0; r < RPT; ++r) {
+        const int64_t ro = row[r] * g.k_len;
+        const int lim = limit[r];
+        float yv[VPL][8], gv[VPL][8];
+        float dot = 0.0f;
+#pragma unroll
+        for (int k = 0; k < VPL; ++k) {
+            const int idx = sub + k * LPR;
+            const int j0 = idx * kPack;
+            unpack<T>(ry[r][k], yv[k]);
+            unpack<T>(rg[r][k], gv[k]);
+            if constexpr (DROP) {
+                if (j0 < lim) {
+                    float kf[8];
+                    dropout_factors8(d, static_cast<uint64_t>(row[r]) * nv + idx, kf);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) gv[k][j] *= kf[j];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (j0 + j >= lim) yv[k][j] = 0.0f;
+                dot = fmaf(gv[k][j], yv[k][j], dot);
+            }
         }
-    }
-    dot = group_sum<LPR>(dot);
+        dot = group_sum<LPR>(dot);
 #pragma unroll
-    for (int k = 0; k < VPL; ++k) {
-        const int idx = sub + k * LPR;
-        if (rv && idx < nv) {
-            float o[8];
+        for (int k = 0; k < VPL; ++k) {
+            const int idx = sub + k * LPR;
+            if (row[r] < g.nrows && idx < nv) {
+                float o[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j)      // outside the allowed set: +0, not the -0 a product could give
-                o[j] = (idx * kPack + j < limit) ? g.scale * yv[k][j] * (gv[k][j] - dot) : 0.0f;
-            store8<T, kNT>(dx + ro + idx * kPack, o);
+                for (int j = 0; j < 8; ++j)      // outside the allowed set: +0, not the -0 a product could give
+                    o[j] = (idx * kPack + j < lim) ? g.scale * yv[k][j] * (gv[k][j] - dot) : 0.0f;
+                store8<T, kNT>(dx + ro + idx * kPack, o);
+            }
         }
     }
 }
@@ -260,6 +289,14 @@ inline SmShape softmax_shape(int k_len)
 
 #define LSQ_SM_CASES(X) X(1, 1) X(2, 1) X(4, 1) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 3) X(64, 4)
 
+// rows per lane group: about LSQ_SM_PACKS packs in flight per lane, and one row per
+// group whenever the grid would otherwise fall under kSmMinBlocks workgroups
+#ifndef LSQ_SM_PACKS
+#define LSQ_SM_PACKS 2
+#endif
+constexpr int sm_rpt(int vpl) { return LSQ_SM_PACKS / vpl > 1 ? LSQ_SM_PACKS / vpl : 1; }
+constexpr int64_t kSmMinBlocks = 1024;
+
 template <typename T>
 static lsq_status softmax_fwd_dispatch(void* y, void* yd, const void* x, SoftmaxLens key_len, const SoftmaxGeom& g,
                                        const DropoutParams& d, hipStream_t s)
@@ -274,11 +311,20 @@ static lsq_status softmax_fwd_dispatch(void* y, void* yd, const void* x, Softmax
                            yp, ydp, xp, key_len, g, d);
         return launch_status();
     }
-    const dim3 grid(static_cast<unsigned>(ceil_div(g.nrows, 256 / sh.lpr))), block(256);
+    const int64_t blocks1 = ceil_div(g.nrows, 256 / sh.lpr);
+    const dim3 block(256);
 #define X(L, V)                                                                                              \
     if (sh.lpr == L && sh.vpl == V) {                                                                        \
-        if (drop) hipLaunchKernelGGL((softmax_fwd_kernel<T, L, V, true>), grid, block, 0, s, yp, ydp, xp, key_len, g, d); \
-        else hipLaunchKernelGGL((softmax_fwd_kernel<T, L, V, false>), grid, block, 0, s, yp, ydp, xp, key_len, g, d);    \
+        constexpr int R = sm_rpt(V);                                                                         \
+        if (R > 1 && blocks1 >= kSmMinBlocks * R) {                                                          \
+            const dim3 grid(static_cast<unsigned>(ceil_div(blocks1, R)));                                    \
+            if (drop) hipLaunchKernelGGL((softmax_fwd_kernel<T, L, V, R, true>), grid, block, 0, s, yp, ydp, xp, key_len, g, d); \
+            else hipLaunchKernelGGL((softmax_fwd_kernel<T, L, V, R, false>), grid, block, 0, s, yp, ydp, xp, key_len, g, d);    \
+        } else {                                                                                             \
+            const dim3 grid(static_cast<unsigned>(blocks1));                                                 \
+            if (drop) hipLaunchKernelGGL((softmax_fwd_kernel<T, L, V, 1, true>), grid, block, 0, s, yp, ydp, xp, key_len, g, d); \
+            else hipLaunchKernelGGL((softmax_fwd_kernel<T, L, V, 1, false>), grid, block, 0, s, yp, ydp, xp, key_len, g, d);    \
+        }                                                                                                    \
     }
     LSQ_SM_CASES(X)
 #undef X
@@ -299,11 +345,20 @@ static lsq_status softmax_bwd_dispatch(void* dx, const void* dy, const void* y, 
                            dxp, dyp, yp, key_len, g, d);
         return launch_status();
     }
-    const dim3 grid(static_cast<unsigned>(ceil_div(g.nrows, 256 / sh.lpr))), block(256);
+    const int64_t blocks1 = ceil_div(g.nrows, 256 / sh.lpr);
+    const dim3 block(256);
 #define X(L, V)                                                                                              \
     if (sh.lpr == L && sh.vpl == V) {                                                                        \
-        if (drop) hipLaunchKernelGGL((softmax_bwd_kernel<T, L, V, true>), grid, block, 0, s, dxp, dyp, yp, key_len, g, d); \
-        else hipLaunchKernelGGL((softmax_bwd_kernel<T, L, V, false>), grid, block, 0, s, dxp, dyp, yp, key_len, g, d);    \
+        constexpr int R = sm_rpt(V);                                                                         \
+        if (R > 1 && blocks1 >= kSmMinBlocks * R) {                                                          \
+            const dim3 grid(static_cast<unsigned>(ceil_div(blocks1, R)));                                    \
+            if (drop) hipLaunchKernelGGL((softmax_bwd_kernel<T, L, V, R, true>), grid, block, 0, s, dxp, dyp, yp, key_len, g, d); \
+            else hipLaunchKernelGGL((softmax_bwd_kernel<T, L, V, R, false>), grid, block, 0, s, dxp, dyp, yp, key_len, g, d);    \
+        } else {                                                                                             \
+            const dim3 grid(static_cast<unsigned>(blocks1));                                                 \
+            if (drop) hipLaunchKernelGGL((softmax_bwd_kernel<T, L, V, 1, true>), grid, block, 0, s, dxp, dyp, yp, key_len, g, d); \
+            else hipLaunchKernelGGL((softmax_bwd_kernel<T, L, V, 1, false>), grid, block, 0, s, dxp, dyp, yp, key_len, g, d);    \
+        }                                                                                                    \
     }
     LSQ_SM_CASES(X)
 #undef X
