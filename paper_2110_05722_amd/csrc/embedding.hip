@@ -220,31 +220,64 @@ __global__ __launch_bounds__(256) void emb_combine(T* __restrict__ demb, const f
     }
 }
 
-// dP[l,:] += sum over the batch, in batch order; one workgroup per position
+// dP[l,:] += sum over the batch.  A workgroup owns 64 packs of one position; its four
+// waves take every fourth sentence each (four loads in flight per wave) and their
+// partial sums are added in wave order, so the result does not depend on timing.
 template <typename T, bool DROP>
 __global__ __launch_bounds__(256) void emb_dpos(T* __restrict__ dpos, const T* __restrict__ dy,
                                                 const int32_t* __restrict__ tokens, int batch, int len, int ppr,
                                                 int vocab, int pad_idx, DropoutParams d)
 {
-    const int l = blockIdx.x;
-    for (int cp = threadIdx.x; cp < ppr; cp += 256) {
-        float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        for (int b = 0; b < batch; ++b) {
-            const int64_t t = static_cast<int64_t>(b) * len + l;
-            if (emb_is_pad(tokens[t], vocab, pad_idx)) continue;
-            const int64_t pack = t * ppr + cp;
-            float g[8];
-            load8<T>(dy + pack * kPack, g);
-            if constexpr (DROP) {
-                float kf[8];
-                dropout_factors8(d, static_cast<uint64_t>(pack), kf);
+    constexpr int U = 4;
+    __shared__ float sm[kEmbWaves - 1][8][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l = blockIdx.y;
+    const int cp = blockIdx.x * 64 + lane;
+    const bool active = cp < ppr;
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (active) {
+        for (int b0 = wave; b0 < batch; b0 += kEmbWaves * U) {
+            RawPack<T> raw[U];
+            bool ok[U];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) acc[j] = fmaf(g[j], kf[j], acc[j]);
-            } else {
+            for (int u = 0; u < U; ++u) {
+                const int b = b0 + u * kEmbWaves;
+                ok[u] = false;
+                if (b < batch) {
+                    const int64_t t = static_cast<int64_t>(b) * len + l;
+                    ok[u] = !emb_is_pad(tokens[t], vocab, pad_idx);
+                    if (ok[u]) raw[u] = load_raw<T, true>(dy + (t * ppr + cp) * kPack);
+                }
+                if (!ok[u]) raw[u] = zero_raw<T>();
+            }
 #pragma unroll
-                for (int j = 0; j < 8; ++j) acc[j] += g[j];
+            for (int u = 0; u < U; ++u) {
+                if (!ok[u]) continue;
+                const int64_t pack = (static_cast<int64_t>(b0 + u * kEmbWaves) * len + l) * ppr + cp;
+                float g[8];
+                unpack<T>(raw[u], g);
+                if constexpr (DROP) {
+                    float kf[8];
+                    dropout_factors8(d, static_cast<uint64_t>(pack), kf);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[j] = fmaf(g[j], kf[j], acc[j]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[j] += g[j];
+                }
             }
         }
+    }
+    if (wave > 0) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) sm[wave - 1][j][lane] = acc[j];
+    }
+    __syncthreads();
+    if (wave == 0 && active) {
+#pragma unroll
+        for (int w = 0; w < kEmbWaves - 1; ++w)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] += sm[w][j][lane];
         T* dst = dpos + (static_cast<int64_t>(l) * ppr + cp) * kPack;
         float o[8];
         load8<T>(dst, o);
@@ -364,8 +397,9 @@ static lsq_status emb_bwd_dispatch(void* demb, void* dpos, const void* dy, const
         else hipLaunchKernelGGL((emb_accumulate<T, false>), grid, block, 0, s, de, chunk_rows, g, order, ppr, scale, d);
         hipLaunchKernelGGL((emb_combine<T>), grid, block, 0, s, de, chunk_rows, order, ppr, scale);
         if (dp) {
-            if (d.t16) hipLaunchKernelGGL((emb_dpos<T, true>), dim3(len), dim3(256), 0, s, dp, g, tokens, batch, len, ppr, vocab, pad_idx, d);
-            else hipLaunchKernelGGL((emb_dpos<T, false>), dim3(len), dim3(256), 0, s, dp, g, tokens, batch, len, ppr, vocab, pad_idx, d);
+            const dim3 pgrid(static_cast<unsigned>(ceil_div(ppr, 64)), static_cast<unsigned>(len));
+            if (d.t16) hipLaunchKernelGGL((emb_dpos<T, true>), pgrid, dim3(256), 0, s, dp, g, tokens, batch, len, ppr, vocab, pad_idx, d);
+            else hipLaunchKernelGGL((emb_dpos<T, false>), pgrid, dim3(256), 0, s, dp, g, tokens, batch, len, ppr, vocab, pad_idx, d);
         }
     } else {
         hipLaunchKernelGGL((emb_accumulate_flat<T>), grid, block, 0, s, de, g, order, hidden, scale, d);
@@ -413,6 +447,7 @@ extern "C" lsq_status lsq_embedding_bwd(void* demb, void* dpos, const void* dy, 
     const int64_t rows = static_cast<int64_t>(batch) * len;
     if (rows == 0) return LSQ_OK;
     LSQ_REQUIRE(rows <= 0x7FFFFFFF / 2 && ceil_div(rows, kTile) <= 65535);
+    LSQ_REQUIRE(!dpos || len <= 65535);       // one grid row per position
     LSQ_REQUIRE(demb && dy && tokens);
     LSQ_ALIGNED(demb); LSQ_ALIGNED(dpos); LSQ_ALIGNED(dy); LSQ_ALIGNED(workspace);
     const size_t need = lsq_workspace_bytes(LSQ_OP_EMBEDDING_BWD, rows, hidden);
