@@ -8,7 +8,10 @@
 // of a wave64), each lane keeps VPL packs of 8 scores in registers, so a row is
 // read from HBM once, both reductions run on DPP inside the wave, and nothing
 // goes through LDS.  Short rows put many rows in one wave (k_len 32 -> 16 rows per
-// wave) so lanes are never idle.
+// wave) so lanes are never idle.  Rows of 2049..16384 keys take one workgroup
+// each (the reductions cross its four waves through LDS); anything else (k_len not
+// a multiple of 8, or longer still) falls to a three-pass kernel that re-reads
+// the row from cache.
 //
 // Masks restrict the SET the softmax runs over: packs that lie wholly beyond the
 // row's limit (key padding, or the causal diagonal) are not even loaded, and
@@ -212,6 +215,127 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(T* dx, const T* dy, co
     }
 }
 
+// ---- long rows (2048 < k_len <= 16384): one workgroup per row, VPL packs per thread in
+// registers, the two reductions cross the four waves through LDS.  Still one read of the row.
+template <typename T, int VPL, bool DROP>
+__global__ __launch_bounds__(256) void softmax_fwd_wide(T* y, T* __restrict__ yd, const T* x,
+                                                        SoftmaxLens len, SoftmaxGeom g, DropoutParams d)
+{
+    __shared__ float red[4];
+    const int64_t row = blockIdx.x;
+    const int nv = g.k_len / kPack;
+    const int limit = row_limit(g, len, row);
+    const int64_t ro = row * g.k_len;
+    RawPack<T> raw[VPL];
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        const int j0 = (threadIdx.x + k * 256) * kPack;
+        if (j0 < limit) raw[k] = load_raw<T, kNT>(x + ro + j0);
+        else raw[k] = zero_raw<T>();
+    }
+    float v[VPL][8];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        const int j0 = (threadIdx.x + k * 256) * kPack;
+        unpack<T>(raw[k], v[k]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            v[k][j] = (j0 + j < limit) ? v[k][j] * g.scale : -INFINITY;
+            mx = fmaxf(mx, v[k][j]);
+        }
+    }
+    mx = block_allreduce<4, OpMax>(mx, red);
+    const float mxs = (limit > 0 ? mx : 0.0f) * kLog2e;
+    float z = 0.0f;
+#pragma unroll
+    for (int k = 0; k < VPL; ++k)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float e = __builtin_amdgcn_exp2f(fmaf(v[k][j], kLog2e, -mxs));
+            v[k][j] = e;
+            z += e;
+        }
+    z = block_allreduce<4, OpSum>(z, red);
+    const float inv = limit > 0 ? 1.0f / z : 0.0f;
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        const int idx = threadIdx.x + k * 256;
+        if (idx < nv) {
+            float o[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o[j] = v[k][j] * inv;
+            store8<T, kNT>(y + ro + idx * kPack, o);
+            if constexpr (DROP) {
+                if (idx * kPack < limit) {
+                    float kf[8];
+                    dropout_factors8(d, static_cast<uint64_t>(row) * nv + idx, kf);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) o[j] *= kf[j];
+                }
+                store8<T, kNT>(yd + ro + idx * kPack, o);
+            }
+        }
+    }
+}
+
+template <typename T, int VPL, bool DROP>
+__global__ __launch_bounds__(256) void softmax_bwd_wide(T* dx, const T* dy, const T* __restrict__ y,
+                                                        SoftmaxLens len, SoftmaxGeom g, DropoutParams d)
+{
+    __shared__ float red[4];
+    const int64_t row = blockIdx.x;
+    const int nv = g.k_len / kPack;
+    const int limit = row_limit(g, len, row);
+    const int64_t ro = row * g.k_len;
+    RawPack<T> ry[VPL], rg[VPL];
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        const int j0 = (threadIdx.x + k * 256) * kPack;
+        if (j0 < limit) {
+            ry[k] = load_raw<T, kNT>(y + ro + j0);
+            rg[k] = load_raw<T, kNT>(dy + ro + j0);
+        } else {
+            ry[k] = zero_raw<T>();
+            rg[k] = zero_raw<T>();
+        }
+    }
+    float yv[VPL][8], gv[VPL][8];
+    float dot = 0.0f;
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        const int idx = threadIdx.x + k * 256;
+        const int j0 = idx * kPack;
+        unpack<T>(ry[k], yv[k]);
+        unpack<T>(rg[k], gv[k]);
+        if constexpr (DROP) {
+            if (j0 < limit) {
+                float kf[8];
+                dropout_factors8(d, static_cast<uint64_t>(row) * nv + idx, kf);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) gv[k][j] *= kf[j];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (j0 + j >= limit) yv[k][j] = 0.0f;
+            dot = fmaf(gv[k][j], yv[k][j], dot);
+        }
+    }
+    dot = block_allreduce<4, OpSum>(dot, red);
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        const int idx = threadIdx.x + k * 256;
+        if (idx < nv) {
+            float o[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                o[j] = (idx * kPack + j < limit) ? g.scale * yv[k][j] * (gv[k][j] - dot) : 0.0f;
+            store8<T, kNT>(dx + ro + idx * kPack, o);
+        }
+    }
+}
+
 // ---- generic path: any k_len; one wave per row, element-strided, row re-read from cache
 template <typename T>
 __global__ __launch_bounds__(256) void softmax_fwd_generic(T* y, T* __restrict__ yd, const T* x,
@@ -284,6 +408,9 @@ inline SmShape softmax_shape(int k_len)
     if (nv <= 128) return {64, 2};
     if (nv <= 192) return {64, 3};
     if (nv <= 256) return {64, 4};
+    if (nv <= 512) return {256, 2};      // one workgroup per row from here on
+    if (nv <= 1024) return {256, 4};
+    if (nv <= 2048) return {256, 8};
     return {0, 0};
 }
 
@@ -313,6 +440,14 @@ static lsq_status softmax_fwd_dispatch(void* y, void* yd, const void* x, Softmax
     }
     const int64_t blocks1 = ceil_div(g.nrows, 256 / sh.lpr);
     const dim3 block(256);
+#define W(V)                                                                                                 \
+    if (sh.lpr == 256 && sh.vpl == V) {                                                                      \
+        const dim3 grid(static_cast<unsigned>(g.nrows));                                                     \
+        if (drop) hipLaunchKernelGGL((softmax_fwd_wide<T, V, true>), grid, block, 0, s, yp, ydp, xp, key_len, g, d); \
+        else hipLaunchKernelGGL((softmax_fwd_wide<T, V, false>), grid, block, 0, s, yp, ydp, xp, key_len, g, d);    \
+    }
+    W(2) W(4) W(8)
+#undef W
 #define X(L, V)                                                                                              \
     if (sh.lpr == L && sh.vpl == V) {                                                                        \
         constexpr int R = sm_rpt(V);                                                                         \
@@ -347,6 +482,14 @@ static lsq_status softmax_bwd_dispatch(void* dx, const void* dy, const void* y, 
     }
     const int64_t blocks1 = ceil_div(g.nrows, 256 / sh.lpr);
     const dim3 block(256);
+#define W(V)                                                                                                 \
+    if (sh.lpr == 256 && sh.vpl == V) {                                                                      \
+        const dim3 grid(static_cast<unsigned>(g.nrows));                                                     \
+        if (drop) hipLaunchKernelGGL((softmax_bwd_wide<T, V, true>), grid, block, 0, s, dxp, dyp, yp, key_len, g, d); \
+        else hipLaunchKernelGGL((softmax_bwd_wide<T, V, false>), grid, block, 0, s, dxp, dyp, yp, key_len, g, d);    \
+    }
+    W(2) W(4) W(8)
+#undef W
 #define X(L, V)                                                                                              \
     if (sh.lpr == L && sh.vpl == V) {                                                                        \
         constexpr int R = sm_rpt(V);                                                                         \
@@ -380,7 +523,7 @@ static lsq_status softmax_check(const void* a, const void* b, int32_t batch, int
     g->k_len = k_len;
     g->shift = k_len - q_len;
     g->scale = scale;
-    if (ceil_div(g->nrows, 4) > 0x7FFFFFFF) return LSQ_INVALID_ARG;
+    if (g->nrows > 0x7FFFFFFF) return LSQ_INVALID_ARG;
     return LSQ_OK;
 }
 

@@ -22,6 +22,9 @@ CASES = [
     (2, 2, 7, 24, "causal", 0.0), (2, 2, 24, 40, "pad+causal", 0.1),          # q_len != k_len, end-aligned
     (2, 2, 9, 256, "pad", 0.0), (2, 2, 9, 768, "pad", 0.1), (1, 2, 5, 1536, "causal", 0.0),
     (1, 2, 3, 2048, "pad", 0.1), (1, 1, 3, 4096, "pad", 0.1), (1, 1, 2, 1, "none", 0.0),
+    # long rows: one workgroup per row (2048 < k_len <= 16384), and the fallback beyond
+    (2, 1, 4, 2056, "pad", 0.1), (1, 2, 3, 8192, "pad+causal", 0.1), (1, 1, 2, 16384, "pad", 0.0),
+    (1, 1, 2, 16392, "pad", 0.1),
 ]
 
 
