@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="time the per-op table with eager launches")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain 1 GiB -> 1 GiB elementwise copy three times (counter calibration under rocprofv3 --pmc)")
+    ap.add_argument("--skip-ops", default="", help="comma-separated operators left out of the per-op table "
+                    "(profiling runs: rows that reuse a kernel at another size would blur its per-kernel average)")
     ap.add_argument("--ops", default="", help="comma-separated subset of operators (tuning runs; the default is all nine)")
     return ap.parse_args()
 
@@ -315,6 +317,9 @@ def main():
              ("pad_remove", op_pad_remove), ("pad_restore", op_pad_restore), ("layernorm_fwd_packed", op_ln_fwd_packed),
              ("softmax_varlen_fwd", op_smv_fwd), ("softmax_varlen_bwd", op_smv_bwd),
              ("adam_step_lp", op_adam_lp), ("sgd_step", op_sgd)]
+    if args.skip_ops:
+        drop = set(args.skip_ops.split(","))
+        extra = [o for o in extra if o[0] not in drop]
     if args.ops:
         keep = set(args.ops.split(","))
         ops = [o for o in ops if o[0] in keep]

@@ -19,6 +19,10 @@ namespace lsq {
 constexpr bool kNT = LSQ_NT != 0;
 
 constexpr int kBadWaves = 4;
+#ifndef LSQ_BAD_UNROLL
+#define LSQ_BAD_UNROLL 1
+#endif
+constexpr int kBadUnroll = LSQ_BAD_UNROLL;   // rows a wave has in flight in backward
 enum { ACT_RELU = 0, ACT_GELU = 1, ACT_GELU_TANH = 2 };
 
 // sigmoid(t) = 1/(1 + 2^(-t*log2 e)): one v_exp_f32 and one v_rcp_f32 (1 ulp; an IEEE
@@ -28,10 +32,34 @@ __device__ __forceinline__ float sigmoidf_fast(float t)
     return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * t));
 }
 
+// Standard normal CDF Phi(z).  erfc(u / sqrt 2) = 2 Phi(-u), u >= 0, is evaluated as
+// 2^q(u) with q a degree-10 least-squares fit (fit_normal_cdf.py) of log2 erfc(u / sqrt 2) on Chebyshev nodes
+// of [0, 6.5] (relative error 5e-7 in exact arithmetic, 3e-6 in fp32 Horner form; beyond
+// 6.5 the tail is held at 8e-11).  The lower tail comes out with that RELATIVE accuracy
+// (no 1 + erf cancellation), the upper one as 1 - tail.  Branch-free, one v_exp_f32:
+// about half the instructions of a library erff, which made the GELU kernels ALU-bound.
+__device__ __forceinline__ float normal_cdf(float z)
+{
+    const float u = fminf(fabsf(z), 6.5f);
+    float q = -7.934565005e-09f;
+    q = fmaf(q, u, 2.847633596e-07f);
+    q = fmaf(q, u, -4.305318271e-06f);
+    q = fmaf(q, u, 3.393354200e-05f);
+    q = fmaf(q, u, -1.167951486e-04f);
+    q = fmaf(q, u, -3.832164512e-04f);
+    q = fmaf(q, u, 7.491793949e-03f);
+    q = fmaf(q, u, -5.288341269e-02f);
+    q = fmaf(q, u, -4.590395689e-01f);
+    q = fmaf(q, u, -1.151132941e+00f);
+    q = fmaf(q, u, 7.463755196e-07f);
+    const float tail = 0.5f * __builtin_amdgcn_exp2f(q);        // Phi(-|z|)
+    return z < 0.0f ? tail : 1.0f - tail;
+}
+
 template <int ACT> __device__ __forceinline__ float act_value(float z)
 {
     if constexpr (ACT == ACT_RELU) return fmaxf(z, 0.0f);
-    else if constexpr (ACT == ACT_GELU) return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
+    else if constexpr (ACT == ACT_GELU) return z * normal_cdf(z);
     else {
         // 0.5*(1 + tanh(u)) == sigmoid(2u): no cancellation in the negative tail, no tanh call
         const float u2 = 1.5957691216057308f * fmaf(0.044715f * z * z, z, z);
@@ -43,7 +71,8 @@ template <int ACT> __device__ __forceinline__ float act_slope(float z)
 {
     if constexpr (ACT == ACT_RELU) return z > 0.0f ? 1.0f : 0.0f;
     else if constexpr (ACT == ACT_GELU)
-        return fmaf(z * 0.3989422804014327f, __expf(-0.5f * z * z), 0.5f * (1.0f + erff(z * 0.70710678118654752f)));
+        // Phi(z) + z * phi(z), phi = exp(-z^2/2) / sqrt(2 pi) through one v_exp_f32
+        return fmaf(z * 0.3989422804014327f, __builtin_amdgcn_exp2f(-0.72134752044448170f * z * z), normal_cdf(z));
     else {
         // d/dz [z*sigmoid(2u)] = s + z*s*(1-s)*d(2u)/dz
         const float z2 = z * z;
@@ -90,19 +119,38 @@ __global__ __launch_bounds__(256) void bad_bwd_cols(T* dx, float* __restrict__ p
     if (active) {
         float b[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         if constexpr (HAS_BIAS) load8<T>(bias + static_cast<int64_t>(cp) * kPack, b);
-        for (int64_t r = static_cast<int64_t>(blockIdx.y) * kBadWaves + wave; r < rows; r += stride) {
-            const int64_t pack = r * ppr + cp;
-            float g[8], xf[8], k[8];
-            load8<T, kNT>(dy + pack * kPack, g);
-            load8<T, kNT>(x + pack * kPack, xf);
-            if constexpr (DROP) dropout_factors8(d, static_cast<uint64_t>(pack), k);
+        // kBadUnroll rows per trip: all their loads are issued before the first Philox call
+        for (int64_t r0 = static_cast<int64_t>(blockIdx.y) * kBadWaves + wave; r0 < rows; r0 += stride * kBadUnroll) {
+            RawPack<T> rg[kBadUnroll], rx[kBadUnroll];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float s = act_slope<ACT>(xf[j] + b[j]);
-                g[j] = DROP ? g[j] * k[j] * s : g[j] * s;
-                acc[j] += g[j];
+            for (int u = 0; u < kBadUnroll; ++u) {
+                const int64_t r = r0 + u * stride;
+                if (r < rows) {
+                    rg[u] = load_raw<T, kNT>(dy + (r * ppr + cp) * kPack);
+                    rx[u] = load_raw<T, kNT>(x + (r * ppr + cp) * kPack);
+                } else {
+                    rg[u] = zero_raw<T>();
+                    rx[u] = zero_raw<T>();
+                }
             }
-            store8<T, kNT>(dx + pack * kPack, g);
+#pragma unroll
+            for (int u = 0; u < kBadUnroll; ++u) {
+                const int64_t r = r0 + u * stride;
+                if (r < rows) {
+                    const int64_t pack = r * ppr + cp;
+                    float g[8], xf[8], k[8];
+                    unpack<T>(rg[u], g);
+                    unpack<T>(rx[u], xf);
+                    if constexpr (DROP) dropout_factors8(d, static_cast<uint64_t>(pack), k);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const float s = act_slope<ACT>(xf[j] + b[j]);
+                        g[j] = DROP ? g[j] * k[j] * s : g[j] * s;
+                        acc[j] += g[j];
+                    }
+                    store8<T, kNT>(dx + pack * kPack, g);
+                }
+            }
         }
     }
     if (partial == nullptr) return;        // uniform over the grid

@@ -311,7 +311,7 @@ __global__ __launch_bounds__(1024) void xent_sums_kernel(float* __restrict__ sum
                                                          const int32_t* __restrict__ target, int64_t tokens, int vocab,
                                                          int ignore_index)
 {
-    __shared__ double sm[3][1024];
+    __shared__ double sm[3][16];
     const int tid = threadIdx.x;
     double a = 0.0, b = 0.0, c = 0.0;
     for (int64_t t0 = tid; t0 < tokens; t0 += 8 * 1024) {
@@ -343,17 +343,21 @@ __global__ __launch_bounds__(1024) void xent_sums_kernel(float* __restrict__ sum
             }
         }
     }
-    sm[0][tid] = a; sm[1][tid] = b; sm[2][tid] = c;
-    __syncthreads();
-    for (int w = 512; w > 0; w >>= 1) {
-        if (tid < w) {
-            sm[0][tid] += sm[0][tid + w];
-            sm[1][tid] += sm[1][tid + w];
-            sm[2][tid] += sm[2][tid + w];
-        }
-        __syncthreads();
+    // fixed butterfly inside each wave, then the 16 wave totals in wave order: one barrier
+#pragma unroll
+    for (int w = 32; w > 0; w >>= 1) {
+        a += __shfl_xor(a, w, 64);
+        b += __shfl_xor(b, w, 64);
+        c += __shfl_xor(c, w, 64);
     }
-    if (tid < 3) sums[tid] = static_cast<float>(sm[tid][0]);
+    if ((tid & 63) == 0) { sm[0][tid >> 6] = a; sm[1][tid >> 6] = b; sm[2][tid >> 6] = c; }
+    __syncthreads();
+    if (tid < 3) {
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) t += sm[tid][w];
+        sums[tid] = static_cast<float>(t);
+    }
 }
 
 template <typename T>
