@@ -123,6 +123,16 @@ def _stream():
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
+def _need(name: str, t, numel: int, dtype=None):
+    """The library takes bare pointers: a tensor shorter than what the kernel will touch is refused here."""
+    if t is None:
+        return
+    if t.numel() < numel:
+        raise LsqError(f"{name} holds {t.numel()} elements, the call needs {numel}")
+    if dtype is not None and t.dtype != dtype:
+        raise LsqError(f"{name} is {t.dtype}, expected {dtype}")
+
+
 def _workspace(nbytes: int, like, ws):
     if ws is not None:
         return ws
@@ -136,6 +146,8 @@ def lsq_layernorm_fwd(x, gamma, beta, eps: float = 1e-5, y=None, mean=None, rstd
     y = torch.empty_like(x) if y is None else y
     mean = torch.empty(rows, dtype=torch.float32, device=x.device) if mean is None else mean
     rstd = torch.empty(rows, dtype=torch.float32, device=x.device) if rstd is None else rstd
+    _need("y", y, rows * hidden, x.dtype); _need("gamma", gamma, hidden, x.dtype); _need("beta", beta, hidden, x.dtype)
+    _need("mean", mean, rows, torch.float32); _need("rstd", rstd, rows, torch.float32)
     _check(load().lsq_layernorm_fwd(_ptr(y), _ptr(mean), _ptr(rstd), _ptr(x), _ptr(gamma), _ptr(beta), rows, hidden,
                                     eps, _dt(x), _stream()), "lsq_layernorm_fwd")
     return y, mean, rstd
@@ -148,6 +160,11 @@ def lsq_layernorm_bwd(dy, x, gamma, mean, rstd, dres_in=None, dx=None, dgamma=No
     dgamma = torch.empty(hidden, dtype=torch.float32, device=x.device) if dgamma is None else dgamma
     dbeta = torch.empty(hidden, dtype=torch.float32, device=x.device) if dbeta is None else dbeta
     ws = _workspace(lsq_workspace_bytes(LSQ_OP_LAYERNORM_BWD, rows, hidden), x, workspace)
+    for name, t in (("dy", dy), ("dx", dx), ("dres_in", dres_in)):
+        _need(name, t, rows * hidden, x.dtype)
+    _need("gamma", gamma, hidden, x.dtype)
+    for name, t, k in (("mean", mean, rows), ("rstd", rstd, rows), ("dgamma", dgamma, hidden), ("dbeta", dbeta, hidden)):
+        _need(name, t, k, torch.float32)
     _check(load().lsq_layernorm_bwd(_ptr(dx), _ptr(dgamma), _ptr(dbeta), _ptr(dy), _ptr(x), _ptr(gamma), _ptr(mean),
                                     _ptr(rstd), _ptr(dres_in), _ptr(ws), ws.numel() * ws.element_size(), rows, hidden,
                                     _dt(x), _stream()), "lsq_layernorm_bwd")
@@ -157,6 +174,8 @@ def lsq_layernorm_bwd(dy, x, gamma, mean, rstd, dres_in=None, dx=None, dgamma=No
 def lsq_bias_dropout_residual_fwd(x, bias, residual, p: float, seed: int, offset: int, out=None):
     rows, hidden = x.shape
     out = torch.empty_like(x) if out is None else out
+    _need("out", out, rows * hidden, x.dtype); _need("residual", residual, rows * hidden, x.dtype)
+    _need("bias", bias, hidden, x.dtype)
     _check(load().lsq_bias_dropout_residual_fwd(_ptr(out), _ptr(x), _ptr(bias), _ptr(residual), rows, hidden, p, seed,
                                                 offset, _dt(x), _stream()), "lsq_bias_dropout_residual_fwd")
     return out
@@ -170,6 +189,7 @@ def lsq_bias_dropout_residual_bwd(dy, p: float, seed: int, offset: int, want_dbi
     if want_dbias and dbias is None:
         dbias = torch.empty(hidden, dtype=torch.float32, device=dy.device)
     ws = _workspace(lsq_workspace_bytes(LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD, rows, hidden), dy, workspace)
+    _need("dx", dx, rows * hidden, dy.dtype); _need("dbias", dbias, hidden, torch.float32)
     _check(load().lsq_bias_dropout_residual_bwd(_ptr(dx), _ptr(dbias) if want_dbias else None, _ptr(dy), rows, hidden,
                                                 p, seed, offset, _ptr(ws), ws.numel() * ws.element_size(), _dt(dy),
                                                 _stream()), "lsq_bias_dropout_residual_bwd")
@@ -183,6 +203,8 @@ def lsq_softmax_fwd(x, key_len=None, causal: bool = False, scale: float = 1.0, p
     y = torch.empty_like(x) if y is None else y
     if p_attn > 0 and y_drop is None:
         y_drop = torch.empty_like(x)
+    _need("y", y, x.numel(), x.dtype); _need("y_drop", y_drop, x.numel(), x.dtype)
+    _need("key_len", key_len, B, torch.int32)
     _check(load().lsq_softmax_fwd(_ptr(y), _ptr(y_drop) if p_attn > 0 else None, _ptr(x), _ptr(key_len), B, N, Lq, Lk,
                                   int(causal), scale, p_attn, seed, offset, _dt(x), _stream()), "lsq_softmax_fwd")
     return y, (y_drop if p_attn > 0 else None)
@@ -192,6 +214,7 @@ def lsq_softmax_bwd(dy, y, key_len=None, causal: bool = False, scale: float = 1.
                     offset: int = 0, dx=None):
     B, N, Lq, Lk = y.shape
     dx = torch.empty_like(y) if dx is None else dx
+    _need("dx", dx, y.numel(), y.dtype); _need("dy", dy, y.numel(), y.dtype); _need("key_len", key_len, B, torch.int32)
     _check(load().lsq_softmax_bwd(_ptr(dx), _ptr(dy), _ptr(y), _ptr(key_len), B, N, Lq, Lk, int(causal), scale, p_attn,
                                   seed, offset, _dt(y), _stream()), "lsq_softmax_bwd")
     return dx
@@ -208,8 +231,9 @@ def lsq_ls_xent_fwd(logits, target, alpha: float, ignore_index: int = -100, want
         nll = torch.empty(T, dtype=torch.float32, device=logits.device)
     if want_sums and sums is None:
         sums = torch.empty(3, dtype=torch.float32, device=logits.device)
-    if target.dtype != torch.int32:
-        raise LsqError("target must be int32")
+    _need("target", target, T, torch.int32)
+    for name, t, k in (("loss", loss, T), ("nll", nll, T), ("lse", lse, T), ("sums", sums, 3)):
+        _need(name, t, k, torch.float32)
     _check(load().lsq_ls_xent_fwd(_ptr(loss), _ptr(nll) if want_nll else None, _ptr(lse),
                                   _ptr(sums) if want_sums else None, _ptr(logits), _ptr(target), T, V, alpha,
                                   ignore_index, _dt(logits), _stream()), "lsq_ls_xent_fwd")
@@ -220,8 +244,8 @@ def lsq_ls_xent_bwd(logits, lse, target, alpha: float, ignore_index: int = -100,
                     dlogits=None):
     T, V = logits.shape
     dlogits = torch.empty_like(logits) if dlogits is None else dlogits
-    if target.dtype != torch.int32:
-        raise LsqError("target must be int32")
+    _need("target", target, T, torch.int32); _need("lse", lse, T, torch.float32)
+    _need("dlogits", dlogits, T * V, logits.dtype)
     _check(load().lsq_ls_xent_bwd(_ptr(dlogits), _ptr(logits), _ptr(lse), _ptr(target), T, V, alpha, ignore_index,
                                   grad_scale, _dt(logits), _stream()), "lsq_ls_xent_bwd")
     return dlogits
@@ -235,6 +259,7 @@ def lsq_adam_step(p, m, v, g, p_lp=None, *, lr: float, beta1: float, beta2: floa
         if t.dtype != torch.float32:
             raise LsqError("p, m, v must be fp32")
     n = p.numel()
+    _need("m", m, n); _need("v", v, n); _need("g", g, n); _need("p_lp", p_lp, n)
     _check(load().lsq_adam_step(_ptr(p), _ptr(m), _ptr(v), _ptr(g), _ptr(p_lp), n, lr, beta1, beta2, eps, weight_decay,
                                 step, int(adamw), int(bias_correction), inv_grad_scale, _dt(g),
                                 _dt(p_lp) if p_lp is not None else LSQ_F16, _stream()), "lsq_adam_step")
@@ -245,6 +270,7 @@ def lsq_bias_act_dropout_fwd(x, bias, act: str, p: float, seed: int, offset: int
     """out = Dropout_p(act(x + bias)); act in {"relu", "gelu", "gelu_tanh"}."""
     rows, hidden = x.shape
     out = torch.empty_like(x) if out is None else out
+    _need("out", out, rows * hidden, x.dtype); _need("bias", bias, hidden, x.dtype)
     _check(load().lsq_bias_act_dropout_fwd(_ptr(out), _ptr(x), _ptr(bias), rows, hidden, LSQ_ACT[act], p, seed, offset,
                                            _dt(x), _stream()), "lsq_bias_act_dropout_fwd")
     return out
@@ -258,6 +284,8 @@ def lsq_bias_act_dropout_bwd(dy, x, bias, act: str, p: float, seed: int, offset:
     if want_dbias and dbias is None:
         dbias = torch.empty(hidden, dtype=torch.float32, device=x.device)
     ws = _workspace(lsq_workspace_bytes(LSQ_OP_BIAS_ACT_DROPOUT_BWD, rows, hidden), x, workspace)
+    _need("dy", dy, rows * hidden, x.dtype); _need("dx", dx, rows * hidden, x.dtype)
+    _need("bias", bias, hidden, x.dtype); _need("dbias", dbias, hidden, torch.float32)
     _check(load().lsq_bias_act_dropout_bwd(_ptr(dx), _ptr(dbias) if want_dbias else None, _ptr(dy), _ptr(x), _ptr(bias),
                                            rows, hidden, LSQ_ACT[act], p, seed, offset, _ptr(ws),
                                            ws.numel() * ws.element_size(), _dt(x), _stream()), "lsq_bias_act_dropout_bwd")
@@ -270,6 +298,7 @@ def lsq_adam_step_lp(p_lp, m, v, g, *, lr: float, beta1: float, beta2: float, ep
     """In place on the low-precision p_lp and fp32 m, v (flat); g in the same low precision."""
     if g.dtype != p_lp.dtype:
         raise LsqError("g and p_lp must share one low-precision dtype")
+    _need("m", m, p_lp.numel(), torch.float32); _need("v", v, p_lp.numel(), torch.float32); _need("g", g, p_lp.numel())
     _check(load().lsq_adam_step_lp(_ptr(p_lp), _ptr(m), _ptr(v), _ptr(g), p_lp.numel(), lr, beta1, beta2, eps,
                                    weight_decay, step, int(adamw), int(bias_correction), inv_grad_scale, _dt(p_lp),
                                    _stream()), "lsq_adam_step_lp")
@@ -281,6 +310,7 @@ def lsq_sgd_step(p, momentum_buf, g, p_lp=None, *, lr: float, momentum: float = 
     """In place on fp32 p (and momentum_buf if momentum > 0); p_lp optional low-precision copy out."""
     if p.dtype != torch.float32:
         raise LsqError("p must be fp32")
+    _need("momentum_buf", momentum_buf, p.numel(), torch.float32); _need("g", g, p.numel()); _need("p_lp", p_lp, p.numel())
     _check(load().lsq_sgd_step(_ptr(p), _ptr(momentum_buf), _ptr(g), _ptr(p_lp), p.numel(), lr, momentum, weight_decay,
                                int(nesterov), inv_grad_scale, _dt(g), _dt(p_lp) if p_lp is not None else LSQ_F16,
                                _stream()), "lsq_sgd_step")
@@ -291,7 +321,13 @@ def lsq_split_heads_fwd(x, bias, batch: int, length: int, heads: int, head_dim: 
     """x: [batch*len, parts*heads*head_dim] (+ bias) -> list of `parts` tensors [batch, heads, len, head_dim]."""
     if outs is None:
         outs = [torch.empty((batch, heads, length, head_dim), dtype=x.dtype, device=x.device) for _ in range(parts)]
-    ptrs = [_ptr(o) for o in outs] + [None] * (3 - parts)
+    hidden = heads * head_dim
+    _need("x", x, batch * length * parts * hidden); _need("bias", bias, parts * hidden, x.dtype)
+    if len(outs) < parts:
+        raise LsqError(f"{parts} parts need {parts} output tensors")
+    for o in outs[:parts]:
+        _need("out", o, batch * length * hidden, x.dtype)
+    ptrs = [_ptr(o) for o in outs[:parts]] + [None] * (3 - parts)
     _check(load().lsq_split_heads_fwd(ptrs[0], ptrs[1], ptrs[2], _ptr(x), _ptr(bias), batch, length, heads, head_dim,
                                       parts, _dt(x), _stream()), "lsq_split_heads_fwd")
     return outs
@@ -307,6 +343,11 @@ def lsq_split_heads_bwd(grads, batch: int, length: int, heads: int, head_dim: in
     if want_dbias and dbias is None:
         dbias = torch.empty(cols, dtype=torch.float32, device=g0.device)
     ws = _workspace(lsq_workspace_bytes(LSQ_OP_SPLIT_HEADS_BWD, batch * length, cols), g0, workspace)
+    if not 1 <= parts <= 3:
+        raise LsqError("1 to 3 parts")
+    for g in grads:
+        _need("grad", g, batch * length * heads * head_dim, g0.dtype)
+    _need("din", din, batch * length * cols, g0.dtype); _need("dbias", dbias, cols, torch.float32)
     ptrs = [_ptr(g) for g in grads] + [None] * (3 - parts)
     _check(load().lsq_split_heads_bwd(_ptr(din), _ptr(dbias) if want_dbias else None, ptrs[0], ptrs[1], ptrs[2], batch,
                                       length, heads, head_dim, parts, _ptr(ws), ws.numel() * ws.element_size(), _dt(g0),
@@ -318,6 +359,7 @@ def lsq_merge_heads_fwd(x, out=None):
     """x: [batch, heads, len, head_dim] -> [batch*len, heads*head_dim]."""
     B, N, Ln, D = x.shape
     out = torch.empty((B * Ln, N * D), dtype=x.dtype, device=x.device) if out is None else out
+    _need("out", out, x.numel(), x.dtype)
     _check(load().lsq_merge_heads_fwd(_ptr(out), _ptr(x), B, Ln, N, D, _dt(x), _stream()), "lsq_merge_heads_fwd")
     return out
 
@@ -325,6 +367,7 @@ def lsq_merge_heads_fwd(x, out=None):
 def lsq_merge_heads_bwd(dy, batch: int, length: int, heads: int, head_dim: int, dx=None):
     """dy: [batch*len, heads*head_dim] -> [batch, heads, len, head_dim]."""
     dx = torch.empty((batch, heads, length, head_dim), dtype=dy.dtype, device=dy.device) if dx is None else dx
+    _need("dy", dy, batch * heads * length * head_dim); _need("dx", dx, batch * heads * length * head_dim, dy.dtype)
     _check(load().lsq_merge_heads_bwd(_ptr(dx), _ptr(dy), batch, length, heads, head_dim, _dt(dy), _stream()),
            "lsq_merge_heads_bwd")
     return dx
@@ -337,6 +380,9 @@ def lsq_embedding_fwd(tokens, emb, pos, pad_idx: int, scale: float, p: float, se
     B, Ln = tokens.shape
     V, H = emb.shape
     out = torch.empty((B * Ln, H), dtype=emb.dtype, device=emb.device) if out is None else out
+    _need("out", out, B * Ln * H, emb.dtype); _need("pos", pos, Ln * H, emb.dtype)
+    if pos.shape[-1] != H:
+        raise LsqError("pos must be [>= len, hidden]")
     _check(load().lsq_embedding_fwd(_ptr(out), _ptr(tokens), _ptr(emb), _ptr(pos), B, Ln, H, V, pad_idx, scale, p, seed,
                                     offset, _dt(emb), _stream()), "lsq_embedding_fwd")
     return out
@@ -350,6 +396,7 @@ def lsq_embedding_bwd(demb, dpos, dy, tokens, pad_idx: int, scale: float, p: flo
     B, Ln = tokens.shape
     V, H = demb.shape
     ws = _workspace(lsq_workspace_bytes(LSQ_OP_EMBEDDING_BWD, B * Ln, H), dy, workspace)
+    _need("dy", dy, B * Ln * H, demb.dtype); _need("dpos", dpos, Ln * H, demb.dtype)
     _check(load().lsq_embedding_bwd(_ptr(demb), _ptr(dpos), _ptr(dy), _ptr(tokens), B, Ln, H, V, pad_idx, scale, p, seed,
                                     offset, _ptr(ws), ws.numel() * ws.element_size(), _dt(demb), _stream()),
            "lsq_embedding_bwd")
@@ -361,6 +408,7 @@ def lsq_pad_offsets(key_len, batch: int, max_len: int, offsets=None):
     if offsets is None:
         dev = key_len.device if key_len is not None else torch.device("cuda", torch.cuda.current_device())
         offsets = torch.empty(batch + 1, dtype=torch.int32, device=dev)
+    _need("key_len", key_len, batch, torch.int32); _need("offsets", offsets, batch + 1, torch.int32)
     _check(load().lsq_pad_offsets(_ptr(offsets), _ptr(key_len), batch, max_len, _stream()), "lsq_pad_offsets")
     return offsets
 
@@ -369,6 +417,9 @@ def lsq_pad_remove(padded, offsets, packed_rows: int, packed=None):
     """padded: [batch, max_len, hidden] -> packed [packed_rows, hidden] (rows from sum(len) on are not written)."""
     B, L, H = padded.shape
     packed = torch.empty((packed_rows, H), dtype=padded.dtype, device=padded.device) if packed is None else packed
+    _need("offsets", offsets, B + 1, torch.int32)
+    if packed.dim() != 2 or packed.shape[1] != H or packed.dtype != padded.dtype:
+        raise LsqError("packed must be [rows, hidden] of the padded tensor's dtype")
     _check(load().lsq_pad_remove(_ptr(packed) if packed.numel() else None, _ptr(padded) if padded.numel() else None,
                                  _ptr(offsets), B, L, H, packed.shape[0], _dt(padded), _stream()), "lsq_pad_remove")
     return packed
@@ -378,6 +429,7 @@ def lsq_pad_restore(packed, offsets, batch: int, max_len: int, padded=None):
     """packed: [rows, hidden] -> padded [batch, max_len, hidden], zeros on the padding."""
     H = packed.shape[1]
     padded = torch.empty((batch, max_len, H), dtype=packed.dtype, device=packed.device) if padded is None else padded
+    _need("offsets", offsets, batch + 1, torch.int32); _need("padded", padded, batch * max_len * H, packed.dtype)
     _check(load().lsq_pad_restore(_ptr(padded) if padded.numel() else None, _ptr(packed) if packed.numel() else None,
                                   _ptr(offsets), batch, max_len, H, packed.shape[0], _dt(packed), _stream()),
            "lsq_pad_restore")
@@ -391,6 +443,8 @@ def lsq_softmax_varlen_fwd(x, key_len=None, query_len=None, causal: bool = False
     y = torch.empty_like(x) if y is None else y
     if p_attn > 0 and y_drop is None:
         y_drop = torch.empty_like(x)
+    _need("y", y, x.numel(), x.dtype); _need("y_drop", y_drop, x.numel(), x.dtype)
+    _need("key_len", key_len, B, torch.int32); _need("query_len", query_len, B, torch.int32)
     _check(load().lsq_softmax_varlen_fwd(_ptr(y), _ptr(y_drop) if p_attn > 0 else None, _ptr(x), _ptr(key_len),
                                          _ptr(query_len), B, N, Lq, Lk, int(causal), scale, p_attn, seed, offset,
                                          _dt(x), _stream()), "lsq_softmax_varlen_fwd")
@@ -401,6 +455,8 @@ def lsq_softmax_varlen_bwd(dy, y, key_len=None, query_len=None, causal: bool = F
                            p_attn: float = 0.0, seed: int = 0, offset: int = 0, dx=None):
     B, N, Lq, Lk = y.shape
     dx = torch.empty_like(y) if dx is None else dx
+    _need("dx", dx, y.numel(), y.dtype); _need("dy", dy, y.numel(), y.dtype)
+    _need("key_len", key_len, B, torch.int32); _need("query_len", query_len, B, torch.int32)
     _check(load().lsq_softmax_varlen_bwd(_ptr(dx), _ptr(dy), _ptr(y), _ptr(key_len), _ptr(query_len), B, N, Lq, Lk,
                                          int(causal), scale, p_attn, seed, offset, _dt(y), _stream()),
            "lsq_softmax_varlen_bwd")

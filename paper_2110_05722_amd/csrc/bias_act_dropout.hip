@@ -34,7 +34,7 @@ __device__ __forceinline__ float sigmoidf_fast(float t)
 
 // Standard normal CDF Phi(z).  erfc(u / sqrt 2) = 2 Phi(-u), u >= 0, is evaluated as
 // 2^q(u) with q a degree-10 least-squares fit (fit_normal_cdf.py) of log2 erfc(u / sqrt 2) on Chebyshev nodes
-// of [0, 6.5] (relative error 5e-7 in exact arithmetic, 3e-6 in fp32 Horner form; beyond
+// of [0, 6.5] (relative error 5e-7 in exact arithmetic, 5e-6 in fp32 Horner form; beyond
 // 6.5 the tail is held at 8e-11).  The lower tail comes out with that RELATIVE accuracy
 // (no 1 + erf cancellation), the upper one as 1 - tail.  Branch-free, one v_exp_f32:
 // about half the instructions of a library erff, which made the GELU kernels ALU-bound.

@@ -142,3 +142,15 @@ def test_binding_refuses_cpu_tensors(lib):
     x = torch.zeros(4, 8, dtype=torch.float16)
     with pytest.raises(L.LsqError):
         L.lsq_layernorm_fwd(x, x[0], x[0])
+
+
+def test_binding_refuses_operands_shorter_than_the_call_needs(lib):
+    import torch
+    x = torch.zeros(4, 8, dtype=torch.float16)
+    with pytest.raises(L.LsqError, match="gamma holds 4 elements"):
+        L.lsq_layernorm_fwd(x, x[0][:4], x[0])
+    p = torch.zeros(16)
+    with pytest.raises(L.LsqError, match="v holds 8 elements"):
+        L.lsq_adam_step(p, p.clone(), p[:8].clone(), p.half(), None, lr=1e-3, beta1=0.9, beta2=0.98, eps=1e-8, step=1)
+    with pytest.raises(L.LsqError, match="mean is torch.float16"):
+        L.lsq_layernorm_fwd(x, x[0], x[0], mean=torch.zeros(4, dtype=torch.float16))
