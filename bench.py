@@ -7,6 +7,10 @@ A "step" is one pass of the whole hot path over one synthetic batch of the chose
 configuration: layernorm fwd, softmax fwd, bias+dropout+residual fwd, criterion
 fwd, criterion bwd, bias+dropout+residual bwd, softmax bwd, layernorm bwd and one
 Adam step over the flat workspace, each through the C-ABI, inputs resident in HBM.
+The Adam leg runs on the blocked optimizer state by default (lsq_adam_step_blocked:
+same arithmetic and bytes as lsq_adam_step, the trainer's private p, m, v interleaved
+in 8 Ki-element blocks); the same step with lsq_adam_step on three separate arrays is
+timed right after it and reported under "same_step_other_adam_layout".
 The layer-sized tensors (tens of MiB) rotate through enough buffer sets that
 neither L2 nor the 256 MB Infinity Cache can serve them ("cold" numbers).
 
@@ -45,6 +49,9 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="time the per-op table with eager launches")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain 1 GiB -> 1 GiB elementwise copy three times (counter calibration under rocprofv3 --pmc)")
+    ap.add_argument("--adam-state", default="blocked", choices=["blocked", "flat"],
+                    help="trainer leg of the step: lsq_adam_step_blocked on the blocked optimizer state (default), or "
+                         "lsq_adam_step on three separate fp32 arrays; the other one is timed too and reported beside it")
     ap.add_argument("--skip-ops", default="", help="comma-separated operators left out of the per-op table "
                     "(profiling runs: rows that reuse a kernel at another size would blur its per-kernel average)")
     ap.add_argument("--ops", default="", help="comma-separated subset of operators (tuning runs; the default is all nine)")
@@ -277,6 +284,15 @@ def main():
         a = soft[i % soft_sets]
         L.lsq_softmax_varlen_bwd(a["dy"], a["y"], key_len, key_len, causal, scale, pa, ps, 1000 + i, dx=a["dx"])
 
+    # the same Adam step on the blocked optimizer state (p, m, v interleaved in 8 Ki-element blocks)
+    state_blocked = None
+    if not args.ops or "adam_step_blocked" in args.ops.split(",") or args.adam_state == "blocked":
+        state_blocked = L.lsq_adam_state_pack(p, m, v)
+
+    def op_adam_blocked(i):
+        state["step"] += 1
+        L.lsq_adam_step_blocked(state_blocked, g, p_lp, step=state["step"], **ADAM_HYPER)
+
     def op_adam_lp(i):
         state["step"] += 1
         L.lsq_adam_step_lp(p_lp, m, v, g, step=state["step"], **ADAM_HYPER)
@@ -296,7 +312,7 @@ def main():
         "ls_xent_bwd": 2 * t_active * V + 2 * T * V + 8 * T,
         "adam_step": 28 * n,
         "bias_act_dropout_fwd": 4 * EF + 2 * F, "bias_act_dropout_bwd": 6 * EF + 6 * F,
-        "adam_step_lp": 22 * n, "sgd_step": 20 * n,
+        "adam_step_lp": 22 * n, "sgd_step": 20 * n, "adam_step_blocked": 28 * n,
         "embedding_fwd": 4 * E + 4 * T, "embedding_bwd": 2 * E + 4 * n_unique * H + 4 * Lq * H + 4 * T,
         "split_heads_fwd": 12 * E + 6 * H, "split_heads_bwd": 12 * E + 12 * H, "merge_heads_fwd": 4 * E,
         "pad_remove": 4 * T_real * H + 4 * B, "pad_restore": 2 * T_real * H + 2 * E + 4 * B,
@@ -307,11 +323,15 @@ def main():
     ops = [
         ("layernorm_fwd", op_ln_fwd), ("softmax_fwd", op_sm_fwd), ("bias_dropout_residual_fwd", op_bdr_fwd),
         ("ls_xent_fwd", op_xent_fwd), ("ls_xent_bwd", op_xent_bwd), ("bias_dropout_residual_bwd", op_bdr_bwd),
-        ("softmax_bwd", op_sm_bwd), ("layernorm_bwd", op_ln_bwd), ("adam_step", op_adam),
+        ("softmax_bwd", op_sm_bwd), ("layernorm_bwd", op_ln_bwd),
     ]
+    # the trainer leg: same arithmetic and bytes either way, the layout of the private fp32 state differs
+    adam_main = ("adam_step_blocked", op_adam_blocked) if args.adam_state == "blocked" else ("adam_step", op_adam)
+    adam_other = ("adam_step", op_adam) if args.adam_state == "blocked" else ("adam_step_blocked", op_adam_blocked)
+    ops.append(adam_main)
 
     all_nine = list(ops)
-    extra = [("bias_act_dropout_fwd", op_bad_fwd), ("bias_act_dropout_bwd", op_bad_bwd),
+    extra = [adam_other, ("bias_act_dropout_fwd", op_bad_fwd), ("bias_act_dropout_bwd", op_bad_bwd),
              ("embedding_fwd", op_emb_fwd), ("embedding_bwd", op_emb_bwd),
              ("split_heads_fwd", op_split_fwd), ("split_heads_bwd", op_split_bwd), ("merge_heads_fwd", op_merge_fwd),
              ("pad_remove", op_pad_remove), ("pad_restore", op_pad_restore), ("layernorm_fwd_packed", op_ln_fwd_packed),
@@ -332,28 +352,39 @@ def main():
             f(i)
 
     # ---------------------------------------------------------- timed region
-    for i in range(args.warmup):
-        one_step(i)
-    torch.cuda.synchronize()
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        for name, f in ops:
-            if name == "adam_step":
-                ev[i][0].record()
-                f(args.warmup + i)
-                ev[i][1].record()
-            else:
-                f(args.warmup + i)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    def time_steps(op_list):
+        """W warm-up steps, then K timed steps; events bracket the trainer launch inside the timed region."""
+        for i in range(args.warmup):
+            for _, f in op_list:
+                f(i)
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            for name, f in op_list:
+                if name.startswith("adam_step"):
+                    ev[i][0].record()
+                    f(args.warmup + i)
+                    ev[i][1].record()
+                else:
+                    f(args.warmup + i)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        has_adam = any(nm.startswith("adam_step") for nm, _ in op_list)
+        return (t1 - t0) * 1e3 / args.steps, (float(np.mean([a.elapsed_time(b) for a, b in ev])) if has_adam else float("nan"))
+
+    ms_per_step, adam_ms = time_steps(ops)
     names = [o[0] for o in ops]
-    adam_ms = float(np.mean([a.elapsed_time(b) for a, b in ev])) if "adam_step" in names else float("nan")
     step_bytes = sum(bts[k] for k in names)
     if not names:
         ms_per_step, step_bytes = float("nan"), 0
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    other = None
+    if not args.ops:      # the same step with the other trainer layout, for the record
+        ms_o, adam_ms_o = time_steps(ops[:-1] + [adam_other])
+        other = {"entry_point": "lsq_" + adam_other[0], "value": round(step_bytes / (ms_o * 1e-3) / 1e9, 1),
+                 "ms_per_step": round(ms_o, 4), "adam_avg_launch_ms": round(adam_ms_o, 4),
+                 "adam_frac_of_peak": round(bts["adam_step"] / (adam_ms_o * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
 
     # ------------------------------------------- per-operator table (cold, back to back)
     # `reps` launches of one operator are captured into a HIP graph and the graph is replayed
@@ -409,8 +440,9 @@ def main():
         del src, dst
 
     achieved = bts["adam_step"] / (adam_ms * 1e-3) / 1e9
-    roofline = {"kernel": "adam_kernel", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": _traffic(cfg.name, dt),
+    roofline = {"kernel": "adam_kernel (" + ("blocked optimizer state" if args.adam_state == "blocked" else "separate p, m, v arrays") + ")",
+                "entry_point": "lsq_" + adam_main[0], "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": _traffic(cfg.name, dt, args.adam_state),
                 "bytes_per_launch": int(bts["adam_step"]), "avg_launch_ms": round(adam_ms, 4)}
 
     out = {
@@ -423,9 +455,11 @@ def main():
                                f"{'causal' if causal else 'key-padding'} softmax, storage {dt}",
                    "buffers": "warm" if args.warm else f"cold (layer tensors rotate over {sets} sets, softmax over {soft_sets})"},
         "roofline": roofline,
+        "same_step_other_adam_layout": other,
         "ops": table, "ops_timing": timing,
         "ops_next": dict(next_table, note=f"rows beyond the nine: FFN bias+{act}+dropout(p={pa}) on [{T}, {F}], the paper's "
-                                          "low-precision-parameter Adam (22 B/param), SGD with momentum (20 B/param), "
+                                          "low-precision-parameter Adam (22 B/param), SGD with momentum (20 B/param), Adam on the blocked "
+                                          "optimizer state (p, m, v interleaved in 8 Ki-element blocks; same 28 B/param), "
                                           f"QKV bias + head split on [{T}, {3 * H}] and its backward, head merge, embedding of {T} Zipf-"
                                           f"distributed tokens ({n_unique} distinct ids) into [{T}, {H}] and its backward; padding removal "
                                           f"({T_real} real rows of {T}): pack, unpack, LayerNorm on the packed rows, softmax "
@@ -454,13 +488,13 @@ def _allowed_elements(cfg, key_len, query_len=None):
     return total
 
 
-def _traffic(cfg_name, dt):
+def _traffic(cfg_name, dt, adam_state="blocked"):
     """HBM bytes per Adam launch as measured by rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by the
     copy-kernel calibration): read from the committed profile summary of this workload, if there is one."""
     path = os.path.join(ROOT, "profiles", f"adam_kernel_{cfg_name}_{dt}_pmc.txt")
     try:
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
+            if line.startswith(f"traffic_bytes_per_launch_{adam_state}:"):
                 return int(float(line.split(":", 1)[1].strip()))
     except OSError:
         pass

@@ -30,6 +30,7 @@ EXPORTS = [
     "lsq_bias_act_dropout_fwd", "lsq_bias_act_dropout_bwd", "lsq_adam_step_lp", "lsq_sgd_step",
     "lsq_split_heads_fwd", "lsq_split_heads_bwd", "lsq_merge_heads_fwd", "lsq_merge_heads_bwd",
     "lsq_embedding_fwd", "lsq_embedding_bwd",
+    "lsq_adam_state_bytes", "lsq_adam_state_pack", "lsq_adam_state_unpack", "lsq_adam_step_blocked",
     "lsq_pad_offsets", "lsq_pad_remove", "lsq_pad_restore", "lsq_softmax_varlen_fwd", "lsq_softmax_varlen_bwd",
 ]
 
@@ -75,6 +76,10 @@ def load():
         "lsq_merge_heads_bwd": (C.c_int, [vp, vp, i32, i32, i32, i32, C.c_int, vp]),
         "lsq_embedding_fwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64, C.c_int, vp]),
         "lsq_embedding_bwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64, vp, sz, C.c_int, vp]),
+        "lsq_adam_state_bytes": (sz, [i64]),
+        "lsq_adam_state_pack": (C.c_int, [vp, vp, vp, vp, i64, vp]),
+        "lsq_adam_state_unpack": (C.c_int, [vp, vp, vp, vp, i64, vp]),
+        "lsq_adam_step_blocked": (C.c_int, [vp, vp, vp, i64, f32, f32, f32, f32, f32, i32, i32, i32, f32, C.c_int, C.c_int, vp]),
         "lsq_pad_offsets": (C.c_int, [vp, vp, i32, i32, vp]),
         "lsq_pad_remove": (C.c_int, [vp, vp, vp, i32, i32, i32, i64, C.c_int, vp]),
         "lsq_pad_restore": (C.c_int, [vp, vp, vp, i32, i32, i32, i64, C.c_int, vp]),
@@ -401,6 +406,49 @@ def lsq_embedding_bwd(demb, dpos, dy, tokens, pad_idx: int, scale: float, p: flo
                                     offset, _ptr(ws), ws.numel() * ws.element_size(), _dt(demb), _stream()),
            "lsq_embedding_bwd")
     return demb, dpos
+
+
+LSQ_ADAM_BLOCK = 8192
+
+
+def lsq_adam_state_bytes(n: int) -> int:
+    return int(load().lsq_adam_state_bytes(n))
+
+
+def lsq_adam_state_pack(p, m=None, v=None, state=None):
+    """fp32 p (and m, v; None = zeros) -> blocked optimizer state (fp32, lsq_adam_state_bytes(n) bytes)."""
+    n = p.numel()
+    need = lsq_adam_state_bytes(n) // 4
+    state = torch.empty(need, dtype=torch.float32, device=p.device) if state is None else state
+    _need("state", state, need, torch.float32); _need("p", p, n, torch.float32)
+    _need("m", m, n, torch.float32); _need("v", v, n, torch.float32)
+    _check(load().lsq_adam_state_pack(_ptr(state), _ptr(p), _ptr(m), _ptr(v), n, _stream()), "lsq_adam_state_pack")
+    return state
+
+
+def lsq_adam_state_unpack(state, n: int, p=None, m=None, v=None, want=("p", "m", "v")):
+    """Blocked optimizer state -> (p, m, v) fp32[n]; entries not in `want` (and not passed) come back as None."""
+    dev = state.device
+    p = torch.empty(n, dtype=torch.float32, device=dev) if p is None and "p" in want else p
+    m = torch.empty(n, dtype=torch.float32, device=dev) if m is None and "m" in want else m
+    v = torch.empty(n, dtype=torch.float32, device=dev) if v is None and "v" in want else v
+    _need("state", state, lsq_adam_state_bytes(n) // 4, torch.float32)
+    for name, t in (("p", p), ("m", m), ("v", v)):
+        _need(name, t, n, torch.float32)
+    _check(load().lsq_adam_state_unpack(_ptr(p), _ptr(m), _ptr(v), _ptr(state), n, _stream()), "lsq_adam_state_unpack")
+    return p, m, v
+
+
+def lsq_adam_step_blocked(state, g, p_lp=None, *, lr: float, beta1: float, beta2: float, eps: float, step: int,
+                          weight_decay: float = 0.0, adamw: bool = False, bias_correction: bool = True,
+                          inv_grad_scale: float = 1.0):
+    """lsq_adam_step on the blocked state (in place); g [n] low precision or fp32; p_lp optional copy out."""
+    n = g.numel()
+    _need("state", state, lsq_adam_state_bytes(n) // 4, torch.float32); _need("p_lp", p_lp, n)
+    _check(load().lsq_adam_step_blocked(_ptr(state), _ptr(g), _ptr(p_lp), n, lr, beta1, beta2, eps, weight_decay, step,
+                                        int(adamw), int(bias_correction), inv_grad_scale, _dt(g),
+                                        _dt(p_lp) if p_lp is not None else LSQ_F16, _stream()), "lsq_adam_step_blocked")
+    return state, p_lp
 
 
 def lsq_pad_offsets(key_len, batch: int, max_len: int, offsets=None):

@@ -32,12 +32,33 @@ __device__ __forceinline__ void adam_update(float& p, float& m, float& v, float 
 
 constexpr int kAdamPack = 4;
 
-template <typename G, typename PL, bool HAS_PL>
+// Blocked optimizer state: the three fp32 arrays that only the trainer reads are kept
+// as blocks of kAdamBlock elements, [p block | m block | v block] back to back, instead
+// of three arrays a gigabyte apart.  The bytes moved are the same; the read-modify-write
+// then walks ONE address stream (plus g in, p_lp out) instead of three, which the
+// memory system rewards: 6.3 TB/s against 5.5-5.85 TB/s measured at 774 M parameters.
+// Swept 1 Ki .. 1 Mi elements per block: 8 Ki is the optimum, 64 Ki+ gives back half of it.
+constexpr int kAdamBlock = LSQ_ADAM_BLOCK;
+static_assert(kAdamBlock % (256 * kAdamPack) == 0, "a workgroup must not straddle a block");
+
+// offset of element e of the p array inside the blocked state; m and v follow at +1 and +2 blocks
+__device__ __host__ __forceinline__ int64_t adam_state_offset(int64_t e)
+{
+    return (e / kAdamBlock) * (3 * static_cast<int64_t>(kAdamBlock)) + (e % kAdamBlock);
+}
+
+template <typename G, typename PL, bool HAS_PL, bool BLOCKED>
 __global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ p, float* __restrict__ m,
                                                    float* __restrict__ v, const G* __restrict__ g,
                                                    PL* __restrict__ plp, int64_t n, AdamParams a)
 {
     const int64_t e = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * kAdamPack;
+    if constexpr (BLOCKED) {        // p is the state; this thread's pack sits at one offset in all three blocks
+        const int64_t so = adam_state_offset(e) - e;
+        p += so;
+        m = p + kAdamBlock;
+        v = p + 2 * kAdamBlock;
+    }
     if (e + kAdamPack <= n) {
         float pf[4], mf[4], vf[4], gf[4];
         load4<float, true>(p + e, pf);
@@ -67,7 +88,7 @@ __global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ p, float*
     }
 }
 
-template <typename G>
+template <typename G, bool BLOCKED>
 static lsq_status adam_dispatch(float* p, float* m, float* v, const void* g, void* plp, int64_t n,
                                 const AdamParams& a, int p_lp_dt, hipStream_t s)
 {
@@ -75,12 +96,44 @@ static lsq_status adam_dispatch(float* p, float* m, float* v, const void* g, voi
     const dim3 grid(static_cast<unsigned>(ceil_div(packs, 256))), block(256);
     const G* gp = static_cast<const G*>(g);
     if (!plp)
-        hipLaunchKernelGGL((adam_kernel<G, f16, false>), grid, block, 0, s, p, m, v, gp, static_cast<f16*>(nullptr), n, a);
+        hipLaunchKernelGGL((adam_kernel<G, f16, false, BLOCKED>), grid, block, 0, s, p, m, v, gp, static_cast<f16*>(nullptr), n, a);
     else if (p_lp_dt == LSQ_F16)
-        hipLaunchKernelGGL((adam_kernel<G, f16, true>), grid, block, 0, s, p, m, v, gp, static_cast<f16*>(plp), n, a);
+        hipLaunchKernelGGL((adam_kernel<G, f16, true, BLOCKED>), grid, block, 0, s, p, m, v, gp, static_cast<f16*>(plp), n, a);
     else
-        hipLaunchKernelGGL((adam_kernel<G, bf16, true>), grid, block, 0, s, p, m, v, gp, static_cast<bf16*>(plp), n, a);
+        hipLaunchKernelGGL((adam_kernel<G, bf16, true, BLOCKED>), grid, block, 0, s, p, m, v, gp, static_cast<bf16*>(plp), n, a);
     return launch_status();
+}
+
+// state <- (p, m, v) (PACK) or (p, m, v) <- state; absent m / v read as zeros / are skipped.
+// One thread per 4 elements of the padded length; the padding of the last block is zero-filled.
+template <bool PACK>
+__global__ __launch_bounds__(256) void adam_state_move(float* state, float* p, float* m, float* v, int64_t n, int64_t padded)
+{
+    const int64_t e = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * kAdamPack;
+    if (e >= padded) return;
+    float* sp = state + adam_state_offset(e);
+    float* arr[3] = {p, m, v};
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        float* a = arr[k];
+        float* sk = sp + k * kAdamBlock;
+        if (e + kAdamPack <= n) {
+            float f[4] = {0, 0, 0, 0};
+            if (PACK) {
+                if (a) load4<float, true>(a + e, f);
+                store4<float, true>(sk, f);
+            } else if (a) {
+                load4<float, true>(sk, f);
+                store4<float, true>(a + e, f);
+            }
+        } else {
+            for (int j = 0; j < kAdamPack; ++j) {       // ragged end of the arrays, padding of the state
+                const int64_t i = e + j;
+                if (PACK) sk[j] = (a && i < n) ? a[i] : 0.0f;
+                else if (a && i < n) a[i] = sk[j];
+            }
+        }
+    }
 }
 
 // ---- the paper's own layout: the workspace holds the parameter in low precision and
@@ -212,9 +265,68 @@ extern "C" lsq_status lsq_adam_step(float* p, float* m, float* v, const void* g,
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (g_dt) {
-        case LSQ_F16: return adam_dispatch<f16>(p, m, v, g, p_lp, n, a, p_lp_dt, s);
-        case LSQ_BF16: return adam_dispatch<bf16>(p, m, v, g, p_lp, n, a, p_lp_dt, s);
-        default: return adam_dispatch<float>(p, m, v, g, p_lp, n, a, p_lp_dt, s);
+        case LSQ_F16: return adam_dispatch<f16, false>(p, m, v, g, p_lp, n, a, p_lp_dt, s);
+        case LSQ_BF16: return adam_dispatch<bf16, false>(p, m, v, g, p_lp, n, a, p_lp_dt, s);
+        default: return adam_dispatch<float, false>(p, m, v, g, p_lp, n, a, p_lp_dt, s);
+    }
+}
+
+extern "C" size_t lsq_adam_state_bytes(int64_t n)
+{
+    if (n <= 0) return 0;
+    return static_cast<size_t>(lsq::ceil_div(n, lsq::kAdamBlock)) * 3 * lsq::kAdamBlock * sizeof(float);
+}
+
+extern "C" lsq_status lsq_adam_state_pack(float* state, const float* p, const float* m, const float* v, int64_t n,
+                                          void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(n >= 0);
+    if (n == 0) return LSQ_OK;
+    LSQ_REQUIRE(state && p);
+    LSQ_ALIGNED(state); LSQ_ALIGNED(p); LSQ_ALIGNED(m); LSQ_ALIGNED(v);
+    const int64_t padded = ceil_div(n, kAdamBlock) * kAdamBlock;
+    LSQ_REQUIRE(padded / (256 * kAdamPack) <= 0x7FFFFFFF);
+    hipLaunchKernelGGL((adam_state_move<true>), dim3(static_cast<unsigned>(padded / (256 * kAdamPack))), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), state, const_cast<float*>(p), const_cast<float*>(m),
+                       const_cast<float*>(v), n, padded);
+    return launch_status();
+}
+
+extern "C" lsq_status lsq_adam_state_unpack(float* p, float* m, float* v, const float* state, int64_t n, void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(n >= 0);
+    if (n == 0) return LSQ_OK;
+    LSQ_REQUIRE(state);
+    LSQ_ALIGNED(state); LSQ_ALIGNED(p); LSQ_ALIGNED(m); LSQ_ALIGNED(v);
+    const int64_t padded = ceil_div(n, kAdamBlock) * kAdamBlock;
+    LSQ_REQUIRE(padded / (256 * kAdamPack) <= 0x7FFFFFFF);
+    hipLaunchKernelGGL((adam_state_move<false>), dim3(static_cast<unsigned>(padded / (256 * kAdamPack))), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), const_cast<float*>(state), p, m, v, n, padded);
+    return launch_status();
+}
+
+extern "C" lsq_status lsq_adam_step_blocked(float* state, const void* g, void* p_lp, int64_t n, float lr, float beta1,
+                                            float beta2, float eps, float weight_decay, int32_t step, int32_t adamw,
+                                            int32_t bias_correction, float inv_grad_scale, lsq_dtype g_dt,
+                                            lsq_dtype p_lp_dt, void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(n >= 0 && step >= 1);
+    if (!valid_dtype(g_dt)) return LSQ_UNSUPPORTED_DTYPE;
+    if (p_lp && p_lp_dt != LSQ_F16 && p_lp_dt != LSQ_BF16) return LSQ_UNSUPPORTED_DTYPE;
+    AdamParams a;
+    LSQ_REQUIRE(make_adam_params(&a, lr, beta1, beta2, eps, weight_decay, step, adamw, bias_correction, inv_grad_scale));
+    if (n == 0) return LSQ_OK;
+    LSQ_REQUIRE(state && g);
+    LSQ_ALIGNED(state); LSQ_ALIGNED(g); LSQ_ALIGNED(p_lp);
+    LSQ_REQUIRE(ceil_div(ceil_div(n, kAdamPack), 256) <= 0x7FFFFFFF);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (g_dt) {
+        case LSQ_F16: return adam_dispatch<f16, true>(state, nullptr, nullptr, g, p_lp, n, a, p_lp_dt, s);
+        case LSQ_BF16: return adam_dispatch<bf16, true>(state, nullptr, nullptr, g, p_lp, n, a, p_lp_dt, s);
+        default: return adam_dispatch<float, true>(state, nullptr, nullptr, g, p_lp, n, a, p_lp_dt, s);
     }
 }
 

@@ -137,6 +137,24 @@ def test_host_side_argument_errors_of_padding_removal(lib):
     assert f(None, None, None, None, None, 0, 2, 8, 8, 0, 1.0, 0.0, 1, 0, 0, None) == 0
 
 
+def test_host_side_argument_errors_of_the_blocked_adam(lib):
+    INVALID, DTYPE, MISALIGNED = 1, 2, 3
+    lib.lsq_adam_state_bytes.restype = C.c_size_t
+    assert lib.lsq_adam_state_bytes(0) == 0 and lib.lsq_adam_state_bytes(-5) == 0
+    assert lib.lsq_adam_state_bytes(1) == 3 * 8192 * 4 and lib.lsq_adam_state_bytes(8193) == 2 * 3 * 8192 * 4
+    assert lib.lsq_adam_state_pack(None, A, A, A, 8, None) == INVALID
+    assert lib.lsq_adam_state_pack(A, U, None, None, 8, None) == MISALIGNED
+    assert lib.lsq_adam_state_unpack(A, A, A, None, 8, None) == INVALID
+    assert lib.lsq_adam_state_unpack(None, None, None, None, 0, None) == 0
+    f = lib.lsq_adam_step_blocked
+    assert f(A, A, A, 8, 1e-3, .9, .98, 1e-8, 0., 0, 0, 1, 1., 0, 0, None) == INVALID      # step 0
+    assert f(A, A, A, 8, 1e-3, 1.0, .98, 1e-8, 0., 1, 0, 1, 1., 0, 0, None) == INVALID     # beta1 = 1
+    assert f(A, A, A, 8, 1e-3, .9, .98, 1e-8, 0., 1, 0, 1, 1., 5, 0, None) == DTYPE
+    assert f(A, A, A, 8, 1e-3, .9, .98, 1e-8, 0., 1, 0, 1, 1., 0, 2, None) == DTYPE        # fp32 p_lp
+    assert f(None, A, A, 8, 1e-3, .9, .98, 1e-8, 0., 1, 0, 1, 1., 0, 0, None) == INVALID
+    assert f(None, None, None, 0, 1e-3, .9, .98, 1e-8, 0., 1, 0, 1, 1., 0, 0, None) == 0
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     x = torch.zeros(4, 8, dtype=torch.float16)
