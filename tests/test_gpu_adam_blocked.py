@@ -94,3 +94,36 @@ def test_blocked_flags():
         rp, rm, rv = oracle.adam_step(t["p"], m0, v0, t["g"], "f16", step=5, **HY, **kw)
         wd_term = 0.01 * np.abs(t["p"].astype(np.float64)) if not kw.get("adamw", False) else 0.0
         _check(p, m, v, rp, rm, rv, m0, decode(t["g"], "f16") * kw.get("inv_grad_scale", 1.0), extra=wd_term)
+
+
+@pytest.mark.parametrize("ci,dt", [(2, "f16"), (4, "f16"), (4, "bf16")])
+def test_blocked_full_size(ci, dt):
+    """Transformer-big and GPT-2-large workspaces at full size, the launch the benchmark times: the
+    oracle checks sampled chunks, and every element must equal lsq_adam_step's result bit for bit."""
+    from workloads import device_normal, from_torch
+    cfg = CONFIGS[ci]
+    n = cfg.adam_n
+    say(f"[adam-blocked] full size {cfg.name} n={n} dt={dt}")
+    d = dev()
+    p = device_normal((n,), 0.02, "f32", seed=cfg.seed, device=d)
+    g = device_normal((n,), 1e-3, dt, seed=cfg.seed + 100, device=d)
+    m = torch.zeros(n, dtype=torch.float32, device=d)
+    v = torch.zeros(n, dtype=torch.float32, device=d)
+    state = L.lsq_adam_state_pack(p)
+    p_lp = torch.empty(n, dtype=g.dtype, device=d)
+    q_lp = torch.empty(n, dtype=g.dtype, device=d)
+    rng = np.random.default_rng(cfg.seed)
+    starts = np.unique(np.concatenate([[0, n - 4099], rng.integers(0, n - 4099, size=20)]))
+    out = torch.empty(n, dtype=torch.float32, device=d)
+    for step in (1, 2):
+        before = [(s, p[s:s + 4099].cpu().numpy(), m[s:s + 4099].cpu().numpy(), v[s:s + 4099].cpu().numpy(),
+                   from_torch(g[s:s + 4099], dt)) for s in starts]
+        L.lsq_adam_step_blocked(state, g, p_lp, step=step, **HY)
+        L.lsq_adam_step(p, m, v, g, q_lp, step=step, **HY)
+        assert torch.equal(p_lp, q_lp)
+        for k, ref in enumerate((p, m, v)):
+            L.lsq_adam_state_unpack(state, n, **{"pmv"[k]: out}, want=())
+            assert torch.equal(out, ref), "pmv"[k]
+        for s, hp, hm, hv, hg in before:
+            rp, rm, rv = oracle.adam_step(hp, hm, hv, hg, dt, step=step, **HY)
+            _check(p[s:s + 4099], m[s:s + 4099], v[s:s + 4099], rp, rm, rv, hm, decode(hg, dt))
