@@ -61,7 +61,7 @@ def parse():
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path has no collective; see DESIGN.md, sharding). "
+        print("bench.py: this build runs on ONE GPU (the path has no collective: every operator is per row or per element). "
               f"--gpus {args.gpus} is not supported.", file=sys.stderr)
         sys.exit(2)
 
@@ -300,7 +300,7 @@ def main():
     def op_sgd(i):
         L.lsq_sgd_step(p, m, g, p_lp, lr=1e-3, momentum=0.9)      # m doubles as the momentum buffer here
 
-    # algorithmic bytes per launch (what the method must move)
+    # algorithmic bytes per launch: what the method must move, counted per element / row / parameter
     bts = {
         "layernorm_fwd": 4 * E + 8 * T + 4 * H,
         "layernorm_bwd": 6 * E + 8 * T + 2 * H + 8 * H,

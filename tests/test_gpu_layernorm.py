@@ -11,7 +11,7 @@ from workloads import CONFIGS, layer_tensors, to_torch
 pytestmark = pytest.mark.gpu
 EPS = 1e-5
 
-# (rows, hidden): BASELINE shapes first, then every shape bucket, ragged tails and the generic path
+# (rows, hidden): the shapes of the five workload configurations first, then every shape bucket, ragged tails and the generic path
 SHAPES = [
     (512, 512), (4096, 512), (8192, 1024), (8192, 1280),
     (4096, 256), (1000, 768), (37, 64), (5, 8), (129, 128), (3, 1536), (67, 2048),
