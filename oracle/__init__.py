@@ -24,12 +24,19 @@ _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (OpenMP over rows).  Returns the library path."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    """Compile the oracle with gcc (OpenMP over rows).  Returns the library path.
+
+    LSQ_ORACLE_SRC (the mutation test of the pins sets it, nothing else does) names another C
+    source to compile and load instead: an oracle with a planted mistake."""
+    src, lib_path = _SRC, _LIB
+    alt = os.environ.get("LSQ_ORACLE_SRC")
+    if alt:
+        src, lib_path, force = alt, alt + ".so", True
+    if force or not os.path.exists(lib_path) or os.path.getmtime(lib_path) < os.path.getmtime(src):
         cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
-               "-o", _LIB, _SRC, "-lm"]
+               "-o", lib_path, src, "-lm"]
         subprocess.run(cmd, check=True)
-    return _LIB
+    return lib_path
 
 
 def lib():
