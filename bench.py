@@ -256,6 +256,19 @@ def main():
         a = layer[i % sets]
         L.lsq_embedding_bwd(demb_tab, dpos_tab, a["dy"], emb_tokens, 1, float(np.sqrt(H)), pr, ps, 3000 + i, workspace=ews)
 
+    # the sub-layer boundary in one pass: bias+dropout+residual and the next LayerNorm, forward and backward
+    fws3 = torch.empty(max(L.lsq_workspace_bytes(5, T, H), 16), dtype=torch.uint8, device=dev)
+
+    def op_bdr_ln_fwd(i):
+        a = layer[i % sets]
+        L.lsq_bdr_layernorm_fwd(a["x"], bias, a["res"], gamma, beta, pr, ps, i, 1e-5, h=a["out"], y=a["y"], mean=a["mean"],
+                                rstd=a["rstd"])
+
+    def op_bdr_ln_bwd(i):
+        a = layer[i % sets]
+        L.lsq_bdr_layernorm_bwd(a["dy"], a["x"], gamma, a["mean"], a["rstd"], pr, ps, i, dres_in=a["res"], dh=a["dx"],
+                                dx=a["out"], dgamma=dgamma, dbeta=dbeta, dbias=dbias, workspace=fws3)
+
     # padding removal: the layer tensors of the batch packed to sum(len) rows and back; the softmax with
     # query lengths (self-attention: query_len == key_len); LayerNorm on the packed rows
     lens_np = np.full(B, Lq, dtype=np.int64) if key_len is None else np.clip(key_len.cpu().numpy(), 0, Lq).astype(np.int64)
@@ -315,6 +328,7 @@ def main():
         "adam_step_lp": 22 * n, "sgd_step": 20 * n, "adam_step_blocked": 28 * n,
         "embedding_fwd": 4 * E + 4 * T, "embedding_bwd": 2 * E + 4 * n_unique * H + 4 * Lq * H + 4 * T,
         "split_heads_fwd": 12 * E + 6 * H, "split_heads_bwd": 12 * E + 12 * H, "merge_heads_fwd": 4 * E,
+        "bdr_layernorm_fwd": 8 * E + 8 * T + 6 * H, "bdr_layernorm_bwd": 10 * E + 8 * T + 2 * H + 12 * H,
         "pad_remove": 4 * T_real * H + 4 * B, "pad_restore": 2 * T_real * H + 2 * E + 4 * B,
         "layernorm_fwd_packed": 4 * T_real * H + 8 * T_real + 4 * H,
         "softmax_varlen_fwd": 2 * allowed_q + 2 * Es + (2 * Es if pa > 0 else 0),
@@ -334,6 +348,7 @@ def main():
     extra = [adam_other, ("bias_act_dropout_fwd", op_bad_fwd), ("bias_act_dropout_bwd", op_bad_bwd),
              ("embedding_fwd", op_emb_fwd), ("embedding_bwd", op_emb_bwd),
              ("split_heads_fwd", op_split_fwd), ("split_heads_bwd", op_split_bwd), ("merge_heads_fwd", op_merge_fwd),
+             ("bdr_layernorm_fwd", op_bdr_ln_fwd), ("bdr_layernorm_bwd", op_bdr_ln_bwd),
              ("pad_remove", op_pad_remove), ("pad_restore", op_pad_restore), ("layernorm_fwd_packed", op_ln_fwd_packed),
              ("softmax_varlen_fwd", op_smv_fwd), ("softmax_varlen_bwd", op_smv_bwd),
              ("adam_step_lp", op_adam_lp), ("sgd_step", op_sgd)]
@@ -430,6 +445,15 @@ def main():
     dec = 3 * (table["layernorm_fwd"]["us"] + table["bias_dropout_residual_fwd"]["us"] + table["layernorm_bwd"]["us"]
                + table["bias_dropout_residual_bwd"]["us"]) + 2 * (table["softmax_fwd"]["us"] + table["softmax_bwd"]["us"])
 
+    fused_layer = None
+    if "bdr_layernorm_fwd" in next_table and "bdr_layernorm_bwd" in next_table and not np.isnan(enc):
+        # the same layers with every bias+dropout+residual fused into the LayerNorm that follows it (and the
+        # LayerNorm backward with dres into the bias+dropout+residual backward before it)
+        pair = next_table["bdr_layernorm_fwd"]["us"] + next_table["bdr_layernorm_bwd"]["us"]
+        sm = table["softmax_fwd"]["us"] + table["softmax_bwd"]["us"]
+        fused_layer = {"encoder_layer_fwd_bwd_nongemm": round(2 * pair + sm, 1),
+                       "decoder_layer_fwd_bwd_nongemm": round(3 * pair + 2 * sm, 1)}
+
     if args.calibrate:
         # known traffic for scaling FETCH_SIZE / WRITE_SIZE: reads 2^30 bytes, writes 2^30 bytes per launch
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -459,12 +483,14 @@ def main():
         "ops": table, "ops_timing": timing,
         "ops_next": dict(next_table, note=f"rows beyond the nine: FFN bias+{act}+dropout(p={pa}) on [{T}, {F}], the paper's "
                                           "low-precision-parameter Adam (22 B/param), SGD with momentum (20 B/param), Adam on the blocked "
-                                          "optimizer state (p, m, v interleaved in 8 Ki-element blocks; same 28 B/param), "
+                                          "optimizer state (p, m, v interleaved in 8 Ki-element blocks; same 28 B/param), bias+dropout+residual fused "
+                                          "with the LayerNorm that follows it (8 B/elem forward, 10 B/elem backward with dres), "
                                           f"QKV bias + head split on [{T}, {3 * H}] and its backward, head merge, embedding of {T} Zipf-"
                                           f"distributed tokens ({n_unique} distinct ids) into [{T}, {H}] and its backward; padding removal "
                                           f"({T_real} real rows of {T}): pack, unpack, LayerNorm on the packed rows, softmax "
                                           "with query lengths (rows of padded queries neither read nor computed)"),
         "layer_us": {"encoder_layer_fwd_bwd_nongemm": round(enc, 1), "decoder_layer_fwd_bwd_nongemm": round(dec, 1)},
+        "layer_us_fused_boundaries": fused_layer,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, dt)

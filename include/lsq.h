@@ -64,7 +64,8 @@ typedef enum {
     LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD = 1,
     LSQ_OP_BIAS_ACT_DROPOUT_BWD = 2,
     LSQ_OP_SPLIT_HEADS_BWD = 3,         /* cols = parts * heads * head_dim */
-    LSQ_OP_EMBEDDING_BWD = 4            /* rows = batch * len tokens */
+    LSQ_OP_EMBEDDING_BWD = 4,           /* rows = batch * len tokens */
+    LSQ_OP_BDR_LAYERNORM_BWD = 5
 } lsq_op;
 
 /* Activations of the feed-forward block. */
@@ -226,6 +227,35 @@ lsq_status lsq_adam_step_lp(void* p_lp, float* m, float* v, const void* g, int64
                             float lr, float beta1, float beta2, float eps, float weight_decay,
                             int32_t step, int32_t adamw, int32_t bias_correction,
                             float inv_grad_scale, lsq_dtype dt, void* stream);
+
+/* The boundary between two sub-layers of a pre-LN Transformer in ONE pass: the paper
+ * fuses "bias adding, dropout, and residual" (Sec. IV-A) and rewrites LayerNorm
+ * (Sec. IV-B) as two kernels; the output of the first is the input of the second, so
+ * here the row never leaves the registers in between.
+ *   h = residual + Dropout_p(x + bias)          (stored: the next residual)
+ *   y, mean, rstd = LayerNorm(h; gamma, beta)   (from the STORED, rounded h)
+ * Bit for bit the result of lsq_bias_dropout_residual_fwd followed by
+ * lsq_layernorm_fwd on its output; 8 instead of 10 bytes per element, one launch.
+ * Arguments as in those two calls (h: [rows, hidden] dt, written). */
+lsq_status lsq_bdr_layernorm_fwd(void* h, void* y, float* mean, float* rstd, const void* x,
+                                 const void* bias, const void* residual, const void* gamma,
+                                 const void* beta, int64_t rows, int32_t hidden, float p,
+                                 uint64_t seed, uint64_t offset, float eps, lsq_dtype dt, void* stream);
+
+/* Its backward, also one pass:
+ *   dh = LayerNorm_bwd(dy; h, gamma, mean, rstd) + dres_in   (stored: the gradient of the
+ *                                                             residual branch; dres_in nullable)
+ *   dx = keep * dh / (1-p)  from the STORED dh                (gradient of the projection)
+ *   dgamma, dbeta (LayerNorm), dbias = column sums of dx      (fp32, overwritten)
+ * dh and dx equal lsq_layernorm_bwd followed by lsq_bias_dropout_residual_bwd bit for
+ * bit (the three column sums differ from theirs only in summation order); 10 instead
+ * of 12 bytes per element, one second-stage launch instead of two.
+ * workspace: >= lsq_workspace_bytes(LSQ_OP_BDR_LAYERNORM_BWD, rows, hidden) bytes. */
+lsq_status lsq_bdr_layernorm_bwd(void* dh, void* dx, float* dgamma, float* dbeta, float* dbias,
+                                 const void* dy, const void* h, const void* gamma, const float* mean,
+                                 const float* rstd, const void* dres_in, void* workspace,
+                                 size_t workspace_bytes, int64_t rows, int32_t hidden, float p,
+                                 uint64_t seed, uint64_t offset, lsq_dtype dt, void* stream);
 
 /* Adam with the trainer's private state in a blocked layout (Sec. IV-C builds one
  * workspace so that the update is one launch over contiguous memory; this goes one step

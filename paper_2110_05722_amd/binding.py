@@ -20,6 +20,7 @@ LSQ_F16, LSQ_BF16, LSQ_F32 = 0, 1, 2
 LSQ_OP_LAYERNORM_BWD, LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD, LSQ_OP_BIAS_ACT_DROPOUT_BWD = 0, 1, 2
 LSQ_OP_SPLIT_HEADS_BWD = 3
 LSQ_OP_EMBEDDING_BWD = 4
+LSQ_OP_BDR_LAYERNORM_BWD = 5
 LSQ_ACT = {"relu": 0, "gelu": 1, "gelu_tanh": 2}
 _DT = {torch.float16: LSQ_F16, torch.bfloat16: LSQ_BF16, torch.float32: LSQ_F32}
 
@@ -30,6 +31,7 @@ EXPORTS = [
     "lsq_bias_act_dropout_fwd", "lsq_bias_act_dropout_bwd", "lsq_adam_step_lp", "lsq_sgd_step",
     "lsq_split_heads_fwd", "lsq_split_heads_bwd", "lsq_merge_heads_fwd", "lsq_merge_heads_bwd",
     "lsq_embedding_fwd", "lsq_embedding_bwd",
+    "lsq_bdr_layernorm_fwd", "lsq_bdr_layernorm_bwd",
     "lsq_adam_state_bytes", "lsq_adam_state_pack", "lsq_adam_state_unpack", "lsq_adam_step_blocked",
     "lsq_pad_offsets", "lsq_pad_remove", "lsq_pad_restore", "lsq_softmax_varlen_fwd", "lsq_softmax_varlen_bwd",
 ]
@@ -76,6 +78,9 @@ def load():
         "lsq_merge_heads_bwd": (C.c_int, [vp, vp, i32, i32, i32, i32, C.c_int, vp]),
         "lsq_embedding_fwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64, C.c_int, vp]),
         "lsq_embedding_bwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64, vp, sz, C.c_int, vp]),
+        "lsq_bdr_layernorm_fwd": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, f32, u64, u64, f32, C.c_int, vp]),
+        "lsq_bdr_layernorm_bwd": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, i64, i32, f32, u64, u64,
+                                             C.c_int, vp]),
         "lsq_adam_state_bytes": (sz, [i64]),
         "lsq_adam_state_pack": (C.c_int, [vp, vp, vp, vp, i64, vp]),
         "lsq_adam_state_unpack": (C.c_int, [vp, vp, vp, vp, i64, vp]),
@@ -406,6 +411,47 @@ def lsq_embedding_bwd(demb, dpos, dy, tokens, pad_idx: int, scale: float, p: flo
                                     offset, _ptr(ws), ws.numel() * ws.element_size(), _dt(demb), _stream()),
            "lsq_embedding_bwd")
     return demb, dpos
+
+
+def lsq_bdr_layernorm_fwd(x, bias, residual, gamma, beta, p: float, seed: int, offset: int, eps: float = 1e-5,
+                          h=None, y=None, mean=None, rstd=None):
+    """h = residual + Dropout(x + bias); y = LayerNorm(h), one pass -> (h, y, mean, rstd)."""
+    rows, hidden = x.shape
+    h = torch.empty_like(x) if h is None else h
+    y = torch.empty_like(x) if y is None else y
+    mean = torch.empty(rows, dtype=torch.float32, device=x.device) if mean is None else mean
+    rstd = torch.empty(rows, dtype=torch.float32, device=x.device) if rstd is None else rstd
+    for name, t in (("h", h), ("y", y), ("residual", residual)):
+        _need(name, t, rows * hidden, x.dtype)
+    for name, t in (("bias", bias), ("gamma", gamma), ("beta", beta)):
+        _need(name, t, hidden, x.dtype)
+    _need("mean", mean, rows, torch.float32); _need("rstd", rstd, rows, torch.float32)
+    _check(load().lsq_bdr_layernorm_fwd(_ptr(h), _ptr(y), _ptr(mean), _ptr(rstd), _ptr(x), _ptr(bias), _ptr(residual),
+                                        _ptr(gamma), _ptr(beta), rows, hidden, p, seed, offset, eps, _dt(x), _stream()),
+           "lsq_bdr_layernorm_fwd")
+    return h, y, mean, rstd
+
+
+def lsq_bdr_layernorm_bwd(dy, h, gamma, mean, rstd, p: float, seed: int, offset: int, dres_in=None, dh=None, dx=None,
+                          dgamma=None, dbeta=None, dbias=None, workspace=None):
+    """Backward of lsq_bdr_layernorm_fwd -> (dh, dx, dgamma, dbeta, dbias)."""
+    rows, hidden = h.shape
+    dh = torch.empty_like(h) if dh is None else dh
+    dx = torch.empty_like(h) if dx is None else dx
+    mk = lambda t: torch.empty(hidden, dtype=torch.float32, device=h.device) if t is None else t
+    dgamma, dbeta, dbias = mk(dgamma), mk(dbeta), mk(dbias)
+    ws = _workspace(lsq_workspace_bytes(LSQ_OP_BDR_LAYERNORM_BWD, rows, hidden), h, workspace)
+    for name, t in (("dy", dy), ("dh", dh), ("dx", dx), ("dres_in", dres_in)):
+        _need(name, t, rows * hidden, h.dtype)
+    _need("gamma", gamma, hidden, h.dtype)
+    for name, t, k in (("mean", mean, rows), ("rstd", rstd, rows), ("dgamma", dgamma, hidden), ("dbeta", dbeta, hidden),
+                       ("dbias", dbias, hidden)):
+        _need(name, t, k, torch.float32)
+    _check(load().lsq_bdr_layernorm_bwd(_ptr(dh), _ptr(dx), _ptr(dgamma), _ptr(dbeta), _ptr(dbias), _ptr(dy), _ptr(h),
+                                        _ptr(gamma), _ptr(mean), _ptr(rstd), _ptr(dres_in), _ptr(ws),
+                                        ws.numel() * ws.element_size(), rows, hidden, p, seed, offset, _dt(h), _stream()),
+           "lsq_bdr_layernorm_bwd")
+    return dh, dx, dgamma, dbeta, dbias
 
 
 LSQ_ADAM_BLOCK = 8192

@@ -9,6 +9,10 @@ extern "C" size_t lsq_workspace_bytes(int32_t op, int64_t rows, int32_t cols)
         case LSQ_OP_LAYERNORM_BWD:
             // one [2][cols] fp32 partial row (dgamma, dbeta) per workgroup
             return static_cast<size_t>(ln_bwd_blocks(rows, cols)) * 2u * static_cast<size_t>(cols) * sizeof(float);
+        case LSQ_OP_BDR_LAYERNORM_BWD:
+            // one [3][cols] fp32 partial row (dgamma, dbeta, dbias) per workgroup; also enough for the
+            // two separate operators that serve row lengths without a register bucket
+            return static_cast<size_t>(ln_bwd_blocks(rows, cols)) * 3u * static_cast<size_t>(cols) * sizeof(float);
         case LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD:
         case LSQ_OP_BIAS_ACT_DROPOUT_BWD:
         case LSQ_OP_SPLIT_HEADS_BWD:

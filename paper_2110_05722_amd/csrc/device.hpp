@@ -143,6 +143,23 @@ __device__ __forceinline__ void unpack(const RawPack<T>& r, float (&f)[8])
     }
 }
 
+// fp32 -> storage form (one rounding per element), the inverse of unpack
+template <typename T>
+__device__ __forceinline__ RawPack<T> pack_raw(const float (&f)[8])
+{
+    RawPack<T> r;
+    if constexpr (sizeof(T) == 2) {
+        Raw8<T> h;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) h.v[j] = from_f32<T>(f[j]);
+        r.u = __builtin_bit_cast(uvec4, h);
+    } else {
+        r.a = fvec4{f[0], f[1], f[2], f[3]};
+        r.b = fvec4{f[4], f[5], f[6], f[7]};
+    }
+    return r;
+}
+
 // 4 consecutive elements (one 128-bit access of fp32, one 64-bit access of fp16/bf16).
 template <typename T> struct alignas(sizeof(T) * 4 > 16 ? 16 : sizeof(T) * 4) Raw4 { T v[4]; };
 

@@ -57,7 +57,7 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Second stage of the column reductions: out[c] = sum over the P partial rows of
 // partial[y][c], C columns, in a fixed order (reproducible).  Columns below `split`
-// go to out0, the rest to out1.  A workgroup owns 32 columns; its 32 row slices each
+// go to out0, those below `split2` to out1, the rest to out2.  A workgroup owns 32 columns; its 32 row slices each
 // sum a contiguous chunk of rows with the loads of 8 rows in flight at a time (a
 // plain loop would pay one memory latency per row), then the slices are combined in
 // slice order through LDS.
@@ -65,7 +65,9 @@ constexpr int kFinalizeSlices = 32;
 
 template <int = 0>
 __global__ __launch_bounds__(32 * kFinalizeSlices) void colsum_finalize_kernel(float* __restrict__ out0,
-                                                                               float* __restrict__ out1, int split,
+                                                                               float* __restrict__ out1,
+                                                                               float* __restrict__ out2, int split,
+                                                                               int split2,
                                                                                const float* __restrict__ partial,
                                                                                int P, int C)
 {
@@ -92,14 +94,17 @@ __global__ __launch_bounds__(32 * kFinalizeSlices) void colsum_finalize_kernel(f
         float t = sm[0][lane];
 #pragma unroll
         for (int w = 1; w < kFinalizeSlices; ++w) t += sm[w][lane];
-        if (c < split) out0[c] = t; else out1[c - split] = t;
+        if (c < split) out0[c] = t;
+        else if (c < split2) out1[c - split] = t;
+        else out2[c - split2] = t;
     }
 }
 
-inline void launch_colsum_finalize(float* out0, float* out1, int split, const float* partial, int P, int C, hipStream_t s)
+inline void launch_colsum_finalize(float* out0, float* out1, int split, const float* partial, int P, int C, hipStream_t s,
+                                   float* out2 = nullptr, int split2 = 0x7FFFFFFF)
 {
     hipLaunchKernelGGL((colsum_finalize_kernel<0>), dim3(static_cast<unsigned>((C + 31) / 32)), dim3(32 * kFinalizeSlices), 0, s,
-                       out0, out1, split, partial, P, C);
+                       out0, out1, out2, split, split2, partial, P, C);
 }
 
 // Number of partial-sum rows the column reductions write to the workspace.

@@ -46,11 +46,23 @@ __device__ __forceinline__ void ln_load_row(RawPack<T> (&raw)[VPL], const T* __r
     }
 }
 
-template <typename T, int LPR, int VPL>
+// What the fused variants add around the LayerNorm (all unused, and compiled out, otherwise).
+template <typename T>
+struct BdrFuse {
+    T* out;               // forward: h = residual + Dropout(x + bias), stored;  backward: dx of the projection
+    const T* residual;    // forward only
+    const T* bias;        // forward only, nullable
+    DropoutParams d;
+};
+
+// FUSE: the row that is normalised is h = residual + Dropout(x + bias), built in registers from
+// two loads, stored once (the next residual) and normalised from its STORED (rounded) value, so the
+// result equals bias+dropout+residual followed by LayerNorm bit for bit while h is never re-read.
+template <typename T, int LPR, int VPL, bool FUSE = false, bool DROP = false>
 __global__ __launch_bounds__(256) void ln_fwd_kernel(T* __restrict__ y, float* __restrict__ mean,
                                                      float* __restrict__ rstd, const T* __restrict__ x,
                                                      const T* __restrict__ gamma, const T* __restrict__ beta,
-                                                     int64_t rows, int hidden, float eps)
+                                                     int64_t rows, int hidden, float eps, BdrFuse<T> fz)
 {
     __shared__ float lds[4];
     constexpr int RPB = 256 / LPR;            // rows a workgroup handles at a time
@@ -64,17 +76,56 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(T* __restrict__ y, float* _
     ln_load_row<T, LPR, VPL>(gm, gamma, 0, true, hidden, nv, sub);
     ln_load_row<T, LPR, VPL>(bt, beta, 0, true, hidden, nv, sub);
 
+    RawPack<T> bs[FUSE ? VPL : 1];
+    if constexpr (FUSE) {
+        if (fz.bias) ln_load_row<T, LPR, VPL>(bs, fz.bias, 0, true, hidden, nv, sub);
+        else {
+#pragma unroll
+            for (int k = 0; k < VPL; ++k) bs[k] = zero_raw<T>();
+        }
+    }
+
     int64_t base = static_cast<int64_t>(blockIdx.x) * RPB;
-    RawPack<T> nxt[VPL];
+    RawPack<T> nxt[VPL], nres[FUSE ? VPL : 1];
     ln_load_row<T, LPR, VPL>(nxt, x, base + slot, base + slot < rows, hidden, nv, sub);
+    if constexpr (FUSE) ln_load_row<T, LPR, VPL>(nres, fz.residual, base + slot, base + slot < rows, hidden, nv, sub);
     for (; base < rows; base += gstride) {
         const int64_t r = base + slot;
         const bool rv = r < rows;
-        RawPack<T> cur[VPL];
+        RawPack<T> cur[VPL], cres[FUSE ? VPL : 1];
 #pragma unroll
         for (int k = 0; k < VPL; ++k) cur[k] = nxt[k];
-        if (base + gstride < rows)            // prefetch the next row group while this one is reduced
+        if constexpr (FUSE) {
+#pragma unroll
+            for (int k = 0; k < VPL; ++k) cres[k] = nres[k];
+        }
+        if (base + gstride < rows) {          // prefetch the next row group while this one is reduced
             ln_load_row<T, LPR, VPL>(nxt, x, r + gstride, r + gstride < rows, hidden, nv, sub);
+            if constexpr (FUSE)
+                ln_load_row<T, LPR, VPL>(nres, fz.residual, r + gstride, r + gstride < rows, hidden, nv, sub);
+        }
+        if constexpr (FUSE) {
+            // same expressions as the stand-alone bias+dropout+residual kernel; the pack index of
+            // the dropout stream is the flat one (row * packs per row + pack)
+#pragma unroll
+            for (int k = 0; k < VPL; ++k) {
+                const int idx = sub + k * LPR;
+                if (rv && idx < nv) {
+                    float xf[8], rf[8], b8[8], kf[8];
+                    unpack<T>(cur[k], xf);
+                    unpack<T>(cres[k], rf);
+                    unpack<T>(bs[k], b8);
+                    if constexpr (DROP) dropout_factors8(fz.d, static_cast<uint64_t>(r) * nv + idx, kf);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const float z = xf[j] + b8[j];
+                        rf[j] = DROP ? fmaf(z, kf[j], rf[j]) : rf[j] + z;
+                    }
+                    cur[k] = pack_raw<T>(rf);
+                    store_raw<T, kNT>(fz.out + r * hidden + idx * kPack, cur[k]);
+                }
+            }
+        }
 
         float xv[VPL][8];
         float s = 0.0f;
@@ -143,13 +194,18 @@ constexpr int kLnBwdThreads = LSQ_LN_BWD_THREADS;
 // THREADS lanes per workgroup: THREADS/LPR rows in flight per workgroup (plus their
 // prefetched successors).  With one wave per SIMD the kernel is bound by memory latency,
 // not bandwidth: the bytes in flight per compute unit are what THREADS buys.
-template <typename T, int LPR, int VPL, bool HAS_RES, int THREADS>
+// FUSE: the LayerNorm gradient (plus dres) is the gradient of h = residual + Dropout(x + bias): it is
+// stored (the residual branch's gradient), then masked and scaled from its STORED value into
+// fz.out (the projection's gradient), whose column sums (dbias) join dgamma/dbeta as a third
+// partial row.  Equal to LayerNorm backward followed by bias+dropout+residual backward, one pass.
+template <typename T, int LPR, int VPL, bool HAS_RES, int THREADS, bool FUSE = false, bool DROP = false>
 __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restrict__ partial, const T* dy,
                                                          const T* __restrict__ x, const T* __restrict__ gamma,
                                                          const float* __restrict__ mean, const float* __restrict__ rstd,
-                                                         const T* dres, int64_t rows, int hidden)
+                                                         const T* dres, int64_t rows, int hidden, BdrFuse<T> fz)
 {
-    extern __shared__ float colbuf[];         // [2][8][packs | 1] when LPR < 256
+    constexpr int NACC = FUSE ? 3 : 2;        // column accumulators: dgamma, dbeta (, dbias)
+    extern __shared__ float colbuf[];         // [NACC][8][packs | 1] when LPR < 256
     __shared__ float lds[4];
     static_assert(LPR != 256 || THREADS == 256, "a whole-workgroup row needs 256 threads");
     constexpr int RPB = THREADS / LPR;
@@ -161,11 +217,17 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
 
     RawPack<T> gm[VPL];
     ln_load_row<T, LPR, VPL>(gm, gamma, 0, true, hidden, nv, sub);
-    float dg[VPL][8], db[VPL][8];
+    float dg[VPL][8], db[VPL][8], dbi[FUSE ? VPL : 1][8];
 #pragma unroll
     for (int k = 0; k < VPL; ++k)
 #pragma unroll
         for (int j = 0; j < 8; ++j) { dg[k][j] = 0.0f; db[k][j] = 0.0f; }
+    if constexpr (FUSE) {
+#pragma unroll
+        for (int k = 0; k < VPL; ++k)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) dbi[k][j] = 0.0f;
+    }
 
     int64_t base = static_cast<int64_t>(blockIdx.x) * RPB;
     RawPack<T> ndy[VPL], nx[VPL];
@@ -254,7 +316,23 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
                     o[j] = HAS_RES ? o[j] + v : v;
                 }
 #endif
-                store8<T, kNT>(dx + ro + idx * kPack, o);
+                if constexpr (!FUSE) {
+                    store8<T, kNT>(dx + ro + idx * kPack, o);
+                } else {
+                    const RawPack<T> hp = pack_raw<T>(o);
+                    store_raw<T, kNT>(dx + ro + idx * kPack, hp);
+                    float gq[8];
+                    unpack<T>(hp, gq);
+                    if constexpr (DROP) {
+                        float kf[8];
+                        dropout_factors8(fz.d, static_cast<uint64_t>(r) * nv + idx, kf);
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) gq[j] *= kf[j];
+                    }
+                    store8<T, kNT>(fz.out + ro + idx * kPack, gq);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) dbi[k][j] += gq[j];
+                }
             }
         }
 #if !LSQ_LN_BWD_PREFETCH
@@ -269,7 +347,7 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
 #endif
     }
 
-    float* prow = partial + static_cast<int64_t>(blockIdx.x) * 2 * hidden;
+    float* prow = partial + static_cast<int64_t>(blockIdx.x) * NACC * hidden;
     if constexpr (LPR == 256) {
 #pragma unroll
         for (int k = 0; k < VPL; ++k) {
@@ -277,6 +355,7 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
             if (idx < nv) {
                 store8<float>(prow + idx * kPack, dg[k]);
                 store8<float>(prow + hidden + idx * kPack, db[k]);
+                if constexpr (FUSE) store8<float>(prow + 2 * hidden + idx * kPack, dbi[k]);
             }
         }
     } else {
@@ -286,6 +365,7 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
         const int stride = nv | 1;
         float* cg = colbuf;
         float* cb = colbuf + 8 * stride;
+        float* ci = colbuf + 16 * stride;      // FUSE only
         for (int turn = 0; turn < RPB; ++turn) {
             if (slot == turn) {
                 // all reads of the turn first, then the adds, then all writes: a read-add-write
@@ -298,6 +378,7 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
                         for (int j = 0; j < 8; ++j) {
                             dg[k][j] += cg[j * stride + idx];
                             db[k][j] += cb[j * stride + idx];
+                            if constexpr (FUSE) dbi[k][j] += ci[j * stride + idx];
                         }
                     }
                 }
@@ -309,16 +390,17 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
                         for (int j = 0; j < 8; ++j) {
                             cg[j * stride + idx] = dg[k][j];
                             cb[j * stride + idx] = db[k][j];
+                            if constexpr (FUSE) ci[j * stride + idx] = dbi[k][j];
                         }
                     }
                 }
             }
             __syncthreads();
         }
-        for (int c = threadIdx.x; c < 2 * hidden; c += THREADS) {
-            const int half = c >= hidden;
-            const int cc = c - half * hidden;
-            prow[c] = colbuf[half * 8 * stride + (cc & 7) * stride + (cc >> 3)];
+        for (int c = threadIdx.x; c < NACC * hidden; c += THREADS) {
+            const int which = c / hidden;
+            const int cc = c - which * hidden;
+            prow[c] = colbuf[which * 8 * stride + (cc & 7) * stride + (cc >> 3)];
         }
     }
 }
@@ -426,9 +508,11 @@ inline int ln_fwd_blocks(int64_t rows, int lpr)
 
 #define LSQ_LN_CASES(X) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 3) X(64, 4) X(256, 2) X(256, 4)
 
+// fuse != nullptr: x is the projection output and *fuse carries h / residual / bias / dropout
 template <typename T>
 static lsq_status ln_fwd_dispatch(void* y, float* mean, float* rstd, const void* x, const void* gamma, const void* beta,
-                                  int64_t rows, int32_t hidden, float eps, hipStream_t s)
+                                  int64_t rows, int32_t hidden, float eps, hipStream_t s,
+                                  const BdrFuse<T>* fuse = nullptr)
 {
     T* yp = static_cast<T*>(y);
     const T* xp = static_cast<const T*>(x);
@@ -441,9 +525,13 @@ static lsq_status ln_fwd_dispatch(void* y, float* mean, float* rstd, const void*
         return launch_status();
     }
     const dim3 grid(ln_fwd_blocks(rows, sh.lpr)), block(256);
+    const BdrFuse<T> none{};
 #define X(L, V)                                                                                              \
-    if (sh.lpr == L && sh.vpl == V)                                                                          \
-        hipLaunchKernelGGL((ln_fwd_kernel<T, L, V>), grid, block, 0, s, yp, mean, rstd, xp, gp, bp, rows, hidden, eps);
+    if (sh.lpr == L && sh.vpl == V) {                                                                        \
+        if (!fuse) hipLaunchKernelGGL((ln_fwd_kernel<T, L, V>), grid, block, 0, s, yp, mean, rstd, xp, gp, bp, rows, hidden, eps, none); \
+        else if (fuse->d.t16) hipLaunchKernelGGL((ln_fwd_kernel<T, L, V, true, true>), grid, block, 0, s, yp, mean, rstd, xp, gp, bp, rows, hidden, eps, *fuse); \
+        else hipLaunchKernelGGL((ln_fwd_kernel<T, L, V, true, false>), grid, block, 0, s, yp, mean, rstd, xp, gp, bp, rows, hidden, eps, *fuse); \
+    }
     LSQ_LN_CASES(X)
 #undef X
     return launch_status();
@@ -452,7 +540,8 @@ static lsq_status ln_fwd_dispatch(void* y, float* mean, float* rstd, const void*
 template <typename T>
 static lsq_status ln_bwd_dispatch(void* dx, float* dgamma, float* dbeta, const void* dy, const void* x,
                                   const void* gamma, const float* mean, const float* rstd, const void* dres,
-                                  void* workspace, int64_t rows, int32_t hidden, hipStream_t s)
+                                  void* workspace, int64_t rows, int32_t hidden, hipStream_t s,
+                                  const BdrFuse<T>* fuse = nullptr, float* dbias = nullptr)
 {
     T* dxp = static_cast<T*>(dx);
     const T* dyp = static_cast<const T*>(dy);
@@ -469,17 +558,28 @@ static lsq_status ln_bwd_dispatch(void* dx, float* dgamma, float* dbeta, const v
     }
     const int P = ln_bwd_blocks(rows, hidden);
     float* partial = static_cast<float*>(workspace);
-    const size_t shmem = sh.lpr == 256 ? 0 : sizeof(float) * 16 * ((hidden / kPack) | 1);
+    const int nacc = fuse ? 3 : 2;
+    const size_t shmem = sh.lpr == 256 ? 0 : sizeof(float) * 8 * nacc * ((hidden / kPack) | 1);
+    const BdrFuse<T> none{};
 #define X(L, V)                                                                                              \
     if (sh.lpr == L && sh.vpl == V) {                                                                        \
         constexpr int TH = L == 256 ? 256 : kLnBwdThreads;                                                   \
         const dim3 grid(P), block(TH);                                                                       \
-        if (rp) hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, true, TH>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden); \
-        else hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, false, TH>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden);   \
+        if (!fuse) {                                                                                         \
+            if (rp) hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, true, TH>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, none); \
+            else hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, false, TH>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, none);   \
+        } else if (fuse->d.t16) {                                                                            \
+            if (rp) hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, true, TH, true, true>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, *fuse); \
+            else hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, false, TH, true, true>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, *fuse);   \
+        } else {                                                                                             \
+            if (rp) hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, true, TH, true, false>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, *fuse); \
+            else hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, false, TH, true, false>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, *fuse);   \
+        }                                                                                                    \
     }
     LSQ_LN_CASES(X)
 #undef X
-    launch_colsum_finalize(dgamma, dbeta, hidden, partial, P, 2 * hidden, s);
+    if (fuse) launch_colsum_finalize(dgamma, dbeta, hidden, partial, P, 3 * hidden, s, dbias, 2 * hidden);
+    else launch_colsum_finalize(dgamma, dbeta, hidden, partial, P, 2 * hidden, s);
     return launch_status();
 }
 
@@ -527,5 +627,90 @@ extern "C" lsq_status lsq_layernorm_bwd(void* dx, float* dgamma, float* dbeta, c
         case LSQ_F16: return ln_bwd_dispatch<f16>(dx, dgamma, dbeta, dy, x, gamma, mean, rstd, dres_in, workspace, rows, hidden, s);
         case LSQ_BF16: return ln_bwd_dispatch<bf16>(dx, dgamma, dbeta, dy, x, gamma, mean, rstd, dres_in, workspace, rows, hidden, s);
         default: return ln_bwd_dispatch<float>(dx, dgamma, dbeta, dy, x, gamma, mean, rstd, dres_in, workspace, rows, hidden, s);
+    }
+}
+
+// ---- fused sub-layer boundary of a pre-LN Transformer
+namespace lsq {
+template <typename T>
+static lsq_status bdr_ln_fwd_typed(void* h, void* y, float* mean, float* rstd, const void* x, const void* bias,
+                                   const void* residual, const void* gamma, const void* beta, int64_t rows,
+                                   int32_t hidden, float eps, const DropoutParams& d, hipStream_t s)
+{
+    const BdrFuse<T> fz{static_cast<T*>(h), static_cast<const T*>(residual), static_cast<const T*>(bias), d};
+    return ln_fwd_dispatch<T>(y, mean, rstd, x, gamma, beta, rows, hidden, eps, s, &fz);
+}
+
+template <typename T>
+static lsq_status bdr_ln_bwd_typed(void* dh, void* dx, float* dgamma, float* dbeta, float* dbias, const void* dy,
+                                   const void* h, const void* gamma, const float* mean, const float* rstd,
+                                   const void* dres_in, void* workspace, int64_t rows, int32_t hidden,
+                                   const DropoutParams& d, hipStream_t s)
+{
+    const BdrFuse<T> fz{static_cast<T*>(dx), nullptr, nullptr, d};
+    return ln_bwd_dispatch<T>(dh, dgamma, dbeta, dy, h, gamma, mean, rstd, dres_in, workspace, rows, hidden, s, &fz, dbias);
+}
+}  // namespace lsq
+
+extern "C" lsq_status lsq_bdr_layernorm_fwd(void* h, void* y, float* mean, float* rstd, const void* x, const void* bias,
+                                            const void* residual, const void* gamma, const void* beta, int64_t rows,
+                                            int32_t hidden, float p, uint64_t seed, uint64_t offset, float eps,
+                                            lsq_dtype dt, void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(rows >= 0 && hidden > 0 && eps >= 0.0f);
+    if (!valid_dtype(dt)) return LSQ_UNSUPPORTED_DTYPE;
+    DropoutParams d;
+    LSQ_REQUIRE(make_dropout(p, seed, offset, &d));
+    if (rows == 0) return LSQ_OK;
+    LSQ_REQUIRE(h && y && mean && rstd && x && residual && gamma && beta);
+    LSQ_ALIGNED(h); LSQ_ALIGNED(y); LSQ_ALIGNED(x); LSQ_ALIGNED(bias); LSQ_ALIGNED(residual); LSQ_ALIGNED(gamma); LSQ_ALIGNED(beta);
+    LSQ_REQUIRE(ceil_div(rows * hidden, 256) <= 0x7FFFFFFF);
+    if (ln_shape(hidden).lpr == 0) {      // no register bucket for this row length: the two operators back to back
+        const lsq_status st = lsq_bias_dropout_residual_fwd(h, x, bias, residual, rows, hidden, p, seed, offset, dt, stream);
+        return st != LSQ_OK ? st : lsq_layernorm_fwd(y, mean, rstd, h, gamma, beta, rows, hidden, eps, dt, stream);
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (dt) {
+        case LSQ_F16: return bdr_ln_fwd_typed<f16>(h, y, mean, rstd, x, bias, residual, gamma, beta, rows, hidden, eps, d, s);
+        case LSQ_BF16: return bdr_ln_fwd_typed<bf16>(h, y, mean, rstd, x, bias, residual, gamma, beta, rows, hidden, eps, d, s);
+        default: return bdr_ln_fwd_typed<float>(h, y, mean, rstd, x, bias, residual, gamma, beta, rows, hidden, eps, d, s);
+    }
+}
+
+extern "C" lsq_status lsq_bdr_layernorm_bwd(void* dh, void* dx, float* dgamma, float* dbeta, float* dbias, const void* dy,
+                                            const void* h, const void* gamma, const float* mean, const float* rstd,
+                                            const void* dres_in, void* workspace, size_t workspace_bytes, int64_t rows,
+                                            int32_t hidden, float p, uint64_t seed, uint64_t offset, lsq_dtype dt,
+                                            void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(rows >= 0 && hidden > 0);
+    if (!valid_dtype(dt)) return LSQ_UNSUPPORTED_DTYPE;
+    DropoutParams d;
+    LSQ_REQUIRE(make_dropout(p, seed, offset, &d));
+    LSQ_REQUIRE(dgamma && dbeta && dbias);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (rows == 0) {
+        lsq_status st = zero_fill(dgamma, hidden, s);
+        if (st == LSQ_OK) st = zero_fill(dbeta, hidden, s);
+        return st != LSQ_OK ? st : zero_fill(dbias, hidden, s);
+    }
+    LSQ_REQUIRE(dh && dx && dy && h && gamma && mean && rstd);
+    LSQ_ALIGNED(dh); LSQ_ALIGNED(dx); LSQ_ALIGNED(dy); LSQ_ALIGNED(h); LSQ_ALIGNED(gamma); LSQ_ALIGNED(dres_in);
+    LSQ_ALIGNED(workspace);
+    LSQ_REQUIRE(ceil_div(rows * hidden, 256) <= 0x7FFFFFFF);
+    const size_t need = lsq_workspace_bytes(LSQ_OP_BDR_LAYERNORM_BWD, rows, hidden);
+    if (need && (!workspace || workspace_bytes < need)) return LSQ_WORKSPACE_TOO_SMALL;
+    if (ln_shape(hidden).lpr == 0) {
+        const lsq_status st = lsq_layernorm_bwd(dh, dgamma, dbeta, dy, h, gamma, mean, rstd, dres_in, workspace,
+                                                workspace_bytes, rows, hidden, dt, stream);
+        return st != LSQ_OK ? st : lsq_bias_dropout_residual_bwd(dx, dbias, dh, rows, hidden, p, seed, offset, workspace,
+                                                                workspace_bytes, dt, stream);
+    }
+    switch (dt) {
+        case LSQ_F16: return bdr_ln_bwd_typed<f16>(dh, dx, dgamma, dbeta, dbias, dy, h, gamma, mean, rstd, dres_in, workspace, rows, hidden, d, s);
+        case LSQ_BF16: return bdr_ln_bwd_typed<bf16>(dh, dx, dgamma, dbeta, dbias, dy, h, gamma, mean, rstd, dres_in, workspace, rows, hidden, d, s);
+        default: return bdr_ln_bwd_typed<float>(dh, dx, dgamma, dbeta, dbias, dy, h, gamma, mean, rstd, dres_in, workspace, rows, hidden, d, s);
     }
 }
