@@ -112,8 +112,11 @@ inline void launch_colsum_finalize(float* out0, float* out1, int split, const fl
 // while the partials stay a small fraction of the tensor traffic.
 inline int ln_bwd_blocks(int64_t rows, int32_t /*hidden*/)
 {
+#ifndef LSQ_LN_BWD_BLOCKS
+#define LSQ_LN_BWD_BLOCKS 256
+#endif
     int64_t b = ceil_div(rows, 8);       // at least 8 rows per workgroup
-    if (b > 256) b = 256;                // one workgroup per compute unit: measured best at 8192 rows
+    if (b > LSQ_LN_BWD_BLOCKS) b = LSQ_LN_BWD_BLOCKS;   // one workgroup per compute unit: measured best at 8192 rows
     if (b < 1) b = 1;
     return static_cast<int>(b);
 }
