@@ -292,6 +292,21 @@ __device__ __forceinline__ void dropout_factors8(const DropoutParams& d, uint64_
     }
 }
 
+// The keep decisions of pack `g` as 8 bits (bit j = element 8g + j survives): what a kernel whose
+// lanes are not aligned with packs stores in LDS, one Philox call per pack instead of per element.
+__device__ __forceinline__ uint32_t dropout_keep_bits8(const DropoutParams& d, uint64_t g)
+{
+    uint32_t w[4];
+    philox4x32_10(static_cast<uint32_t>(g), static_cast<uint32_t>(g >> 32), d.ctr2, d.ctr3, d.key0, d.key1, w);
+    uint32_t bits = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        bits |= ((w[j] & 0xFFFFu) >= d.t16 ? 1u : 0u) << (2 * j);
+        bits |= ((w[j] >> 16) >= d.t16 ? 1u : 0u) << (2 * j + 1);
+    }
+    return bits;
+}
+
 // The factor for one element (generic, unaligned paths: one Philox call per element).
 __device__ __forceinline__ float dropout_factor1(const DropoutParams& d, uint64_t e)
 {

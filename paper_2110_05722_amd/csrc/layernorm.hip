@@ -457,10 +457,12 @@ __global__ __launch_bounds__(256) void ln_bwd_generic(T* dx, const T* dy, const 
     }
 }
 
-// dgamma/dbeta for the generic path: one thread per column walks down the rows.
+// dgamma/dbeta for the generic path, first stage: one thread per column, gridDim.y row
+// blocks that each walk every gridDim.y-th row (four rows in flight); partial[y] =
+// [dgamma | dbeta] of block y, summed by colsum_finalize_kernel like the fast path's.
 // Runs BEFORE ln_bwd_generic so that dx may alias dy.
 template <typename T>
-__global__ __launch_bounds__(256) void ln_dparams_generic(float* __restrict__ dgamma, float* __restrict__ dbeta,
+__global__ __launch_bounds__(256) void ln_dparams_generic(float* __restrict__ partial,
                                                           const T* __restrict__ dy, const T* __restrict__ x,
                                                           const float* __restrict__ mean, const float* __restrict__ rstd,
                                                           int64_t rows, int hidden)
@@ -468,13 +470,27 @@ __global__ __launch_bounds__(256) void ln_dparams_generic(float* __restrict__ dg
     const int c = blockIdx.x * 256 + threadIdx.x;
     if (c >= hidden) return;
     float sg = 0.0f, sb = 0.0f;
-    for (int64_t r = 0; r < rows; ++r) {
-        const float gy = to_f32<T>(dy[r * hidden + c]);
-        sg = fmaf(gy, (to_f32<T>(x[r * hidden + c]) - mean[r]) * rstd[r], sg);
-        sb += gy;
+    const int64_t stride = gridDim.y;
+    for (int64_t r0 = blockIdx.y; r0 < rows; r0 += 4 * stride) {
+        float gy[4], xv[4], mu[4], rs[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t r = r0 + u * stride;
+            const bool ok = r < rows;
+            gy[u] = ok ? to_f32<T>(dy[r * hidden + c]) : 0.0f;
+            xv[u] = ok ? to_f32<T>(x[r * hidden + c]) : 0.0f;
+            mu[u] = ok ? mean[r] : 0.0f;
+            rs[u] = ok ? rstd[r] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            sg = fmaf(gy[u], (xv[u] - mu[u]) * rs[u], sg);
+            sb += gy[u];
+        }
     }
-    dgamma[c] = sg;
-    dbeta[c] = sb;
+    float* prow = partial + static_cast<int64_t>(blockIdx.y) * 2 * hidden;
+    prow[c] = sg;
+    prow[hidden + c] = sb;
 }
 
 // ------------------------------------------------------------------ dispatch
@@ -550,8 +566,11 @@ static lsq_status ln_bwd_dispatch(void* dx, float* dgamma, float* dbeta, const v
     const T* rp = static_cast<const T*>(dres);
     const LnShape sh = ln_shape(hidden);
     if (sh.lpr == 0) {
-        hipLaunchKernelGGL((ln_dparams_generic<T>), dim3(static_cast<unsigned>(ceil_div(hidden, 256))), dim3(256), 0, s,
-                           dgamma, dbeta, dyp, xp, mean, rstd, rows, hidden);
+        const int Pg = ln_bwd_blocks(rows, hidden);
+        float* gpartial = static_cast<float*>(workspace);
+        hipLaunchKernelGGL((ln_dparams_generic<T>), dim3(static_cast<unsigned>(ceil_div(hidden, 256)), static_cast<unsigned>(Pg)),
+                           dim3(256), 0, s, gpartial, dyp, xp, mean, rstd, rows, hidden);
+        launch_colsum_finalize(dgamma, dbeta, hidden, gpartial, Pg, 2 * hidden, s);
         hipLaunchKernelGGL((ln_bwd_generic<T>), dim3(static_cast<unsigned>(ceil_div(rows, 4))), dim3(256), 0, s,
                            dxp, dyp, xp, gp, mean, rstd, rp, rows, hidden);
         return launch_status();

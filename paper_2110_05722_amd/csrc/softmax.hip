@@ -9,9 +9,11 @@
 // read from HBM once, both reductions run on DPP inside the wave, and nothing
 // goes through LDS.  Short rows put many rows in one wave (k_len 32 -> 16 rows per
 // wave) so lanes are never idle.  Rows of 2049..16384 keys take one workgroup
-// each (the reductions cross its four waves through LDS); anything else (k_len not
-// a multiple of 8, or longer still) falls to a three-pass kernel that re-reads
-// the row from cache.
+// each (the reductions cross its four waves through LDS).  Rows whose length is
+// not a multiple of 8 (up to 2048) use the same scheme with element-granular lanes
+// (2-byte accesses: about a third of the aligned speed, so a caller that can pad
+// the key axis to a multiple of 8 and mask the padding with key_len should);
+// anything else falls to a three-pass kernel that re-reads the row from cache.
 //
 // Masks restrict the SET the softmax runs over: packs that lie wholly beyond the
 // row's limit (key padding, or the causal diagonal) are not even loaded, and
@@ -336,6 +338,133 @@ __global__ __launch_bounds__(256) void softmax_bwd_wide(T* dx, const T* dy, cons
     }
 }
 
+// ---- rows whose length is not a multiple of 8 (or whose tensors are not 16-byte aligned), up
+// to 2048 keys: the common case of a sequence-to-sequence batch.  Same register-resident,
+// read-once scheme with ELEMENT-granular lanes: lane `sub` of a row's group holds elements
+// sub, sub + LPR, ... (2-byte accesses, contiguous across the wave).  Dropout decisions are
+// still one Philox call per aligned pack of the flat tensor: the workgroup's rows cover one
+// contiguous element range, its threads compute the keep bits of the packs of that range
+// into LDS, and every element then picks its bit.
+template <int LPR>
+__device__ __forceinline__ float elem_max(float v, float* lds)
+{
+    if constexpr (LPR == 256) return block_allreduce<4, OpMax>(v, lds);
+    else return group_max<LPR>(v);
+}
+template <int LPR>
+__device__ __forceinline__ float elem_sum(float v, float* lds)
+{
+    if constexpr (LPR == 256) return block_allreduce<4, OpSum>(v, lds);
+    else return group_sum<LPR>(v);
+}
+
+// keep bits of the packs that the rows [row0, row0 + rpb) touch; returns the first pack's index
+template <int NBYTES>
+__device__ __forceinline__ int64_t elem_keep_mask(uint8_t (&keep)[NBYTES], const SoftmaxGeom& g, const DropoutParams& d,
+                                                  int64_t row0, int rpb)
+{
+    const int64_t e_begin = row0 * g.k_len;
+    const int64_t r_end = row0 + rpb < g.nrows ? row0 + rpb : g.nrows;
+    const int64_t p_begin = e_begin >> 3, p_end = (r_end * g.k_len + 7) >> 3;
+    for (int64_t pk = p_begin + threadIdx.x; pk < p_end; pk += 256)
+        keep[pk - p_begin] = static_cast<uint8_t>(dropout_keep_bits8(d, static_cast<uint64_t>(pk)));
+    __syncthreads();
+    return p_begin;
+}
+
+template <typename T, int LPR, int EPL, bool DROP>
+__global__ __launch_bounds__(256) void softmax_fwd_elem(T* y, T* __restrict__ yd, const T* x,
+                                                        SoftmaxLens len, SoftmaxGeom g, DropoutParams d)
+{
+    constexpr int RPB = 256 / LPR;
+    __shared__ float red[4];
+    __shared__ uint8_t keep[DROP ? 256 * EPL / 8 + 8 : 1];
+    const int sub = threadIdx.x % LPR;
+    const int64_t row0 = static_cast<int64_t>(blockIdx.x) * RPB;
+    const int64_t row = row0 + threadIdx.x / LPR;
+    const bool rv = row < g.nrows;
+    const int limit = rv ? row_limit(g, len, row) : 0;
+    const int64_t ro = row * g.k_len;
+    float v[EPL];
+#pragma unroll
+    for (int m = 0; m < EPL; ++m) {
+        const int j = sub + m * LPR;
+        v[m] = j < limit ? to_f32<T>(x[ro + j]) * g.scale : -INFINITY;
+    }
+    int64_t p_begin = 0;
+    if constexpr (DROP) p_begin = elem_keep_mask(keep, g, d, row0, RPB);
+    float mx = v[0];
+#pragma unroll
+    for (int m = 1; m < EPL; ++m) mx = fmaxf(mx, v[m]);
+    mx = elem_max<LPR>(mx, red);
+    const float mxs = (limit > 0 ? mx : 0.0f) * kLog2e;
+    float z = 0.0f;
+#pragma unroll
+    for (int m = 0; m < EPL; ++m) {
+        v[m] = __builtin_amdgcn_exp2f(fmaf(v[m], kLog2e, -mxs));
+        z += v[m];
+    }
+    z = elem_sum<LPR>(z, red);
+    const float inv = limit > 0 ? 1.0f / z : 0.0f;
+#pragma unroll
+    for (int m = 0; m < EPL; ++m) {
+        const int j = sub + m * LPR;
+        if (rv && j < g.k_len) {
+            const float o = v[m] * inv;           // 0 beyond the limit (exp2(-inf)), and on empty rows
+            y[ro + j] = from_f32<T>(o);
+            if constexpr (DROP) {
+                const int64_t e = ro + j;
+                const bool kept = (keep[(e >> 3) - p_begin] >> (e & 7)) & 1;
+                yd[e] = from_f32<T>(kept ? o * d.scale : 0.0f);
+            }
+        }
+    }
+}
+
+template <typename T, int LPR, int EPL, bool DROP>
+__global__ __launch_bounds__(256) void softmax_bwd_elem(T* dx, const T* dy, const T* __restrict__ y,
+                                                        SoftmaxLens len, SoftmaxGeom g, DropoutParams d)
+{
+    constexpr int RPB = 256 / LPR;
+    __shared__ float red[4];
+    __shared__ uint8_t keep[DROP ? 256 * EPL / 8 + 8 : 1];
+    const int sub = threadIdx.x % LPR;
+    const int64_t row0 = static_cast<int64_t>(blockIdx.x) * RPB;
+    const int64_t row = row0 + threadIdx.x / LPR;
+    const bool rv = row < g.nrows;
+    const int limit = rv ? row_limit(g, len, row) : 0;
+    const int64_t ro = row * g.k_len;
+    float yv[EPL], gv[EPL];
+#pragma unroll
+    for (int m = 0; m < EPL; ++m) {
+        const int j = sub + m * LPR;
+        yv[m] = j < limit ? to_f32<T>(y[ro + j]) : 0.0f;
+        gv[m] = j < limit ? to_f32<T>(dy[ro + j]) : 0.0f;
+    }
+    if constexpr (DROP) {
+        const int64_t p_begin = elem_keep_mask(keep, g, d, row0, RPB);
+#pragma unroll
+        for (int m = 0; m < EPL; ++m) {
+            const int j = sub + m * LPR;
+            if (j < limit) {
+                const int64_t e = ro + j;
+                const bool kept = (keep[(e >> 3) - p_begin] >> (e & 7)) & 1;
+                gv[m] = kept ? gv[m] * d.scale : 0.0f;
+            }
+        }
+    }
+    float dot = 0.0f;
+#pragma unroll
+    for (int m = 0; m < EPL; ++m) dot = fmaf(gv[m], yv[m], dot);
+    dot = elem_sum<LPR>(dot, red);
+#pragma unroll
+    for (int m = 0; m < EPL; ++m) {
+        const int j = sub + m * LPR;
+        if (rv && j < g.k_len)
+            dx[ro + j] = from_f32<T>(j < limit ? g.scale * yv[m] * (gv[m] - dot) : 0.0f);
+    }
+}
+
 // ---- generic path: any k_len; one wave per row, element-strided, row re-read from cache
 template <typename T>
 __global__ __launch_bounds__(256) void softmax_fwd_generic(T* y, T* __restrict__ yd, const T* x,
@@ -414,6 +543,22 @@ inline SmShape softmax_shape(int k_len)
     return {0, 0};
 }
 
+// element-granular buckets: lanes per row, elements per lane
+inline SmShape softmax_elem_shape(int k_len)
+{
+    if (k_len <= 8) return {8, 1};
+    if (k_len <= 16) return {16, 1};
+    if (k_len <= 32) return {32, 1};
+    if (k_len <= 64) return {64, 1};
+    if (k_len <= 128) return {64, 2};
+    if (k_len <= 256) return {64, 4};
+    if (k_len <= 512) return {64, 8};
+    if (k_len <= 1024) return {256, 4};
+    if (k_len <= 2048) return {256, 8};
+    return {0, 0};
+}
+#define LSQ_SM_ELEM_CASES(X) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 4) X(64, 8) X(256, 4) X(256, 8)
+
 #define LSQ_SM_CASES(X) X(1, 1) X(2, 1) X(4, 1) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 3) X(64, 4)
 
 // rows per lane group: about LSQ_SM_PACKS packs in flight per lane, and one row per
@@ -431,8 +576,21 @@ static lsq_status softmax_fwd_dispatch(void* y, void* yd, const void* x, Softmax
     T* yp = static_cast<T*>(y);
     T* ydp = static_cast<T*>(yd);
     const T* xp = static_cast<const T*>(x);
-    const SmShape sh = softmax_shape(g.k_len);
+    const bool packs_ok = g.k_len % kPack == 0 && aligned16(y) && aligned16(yd) && aligned16(x);
+    const SmShape sh = packs_ok ? softmax_shape(g.k_len) : SmShape{0, 0};
     const bool drop = d.t16 != 0;
+    const SmShape es = softmax_elem_shape(g.k_len);
+    if (sh.lpr == 0 && es.lpr != 0) {
+        const dim3 egrid(static_cast<unsigned>(ceil_div(g.nrows, 256 / es.lpr)));
+#define X(L, E)                                                                                              \
+        if (es.lpr == L && es.vpl == E) {                                                                    \
+            if (drop) hipLaunchKernelGGL((softmax_fwd_elem<T, L, E, true>), egrid, dim3(256), 0, s, yp, ydp, xp, key_len, g, d); \
+            else hipLaunchKernelGGL((softmax_fwd_elem<T, L, E, false>), egrid, dim3(256), 0, s, yp, ydp, xp, key_len, g, d);    \
+        }
+        LSQ_SM_ELEM_CASES(X)
+#undef X
+        return launch_status();
+    }
     if (sh.lpr == 0) {
         hipLaunchKernelGGL((softmax_fwd_generic<T>), dim3(static_cast<unsigned>(ceil_div(g.nrows, 4))), dim3(256), 0, s,
                            yp, ydp, xp, key_len, g, d);
@@ -473,8 +631,21 @@ static lsq_status softmax_bwd_dispatch(void* dx, const void* dy, const void* y, 
     T* dxp = static_cast<T*>(dx);
     const T* dyp = static_cast<const T*>(dy);
     const T* yp = static_cast<const T*>(y);
-    const SmShape sh = softmax_shape(g.k_len);
+    const bool packs_ok = g.k_len % kPack == 0 && aligned16(dx) && aligned16(dy) && aligned16(y);
+    const SmShape sh = packs_ok ? softmax_shape(g.k_len) : SmShape{0, 0};
     const bool drop = d.t16 != 0;
+    const SmShape es = softmax_elem_shape(g.k_len);
+    if (sh.lpr == 0 && es.lpr != 0) {
+        const dim3 egrid(static_cast<unsigned>(ceil_div(g.nrows, 256 / es.lpr)));
+#define X(L, E)                                                                                              \
+        if (es.lpr == L && es.vpl == E) {                                                                    \
+            if (drop) hipLaunchKernelGGL((softmax_bwd_elem<T, L, E, true>), egrid, dim3(256), 0, s, dxp, dyp, yp, key_len, g, d); \
+            else hipLaunchKernelGGL((softmax_bwd_elem<T, L, E, false>), egrid, dim3(256), 0, s, dxp, dyp, yp, key_len, g, d);    \
+        }
+        LSQ_SM_ELEM_CASES(X)
+#undef X
+        return launch_status();
+    }
     if (sh.lpr == 0) {
         hipLaunchKernelGGL((softmax_bwd_generic<T>), dim3(static_cast<unsigned>(ceil_div(g.nrows, 4))), dim3(256), 0, s,
                            dxp, dyp, yp, key_len, g, d);
