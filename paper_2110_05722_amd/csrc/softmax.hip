@@ -11,7 +11,7 @@
 // wave) so lanes are never idle.  Rows of 2049..16384 keys take one workgroup
 // each (the reductions cross its four waves through LDS).  Rows whose length is
 // not a multiple of 8 (up to 2048) use the same scheme with element-granular lanes
-// (2-byte accesses: about a third of the aligned speed, so a caller that can pad
+// (2-byte accesses: about half the aligned speed, so a caller that can pad
 // the key axis to a multiple of 8 and mask the padding with key_len should);
 // anything else falls to a three-pass kernel that re-reads the row from cache.
 //
@@ -543,9 +543,13 @@ inline SmShape softmax_shape(int k_len)
     return {0, 0};
 }
 
+#ifndef LSQ_SM_ELEM_WIDE
+#define LSQ_SM_ELEM_WIDE 0
+#endif
 // element-granular buckets: lanes per row, elements per lane
 inline SmShape softmax_elem_shape(int k_len)
 {
+#if LSQ_SM_ELEM_WIDE
     if (k_len <= 8) return {8, 1};
     if (k_len <= 16) return {16, 1};
     if (k_len <= 32) return {32, 1};
@@ -553,11 +557,25 @@ inline SmShape softmax_elem_shape(int k_len)
     if (k_len <= 128) return {64, 2};
     if (k_len <= 256) return {64, 4};
     if (k_len <= 512) return {64, 8};
+#else
+    // few lanes per row, up to 8 elements per lane: more rows per workgroup, more loads in flight per lane
+    if (k_len <= 8) return {8, 1};
+    if (k_len <= 16) return {8, 2};
+    if (k_len <= 32) return {8, 4};
+    if (k_len <= 64) return {8, 8};
+    if (k_len <= 128) return {16, 8};
+    if (k_len <= 256) return {32, 8};
+    if (k_len <= 512) return {64, 8};
+#endif
     if (k_len <= 1024) return {256, 4};
     if (k_len <= 2048) return {256, 8};
     return {0, 0};
 }
+#if LSQ_SM_ELEM_WIDE
 #define LSQ_SM_ELEM_CASES(X) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 4) X(64, 8) X(256, 4) X(256, 8)
+#else
+#define LSQ_SM_ELEM_CASES(X) X(8, 1) X(8, 2) X(8, 4) X(8, 8) X(16, 8) X(32, 8) X(64, 8) X(256, 4) X(256, 8)
+#endif
 
 #define LSQ_SM_CASES(X) X(1, 1) X(2, 1) X(4, 1) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 3) X(64, 4)
 
