@@ -449,10 +449,15 @@ def main():
     if "bdr_layernorm_fwd" in next_table and "bdr_layernorm_bwd" in next_table and not np.isnan(enc):
         # the same layers with every bias+dropout+residual fused into the LayerNorm that follows it (and the
         # LayerNorm backward with dres into the bias+dropout+residual backward before it)
-        pair = next_table["bdr_layernorm_fwd"]["us"] + next_table["bdr_layernorm_bwd"]["us"]
+        f_fused, b_fused = next_table["bdr_layernorm_fwd"]["us"], next_table["bdr_layernorm_bwd"]["us"]
+        f_sep = table["layernorm_fwd"]["us"] + table["bias_dropout_residual_fwd"]["us"]
+        b_sep = table["layernorm_bwd"]["us"] + table["bias_dropout_residual_bwd"]["us"]
+        pair = min(f_fused, f_sep) + min(b_fused, b_sep)          # per direction, whichever entry points are faster
         sm = table["softmax_fwd"]["us"] + table["softmax_bwd"]["us"]
         fused_layer = {"encoder_layer_fwd_bwd_nongemm": round(2 * pair + sm, 1),
-                       "decoder_layer_fwd_bwd_nongemm": round(3 * pair + 2 * sm, 1)}
+                       "decoder_layer_fwd_bwd_nongemm": round(3 * pair + 2 * sm, 1),
+                       "forward": "fused" if f_fused <= f_sep else "separate",
+                       "backward": "fused" if b_fused <= b_sep else "separate"}
 
     if args.calibrate:
         # known traffic for scaling FETCH_SIZE / WRITE_SIZE: reads 2^30 bytes, writes 2^30 bytes per launch
