@@ -190,6 +190,15 @@ __device__ __forceinline__ void opaque(RawPack<T>& r)
 #endif
 constexpr int kLnBwdThreads = LSQ_LN_BWD_THREADS;
 
+// Whether every row slot of a workgroup gets its own LDS copy of the column accumulators
+// (one barrier in the epilogue) or the slots take turns on one copy: decided by the LDS
+// it takes for the widest row of the bucket, kept under 64 KiB.
+template <int LPR, int VPL, int THREADS, int NACC>
+constexpr bool ln_bwd_slots_parallel()
+{
+    return LPR != 256 && static_cast<long>(THREADS / LPR) * NACC * 8 * ((LPR * VPL) | 1) * 4 <= 63 * 1024;
+}
+
 // partial: [gridDim.x][2][hidden] fp32 (dgamma row, then dbeta row).
 // THREADS lanes per workgroup: THREADS/LPR rows in flight per workgroup (plus their
 // prefetched successors).  With one wave per SIMD the kernel is bound by memory latency,
@@ -359,48 +368,77 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
             }
         }
     } else {
-        // Sum the RPB row slots in slot order through LDS.  Layout [dgamma|dbeta][j][pack] with an
-        // odd pack stride: consecutive lanes (consecutive packs) fall in consecutive banks.  A
+        // Sum the RPB row slots in slot order through LDS.  Layout [dgamma|dbeta(|dbias)][j][pack] with
+        // an odd pack stride: consecutive lanes (consecutive packs) fall in consecutive banks.  A
         // [column] layout would put the lanes of a wave 8 floats apart: a 16-way bank conflict.
         const int stride = nv | 1;
-        float* cg = colbuf;
-        float* cb = colbuf + 8 * stride;
-        float* ci = colbuf + 16 * stride;      // FUSE only
-        for (int turn = 0; turn < RPB; ++turn) {
-            if (slot == turn) {
-                // all reads of the turn first, then the adds, then all writes: a read-add-write
-                // per element would pay one LDS round trip each, 48 in a row
-                if (turn > 0) {
+        if constexpr (ln_bwd_slots_parallel<LPR, VPL, THREADS, NACC>()) {
+            // every slot has its own copy: all slots write at once, one barrier, then all threads
+            // add the RPB copies of their columns in slot order (same sums as taking turns)
+            const int per_slot = NACC * 8 * stride;
+            float* mine = colbuf + slot * per_slot;
 #pragma unroll
-                    for (int k = 0; k < VPL; ++k) {
-                        const int idx = min(sub + k * LPR, nv - 1);
+            for (int k = 0; k < VPL; ++k) {
+                const int idx = sub + k * LPR;
+                if (idx < nv) {
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) {
-                            dg[k][j] += cg[j * stride + idx];
-                            db[k][j] += cb[j * stride + idx];
-                            if constexpr (FUSE) dbi[k][j] += ci[j * stride + idx];
-                        }
-                    }
-                }
-#pragma unroll
-                for (int k = 0; k < VPL; ++k) {
-                    const int idx = sub + k * LPR;
-                    if (idx < nv) {
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) {
-                            cg[j * stride + idx] = dg[k][j];
-                            cb[j * stride + idx] = db[k][j];
-                            if constexpr (FUSE) ci[j * stride + idx] = dbi[k][j];
-                        }
+                    for (int j = 0; j < 8; ++j) {
+                        mine[j * stride + idx] = dg[k][j];
+                        mine[8 * stride + j * stride + idx] = db[k][j];
+                        if constexpr (FUSE) mine[16 * stride + j * stride + idx] = dbi[k][j];
                     }
                 }
             }
             __syncthreads();
-        }
-        for (int c = threadIdx.x; c < NACC * hidden; c += THREADS) {
-            const int which = c / hidden;
-            const int cc = c - which * hidden;
-            prow[c] = colbuf[which * 8 * stride + (cc & 7) * stride + (cc >> 3)];
+            for (int c = threadIdx.x; c < NACC * hidden; c += THREADS) {
+                const int which = c / hidden;
+                const int cc = c - which * hidden;
+                const int off = which * 8 * stride + (cc & 7) * stride + (cc >> 3);
+                float t = colbuf[off];
+#pragma unroll
+                for (int sl = 1; sl < RPB; ++sl) t += colbuf[sl * per_slot + off];
+                prow[c] = t;
+            }
+        } else {
+            float* cg = colbuf;
+            float* cb = colbuf + 8 * stride;
+            float* ci = colbuf + 16 * stride;      // FUSE only
+            for (int turn = 0; turn < RPB; ++turn) {
+                if (slot == turn) {
+                    // all reads of the turn first, then the adds, then all writes: a read-add-write
+                    // per element would pay one LDS round trip each, 48 in a row
+                    if (turn > 0) {
+#pragma unroll
+                        for (int k = 0; k < VPL; ++k) {
+                            const int idx = min(sub + k * LPR, nv - 1);
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) {
+                                dg[k][j] += cg[j * stride + idx];
+                                db[k][j] += cb[j * stride + idx];
+                                if constexpr (FUSE) dbi[k][j] += ci[j * stride + idx];
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int k = 0; k < VPL; ++k) {
+                        const int idx = sub + k * LPR;
+                        if (idx < nv) {
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) {
+                                cg[j * stride + idx] = dg[k][j];
+                                cb[j * stride + idx] = db[k][j];
+                                if constexpr (FUSE) ci[j * stride + idx] = dbi[k][j];
+                            }
+                        }
+                    }
+                }
+                __syncthreads();
+            }
+            for (int c = threadIdx.x; c < NACC * hidden; c += THREADS) {
+                const int which = c / hidden;
+                const int cc = c - which * hidden;
+                prow[c] = colbuf[which * 8 * stride + (cc & 7) * stride + (cc >> 3)];
+            }
         }
     }
 }
@@ -578,11 +616,13 @@ static lsq_status ln_bwd_dispatch(void* dx, float* dgamma, float* dbeta, const v
     const int P = ln_bwd_blocks(rows, hidden);
     float* partial = static_cast<float*>(workspace);
     const int nacc = fuse ? 3 : 2;
-    const size_t shmem = sh.lpr == 256 ? 0 : sizeof(float) * 8 * nacc * ((hidden / kPack) | 1);
+    const size_t one_copy = sh.lpr == 256 ? 0 : sizeof(float) * 8 * nacc * ((hidden / kPack) | 1);
     const BdrFuse<T> none{};
 #define X(L, V)                                                                                              \
     if (sh.lpr == L && sh.vpl == V) {                                                                        \
         constexpr int TH = L == 256 ? 256 : kLnBwdThreads;                                                   \
+        const bool par = fuse ? ln_bwd_slots_parallel<L, V, TH, 3>() : ln_bwd_slots_parallel<L, V, TH, 2>(); \
+        const size_t shmem = par ? one_copy * (TH / L) : one_copy;                                           \
         const dim3 grid(P), block(TH);                                                                       \
         if (!fuse) {                                                                                         \
             if (rp) hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, true, TH>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, none); \
