@@ -102,37 +102,46 @@ __global__ __launch_bounds__(256) void softmax_fwd_kernel(T* y, T* __restrict__ 
         const int64_t ro = row[r] * g.k_len;
         const int lim = limit[r];
         float v[VPL][8];
+        bool live[VPL];       // wave-uniform: does any lane of the wave hold an allowed element of pack k?
         float mx = -INFINITY;
 #pragma unroll
         for (int k = 0; k < VPL; ++k) {
             const int j0 = (sub + k * LPR) * kPack;
-            unpack<T>(raw[r][k], v[k]);
+            live[k] = __ballot(j0 < lim) != 0;
+            if (live[k]) {    // a pack that is masked for the whole wave costs no arithmetic
+                unpack<T>(raw[r][k], v[k]);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                v[k][j] = (j0 + j < lim) ? v[k][j] * g.scale : -INFINITY;
-                mx = fmaxf(mx, v[k][j]);
+                for (int j = 0; j < 8; ++j) {
+                    v[k][j] = (j0 + j < lim) ? v[k][j] * g.scale : -INFINITY;
+                    mx = fmaxf(mx, v[k][j]);
+                }
             }
         }
         mx = group_max<LPR>(mx);
         const float mxs = (lim > 0 ? mx : 0.0f) * kLog2e;
         float z = 0.0f;
 #pragma unroll
-        for (int k = 0; k < VPL; ++k)
+        for (int k = 0; k < VPL; ++k) {
+            if (live[k]) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float e = __builtin_amdgcn_exp2f(fmaf(v[k][j], kLog2e, -mxs));   // exp2(-inf) = 0 on masked lanes
-                v[k][j] = e;
-                z += e;
+                for (int j = 0; j < 8; ++j) {
+                    const float e = __builtin_amdgcn_exp2f(fmaf(v[k][j], kLog2e, -mxs));   // exp2(-inf) = 0 on masked lanes
+                    v[k][j] = e;
+                    z += e;
+                }
             }
+        }
         z = group_sum<LPR>(z);
         const float inv = lim > 0 ? 1.0f / z : 0.0f;
 #pragma unroll
         for (int k = 0; k < VPL; ++k) {
             const int idx = sub + k * LPR;
             if (row[r] < g.nrows && idx < nv) {
-                float o[8];
+                float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (live[k]) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) o[j] = v[k][j] * inv;
+                    for (int j = 0; j < 8; ++j) o[j] = v[k][j] * inv;
+                }
                 store8<T, kNT>(y + ro + idx * kPack, o);
                 if constexpr (DROP) {
                     if (idx * kPack < lim) {    // packs beyond the mask are zeros whatever the draw
