@@ -264,6 +264,11 @@ def main():
         L.lsq_bdr_layernorm_fwd(a["x"], bias, a["res"], gamma, beta, pr, ps, i, 1e-5, h=a["out"], y=a["y"], mean=a["mean"],
                                 rstd=a["rstd"])
 
+    def op_ln_bwd_dres(i):       # LayerNorm backward with the residual gradient added: what the fused backward replaces
+        a = layer[i % sets]
+        L.lsq_layernorm_bwd(a["dy"], a["x"], gamma, a["mean"], a["rstd"], dres_in=a["res"], dx=a["dx"], dgamma=dgamma,
+                            dbeta=dbeta, workspace=ws)
+
     def op_bdr_ln_bwd(i):
         a = layer[i % sets]
         L.lsq_bdr_layernorm_bwd(a["dy"], a["x"], gamma, a["mean"], a["rstd"], pr, ps, i, dres_in=a["res"], dh=a["dx"],
@@ -328,6 +333,7 @@ def main():
         "adam_step_lp": 22 * n, "sgd_step": 20 * n, "adam_step_blocked": 28 * n,
         "embedding_fwd": 4 * E + 4 * T, "embedding_bwd": 2 * E + 4 * n_unique * H + 4 * Lq * H + 4 * T,
         "split_heads_fwd": 12 * E + 6 * H, "split_heads_bwd": 12 * E + 12 * H, "merge_heads_fwd": 4 * E,
+        "layernorm_bwd_dres": 8 * E + 8 * T + 2 * H + 8 * H,
         "bdr_layernorm_fwd": 8 * E + 8 * T + 6 * H, "bdr_layernorm_bwd": 10 * E + 8 * T + 2 * H + 12 * H,
         "pad_remove": 4 * T_real * H + 4 * B, "pad_restore": 2 * T_real * H + 2 * E + 4 * B,
         "layernorm_fwd_packed": 4 * T_real * H + 8 * T_real + 4 * H,
@@ -348,7 +354,7 @@ def main():
     extra = [adam_other, ("bias_act_dropout_fwd", op_bad_fwd), ("bias_act_dropout_bwd", op_bad_bwd),
              ("embedding_fwd", op_emb_fwd), ("embedding_bwd", op_emb_bwd),
              ("split_heads_fwd", op_split_fwd), ("split_heads_bwd", op_split_bwd), ("merge_heads_fwd", op_merge_fwd),
-             ("bdr_layernorm_fwd", op_bdr_ln_fwd), ("bdr_layernorm_bwd", op_bdr_ln_bwd),
+             ("layernorm_bwd_dres", op_ln_bwd_dres), ("bdr_layernorm_fwd", op_bdr_ln_fwd), ("bdr_layernorm_bwd", op_bdr_ln_bwd),
              ("pad_remove", op_pad_remove), ("pad_restore", op_pad_restore), ("layernorm_fwd_packed", op_ln_fwd_packed),
              ("softmax_varlen_fwd", op_smv_fwd), ("softmax_varlen_bwd", op_smv_bwd),
              ("adam_step_lp", op_adam_lp), ("sgd_step", op_sgd)]
@@ -446,18 +452,19 @@ def main():
                + table["bias_dropout_residual_bwd"]["us"]) + 2 * (table["softmax_fwd"]["us"] + table["softmax_bwd"]["us"])
 
     fused_layer = None
-    if "bdr_layernorm_fwd" in next_table and "bdr_layernorm_bwd" in next_table and not np.isnan(enc):
-        # the same layers with every bias+dropout+residual fused into the LayerNorm that follows it (and the
-        # LayerNorm backward with dres into the bias+dropout+residual backward before it)
-        f_fused, b_fused = next_table["bdr_layernorm_fwd"]["us"], next_table["bdr_layernorm_bwd"]["us"]
-        f_sep = table["layernorm_fwd"]["us"] + table["bias_dropout_residual_fwd"]["us"]
-        b_sep = table["layernorm_bwd"]["us"] + table["bias_dropout_residual_bwd"]["us"]
-        pair = min(f_fused, f_sep) + min(b_fused, b_sep)          # per direction, whichever entry points are faster
+    need = ("bdr_layernorm_fwd", "bdr_layernorm_bwd", "layernorm_bwd_dres")
+    if all(k in next_table for k in need) and not np.isnan(enc):
+        # a pre-LN layer as it really runs: the LayerNorm backward also adds the gradient of the residual
+        # branch (dres_in), which the plain layernorm_bwd row above leaves out.  "separate" = four entry
+        # points per sub-layer boundary, "fused" = lsq_bdr_layernorm_fwd/bwd.
         sm = table["softmax_fwd"]["us"] + table["softmax_bwd"]["us"]
-        fused_layer = {"encoder_layer_fwd_bwd_nongemm": round(2 * pair + sm, 1),
-                       "decoder_layer_fwd_bwd_nongemm": round(3 * pair + 2 * sm, 1),
-                       "forward": "fused" if f_fused <= f_sep else "separate",
-                       "backward": "fused" if b_fused <= b_sep else "separate"}
+        sep = table["layernorm_fwd"]["us"] + table["bias_dropout_residual_fwd"]["us"] \
+            + next_table["layernorm_bwd_dres"]["us"] + table["bias_dropout_residual_bwd"]["us"]
+        fus = next_table["bdr_layernorm_fwd"]["us"] + next_table["bdr_layernorm_bwd"]["us"]
+        fused_layer = {"separate": {"encoder_layer_fwd_bwd_nongemm": round(2 * sep + sm, 1),
+                                    "decoder_layer_fwd_bwd_nongemm": round(3 * sep + 2 * sm, 1)},
+                       "fused": {"encoder_layer_fwd_bwd_nongemm": round(2 * fus + sm, 1),
+                                 "decoder_layer_fwd_bwd_nongemm": round(3 * fus + 2 * sm, 1)}}
 
     if args.calibrate:
         # known traffic for scaling FETCH_SIZE / WRITE_SIZE: reads 2^30 bytes, writes 2^30 bytes per launch
@@ -495,7 +502,7 @@ def main():
                                           f"({T_real} real rows of {T}): pack, unpack, LayerNorm on the packed rows, softmax "
                                           "with query lengths (rows of padded queries neither read nor computed)"),
         "layer_us": {"encoder_layer_fwd_bwd_nongemm": round(enc, 1), "decoder_layer_fwd_bwd_nongemm": round(dec, 1)},
-        "layer_us_fused_boundaries": fused_layer,
+        "layer_us_with_residual_gradient": fused_layer,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, dt)

@@ -239,30 +239,35 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
     }
 
     int64_t base = static_cast<int64_t>(blockIdx.x) * RPB;
-    RawPack<T> ndy[VPL], nx[VPL];
+    RawPack<T> ndy[VPL], nx[VPL], nres[HAS_RES ? VPL : 1];
     float nmu = 0.0f, nrs = 0.0f;
     {
         const int64_t r = base + slot;
         const bool rv = r < rows;
         ln_load_row<T, LPR, VPL>(ndy, dy, r, rv, hidden, nv, sub);
         ln_load_row<T, LPR, VPL>(nx, x, r, rv, hidden, nv, sub);
+        if constexpr (HAS_RES) ln_load_row<T, LPR, VPL>(nres, dres, r, rv, hidden, nv, sub);
         if (rv) { nmu = mean[r]; nrs = rstd[r]; }
     }
     for (; base < rows; base += gstride) {
         const int64_t r = base + slot;
         const bool rv = r < rows;
         const int64_t ro = r * hidden;
-        RawPack<T> cdy[VPL], cx[VPL], cres[VPL];
+        RawPack<T> cdy[VPL], cx[VPL], cres[HAS_RES ? VPL : 1];
 #pragma unroll
         for (int k = 0; k < VPL; ++k) { cdy[k] = ndy[k]; cx[k] = nx[k]; }
+        if constexpr (HAS_RES) {
+#pragma unroll
+            for (int k = 0; k < VPL; ++k) cres[k] = nres[k];
+        }
         const float mu = nmu, rs = nrs;
-        if constexpr (HAS_RES) ln_load_row<T, LPR, VPL>(cres, dres, r, rv, hidden, nv, sub);
 #if LSQ_LN_BWD_PREFETCH
         if (base + gstride < rows) {          // prefetch the next row group
             const int64_t rn = r + gstride;
             const bool rnv = rn < rows;
             ln_load_row<T, LPR, VPL>(ndy, dy, rn, rnv, hidden, nv, sub);
             ln_load_row<T, LPR, VPL>(nx, x, rn, rnv, hidden, nv, sub);
+            if constexpr (HAS_RES) ln_load_row<T, LPR, VPL>(nres, dres, rn, rnv, hidden, nv, sub);
             nmu = 0.0f; nrs = 0.0f;
             if (rnv) { nmu = mean[rn]; nrs = rstd[rn]; }
         }
@@ -350,6 +355,7 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
             const bool rnv = rn < rows;
             ln_load_row<T, LPR, VPL>(ndy, dy, rn, rnv, hidden, nv, sub);
             ln_load_row<T, LPR, VPL>(nx, x, rn, rnv, hidden, nv, sub);
+            if constexpr (HAS_RES) ln_load_row<T, LPR, VPL>(nres, dres, rn, rnv, hidden, nv, sub);
             nmu = 0.0f; nrs = 0.0f;
             if (rnv) { nmu = mean[rn]; nrs = rstd[rn]; }
         }
