@@ -552,22 +552,11 @@ inline SmShape softmax_shape(int k_len)
     return {0, 0};
 }
 
-#ifndef LSQ_SM_ELEM_WIDE
-#define LSQ_SM_ELEM_WIDE 0
-#endif
-// element-granular buckets: lanes per row, elements per lane
+// element-granular buckets: lanes per row, elements per lane.  Few lanes per row with up to 8
+// elements each (more rows per workgroup, more loads in flight per lane) measured 2x faster
+// than one element per lane on 64 lanes.
 inline SmShape softmax_elem_shape(int k_len)
 {
-#if LSQ_SM_ELEM_WIDE
-    if (k_len <= 8) return {8, 1};
-    if (k_len <= 16) return {16, 1};
-    if (k_len <= 32) return {32, 1};
-    if (k_len <= 64) return {64, 1};
-    if (k_len <= 128) return {64, 2};
-    if (k_len <= 256) return {64, 4};
-    if (k_len <= 512) return {64, 8};
-#else
-    // few lanes per row, up to 8 elements per lane: more rows per workgroup, more loads in flight per lane
     if (k_len <= 8) return {8, 1};
     if (k_len <= 16) return {8, 2};
     if (k_len <= 32) return {8, 4};
@@ -575,16 +564,11 @@ inline SmShape softmax_elem_shape(int k_len)
     if (k_len <= 128) return {16, 8};
     if (k_len <= 256) return {32, 8};
     if (k_len <= 512) return {64, 8};
-#endif
     if (k_len <= 1024) return {256, 4};
     if (k_len <= 2048) return {256, 8};
     return {0, 0};
 }
-#if LSQ_SM_ELEM_WIDE
-#define LSQ_SM_ELEM_CASES(X) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 4) X(64, 8) X(256, 4) X(256, 8)
-#else
 #define LSQ_SM_ELEM_CASES(X) X(8, 1) X(8, 2) X(8, 4) X(8, 8) X(16, 8) X(32, 8) X(64, 8) X(256, 4) X(256, 8)
-#endif
 
 #define LSQ_SM_CASES(X) X(1, 1) X(2, 1) X(4, 1) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 3) X(64, 4)
 
