@@ -326,7 +326,7 @@ def main():
         "bias_dropout_residual_bwd": 4 * E + 4 * H,
         "softmax_fwd": 2 * allowed + 2 * Es + (2 * Es if pa > 0 else 0),
         "softmax_bwd": 4 * allowed + 2 * Es,
-        "ls_xent_fwd": 2 * T * V + 16 * T,
+        "ls_xent_fwd": 2 * t_active * V + 16 * T,
         "ls_xent_bwd": 2 * t_active * V + 2 * T * V + 8 * T,
         "adam_step": 28 * n,
         "bias_act_dropout_fwd": 4 * EF + 2 * F, "bias_act_dropout_bwd": 6 * EF + 6 * F,

@@ -165,7 +165,7 @@ lsq_status lsq_softmax_bwd(void* dx, const void* dy, const void* y, const int32_
  *   nll  = -log q_k = lse - h_k,        lse = log sum_i exp(h_i).
  * logits: [tokens, vocab] dt;  target: int32[tokens];  loss, lse: fp32[tokens];
  * nll: nullable fp32[tokens].  A token whose target equals ignore_index or lies
- * outside [0, vocab) is ignored: loss = nll = 0 (lse is still written).
+ * outside [0, vocab) is ignored (padding): its row is not read, loss = nll = lse = 0.
  * sums: nullable fp32[3] = { sum loss, sum nll, number of non-ignored tokens },
  * reduced in a fixed order (bit-reproducible); it is cheapest when nll is given
  * (without it the target logits are gathered a second time). */

@@ -450,14 +450,15 @@ void lsqo_ls_xent_fwd(double* loss, double* nll, double* lse, double* sums, cons
 #pragma omp parallel for schedule(static)
     for (int64_t t = 0; t < tokens; ++t) {
         const int64_t o = t * vocab;
+        int32_t k = target[t];
+        /* a padded token contributes nothing and nothing of it is needed later: all three outputs are 0 */
+        if (ignored(k, vocab, ignore_index)) { loss[t] = 0.0; nll[t] = 0.0; lse[t] = 0.0; continue; }
         double mx = load(logits, o, dt);
         for (int i = 1; i < vocab; ++i) { double h = load(logits, o + i, dt); if (h > mx) mx = h; }
         double z = 0.0;
         for (int i = 0; i < vocab; ++i) z += exp(load(logits, o + i, dt) - mx);
         double l = mx + log(z);
         lse[t] = l;
-        int32_t k = target[t];
-        if (ignored(k, vocab, ignore_index)) { loss[t] = 0.0; nll[t] = 0.0; continue; }
         double acc = 0.0;
         for (int i = 0; i < vocab; ++i) {
             double pi = alpha / vocab + (i == k ? 1.0 - alpha : 0.0);
