@@ -315,6 +315,19 @@ def main():
         state["step"] += 1
         L.lsq_adam_step_lp(p_lp, m, v, g, step=state["step"], **ADAM_HYPER)
 
+    state_lp = state_sgd = None
+    if not args.ops or "adam_step_lp_blocked" in args.ops.split(","):
+        state_lp = L.lsq_trainer_state_pack([m, v])
+    if not args.ops or "sgd_step_blocked" in args.ops.split(","):
+        state_sgd = L.lsq_trainer_state_pack([p, m])
+
+    def op_adam_lp_blocked(i):
+        state["step"] += 1
+        L.lsq_adam_step_lp_blocked(p_lp, state_lp, g, step=state["step"], **ADAM_HYPER)
+
+    def op_sgd_blocked(i):
+        L.lsq_sgd_step_blocked(state_sgd, g, p_lp, lr=1e-3, momentum=0.9)
+
     def op_sgd(i):
         L.lsq_sgd_step(p, m, g, p_lp, lr=1e-3, momentum=0.9)      # m doubles as the momentum buffer here
 
@@ -331,6 +344,7 @@ def main():
         "adam_step": 28 * n,
         "bias_act_dropout_fwd": 4 * EF + 2 * F, "bias_act_dropout_bwd": 6 * EF + 6 * F,
         "adam_step_lp": 22 * n, "sgd_step": 20 * n, "adam_step_blocked": 28 * n,
+        "adam_step_lp_blocked": 22 * n, "sgd_step_blocked": 20 * n,
         "embedding_fwd": 4 * E + 4 * T, "embedding_bwd": 2 * E + 4 * n_unique * H + 4 * Lq * H + 4 * T,
         "split_heads_fwd": 12 * E + 6 * H, "split_heads_bwd": 12 * E + 12 * H, "merge_heads_fwd": 4 * E,
         "layernorm_bwd_dres": 8 * E + 8 * T + 2 * H + 8 * H,
@@ -357,7 +371,8 @@ def main():
              ("layernorm_bwd_dres", op_ln_bwd_dres), ("bdr_layernorm_fwd", op_bdr_ln_fwd), ("bdr_layernorm_bwd", op_bdr_ln_bwd),
              ("pad_remove", op_pad_remove), ("pad_restore", op_pad_restore), ("layernorm_fwd_packed", op_ln_fwd_packed),
              ("softmax_varlen_fwd", op_smv_fwd), ("softmax_varlen_bwd", op_smv_bwd),
-             ("adam_step_lp", op_adam_lp), ("sgd_step", op_sgd)]
+             ("adam_step_lp", op_adam_lp), ("adam_step_lp_blocked", op_adam_lp_blocked),
+             ("sgd_step", op_sgd), ("sgd_step_blocked", op_sgd_blocked)]
     if args.skip_ops:
         drop = set(args.skip_ops.split(","))
         extra = [o for o in extra if o[0] not in drop]

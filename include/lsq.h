@@ -284,6 +284,29 @@ lsq_status lsq_adam_step_blocked(float* state, const void* g, void* p_lp, int64_
                                  int32_t step, int32_t adamw, int32_t bias_correction,
                                  float inv_grad_scale, lsq_dtype g_dt, lsq_dtype p_lp_dt, void* stream);
 
+/* The blocked layout for any trainer: `arrays` (1..3) fp32 arrays of n elements that only
+ * the trainer reads, interleaved in blocks of LSQ_ADAM_BLOCK elements ([a0 | a1 | a2] per
+ * block).  lsq_adam_state_bytes/pack/unpack are the arrays = 3 case (p, m, v).
+ * pack: a0 required, a1 / a2 NULL mean zeros; unpack: NULL outputs are skipped. */
+size_t lsq_trainer_state_bytes(int64_t n, int32_t arrays);
+lsq_status lsq_trainer_state_pack(float* state, const float* a0, const float* a1, const float* a2,
+                                  int64_t n, int32_t arrays, void* stream);
+lsq_status lsq_trainer_state_unpack(float* a0, float* a1, float* a2, const float* state, int64_t n,
+                                    int32_t arrays, void* stream);
+
+/* lsq_sgd_step with the master parameters and the momentum buffer blocked as [p | buf]
+ * (arrays = 2; the buffer's blocks are present but untouched when momentum == 0), and
+ * lsq_adam_step_lp with both moments blocked as [m | v] (arrays = 2) next to the
+ * low-precision parameters that stay flat.  Arithmetic, bytes and errors as in the
+ * entry points they mirror; results are bit-identical. */
+lsq_status lsq_sgd_step_blocked(float* state, const void* g, void* p_lp, int64_t n,
+                                float lr, float momentum, float weight_decay, int32_t nesterov,
+                                float inv_grad_scale, lsq_dtype g_dt, lsq_dtype p_lp_dt, void* stream);
+lsq_status lsq_adam_step_lp_blocked(void* p_lp, float* state, const void* g, int64_t n,
+                                    float lr, float beta1, float beta2, float eps, float weight_decay,
+                                    int32_t step, int32_t adamw, int32_t bias_correction,
+                                    float inv_grad_scale, lsq_dtype dt, void* stream);
+
 /* SGD over the flat workspace, one launch (the paper's second trainer, Sec. VI-C):
  *   ghat = g * inv_grad_scale + weight_decay * p
  *   buf  = momentum * buf + ghat                    (momentum > 0; buf starts at 0)

@@ -33,6 +33,8 @@ EXPORTS = [
     "lsq_embedding_fwd", "lsq_embedding_bwd",
     "lsq_bdr_layernorm_fwd", "lsq_bdr_layernorm_bwd",
     "lsq_adam_state_bytes", "lsq_adam_state_pack", "lsq_adam_state_unpack", "lsq_adam_step_blocked",
+    "lsq_trainer_state_bytes", "lsq_trainer_state_pack", "lsq_trainer_state_unpack", "lsq_sgd_step_blocked",
+    "lsq_adam_step_lp_blocked",
     "lsq_pad_offsets", "lsq_pad_remove", "lsq_pad_restore", "lsq_softmax_varlen_fwd", "lsq_softmax_varlen_bwd",
 ]
 
@@ -85,6 +87,11 @@ def load():
         "lsq_adam_state_pack": (C.c_int, [vp, vp, vp, vp, i64, vp]),
         "lsq_adam_state_unpack": (C.c_int, [vp, vp, vp, vp, i64, vp]),
         "lsq_adam_step_blocked": (C.c_int, [vp, vp, vp, i64, f32, f32, f32, f32, f32, i32, i32, i32, f32, C.c_int, C.c_int, vp]),
+        "lsq_trainer_state_bytes": (sz, [i64, i32]),
+        "lsq_trainer_state_pack": (C.c_int, [vp, vp, vp, vp, i64, i32, vp]),
+        "lsq_trainer_state_unpack": (C.c_int, [vp, vp, vp, vp, i64, i32, vp]),
+        "lsq_sgd_step_blocked": (C.c_int, [vp, vp, vp, i64, f32, f32, f32, i32, f32, C.c_int, C.c_int, vp]),
+        "lsq_adam_step_lp_blocked": (C.c_int, [vp, vp, vp, i64, f32, f32, f32, f32, f32, i32, i32, i32, f32, C.c_int, vp]),
         "lsq_pad_offsets": (C.c_int, [vp, vp, i32, i32, vp]),
         "lsq_pad_remove": (C.c_int, [vp, vp, vp, i32, i32, i32, i64, C.c_int, vp]),
         "lsq_pad_restore": (C.c_int, [vp, vp, vp, i32, i32, i32, i64, C.c_int, vp]),
@@ -495,6 +502,60 @@ def lsq_adam_step_blocked(state, g, p_lp=None, *, lr: float, beta1: float, beta2
                                         int(adamw), int(bias_correction), inv_grad_scale, _dt(g),
                                         _dt(p_lp) if p_lp is not None else LSQ_F16, _stream()), "lsq_adam_step_blocked")
     return state, p_lp
+
+
+def lsq_trainer_state_bytes(n: int, arrays: int) -> int:
+    return int(load().lsq_trainer_state_bytes(n, arrays))
+
+
+def lsq_trainer_state_pack(arrays_in, state=None):
+    """List of 1..3 fp32 tensors [n] (entries after the first may be None = zeros) -> blocked state."""
+    k = len(arrays_in)
+    a0 = arrays_in[0]
+    n = a0.numel()
+    need = lsq_trainer_state_bytes(n, k) // 4
+    state = torch.empty(need, dtype=torch.float32, device=a0.device) if state is None else state
+    _need("state", state, need, torch.float32)
+    for t in arrays_in:
+        _need("array", t, n, torch.float32)
+    ptrs = [_ptr(t) for t in arrays_in] + [None] * (3 - k)
+    _check(load().lsq_trainer_state_pack(_ptr(state), ptrs[0], ptrs[1], ptrs[2], n, k, _stream()), "lsq_trainer_state_pack")
+    return state
+
+
+def lsq_trainer_state_unpack(state, n: int, arrays: int):
+    """Blocked state -> list of `arrays` fp32 tensors [n]."""
+    _need("state", state, lsq_trainer_state_bytes(n, arrays) // 4, torch.float32)
+    outs = [torch.empty(n, dtype=torch.float32, device=state.device) for _ in range(arrays)]
+    ptrs = [_ptr(t) for t in outs] + [None] * (3 - arrays)
+    _check(load().lsq_trainer_state_unpack(ptrs[0], ptrs[1], ptrs[2], _ptr(state), n, arrays, _stream()),
+           "lsq_trainer_state_unpack")
+    return outs
+
+
+def lsq_sgd_step_blocked(state, g, p_lp=None, *, lr: float, momentum: float = 0.0, weight_decay: float = 0.0,
+                         nesterov: bool = False, inv_grad_scale: float = 1.0):
+    """lsq_sgd_step on the [p | momentum buffer] blocked state (in place)."""
+    n = g.numel()
+    _need("state", state, lsq_trainer_state_bytes(n, 2) // 4, torch.float32); _need("p_lp", p_lp, n)
+    _check(load().lsq_sgd_step_blocked(_ptr(state), _ptr(g), _ptr(p_lp), n, lr, momentum, weight_decay, int(nesterov),
+                                       inv_grad_scale, _dt(g), _dt(p_lp) if p_lp is not None else LSQ_F16, _stream()),
+           "lsq_sgd_step_blocked")
+    return state, p_lp
+
+
+def lsq_adam_step_lp_blocked(p_lp, state, g, *, lr: float, beta1: float, beta2: float, eps: float, step: int,
+                             weight_decay: float = 0.0, adamw: bool = False, bias_correction: bool = True,
+                             inv_grad_scale: float = 1.0):
+    """lsq_adam_step_lp with the moments in the [m | v] blocked state (p_lp and the state in place)."""
+    if g.dtype != p_lp.dtype:
+        raise LsqError("g and p_lp must share one low-precision dtype")
+    n = p_lp.numel()
+    _need("state", state, lsq_trainer_state_bytes(n, 2) // 4, torch.float32); _need("g", g, n)
+    _check(load().lsq_adam_step_lp_blocked(_ptr(p_lp), _ptr(state), _ptr(g), n, lr, beta1, beta2, eps, weight_decay, step,
+                                           int(adamw), int(bias_correction), inv_grad_scale, _dt(p_lp), _stream()),
+           "lsq_adam_step_lp_blocked")
+    return p_lp, state
 
 
 def lsq_pad_offsets(key_len, batch: int, max_len: int, offsets=None):

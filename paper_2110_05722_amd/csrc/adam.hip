@@ -41,10 +41,11 @@ constexpr int kAdamPack = 4;
 constexpr int kAdamBlock = LSQ_ADAM_BLOCK;
 static_assert(kAdamBlock % (256 * kAdamPack) == 0, "a workgroup must not straddle a block");
 
-// offset of element e of the p array inside the blocked state; m and v follow at +1 and +2 blocks
-__device__ __host__ __forceinline__ int64_t adam_state_offset(int64_t e)
+// offset of element e of the first array inside a blocked state of `arrays` arrays; the other
+// arrays follow at +1 and +2 blocks
+__device__ __host__ __forceinline__ int64_t adam_state_offset(int64_t e, int arrays = 3)
 {
-    return (e / kAdamBlock) * (3 * static_cast<int64_t>(kAdamBlock)) + (e % kAdamBlock);
+    return (e / kAdamBlock) * (arrays * static_cast<int64_t>(kAdamBlock)) + (e % kAdamBlock);
 }
 
 template <typename G, typename PL, bool HAS_PL, bool BLOCKED>
@@ -107,14 +108,16 @@ static lsq_status adam_dispatch(float* p, float* m, float* v, const void* g, voi
 // state <- (p, m, v) (PACK) or (p, m, v) <- state; absent m / v read as zeros / are skipped.
 // One thread per 4 elements of the padded length; the padding of the last block is zero-filled.
 template <bool PACK>
-__global__ __launch_bounds__(256) void adam_state_move(float* state, float* p, float* m, float* v, int64_t n, int64_t padded)
+__global__ __launch_bounds__(256) void adam_state_move(float* state, float* p, float* m, float* v, int64_t n, int64_t padded,
+                                                       int arrays)
 {
     const int64_t e = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * kAdamPack;
     if (e >= padded) return;
-    float* sp = state + adam_state_offset(e);
+    float* sp = state + adam_state_offset(e, arrays);
     float* arr[3] = {p, m, v};
 #pragma unroll
     for (int k = 0; k < 3; ++k) {
+        if (k >= arrays) break;
         float* a = arr[k];
         float* sk = sp + k * kAdamBlock;
         if (e + kAdamPack <= n) {
@@ -138,11 +141,15 @@ __global__ __launch_bounds__(256) void adam_state_move(float* state, float* p, f
 
 // ---- the paper's own layout: the workspace holds the parameter in low precision and
 // it is updated in place (Sec. IV-C, "on-the-fly conversion"): 22 bytes per parameter.
-template <typename T>
+template <typename T, bool BLOCKED>
 __global__ __launch_bounds__(256) void adam_lp_kernel(T* __restrict__ p, float* __restrict__ m, float* __restrict__ v,
                                                       const T* __restrict__ g, int64_t n, AdamParams a)
 {
     const int64_t e = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * kAdamPack;
+    if constexpr (BLOCKED) {        // m is the [m | v] state
+        m += adam_state_offset(e, 2) - e;
+        v = m + kAdamBlock;
+    }
     if (e + kAdamPack <= n) {
         float pf[4], mf[4], vf[4], gf[4];
         load4<T, true>(p + e, pf);
@@ -179,11 +186,15 @@ __device__ __forceinline__ void sgd_update(float& p, float& b, float g, const Sg
     p = fmaf(-a.lr, d, p);
 }
 
-template <typename G, typename PL, bool HAS_PL, bool MOM>
+template <typename G, typename PL, bool HAS_PL, bool MOM, bool BLOCKED>
 __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ p, float* __restrict__ buf,
                                                   const G* __restrict__ g, PL* __restrict__ plp, int64_t n, SgdParams a)
 {
     const int64_t e = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * kAdamPack;
+    if constexpr (BLOCKED) {        // p is the [p | momentum buffer] state
+        p += adam_state_offset(e, 2) - e;
+        buf = p + kAdamBlock;
+    }
     if (e + kAdamPack <= n) {
         float pf[4], bf[4] = {0, 0, 0, 0}, gf[4];
         load4<float, true>(p + e, pf);
@@ -209,18 +220,18 @@ __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ p, float* 
     }
 }
 
-template <typename G, bool MOM>
+template <typename G, bool MOM, bool BLOCKED = false>
 static lsq_status sgd_dispatch(float* p, float* buf, const void* g, void* plp, int64_t n, const SgdParams& a,
                                int p_lp_dt, hipStream_t s)
 {
     const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(n, kAdamPack), 256))), block(256);
     const G* gp = static_cast<const G*>(g);
     if (!plp)
-        hipLaunchKernelGGL((sgd_kernel<G, f16, false, MOM>), grid, block, 0, s, p, buf, gp, static_cast<f16*>(nullptr), n, a);
+        hipLaunchKernelGGL((sgd_kernel<G, f16, false, MOM, BLOCKED>), grid, block, 0, s, p, buf, gp, static_cast<f16*>(nullptr), n, a);
     else if (p_lp_dt == LSQ_F16)
-        hipLaunchKernelGGL((sgd_kernel<G, f16, true, MOM>), grid, block, 0, s, p, buf, gp, static_cast<f16*>(plp), n, a);
+        hipLaunchKernelGGL((sgd_kernel<G, f16, true, MOM, BLOCKED>), grid, block, 0, s, p, buf, gp, static_cast<f16*>(plp), n, a);
     else
-        hipLaunchKernelGGL((sgd_kernel<G, bf16, true, MOM>), grid, block, 0, s, p, buf, gp, static_cast<bf16*>(plp), n, a);
+        hipLaunchKernelGGL((sgd_kernel<G, bf16, true, MOM, BLOCKED>), grid, block, 0, s, p, buf, gp, static_cast<bf16*>(plp), n, a);
     return launch_status();
 }
 
@@ -271,40 +282,54 @@ extern "C" lsq_status lsq_adam_step(float* p, float* m, float* v, const void* g,
     }
 }
 
-extern "C" size_t lsq_adam_state_bytes(int64_t n)
+extern "C" size_t lsq_trainer_state_bytes(int64_t n, int32_t arrays)
 {
-    if (n <= 0) return 0;
-    return static_cast<size_t>(lsq::ceil_div(n, lsq::kAdamBlock)) * 3 * lsq::kAdamBlock * sizeof(float);
+    if (n <= 0 || arrays < 1 || arrays > 3) return 0;
+    return static_cast<size_t>(lsq::ceil_div(n, lsq::kAdamBlock)) * arrays * lsq::kAdamBlock * sizeof(float);
 }
+
+extern "C" lsq_status lsq_trainer_state_pack(float* state, const float* a0, const float* a1, const float* a2, int64_t n,
+                                             int32_t arrays, void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(n >= 0 && arrays >= 1 && arrays <= 3);
+    if (n == 0) return LSQ_OK;
+    LSQ_REQUIRE(state && a0);
+    LSQ_ALIGNED(state); LSQ_ALIGNED(a0); LSQ_ALIGNED(a1); LSQ_ALIGNED(a2);
+    const int64_t padded = ceil_div(n, kAdamBlock) * kAdamBlock;
+    LSQ_REQUIRE(padded / (256 * kAdamPack) <= 0x7FFFFFFF);
+    hipLaunchKernelGGL((adam_state_move<true>), dim3(static_cast<unsigned>(padded / (256 * kAdamPack))), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), state, const_cast<float*>(a0), const_cast<float*>(a1),
+                       const_cast<float*>(a2), n, padded, arrays);
+    return launch_status();
+}
+
+extern "C" lsq_status lsq_trainer_state_unpack(float* a0, float* a1, float* a2, const float* state, int64_t n,
+                                               int32_t arrays, void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(n >= 0 && arrays >= 1 && arrays <= 3);
+    if (n == 0) return LSQ_OK;
+    LSQ_REQUIRE(state);
+    LSQ_ALIGNED(state); LSQ_ALIGNED(a0); LSQ_ALIGNED(a1); LSQ_ALIGNED(a2);
+    const int64_t padded = ceil_div(n, kAdamBlock) * kAdamBlock;
+    LSQ_REQUIRE(padded / (256 * kAdamPack) <= 0x7FFFFFFF);
+    hipLaunchKernelGGL((adam_state_move<false>), dim3(static_cast<unsigned>(padded / (256 * kAdamPack))), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), const_cast<float*>(state), a0, a1, a2, n, padded, arrays);
+    return launch_status();
+}
+
+extern "C" size_t lsq_adam_state_bytes(int64_t n) { return lsq_trainer_state_bytes(n, 3); }
 
 extern "C" lsq_status lsq_adam_state_pack(float* state, const float* p, const float* m, const float* v, int64_t n,
                                           void* stream)
 {
-    using namespace lsq;
-    LSQ_REQUIRE(n >= 0);
-    if (n == 0) return LSQ_OK;
-    LSQ_REQUIRE(state && p);
-    LSQ_ALIGNED(state); LSQ_ALIGNED(p); LSQ_ALIGNED(m); LSQ_ALIGNED(v);
-    const int64_t padded = ceil_div(n, kAdamBlock) * kAdamBlock;
-    LSQ_REQUIRE(padded / (256 * kAdamPack) <= 0x7FFFFFFF);
-    hipLaunchKernelGGL((adam_state_move<true>), dim3(static_cast<unsigned>(padded / (256 * kAdamPack))), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), state, const_cast<float*>(p), const_cast<float*>(m),
-                       const_cast<float*>(v), n, padded);
-    return launch_status();
+    return lsq_trainer_state_pack(state, p, m, v, n, 3, stream);
 }
 
 extern "C" lsq_status lsq_adam_state_unpack(float* p, float* m, float* v, const float* state, int64_t n, void* stream)
 {
-    using namespace lsq;
-    LSQ_REQUIRE(n >= 0);
-    if (n == 0) return LSQ_OK;
-    LSQ_REQUIRE(state);
-    LSQ_ALIGNED(state); LSQ_ALIGNED(p); LSQ_ALIGNED(m); LSQ_ALIGNED(v);
-    const int64_t padded = ceil_div(n, kAdamBlock) * kAdamBlock;
-    LSQ_REQUIRE(padded / (256 * kAdamPack) <= 0x7FFFFFFF);
-    hipLaunchKernelGGL((adam_state_move<false>), dim3(static_cast<unsigned>(padded / (256 * kAdamPack))), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), const_cast<float*>(state), p, m, v, n, padded);
-    return launch_status();
+    return lsq_trainer_state_unpack(p, m, v, state, n, 3, stream);
 }
 
 extern "C" lsq_status lsq_adam_step_blocked(float* state, const void* g, void* p_lp, int64_t n, float lr, float beta1,
@@ -330,50 +355,86 @@ extern "C" lsq_status lsq_adam_step_blocked(float* state, const void* g, void* p
     }
 }
 
-extern "C" lsq_status lsq_adam_step_lp(void* p_lp, float* m, float* v, const void* g, int64_t n, float lr, float beta1,
-                                       float beta2, float eps, float weight_decay, int32_t step, int32_t adamw,
-                                       int32_t bias_correction, float inv_grad_scale, lsq_dtype dt, void* stream)
+namespace lsq {
+template <bool BLOCKED>
+static lsq_status adam_lp_entry(void* p_lp, float* m, float* v, const void* g, int64_t n, float lr, float beta1,
+                                float beta2, float eps, float weight_decay, int32_t step, int32_t adamw,
+                                int32_t bias_correction, float inv_grad_scale, lsq_dtype dt, void* stream)
 {
-    using namespace lsq;
     LSQ_REQUIRE(n >= 0);
     AdamParams a;
     LSQ_REQUIRE(make_adam_params(&a, lr, beta1, beta2, eps, weight_decay, step, adamw, bias_correction, inv_grad_scale));
     if (dt != LSQ_F16 && dt != LSQ_BF16) return LSQ_UNSUPPORTED_DTYPE;
     if (n == 0) return LSQ_OK;
-    LSQ_REQUIRE(p_lp && m && v && g);
+    LSQ_REQUIRE(p_lp && m && (BLOCKED || v) && g);
     LSQ_ALIGNED(p_lp); LSQ_ALIGNED(m); LSQ_ALIGNED(v); LSQ_ALIGNED(g);
     LSQ_REQUIRE(ceil_div(ceil_div(n, kAdamPack), 256) <= 0x7FFFFFFF);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(n, kAdamPack), 256))), block(256);
     if (dt == LSQ_F16)
-        hipLaunchKernelGGL((adam_lp_kernel<f16>), grid, block, 0, s, static_cast<f16*>(p_lp), m, v, static_cast<const f16*>(g), n, a);
+        hipLaunchKernelGGL((adam_lp_kernel<f16, BLOCKED>), grid, block, 0, s, static_cast<f16*>(p_lp), m, v, static_cast<const f16*>(g), n, a);
     else
-        hipLaunchKernelGGL((adam_lp_kernel<bf16>), grid, block, 0, s, static_cast<bf16*>(p_lp), m, v, static_cast<const bf16*>(g), n, a);
+        hipLaunchKernelGGL((adam_lp_kernel<bf16, BLOCKED>), grid, block, 0, s, static_cast<bf16*>(p_lp), m, v, static_cast<const bf16*>(g), n, a);
     return launch_status();
 }
+}  // namespace lsq
 
-extern "C" lsq_status lsq_sgd_step(float* p, float* momentum_buf, const void* g, void* p_lp, int64_t n, float lr,
-                                   float momentum, float weight_decay, int32_t nesterov, float inv_grad_scale,
-                                   lsq_dtype g_dt, lsq_dtype p_lp_dt, void* stream)
+extern "C" lsq_status lsq_adam_step_lp(void* p_lp, float* m, float* v, const void* g, int64_t n, float lr, float beta1,
+                                       float beta2, float eps, float weight_decay, int32_t step, int32_t adamw,
+                                       int32_t bias_correction, float inv_grad_scale, lsq_dtype dt, void* stream)
 {
-    using namespace lsq;
+    return lsq::adam_lp_entry<false>(p_lp, m, v, g, n, lr, beta1, beta2, eps, weight_decay, step, adamw, bias_correction,
+                                     inv_grad_scale, dt, stream);
+}
+
+extern "C" lsq_status lsq_adam_step_lp_blocked(void* p_lp, float* state, const void* g, int64_t n, float lr, float beta1,
+                                               float beta2, float eps, float weight_decay, int32_t step, int32_t adamw,
+                                               int32_t bias_correction, float inv_grad_scale, lsq_dtype dt, void* stream)
+{
+    return lsq::adam_lp_entry<true>(p_lp, state, nullptr, g, n, lr, beta1, beta2, eps, weight_decay, step, adamw,
+                                    bias_correction, inv_grad_scale, dt, stream);
+}
+
+namespace lsq {
+template <bool BLOCKED>
+static lsq_status sgd_entry(float* p, float* momentum_buf, const void* g, void* p_lp, int64_t n, float lr,
+                            float momentum, float weight_decay, int32_t nesterov, float inv_grad_scale,
+                            lsq_dtype g_dt, lsq_dtype p_lp_dt, void* stream)
+{
     LSQ_REQUIRE(n >= 0 && momentum >= 0.0f);
     LSQ_REQUIRE(!(nesterov && momentum == 0.0f));
     if (!valid_dtype(g_dt)) return LSQ_UNSUPPORTED_DTYPE;
     if (p_lp && p_lp_dt != LSQ_F16 && p_lp_dt != LSQ_BF16) return LSQ_UNSUPPORTED_DTYPE;
     if (n == 0) return LSQ_OK;
-    LSQ_REQUIRE(p && g && (momentum == 0.0f || momentum_buf));
+    LSQ_REQUIRE(p && g && (BLOCKED || momentum == 0.0f || momentum_buf));
     LSQ_ALIGNED(p); LSQ_ALIGNED(momentum_buf); LSQ_ALIGNED(g); LSQ_ALIGNED(p_lp);
     LSQ_REQUIRE(ceil_div(ceil_div(n, kAdamPack), 256) <= 0x7FFFFFFF);
     SgdParams a{lr, momentum, weight_decay, inv_grad_scale, nesterov != 0};
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool mom = momentum != 0.0f;
     switch (g_dt) {
-        case LSQ_F16: return mom ? sgd_dispatch<f16, true>(p, momentum_buf, g, p_lp, n, a, p_lp_dt, s)
-                                 : sgd_dispatch<f16, false>(p, momentum_buf, g, p_lp, n, a, p_lp_dt, s);
-        case LSQ_BF16: return mom ? sgd_dispatch<bf16, true>(p, momentum_buf, g, p_lp, n, a, p_lp_dt, s)
-                                  : sgd_dispatch<bf16, false>(p, momentum_buf, g, p_lp, n, a, p_lp_dt, s);
-        default: return mom ? sgd_dispatch<float, true>(p, momentum_buf, g, p_lp, n, a, p_lp_dt, s)
-                            : sgd_dispatch<float, false>(p, momentum_buf, g, p_lp, n, a, p_lp_dt, s);
+        case LSQ_F16: return mom ? sgd_dispatch<f16, true, BLOCKED>(p, momentum_buf, g, p_lp, n, a, p_lp_dt, s)
+                                 : sgd_dispatch<f16, false, BLOCKED>(p, momentum_buf, g, p_lp, n, a, p_lp_dt, s);
+        case LSQ_BF16: return mom ? sgd_dispatch<bf16, true, BLOCKED>(p, momentum_buf, g, p_lp, n, a, p_lp_dt, s)
+                                  : sgd_dispatch<bf16, false, BLOCKED>(p, momentum_buf, g, p_lp, n, a, p_lp_dt, s);
+        default: return mom ? sgd_dispatch<float, true, BLOCKED>(p, momentum_buf, g, p_lp, n, a, p_lp_dt, s)
+                            : sgd_dispatch<float, false, BLOCKED>(p, momentum_buf, g, p_lp, n, a, p_lp_dt, s);
     }
+}
+}  // namespace lsq
+
+extern "C" lsq_status lsq_sgd_step(float* p, float* momentum_buf, const void* g, void* p_lp, int64_t n, float lr,
+                                   float momentum, float weight_decay, int32_t nesterov, float inv_grad_scale,
+                                   lsq_dtype g_dt, lsq_dtype p_lp_dt, void* stream)
+{
+    return lsq::sgd_entry<false>(p, momentum_buf, g, p_lp, n, lr, momentum, weight_decay, nesterov, inv_grad_scale, g_dt,
+                                 p_lp_dt, stream);
+}
+
+extern "C" lsq_status lsq_sgd_step_blocked(float* state, const void* g, void* p_lp, int64_t n, float lr, float momentum,
+                                           float weight_decay, int32_t nesterov, float inv_grad_scale, lsq_dtype g_dt,
+                                           lsq_dtype p_lp_dt, void* stream)
+{
+    return lsq::sgd_entry<true>(state, nullptr, g, p_lp, n, lr, momentum, weight_decay, nesterov, inv_grad_scale, g_dt,
+                                p_lp_dt, stream);
 }

@@ -155,6 +155,25 @@ def test_host_side_argument_errors_of_the_blocked_adam(lib):
     assert f(None, None, None, 0, 1e-3, .9, .98, 1e-8, 0., 1, 0, 1, 1., 0, 0, None) == 0
 
 
+def test_host_side_argument_errors_of_the_blocked_trainers(lib):
+    INVALID, DTYPE = 1, 2
+    lib.lsq_trainer_state_bytes.restype = C.c_size_t
+    assert lib.lsq_trainer_state_bytes(10, 0) == 0 and lib.lsq_trainer_state_bytes(10, 4) == 0
+    assert lib.lsq_trainer_state_bytes(10, 2) == 2 * 8192 * 4
+    assert lib.lsq_trainer_state_pack(A, A, A, A, 8, 4, None) == INVALID
+    assert lib.lsq_trainer_state_pack(A, None, A, A, 8, 2, None) == INVALID
+    assert lib.lsq_trainer_state_unpack(A, A, A, A, 8, 0, None) == INVALID
+    f = lib.lsq_sgd_step_blocked
+    assert f(A, A, None, 8, 0.1, -0.5, 0., 0, 1., 0, 0, None) == INVALID
+    assert f(A, A, None, 8, 0.1, 0.0, 0., 1, 1., 0, 0, None) == INVALID          # nesterov without momentum
+    assert f(None, A, None, 8, 0.1, 0.9, 0., 0, 1., 0, 0, None) == INVALID
+    assert f(A, A, A, 8, 0.1, 0.9, 0., 0, 1., 0, 2, None) == DTYPE
+    f = lib.lsq_adam_step_lp_blocked
+    assert f(A, A, A, 8, 1e-3, .9, .98, 1e-8, 0., 0, 0, 1, 1., 0, None) == INVALID  # step 0
+    assert f(A, A, A, 8, 1e-3, .9, .98, 1e-8, 0., 1, 0, 1, 1., 2, None) == DTYPE
+    assert f(A, None, A, 8, 1e-3, .9, .98, 1e-8, 0., 1, 0, 1, 1., 0, None) == INVALID
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     x = torch.zeros(4, 8, dtype=torch.float16)

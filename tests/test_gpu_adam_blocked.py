@@ -127,3 +127,67 @@ def test_blocked_full_size(ci, dt):
         for s, hp, hm, hv, hg in before:
             rp, rm, rv = oracle.adam_step(hp, hm, hv, hg, dt, step=step, **HY)
             _check(p[s:s + 4099], m[s:s + 4099], v[s:s + 4099], rp, rm, rv, hm, decode(hg, dt))
+
+
+# ---- the general blocked trainer state: SGD ([p | buf]) and the low-precision-parameter Adam ([m | v])
+@pytest.mark.parametrize("arrays", [1, 2, 3])
+@pytest.mark.parametrize("n", [1, 9, BLK - 3, BLK, 2 * BLK + 5])
+def test_trainer_state_layout(n, arrays):
+    say(f"[trainer-state] n={n} arrays={arrays}")
+    d = dev()
+    r = np.random.default_rng(n + arrays)
+    host = [r.standard_normal(n).astype(np.float32) for _ in range(arrays)]
+    state = L.lsq_trainer_state_pack([torch.from_numpy(a).to(d) for a in host])
+    nb = -(-n // BLK)
+    assert state.numel() == nb * arrays * BLK == L.lsq_trainer_state_bytes(n, arrays) // 4
+    s = state.cpu().numpy().reshape(nb, arrays, BLK)
+    for k, a in enumerate(host):
+        assert np.array_equal(s[:, k, :].reshape(-1), np.concatenate([a, np.zeros(nb * BLK - n, np.float32)]))
+    back = L.lsq_trainer_state_unpack(state, n, arrays)
+    for a, b in zip(host, back):
+        assert np.array_equal(b.cpu().numpy(), a)
+
+
+@pytest.mark.parametrize("kw", [dict(momentum=0.0), dict(momentum=0.9), dict(momentum=0.9, nesterov=True),
+                                dict(momentum=0.5, weight_decay=0.01, inv_grad_scale=0.25)])
+@pytest.mark.parametrize("g_dt,lp_dt", [("f16", "f16"), ("bf16", "bf16"), ("f32", None)])
+@pytest.mark.parametrize("n", [3, BLK + 1, 1000003])
+def test_sgd_blocked_equals_flat_entry_point(n, g_dt, lp_dt, kw):
+    """lsq_sgd_step is checked against the oracle in test_gpu_trainers.py; the blocked form must equal it bit for bit."""
+    say(f"[sgd-blocked] n={n} g={g_dt} p_lp={lp_dt} {kw}")
+    d = dev()
+    t = adam_tensors(CONFIGS[0], g_dt, n=n)
+    p = torch.from_numpy(t["p"].copy()).to(d)
+    buf = torch.zeros(n, dtype=torch.float32, device=d)
+    state = L.lsq_trainer_state_pack([p, None])
+    lpt = None if lp_dt is None else (torch.float16 if lp_dt == "f16" else torch.bfloat16)
+    a_lp = None if lpt is None else torch.empty(n, dtype=lpt, device=d)
+    b_lp = None if lpt is None else torch.empty(n, dtype=lpt, device=d)
+    for step in range(3):
+        g = to_torch(adam_tensors(CONFIGS[0], g_dt, n=n, stream=70 + step)["g"], g_dt, d)
+        L.lsq_sgd_step(p, buf if kw.get("momentum", 0.0) else None, g, a_lp, lr=0.1, **kw)
+        L.lsq_sgd_step_blocked(state, g, b_lp, lr=0.1, **kw)
+        sp, sb = L.lsq_trainer_state_unpack(state, n, 2)
+        assert torch.equal(sp, p) and torch.equal(sb, buf)
+        if a_lp is not None:
+            assert torch.equal(a_lp, b_lp)
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+@pytest.mark.parametrize("n", [5, BLK - 1, 1000003])
+def test_adam_lp_blocked_equals_flat_entry_point(n, dt):
+    say(f"[adam_lp-blocked] n={n} dt={dt}")
+    from workloads import encode
+    d = dev()
+    t = adam_tensors(CONFIGS[0], dt, n=n)
+    p = to_torch(encode(t["p"], dt), dt, d)
+    q = p.clone()
+    m = torch.zeros(n, dtype=torch.float32, device=d)
+    v = torch.zeros(n, dtype=torch.float32, device=d)
+    state = L.lsq_trainer_state_pack([m, v])
+    for step in range(1, 4):
+        g = to_torch(adam_tensors(CONFIGS[0], dt, n=n, stream=60 + step)["g"], dt, d)
+        L.lsq_adam_step_lp(p, m, v, g, step=step, **HY)
+        L.lsq_adam_step_lp_blocked(q, state, g, step=step, **HY)
+        sm, sv = L.lsq_trainer_state_unpack(state, n, 2)
+        assert torch.equal(q, p) and torch.equal(sm, m) and torch.equal(sv, v)
