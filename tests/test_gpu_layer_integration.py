@@ -103,3 +103,78 @@ def test_encoder_layer_forward_backward(act, tdt, rel, floor):
     for name, got in (("g1", dg1), ("b1", db1), ("Wqkv", dWqkv), ("bqkv", dbqkv), ("Wo", dWo), ("bo", dbo), ("g2", dg2),
                       ("b2", db2), ("W1", dW1), ("bf1", dbf1), ("W2", dW2), ("bf2", dbf2)):
         _close("d" + name, got, R[name].grad, rel, floor)
+
+
+@pytest.mark.parametrize("kind", ["decoder-self-causal", "cross"])
+def test_decoder_attention_blocks(kind):
+    """The two attention blocks a decoder adds: causal self-attention with target padding, and
+    cross-attention whose keys come from a source of another length (q_len != k_len, key padding by
+    source lengths, separate Q and KV projections).  fp32 storage, float64 autograd reference."""
+    B, Lq, H, N = 3, 13, 64, 4
+    Lk = Lq if kind != "cross" else 21
+    D, Tq, Tk = H // N, B * Lq, B * Lk
+    p_attn, p_res, seed = 0.1, 0.1, 4242
+    causal = kind != "cross"
+    say(f"[layer] {kind} attention block B={B} Lq={Lq} Lk={Lk} H={H} heads={N}")
+    d = dev()
+    gen = torch.Generator(device="cpu").manual_seed(11)
+    rn = lambda *s, std=1.0, mean=0.0: (torch.randn(*s, generator=gen) * std + mean).to(d)
+    x = rn(Tq, H)
+    mem = x if kind != "cross" else rn(Tk, H)            # encoder output for cross-attention
+    W = dict(g=rn(H, std=0.1, mean=1.0), b=rn(H, std=0.1), Wq=rn(H, H, std=H ** -0.5), bq=rn(H, std=0.1),
+             Wkv=rn(2 * H, H, std=H ** -0.5), bkv=rn(2 * H, std=0.1), Wo=rn(H, H, std=H ** -0.5), bo=rn(H, std=0.1))
+    w_out = rn(Tq, H)
+    key_len = torch.tensor([Lk, Lk - 4, 2], dtype=torch.int32, device=d)
+    scale = D ** -0.5
+    mm = torch.matmul
+
+    # ---- this library (Q from the normalised decoder state, K and V from `src`)
+    y, mean, rstd = L.lsq_layernorm_fwd(x, W["g"], W["b"])
+    src = y if kind != "cross" else mem
+    (q,) = L.lsq_split_heads_fwd(mm(y, W["Wq"].t()), W["bq"], B, Lq, N, D, 1)
+    k, v = L.lsq_split_heads_fwd(mm(src, W["Wkv"].t()), W["bkv"], B, Lk, N, D, 2)
+    pr, prd = L.lsq_softmax_fwd(mm(q, k.transpose(-1, -2)), key_len, causal, scale, p_attn, seed, 1)
+    c = L.lsq_merge_heads_fwd(mm(prd, v))
+    out = L.lsq_bias_dropout_residual_fwd(mm(c, W["Wo"].t()), W["bo"], x, p_res, seed, 2)
+
+    do, dbo = L.lsq_bias_dropout_residual_bwd(w_out, p_res, seed, 2)
+    dc, dWo = mm(do, W["Wo"]), mm(do.t(), c)
+    dctx = L.lsq_merge_heads_bwd(dc, B, Lq, N, D)
+    dprd, dv = mm(dctx, v.transpose(-1, -2)), mm(prd.transpose(-1, -2), dctx)
+    ds = L.lsq_softmax_bwd(dprd, pr, key_len, causal, scale, p_attn, seed, 1)
+    dq, dk = mm(ds, k), mm(ds.transpose(-1, -2), q)
+    dqp, dbq = L.lsq_split_heads_bwd([dq], B, Lq, N, D)
+    dkvp, dbkv = L.lsq_split_heads_bwd([dk, dv], B, Lk, N, D)
+    dWq, dWkv = mm(dqp.t(), y), mm(dkvp.t(), src)
+    dy = mm(dqp, W["Wq"])
+    dmem = mm(dkvp, W["Wkv"])
+    if kind != "cross":
+        dy = dy + dmem                                    # K and V also come from y
+    dx, dg, db = L.lsq_layernorm_bwd(dy, x, W["g"], mean, rstd, dres_in=w_out)
+
+    # ---- float64 autograd
+    mask = lambda n, p, off: torch.from_numpy(oracle.dropout_mask(n, p, seed, off).astype(np.float64)).to(d) / (1.0 - np.float32(p).astype(np.float64))
+    R = {k_: t.double().detach().clone().requires_grad_(True) for k_, t in W.items()}
+    xr = x.double().detach().clone().requires_grad_(True)
+    mr = mem.double().detach().clone().requires_grad_(True)
+    ln = lambda z, g, b: (z - z.mean(-1, keepdim=True)) / torch.sqrt(z.var(-1, unbiased=False, keepdim=True) + 1e-5) * g + b
+    ry = ln(xr, R["g"], R["b"])
+    rsrc = ry if kind != "cross" else mr
+    rq = (ry @ R["Wq"].t() + R["bq"]).view(B, Lq, N, D).permute(0, 2, 1, 3)
+    rkv = (rsrc @ R["Wkv"].t() + R["bkv"]).view(B, Lk, 2, N, D).permute(2, 0, 3, 1, 4)
+    rs = (rq @ rkv[0].transpose(-1, -2)) * scale
+    allowed = (torch.arange(Lk, device=d)[None, :] < key_len[:, None])[:, None, None, :].expand(B, N, Lq, Lk).clone()
+    if causal:
+        allowed &= (torch.arange(Lk, device=d)[None, :] <= torch.arange(Lq, device=d)[:, None])[None, None]
+    rp = torch.softmax(rs.masked_fill(~allowed, float("-inf")), dim=-1)
+    rp = torch.where(allowed.any(-1, keepdim=True), rp, torch.zeros_like(rp))          # an empty set gives a zero row
+    rc = ((rp * mask(B * N * Lq * Lk, p_attn, 1).view(B, N, Lq, Lk)) @ rkv[1]).permute(0, 2, 1, 3).reshape(Tq, H)
+    rout = xr + (rc @ R["Wo"].t() + R["bo"]) * mask(Tq * H, p_res, 2).view(Tq, H)
+    (rout * w_out.double()).sum().backward()
+
+    _close("out", out, rout.detach(), 2e-4, 2e-5)
+    _close("dx", dx, xr.grad, 2e-4, 2e-5)
+    if kind == "cross":
+        _close("dmem", dmem, mr.grad, 2e-4, 2e-5)
+    for name, got in (("g", dg), ("b", db), ("Wq", dWq), ("bq", dbq), ("Wkv", dWkv), ("bkv", dbkv), ("Wo", dWo), ("bo", dbo)):
+        _close("d" + name, got, R[name].grad, 2e-4, 2e-5)
