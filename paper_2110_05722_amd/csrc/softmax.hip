@@ -11,8 +11,8 @@
 // wave) so lanes are never idle.  Rows of 2049..16384 keys take one workgroup
 // each (the reductions cross its four waves through LDS).  Rows whose length is
 // not a multiple of 8 (up to 2048) use the same scheme with element-granular lanes
-// (2-byte accesses: about half the aligned speed, so a caller that can pad
-// the key axis to a multiple of 8 and mask the padding with key_len should);
+// working on LDS, which is filled and drained in aligned 128-bit packs (10-30 %
+// slower than a length that is a multiple of 8);
 // anything else falls to a three-pass kernel that re-reads the row from cache.
 //
 // Masks restrict the SET the softmax runs over: packs that lie wholly beyond the
@@ -381,24 +381,78 @@ __device__ __forceinline__ int64_t elem_keep_mask(uint8_t (&keep)[NBYTES], const
     return p_begin;
 }
 
+// The rows of a workgroup are one contiguous element range [e0, e1) of the tensor.  Global memory
+// is touched in aligned 128-bit packs only: the packs that cover the range are copied to LDS (and
+// results back from LDS), the lanes work on LDS with 2-byte accesses.  The first and the last pack
+// may be shared with the neighbouring workgroups: reading them is harmless, writing is done element
+// by element for the part that belongs here.  Element i of LDS = element (e0 & ~7) + i of the tensor.
+#ifndef LSQ_SM_STAGE
+#define LSQ_SM_STAGE 1
+#endif
+constexpr bool kSmStage = LSQ_SM_STAGE != 0;
+
+template <typename T>
+__device__ __forceinline__ void stage_in(T* buf, const T* src, int64_t e0, int64_t e1, int64_t total)
+{
+    const int64_t p0 = e0 >> 3, p1 = (e1 + 7) >> 3;
+    for (int64_t pk = p0 + threadIdx.x; pk < p1; pk += 256) {
+        T* dst = buf + (pk - p0) * kPack;
+        const int64_t base = pk * kPack;
+        if (base + kPack <= total) {
+            *reinterpret_cast<RawPack<T>*>(dst) = load_raw<T, kNT>(src + base);
+        } else {
+            for (int j = 0; j < kPack; ++j)
+                if (base + j < total) dst[j] = src[base + j];
+        }
+    }
+}
+
+template <typename T>
+__device__ __forceinline__ void stage_out(T* dstg, const T* buf, int64_t e0, int64_t e1)
+{
+    const int64_t p0 = e0 >> 3, p1 = (e1 + 7) >> 3;
+    for (int64_t pk = p0 + threadIdx.x; pk < p1; pk += 256) {
+        const T* from = buf + (pk - p0) * kPack;
+        const int64_t base = pk * kPack;
+        if (base >= e0 && base + kPack <= e1) {
+            store_raw<T, kNT>(dstg + base, *reinterpret_cast<const RawPack<T>*>(from));
+        } else {
+            for (int j = 0; j < kPack; ++j)
+                if (base + j >= e0 && base + j < e1) dstg[base + j] = from[j];
+        }
+    }
+}
+
 template <typename T, int LPR, int EPL, bool DROP>
 __global__ __launch_bounds__(256) void softmax_fwd_elem(T* y, T* __restrict__ yd, const T* x,
                                                         SoftmaxLens len, SoftmaxGeom g, DropoutParams d)
 {
     constexpr int RPB = 256 / LPR;
+    constexpr int NBUF = kSmStage ? 256 * EPL + 16 : 8;      // elements per staged tensor
     __shared__ float red[4];
     __shared__ uint8_t keep[DROP ? 256 * EPL / 8 + 8 : 1];
+    __shared__ __align__(16) T xs[NBUF];
+    __shared__ __align__(16) T ys[NBUF];
+    __shared__ __align__(16) T yds[DROP ? NBUF : 8];
     const int sub = threadIdx.x % LPR;
     const int64_t row0 = static_cast<int64_t>(blockIdx.x) * RPB;
     const int64_t row = row0 + threadIdx.x / LPR;
     const bool rv = row < g.nrows;
     const int limit = rv ? row_limit(g, len, row) : 0;
     const int64_t ro = row * g.k_len;
+    const int64_t e0 = row0 * g.k_len;
+    const int64_t e1 = (row0 + RPB < g.nrows ? row0 + RPB : g.nrows) * g.k_len;
+    const int lo = static_cast<int>(ro - (e0 & ~static_cast<int64_t>(7)));     // this row's first element in LDS
+    if constexpr (kSmStage) {
+        stage_in<T>(xs, x, e0, e1, g.nrows * g.k_len);
+        __syncthreads();
+    }
     float v[EPL];
 #pragma unroll
     for (int m = 0; m < EPL; ++m) {
         const int j = sub + m * LPR;
-        v[m] = j < limit ? to_f32<T>(x[ro + j]) * g.scale : -INFINITY;
+        if constexpr (kSmStage) v[m] = j < limit ? to_f32<T>(xs[lo + j]) * g.scale : -INFINITY;
+        else v[m] = j < limit ? to_f32<T>(x[ro + j]) * g.scale : -INFINITY;
     }
     int64_t p_begin = 0;
     if constexpr (DROP) p_begin = elem_keep_mask(keep, g, d, row0, RPB);
@@ -420,13 +474,20 @@ __global__ __launch_bounds__(256) void softmax_fwd_elem(T* y, T* __restrict__ yd
         const int j = sub + m * LPR;
         if (rv && j < g.k_len) {
             const float o = v[m] * inv;           // 0 beyond the limit (exp2(-inf)), and on empty rows
-            y[ro + j] = from_f32<T>(o);
+            if constexpr (kSmStage) ys[lo + j] = from_f32<T>(o);
+            else y[ro + j] = from_f32<T>(o);
             if constexpr (DROP) {
                 const int64_t e = ro + j;
                 const bool kept = (keep[(e >> 3) - p_begin] >> (e & 7)) & 1;
-                yd[e] = from_f32<T>(kept ? o * d.scale : 0.0f);
+                if constexpr (kSmStage) yds[lo + j] = from_f32<T>(kept ? o * d.scale : 0.0f);
+                else yd[e] = from_f32<T>(kept ? o * d.scale : 0.0f);
             }
         }
+    }
+    if constexpr (kSmStage) {
+        __syncthreads();
+        stage_out<T>(y, ys, e0, e1);
+        if constexpr (DROP) stage_out<T>(yd, yds, e0, e1);
     }
 }
 
@@ -435,20 +496,36 @@ __global__ __launch_bounds__(256) void softmax_bwd_elem(T* dx, const T* dy, cons
                                                         SoftmaxLens len, SoftmaxGeom g, DropoutParams d)
 {
     constexpr int RPB = 256 / LPR;
+    constexpr int NBUF = kSmStage ? 256 * EPL + 16 : 8;
     __shared__ float red[4];
     __shared__ uint8_t keep[DROP ? 256 * EPL / 8 + 8 : 1];
+    __shared__ __align__(16) T ysh[NBUF];
+    __shared__ __align__(16) T gsh[NBUF];        // dy in, dx out
     const int sub = threadIdx.x % LPR;
     const int64_t row0 = static_cast<int64_t>(blockIdx.x) * RPB;
     const int64_t row = row0 + threadIdx.x / LPR;
     const bool rv = row < g.nrows;
     const int limit = rv ? row_limit(g, len, row) : 0;
     const int64_t ro = row * g.k_len;
+    const int64_t e0 = row0 * g.k_len;
+    const int64_t e1 = (row0 + RPB < g.nrows ? row0 + RPB : g.nrows) * g.k_len;
+    const int lo = static_cast<int>(ro - (e0 & ~static_cast<int64_t>(7)));
+    if constexpr (kSmStage) {
+        stage_in<T>(ysh, y, e0, e1, g.nrows * g.k_len);
+        stage_in<T>(gsh, dy, e0, e1, g.nrows * g.k_len);
+        __syncthreads();
+    }
     float yv[EPL], gv[EPL];
 #pragma unroll
     for (int m = 0; m < EPL; ++m) {
         const int j = sub + m * LPR;
-        yv[m] = j < limit ? to_f32<T>(y[ro + j]) : 0.0f;
-        gv[m] = j < limit ? to_f32<T>(dy[ro + j]) : 0.0f;
+        if constexpr (kSmStage) {
+            yv[m] = j < limit ? to_f32<T>(ysh[lo + j]) : 0.0f;
+            gv[m] = j < limit ? to_f32<T>(gsh[lo + j]) : 0.0f;
+        } else {
+            yv[m] = j < limit ? to_f32<T>(y[ro + j]) : 0.0f;
+            gv[m] = j < limit ? to_f32<T>(dy[ro + j]) : 0.0f;
+        }
     }
     if constexpr (DROP) {
         const int64_t p_begin = elem_keep_mask(keep, g, d, row0, RPB);
@@ -469,8 +546,15 @@ __global__ __launch_bounds__(256) void softmax_bwd_elem(T* dx, const T* dy, cons
 #pragma unroll
     for (int m = 0; m < EPL; ++m) {
         const int j = sub + m * LPR;
-        if (rv && j < g.k_len)
-            dx[ro + j] = from_f32<T>(j < limit ? g.scale * yv[m] * (gv[m] - dot) : 0.0f);
+        if (rv && j < g.k_len) {
+            const T o = from_f32<T>(j < limit ? g.scale * yv[m] * (gv[m] - dot) : 0.0f);
+            if constexpr (kSmStage) gsh[lo + j] = o;      // every element is read and written by one lane only
+            else dx[ro + j] = o;
+        }
+    }
+    if constexpr (kSmStage) {
+        __syncthreads();
+        stage_out<T>(dx, gsh, e0, e1);
     }
 }
 
