@@ -73,3 +73,67 @@ def test_layer_ops_replay_under_a_hip_graph():
         torch.cuda.synchronize()
         for i, (o, w) in enumerate(zip(outputs, want)):
             assert torch.equal(o, w), f"replay {replay}: output {i} differs from the eager run"
+
+
+def test_newer_entry_points_replay_under_a_hip_graph():
+    say("[graph] capture + 3 replays: padding removal, fused boundary, query-length and unaligned softmax, blocked trainers")
+    d = dev()
+    B, Ln, H, N = 6, 37, 256, 4                       # 37 keys: the LDS-staged softmax path
+    T = B * Ln
+    g0 = torch.Generator(device="cpu").manual_seed(3)
+    rn = lambda *s: torch.randn(*s, generator=g0).to(torch.float16).to(d)
+    x, res, dy, bias, gamma, beta = rn(T, H), rn(T, H), rn(T, H), rn(H), rn(H), rn(H)
+    lens = torch.tensor([37, 5, 0, 20, 37, 1], dtype=torch.int32, device=d)
+    total = int(lens.sum().item())
+    sx, sdy = rn(B, N, Ln, Ln), rn(B, N, Ln, Ln)
+    n = 3 * 8192 + 77
+    p0 = torch.randn(n, generator=g0).mul_(0.02).to(d)
+    gr = torch.randn(n, generator=g0).mul_(1e-3).to(torch.float16).to(d)
+    state0 = L.lsq_adam_state_pack(p0)
+    sgd0 = L.lsq_trainer_state_pack([p0, None])
+
+    offsets = torch.empty(B + 1, dtype=torch.int32, device=d)
+    packed = torch.empty((total, H), dtype=torch.float16, device=d)
+    padded = torch.empty((B, Ln, H), dtype=torch.float16, device=d)
+    h, y, dh, dxp = (torch.empty_like(x) for _ in range(4))
+    mean, rstd = torch.empty(T, device=d), torch.empty(T, device=d)
+    dgm, dbt, dbi = (torch.empty(H, device=d) for _ in range(3))
+    ws = torch.empty(L.lsq_workspace_bytes(5, T, H), dtype=torch.uint8, device=d)
+    sy, syd, sdx = (torch.empty_like(sx) for _ in range(3))
+    state, sgd, p_lp = state0.clone(), sgd0.clone(), torch.empty(n, dtype=torch.float16, device=d)
+
+    def run():
+        L.lsq_pad_offsets(lens, B, Ln, offsets=offsets)
+        L.lsq_pad_remove(x.view(B, Ln, H), offsets, total, packed=packed)
+        L.lsq_pad_restore(packed, offsets, B, Ln, padded=padded)
+        L.lsq_bdr_layernorm_fwd(x, bias, res, gamma, beta, 0.1, 9, 1, h=h, y=y, mean=mean, rstd=rstd)
+        L.lsq_bdr_layernorm_bwd(dy, h, gamma, mean, rstd, 0.1, 9, 1, dres_in=res, dh=dh, dx=dxp, dgamma=dgm, dbeta=dbt,
+                                dbias=dbi, workspace=ws)
+        L.lsq_softmax_varlen_fwd(sx, lens, lens, True, 0.2, 0.1, 9, 2, y=sy, y_drop=syd)
+        L.lsq_softmax_varlen_bwd(sdy, sy, lens, lens, True, 0.2, 0.1, 9, 2, dx=sdx)
+        L.lsq_adam_step_blocked(state, gr, p_lp, step=2, **HY)
+        L.lsq_sgd_step_blocked(sgd, gr, None, lr=0.1, momentum=0.9)
+
+    outputs = (offsets, packed, padded, h, y, mean, rstd, dh, dxp, dgm, dbt, dbi, sy, syd, sdx, state, sgd, p_lp)
+
+    def reset_state():
+        state.copy_(state0); sgd.copy_(sgd0)
+
+    reset_state()
+    run()
+    torch.cuda.synchronize()
+    want = [o.clone() for o in outputs]
+    reset_state()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for replay in range(3):
+        for o in outputs[:-3]:
+            o.fill_(float("nan")) if o.is_floating_point() else o.fill_(-7)
+        reset_state()
+        torch.cuda.synchronize()
+        (x.float() @ x.float().t()).sum().item()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (o, w) in enumerate(zip(outputs, want)):
+            assert torch.equal(o, w), f"replay {replay}: output {i} differs from the eager run"
