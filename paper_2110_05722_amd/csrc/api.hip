@@ -18,14 +18,9 @@ extern "C" size_t lsq_workspace_bytes(int32_t op, int64_t rows, int32_t cols)
         case LSQ_OP_SPLIT_HEADS_BWD:
             // one [cols] fp32 partial row (dbias) per row block
             return static_cast<size_t>(bdr_bwd_row_blocks(rows, cols)) * static_cast<size_t>(cols) * sizeof(float);
-        case LSQ_OP_EMBEDDING_BWD: {
-            // sorted order (int4 per token) + fp32 chunk rows [2*ceil(rows/32)][cols] + rank counts [3][tiles][rows]
-            const size_t r = static_cast<size_t>(rows);
-            const size_t tiles = static_cast<size_t>(ceil_div(rows, 256));
-            const size_t colsp = (static_cast<size_t>(cols) + 7u) / 8u * 8u;
-            return r * 16u + 2u * static_cast<size_t>(ceil_div(rows, 32)) * colsp * sizeof(float)
-                   + 3u * tiles * r * sizeof(int32_t);
-        }
+        case LSQ_OP_EMBEDDING_BWD:
+            // sorted order, fp32 rows of the id segments that cross a window, rank counts
+            return emb_bwd_plan(rows, cols).total();
         default:
             return 0;
     }

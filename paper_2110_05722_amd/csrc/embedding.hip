@@ -6,14 +6,15 @@
 // atomics make the result depend on the arrival order; here the sum has a fixed order
 // instead, with no atomics at all:
 //   1. rank: every token's position in the order sorted by (token id, position) is
-//      COUNTED — tile against tile, 256 x 256 comparisons per workgroup out of LDS —
-//      rather than sorted: counting is order-free, so the result is deterministic; the
-//      same counts give the start and the length of each id segment;
-//   2. scatter: order[rank[t]] = (t, id, segment start, segment length);
-//   3. accumulate: a segment is cut into chunks of 32 rows; one workgroup per chunk sums
-//      m (.) dy rows in ascending position in fp32 (eight rows in flight).  A segment of one
-//      chunk is added to dE[w,:] at once; a longer one (a frequent token) leaves fp32 chunk
-//      rows that a last kernel adds in chunk order: one rounding of dE per call either way.
+//      COUNTED — tile against tile, 256 x 256 comparisons per workgroup out of LDS, one
+//      compare per pair — rather than sorted: counting is order-free, so the result is
+//      deterministic;
+//   2. scatter: order[rank[t]] = (t, id);
+//   3. accumulate: the sorted order is cut into windows of 8 entries; one wave per (window,
+//      64-pack column block) sums m (.) dy in ascending position in fp32, the eight rows and
+//      the destination rows in flight together.  An id whose rows lie inside one window is
+//      added to dE[w,:] at once; a more frequent one leaves one fp32 row per window that a
+//      last kernel adds in window order: one rounding of dE per call either way.
 // Tokens equal to pad_idx (or outside the vocabulary) produce zero rows and no gradient.
 #include <limits.h>
 
@@ -26,7 +27,7 @@ namespace lsq {
 #endif
 constexpr bool kNT = LSQ_NT != 0;
 constexpr int kEmbWaves = 4;
-constexpr int kTile = 256;
+constexpr int kTile = kEmbTile;
 
 __device__ __forceinline__ bool emb_is_pad(int w, int vocab, int pad_idx) { return w == pad_idx || w < 0 || w >= vocab; }
 
@@ -62,162 +63,233 @@ __global__ __launch_bounds__(256) void emb_fwd_cols(T* __restrict__ out, const i
     }
 }
 
-// sort key of a token: its id, with padding last
-__device__ __forceinline__ int emb_key(int w, int vocab, int pad_idx) { return emb_is_pad(w, vocab, pad_idx) ? INT_MAX : w; }
-
-// Three counts per (token i, tile jt), tile against tile out of LDS:
-//   less[jt][i]   tokens j of the tile with key_j <  key_i          -> start of i's id segment
-//   before[jt][i] tokens j of the tile with key_j == key_i, j < i   -> i's place inside the segment
-//   equal[jt][i]  tokens j of the tile with key_j == key_i          -> length of the segment
-__global__ __launch_bounds__(kTile) void emb_rank_partial(int32_t* __restrict__ partial, const int32_t* __restrict__ tokens,
-                                                          int64_t rows, int ntiles, int vocab, int pad_idx)
+// sort key of a token: its id, with padding last; kNoKey stands for "beyond the data"
+constexpr unsigned kPadKey = 0x7FFFFFFFu;
+constexpr unsigned kNoKey = 0xFFFFFFFFu;
+__device__ __forceinline__ unsigned emb_key(int w, int vocab, int pad_idx)
 {
-    __shared__ int keys[kTile];
-    const int64_t i = static_cast<int64_t>(blockIdx.x) * kTile + threadIdx.x;
-    const int64_t j0 = static_cast<int64_t>(blockIdx.y) * kTile;
-    const int64_t jl = j0 + threadIdx.x;
-    keys[threadIdx.x] = jl < rows ? emb_key(tokens[jl], vocab, pad_idx) : INT_MAX;
-    __syncthreads();
-    if (i >= rows) return;
-    const int ki = emb_key(tokens[i], vocab, pad_idx);
-    const int nj = static_cast<int>(min(static_cast<int64_t>(kTile), rows - j0));
-    int less = 0, before = 0, equal = 0;
-    for (int jj = 0; jj < nj; ++jj) {
-        const int kj = keys[jj];                       // LDS broadcast
-        less += kj < ki ? 1 : 0;
-        equal += kj == ki ? 1 : 0;
-        before += (kj == ki && j0 + jj < i) ? 1 : 0;
-    }
-    const int64_t plane = static_cast<int64_t>(ntiles) * rows;
-    const int64_t o = static_cast<int64_t>(blockIdx.y) * rows + i;
-    partial[o] = less;
-    partial[plane + o] = before;
-    partial[2 * plane + o] = equal;
+    return emb_is_pad(w, vocab, pad_idx) ? kPadKey : static_cast<unsigned>(w);
 }
 
-// order[q] = { token position, key, segment start, segment length } for sorted position q
-__global__ __launch_bounds__(256) void emb_scatter(int4* __restrict__ order, const int32_t* __restrict__ partial,
-                                                   const int32_t* __restrict__ tokens, int64_t rows, int ntiles,
+// Workgroup (it, js): for the 256 tokens i of tile `it`, how many tokens j of span `js` sort
+// before i by (key, position).  Every j of an earlier tile has j < i, so key_j <= key_i decides;
+// in a later tile key_j < key_i does; both are one unsigned compare against key_i + 1 or key_i.
+// Only the tile's own diagonal looks at the position.  Keys come out of LDS four at a time.
+__global__ __launch_bounds__(kTile) void emb_rank_partial(int32_t* __restrict__ partial, const int32_t* __restrict__ tokens,
+                                                          int64_t rows, int ntiles, int span_tiles, int vocab, int pad_idx)
+{
+    __shared__ __align__(16) unsigned keys[kTile];
+    const int it = blockIdx.x;
+    const int me = threadIdx.x;
+    const int64_t i = static_cast<int64_t>(it) * kTile + me;
+    const unsigned ki = i < rows ? emb_key(tokens[i], vocab, pad_idx) : 0u;
+    const int jt0 = static_cast<int>(blockIdx.y) * span_tiles;
+    const int jt1 = min(ntiles, jt0 + span_tiles);
+    const uint4* k4 = reinterpret_cast<const uint4*>(keys);
+    int count = 0;
+    for (int jt = jt0; jt < jt1; ++jt) {                   // uniform: every thread reaches both barriers
+        const int64_t j = static_cast<int64_t>(jt) * kTile + me;
+        __syncthreads();
+        keys[me] = j < rows ? emb_key(tokens[j], vocab, pad_idx) : kNoKey;   // kNoKey is below no bound
+        __syncthreads();
+        if (jt != it) {
+            const unsigned bound = ki + (jt < it ? 1u : 0u);
+#pragma unroll 8
+            for (int q = 0; q < kTile / 4; ++q) {
+                const uint4 k = k4[q];                     // LDS broadcast
+                count += (k.x < bound ? 1 : 0) + (k.y < bound ? 1 : 0) + (k.z < bound ? 1 : 0) + (k.w < bound ? 1 : 0);
+            }
+        } else {
+#pragma unroll 4
+            for (int q = 0; q < kTile / 4; ++q) {
+                const uint4 k = k4[q];
+                const int j4 = 4 * q;
+                count += (k.x < ki || (k.x == ki && j4 + 0 < me) ? 1 : 0) + (k.y < ki || (k.y == ki && j4 + 1 < me) ? 1 : 0)
+                       + (k.z < ki || (k.z == ki && j4 + 2 < me) ? 1 : 0) + (k.w < ki || (k.w == ki && j4 + 3 < me) ? 1 : 0);
+            }
+        }
+    }
+    if (i < rows) partial[static_cast<int64_t>(blockIdx.y) * rows + i] = count;
+}
+
+// order[rank of t] = (t, key of t): the counts are a permutation of 0..rows-1
+__global__ __launch_bounds__(256) void emb_scatter(int2* __restrict__ order, const int32_t* __restrict__ partial,
+                                                   const int32_t* __restrict__ tokens, int64_t rows, int nspans,
                                                    int vocab, int pad_idx)
 {
     const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     if (t >= rows) return;
-    const int64_t plane = static_cast<int64_t>(ntiles) * rows;
-    int less = 0, before = 0, equal = 0;
-    int jt = 0;
-    for (; jt + 4 <= ntiles; jt += 4) {               // twelve loads in flight per trip (integer sums: any order)
-        int a[4], b[4], c[4];
+    int rank = 0;
+    int js = 0;
+    for (; js + 8 <= nspans; js += 8) {                // eight loads in flight per trip (integer sums: any order)
+        int a[8];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int64_t o = static_cast<int64_t>(jt + k) * rows + t;
-            a[k] = partial[o]; b[k] = partial[plane + o]; c[k] = partial[2 * plane + o];
-        }
+        for (int k = 0; k < 8; ++k) a[k] = partial[static_cast<int64_t>(js + k) * rows + t];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) { less += a[k]; before += b[k]; equal += c[k]; }
+        for (int k = 0; k < 8; ++k) rank += a[k];
     }
-    for (; jt < ntiles; ++jt) {
-        const int64_t o = static_cast<int64_t>(jt) * rows + t;
-        less += partial[o];
-        before += partial[plane + o];
-        equal += partial[2 * plane + o];
-    }
-    order[less + before] = make_int4(static_cast<int>(t), emb_key(tokens[t], vocab, pad_idx), less, equal);
+    for (; js < nspans; ++js) rank += partial[static_cast<int64_t>(js) * rows + t];
+    order[rank] = make_int2(static_cast<int>(t), static_cast<int>(emb_key(tokens[t], vocab, pad_idx)));
 }
 
-constexpr int kEmbChunk = 32;    // rows of one id summed by one workgroup
-
-// slot of the partial row written by the chunk that starts at sorted position q (segment start s):
-// a window of kEmbChunk sorted positions holds at most one chunk head that is not a segment start
-// and at most one start of a segment longer than a chunk
-__device__ __forceinline__ int64_t emb_slot(int64_t q, int64_t s) { return 2 * (q / kEmbChunk) + (q == s ? 1 : 0); }
-
-// One workgroup per sorted entry; only chunk heads work.  A chunk sums up to kEmbChunk rows of one id
-// in ascending position.  Segments of one chunk are added to dE at once; longer ones leave fp32
-// partial rows that emb_combine sums in chunk order.
-template <typename T, bool DROP>
-__global__ __launch_bounds__(256) void emb_accumulate(T* __restrict__ demb, float* __restrict__ chunk_rows,
-                                                      const T* __restrict__ dy, const int4* __restrict__ order,
-                                                      int ppr, float scale, DropoutParams d)
+// The sorted order is cut into windows of kEmbWin entries and 64-pack column blocks; one wave
+// takes one (window, column block).  Lane 0 gets the entry before the window, lanes
+// 1..kEmbWin the window, lane kEmbWin+1 the entry after it; beyond the data the key is kNoKey
+// (-1 as int), which equals no token's key.
+__device__ __forceinline__ int2 emb_window(const int2* __restrict__ order, int64_t win, int64_t rows, int lane)
 {
-    const int64_t q = blockIdx.x;
-    const int4 me = order[q];                                    // uniform
-    const int key = me.y;
-    const int64_t s = me.z;
-    const int len = me.w;
-    if (key == INT_MAX) return;                                  // padding
-    if ((q - s) % kEmbChunk != 0) return;                        // not a chunk head
-    const int cnt = static_cast<int>(min(static_cast<int64_t>(kEmbChunk), s + len - q));
+    const int64_t idx = win * kEmbWin - 1 + lane;
+    int2 e = make_int2(0, static_cast<int>(kNoKey));
+    if (lane <= kEmbWin + 1 && idx >= 0 && idx < rows) e = order[idx];
+    return e;
+}
+
+__device__ __forceinline__ bool emb_live_key(int key) { return key >= 0 && key != static_cast<int>(kPadKey); }
+
+// Sums m (.) dy over each run of equal ids inside the window, in ascending position.  A run
+// that starts and ends inside the window is added to dE[w,:] at once (the destination row is
+// fetched together with the dy rows).  A run that comes from the previous window or goes on
+// into the next leaves an fp32 row for emb_combine: slot 0 of the window if it is the window's
+// first run, slot 1 otherwise (only the last run can be the other one).
+template <typename T, bool DROP>
+__global__ __launch_bounds__(256) void emb_accumulate(T* __restrict__ demb, float* __restrict__ win_rows,
+                                                      const T* __restrict__ dy, const int2* __restrict__ order,
+                                                      int64_t rows, int64_t nwin, int ncb, int ppr, float scale,
+                                                      DropoutParams d)
+{
     const int lane = threadIdx.x & 63;
-    const int tt = lane < cnt ? order[q + lane].x : 0;           // the chunk's token positions, one per lane
-    for (int cp = threadIdx.x; cp < ppr; cp += 256) {
-        float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        for (int u0 = 0; u0 < cnt; u0 += 8) {
-            // eight rows in flight, then added in order
-            RawPack<T> raw[8];
+    const int64_t gw = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (gw >= nwin * ncb) return;                                   // wave-uniform
+    const int64_t win = gw / ncb;
+    const int cp = static_cast<int>(gw % ncb) * 64 + lane;
+    const int2 e = emb_window(order, win, rows, lane);
+    int key[kEmbWin + 2], tok[kEmbWin];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                if (u0 + k < cnt) {
-                    const int64_t t = __builtin_amdgcn_readlane(tt, u0 + k);
-                    raw[k] = load_raw<T, kNT>(dy + (t * ppr + cp) * kPack);
-                } else {
-                    raw[k] = zero_raw<T>();
-                }
-            }
+    for (int k = 0; k < kEmbWin + 2; ++k) key[k] = __builtin_amdgcn_readlane(e.y, k);
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                if (u0 + k < cnt) {
-                    float g[8];
-                    unpack<T>(raw[k], g);
-                    if constexpr (DROP) {
-                        const int64_t t = __builtin_amdgcn_readlane(tt, u0 + k);
-                        float kf[8];
-                        dropout_factors8(d, static_cast<uint64_t>(t * ppr + cp), kf);
+    for (int k = 0; k < kEmbWin; ++k) tok[k] = __builtin_amdgcn_readlane(e.x, k + 1);
+    if (cp >= ppr) return;
+
+    // what happens after entry k (all wave-uniform): 0 nothing, 1 add to dE, 2 / 3 leave slot 0 / 1
+    int action[kEmbWin];
+    {
+        bool open_partial = key[1] == key[0], first_run = true;
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) acc[j] = fmaf(g[j], kf[j], acc[j]);
-                    } else {
+        for (int k = 0; k < kEmbWin; ++k) {
+            const bool live = emb_live_key(key[k + 1]);
+            const bool tail = key[k + 1] != key[k + 2];
+            action[k] = 0;
+            if (live && tail) action[k] = open_partial ? 2 : 1;            // a run from the previous window is the first run
+            else if (live && k == kEmbWin - 1) action[k] = first_run ? 2 : 3;
+            if (tail) { open_partial = false; first_run = false; }
+        }
+    }
+    RawPack<T> raw[kEmbWin], dst_raw[kEmbWin];
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) acc[j] += g[j];
-                    }
-                }
+    for (int k = 0; k < kEmbWin; ++k) {
+        if (emb_live_key(key[k + 1])) raw[k] = load_raw<T, kNT>(dy + (static_cast<int64_t>(tok[k]) * ppr + cp) * kPack);
+        else raw[k] = zero_raw<T>();
+    }
+#pragma unroll
+    for (int k = 0; k < kEmbWin; ++k) {
+        if (action[k] == 1) dst_raw[k] = load_raw<T, false>(demb + (static_cast<int64_t>(key[k + 1]) * ppr + cp) * kPack);
+        else dst_raw[k] = zero_raw<T>();
+    }
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int k = 0; k < kEmbWin; ++k) {
+        if (emb_live_key(key[k + 1])) {
+            float g[8];
+            unpack<T>(raw[k], g);
+            if constexpr (DROP) {
+                float kf[8];
+                dropout_factors8(d, static_cast<uint64_t>(static_cast<int64_t>(tok[k]) * ppr + cp), kf);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j] = fmaf(g[j], kf[j], acc[j]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j] += g[j];
             }
         }
-        if (len <= kEmbChunk) {
-            T* dst = demb + (static_cast<int64_t>(key) * ppr + cp) * kPack;
+        if (action[k] == 1) {
             float o[8];
-            load8<T>(dst, o);
+            unpack<T>(dst_raw[k], o);
 #pragma unroll
             for (int j = 0; j < 8; ++j) o[j] = fmaf(scale, acc[j], o[j]);
-            store8<T>(dst, o);
-        } else {
-            store8<float>(chunk_rows + (emb_slot(q, s) * ppr + cp) * kPack, acc);
+            store8<T>(demb + (static_cast<int64_t>(key[k + 1]) * ppr + cp) * kPack, o);
+        } else if (action[k] >= 2) {
+            store8<float>(win_rows + ((2 * win + (action[k] - 2)) * ppr + cp) * kPack, acc);
+        }
+        if (action[k] != 0) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
         }
     }
 }
 
-// segments longer than a chunk: the workgroup of the segment start adds the chunk rows in chunk order
+// The wave of the window in which a window-crossing id segment ENDS adds its fp32 rows in window
+// order and rounds dE[w,:] once.  The segment's first window is found by looking back, 64
+// windows per trip: window v is the first one if the entry before it has another key (or v = 0).
 template <typename T>
-__global__ __launch_bounds__(256) void emb_combine(T* __restrict__ demb, const float* __restrict__ chunk_rows,
-                                                   const int4* __restrict__ order, int ppr, float scale)
+__global__ __launch_bounds__(256) void emb_combine(T* __restrict__ demb, const float* __restrict__ win_rows,
+                                                   const int2* __restrict__ order, int64_t rows, int64_t nwin, int ncb,
+                                                   int ppr, float scale)
 {
-    const int64_t q = blockIdx.x;
-    const int4 me = order[q];
-    if (me.y == INT_MAX || me.z != q || me.w <= kEmbChunk) return;
-    const int nchunks = (me.w + kEmbChunk - 1) / kEmbChunk;
-    for (int cp = threadIdx.x; cp < ppr; cp += 256) {
-        float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        for (int c = 0; c < nchunks; ++c) {
-            float r[8];
-            load8<float>(chunk_rows + (emb_slot(q + static_cast<int64_t>(c) * kEmbChunk, q) * ppr + cp) * kPack, r);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j] += r[j];
+    const int lane = threadIdx.x & 63;
+    const int64_t gw = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (gw >= nwin * ncb) return;                                   // wave-uniform
+    const int64_t win = gw / ncb;
+    const int cp = static_cast<int>(gw % ncb) * 64 + lane;
+    const int2 e = emb_window(order, win, rows, lane);
+    const int key = __builtin_amdgcn_readlane(e.y, 1);
+    if (!emb_live_key(key) || __builtin_amdgcn_readlane(e.y, 0) != key) return;   // first run starts here: nothing to combine
+    constexpr uint64_t kAll = ((1ull << (kEmbWin + 1)) - 1) << 1;  // lanes 1..kEmbWin+1
+    if ((__ballot(e.y == key) & kAll) == kAll) return;              // the run goes on into the next window
+    // here win >= 1 (the entry before the window exists), so the search starts at a valid window
+    int64_t head = 0;
+    int head_first_key = 0;
+    for (int64_t base = win - 1;; base -= 64) {
+        const int64_t v = base - lane;
+        bool stop = false;
+        int first_key = 0;
+        if (v >= 0) {
+            first_key = order[v * kEmbWin].y;
+            stop = v == 0 || order[v * kEmbWin - 1].y != key;
         }
-        T* dst = demb + (static_cast<int64_t>(me.y) * ppr + cp) * kPack;
-        float o[8];
-        load8<T>(dst, o);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) o[j] = fmaf(scale, acc[j], o[j]);
-        store8<T>(dst, o);
+        const uint64_t m = __ballot(stop);
+        if (m != 0) {                                               // v = 0 stops: every wave leaves the loop
+            const int l = __builtin_ctzll(m);
+            head = base - l;
+            head_first_key = __builtin_amdgcn_readlane(first_key, l);
+            break;
+        }
     }
+    if (cp >= ppr) return;
+    // the segment is the first run of its first window exactly if it starts at that window's first entry
+    float acc[8];
+    load8<float>(win_rows + ((2 * head + (head_first_key == key ? 0 : 1)) * ppr + cp) * kPack, acc);
+    int64_t v = head + 1;
+    for (; v + 4 <= win + 1; v += 4) {                              // four rows in flight, added in window order
+        float r[4][8];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) load8<float>(win_rows + (2 * (v + k) * ppr + cp) * kPack, r[k]);
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] += r[k][j];
+    }
+    for (; v <= win; ++v) {
+        float r[8];
+        load8<float>(win_rows + (2 * v * ppr + cp) * kPack, r);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] += r[j];
+    }
+    T* dst = demb + (static_cast<int64_t>(key) * ppr + cp) * kPack;
+    float o[8];
+    load8<T>(dst, o);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = fmaf(scale, acc[j], o[j]);
+    store8<T>(dst, o);
 }
 
 // dP[l,:] += sum over the batch.  A workgroup owns 64 packs of one position; its four
@@ -310,21 +382,23 @@ __global__ __launch_bounds__(256) void emb_fwd_flat(T* __restrict__ out, const i
 // one thread per (id segment head, column): walks the segment sequentially
 template <typename T>
 __global__ __launch_bounds__(256) void emb_accumulate_flat(T* __restrict__ demb, const T* __restrict__ dy,
-                                                           const int4* __restrict__ order, int hidden, float scale,
-                                                           DropoutParams d)
+                                                           const int2* __restrict__ order, int64_t rows, int hidden,
+                                                           float scale, DropoutParams d)
 {
     const int64_t q = blockIdx.x;
-    const int4 me = order[q];
-    if (me.y == INT_MAX || me.z != q) return;
+    const int key = order[q].y;
+    if (!emb_live_key(key) || (q > 0 && order[q - 1].y == key)) return;    // padding, or not the head of its segment
     for (int i = threadIdx.x; i < hidden; i += 256) {
         float acc = 0.0f;
-        for (int c = 0; c < me.w; ++c) {
-            const int64_t e = static_cast<int64_t>(order[q + c].x) * hidden + i;
+        for (int64_t c = q; c < rows; ++c) {
+            const int2 o = order[c];
+            if (o.y != key) break;
+            const int64_t e = static_cast<int64_t>(o.x) * hidden + i;
             float g = to_f32<T>(dy[e]);
             if (d.t16) g *= dropout_factor1(d, static_cast<uint64_t>(e));
             acc += g;
         }
-        T* dst = demb + static_cast<int64_t>(me.y) * hidden + i;
+        T* dst = demb + static_cast<int64_t>(key) * hidden + i;
         *dst = from_f32<T>(fmaf(scale, acc, to_f32<T>(*dst)));
     }
 }
@@ -378,31 +452,32 @@ static lsq_status emb_bwd_dispatch(void* demb, void* dpos, const void* dy, const
                                    const DropoutParams& d, hipStream_t s)
 {
     const int64_t rows = static_cast<int64_t>(batch) * len;
-    const int ntiles = static_cast<int>(ceil_div(rows, kTile));
-    // workspace: order[rows] (int4) | chunk rows [2*ceil(rows/chunk)][hidden] fp32 | rank counts [3][ntiles][rows] int32
-    int4* order = reinterpret_cast<int4*>(ws);
-    float* chunk_rows = reinterpret_cast<float*>(order + rows);
-    int32_t* partial = reinterpret_cast<int32_t*>(chunk_rows + 2 * ceil_div(rows, kEmbChunk) * ((hidden + 7) / 8 * 8));
+    const EmbBwdPlan plan = emb_bwd_plan(rows, hidden);
+    int2* order = reinterpret_cast<int2*>(ws);
+    float* win_rows = reinterpret_cast<float*>(static_cast<char*>(ws) + plan.order_bytes);
+    int32_t* partial = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + plan.order_bytes + plan.win_bytes);
     T* de = static_cast<T*>(demb);
     T* dp = static_cast<T*>(dpos);
     const T* g = static_cast<const T*>(dy);
     // the dropout scale 1/(1-p) is carried by the per-element factors; `scale` is the embedding scale
-    hipLaunchKernelGGL(emb_rank_partial, dim3(ntiles, ntiles), dim3(kTile), 0, s, partial, tokens, rows, ntiles, vocab, pad_idx);
+    hipLaunchKernelGGL(emb_rank_partial, dim3(plan.ntiles, plan.nspans), dim3(kTile), 0, s, partial, tokens, rows,
+                       plan.ntiles, plan.span_tiles, vocab, pad_idx);
     hipLaunchKernelGGL(emb_scatter, dim3(static_cast<unsigned>(ceil_div(rows, 256))), dim3(256), 0, s, order, partial,
-                       tokens, rows, ntiles, vocab, pad_idx);
-    const dim3 grid(static_cast<unsigned>(rows)), block(256);
+                       tokens, rows, plan.nspans, vocab, pad_idx);
     if (hidden % kPack == 0) {
         const int ppr = hidden / kPack;
-        if (d.t16) hipLaunchKernelGGL((emb_accumulate<T, true>), grid, block, 0, s, de, chunk_rows, g, order, ppr, scale, d);
-        else hipLaunchKernelGGL((emb_accumulate<T, false>), grid, block, 0, s, de, chunk_rows, g, order, ppr, scale, d);
-        hipLaunchKernelGGL((emb_combine<T>), grid, block, 0, s, de, chunk_rows, order, ppr, scale);
+        const int ncb = static_cast<int>(ceil_div(ppr, 64));
+        const dim3 grid(static_cast<unsigned>(ceil_div(plan.nwin * ncb, 4))), block(256);   // one wave per (window, column block)
+        if (d.t16) hipLaunchKernelGGL((emb_accumulate<T, true>), grid, block, 0, s, de, win_rows, g, order, rows, plan.nwin, ncb, ppr, scale, d);
+        else hipLaunchKernelGGL((emb_accumulate<T, false>), grid, block, 0, s, de, win_rows, g, order, rows, plan.nwin, ncb, ppr, scale, d);
+        hipLaunchKernelGGL((emb_combine<T>), grid, block, 0, s, de, win_rows, order, rows, plan.nwin, ncb, ppr, scale);
         if (dp) {
             const dim3 pgrid(static_cast<unsigned>(ceil_div(ppr, 64)), static_cast<unsigned>(len));
             if (d.t16) hipLaunchKernelGGL((emb_dpos<T, true>), pgrid, dim3(256), 0, s, dp, g, tokens, batch, len, ppr, vocab, pad_idx, d);
             else hipLaunchKernelGGL((emb_dpos<T, false>), pgrid, dim3(256), 0, s, dp, g, tokens, batch, len, ppr, vocab, pad_idx, d);
         }
     } else {
-        hipLaunchKernelGGL((emb_accumulate_flat<T>), grid, block, 0, s, de, g, order, hidden, scale, d);
+        hipLaunchKernelGGL((emb_accumulate_flat<T>), dim3(static_cast<unsigned>(rows)), dim3(256), 0, s, de, g, order, rows, hidden, scale, d);
         if (dp)
             hipLaunchKernelGGL((emb_dpos_flat<T>), dim3(len), dim3(256), 0, s, dp, g, tokens, batch, len, hidden, vocab,
                                pad_idx, d);
@@ -447,6 +522,7 @@ extern "C" lsq_status lsq_embedding_bwd(void* demb, void* dpos, const void* dy, 
     const int64_t rows = static_cast<int64_t>(batch) * len;
     if (rows == 0) return LSQ_OK;
     LSQ_REQUIRE(rows <= 0x7FFFFFFF / 2 && ceil_div(rows, kTile) <= 65535);
+    LSQ_REQUIRE(ceil_div(rows, kEmbWin) * ceil_div(hidden, 8 * 64) / 4 < 0x7FFFFFFF);   // one wave per (window, column block)
     LSQ_REQUIRE(!dpos || len <= 65535);       // one grid row per position
     LSQ_REQUIRE(demb && dy && tokens);
     LSQ_ALIGNED(demb); LSQ_ALIGNED(dpos); LSQ_ALIGNED(dy); LSQ_ALIGNED(workspace);

@@ -132,4 +132,32 @@ inline int bdr_bwd_row_blocks(int64_t rows, int32_t /*hidden*/)
     return static_cast<int>(b);
 }
 
+// Workspace of the embedding backward:
+//   order  [rows] (token position, sort key), 8 bytes each
+//   window rows [2 * windows][hidden rounded up to 8] fp32: the partial sums of id segments
+//          that cross a window of kEmbWin sorted entries (at most two per window)
+//   rank counts [spans][rows] int32: token i against the tokens of span js (a span is a run
+//          of 256-token tiles, at most 64 spans)
+constexpr int kEmbTile = 256;
+constexpr int kEmbWin = 8;
+struct EmbBwdPlan {
+    int ntiles, span_tiles, nspans;
+    int64_t nwin;
+    size_t order_bytes, win_bytes, rank_bytes;
+    size_t total() const { return order_bytes + win_bytes + rank_bytes; }
+};
+inline EmbBwdPlan emb_bwd_plan(int64_t rows, int32_t hidden)
+{
+    EmbBwdPlan p;
+    p.ntiles = static_cast<int>(ceil_div(rows, kEmbTile));
+    p.span_tiles = static_cast<int>(ceil_div(p.ntiles, 64));
+    p.nspans = static_cast<int>(ceil_div(p.ntiles, p.span_tiles));
+    p.nwin = ceil_div(rows, kEmbWin);
+    const size_t colsp = (static_cast<size_t>(hidden) + 7u) / 8u * 8u;
+    p.order_bytes = (static_cast<size_t>(rows) * 8u + 15u) / 16u * 16u;
+    p.win_bytes = 2u * static_cast<size_t>(p.nwin) * colsp * sizeof(float);
+    p.rank_bytes = static_cast<size_t>(p.nspans) * static_cast<size_t>(rows) * sizeof(int32_t);
+    return p;
+}
+
 }  // namespace lsq
