@@ -75,15 +75,14 @@ __device__ __forceinline__ unsigned emb_key(int w, int vocab, int pad_idx)
 // before i by (key, position).  Every j of an earlier tile has j < i, so key_j <= key_i decides;
 // in a later tile key_j < key_i does; both are one unsigned compare against key_i + 1 or key_i.
 // Only the tile's own diagonal looks at the position.  Keys come out of LDS four at a time.
-__global__ __launch_bounds__(kTile) void emb_rank_partial(int32_t* __restrict__ partial, const int32_t* __restrict__ tokens,
-                                                          int64_t rows, int ntiles, int span_tiles, int vocab, int pad_idx)
+__device__ __forceinline__ void emb_rank_body(int it, int js, int32_t* __restrict__ partial, const int32_t* __restrict__ tokens,
+                                              int64_t rows, int ntiles, int span_tiles, int vocab, int pad_idx)
 {
     __shared__ __align__(16) unsigned keys[kTile];
-    const int it = blockIdx.x;
     const int me = threadIdx.x;
     const int64_t i = static_cast<int64_t>(it) * kTile + me;
     const unsigned ki = i < rows ? emb_key(tokens[i], vocab, pad_idx) : 0u;
-    const int jt0 = static_cast<int>(blockIdx.y) * span_tiles;
+    const int jt0 = js * span_tiles;
     const int jt1 = min(ntiles, jt0 + span_tiles);
     const uint4* k4 = reinterpret_cast<const uint4*>(keys);
     int count = 0;
@@ -109,27 +108,41 @@ __global__ __launch_bounds__(kTile) void emb_rank_partial(int32_t* __restrict__ 
             }
         }
     }
-    if (i < rows) partial[static_cast<int64_t>(blockIdx.y) * rows + i] = count;
+    if (i < rows) partial[static_cast<int64_t>(js) * rows + i] = count;
 }
 
-// order[rank of t] = (t, key of t): the counts are a permutation of 0..rows-1
+__global__ __launch_bounds__(kTile) void emb_rank_partial(int32_t* __restrict__ partial, const int32_t* __restrict__ tokens,
+                                                          int64_t rows, int ntiles, int span_tiles, int vocab, int pad_idx)
+{
+    emb_rank_body(blockIdx.x % ntiles, blockIdx.x / ntiles, partial, tokens, rows, ntiles, span_tiles, vocab, pad_idx);
+}
+
+// order[rank of t] = (t, key of t): the counts are a permutation of 0..rows-1.  Four lanes per
+// token add every fourth span each (integer sums: any order).
 __global__ __launch_bounds__(256) void emb_scatter(int2* __restrict__ order, const int32_t* __restrict__ partial,
                                                    const int32_t* __restrict__ tokens, int64_t rows, int nspans,
                                                    int vocab, int pad_idx)
 {
-    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (t >= rows) return;
+    const int part = threadIdx.x >> 6;                                       // the wave: tokens stay coalesced
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 64 + (threadIdx.x & 63);
+    __shared__ int sm[3][64];
     int rank = 0;
-    int js = 0;
-    for (; js + 8 <= nspans; js += 8) {                // eight loads in flight per trip (integer sums: any order)
-        int a[8];
+    if (t < rows) {
+        int js = part;
+        for (; js + 12 < nspans; js += 16) {            // four loads in flight per trip
+            int a[4];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) a[k] = partial[static_cast<int64_t>(js + k) * rows + t];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) rank += a[k];
+            for (int k = 0; k < 4; ++k) a[k] = partial[static_cast<int64_t>(js + 4 * k) * rows + t];
+            rank += a[0] + a[1] + a[2] + a[3];
+        }
+        for (; js < nspans; js += 4) rank += partial[static_cast<int64_t>(js) * rows + t];
     }
-    for (; js < nspans; ++js) rank += partial[static_cast<int64_t>(js) * rows + t];
-    order[rank] = make_int2(static_cast<int>(t), static_cast<int>(emb_key(tokens[t], vocab, pad_idx)));
+    if (part > 0) sm[part - 1][threadIdx.x & 63] = rank;
+    __syncthreads();
+    if (part == 0 && t < rows) {
+        rank += sm[0][threadIdx.x] + sm[1][threadIdx.x] + sm[2][threadIdx.x];
+        order[rank] = make_int2(static_cast<int>(t), static_cast<int>(emb_key(tokens[t], vocab, pad_idx)));
+    }
 }
 
 // The sorted order is cut into windows of kEmbWin entries and 64-pack column blocks; one wave
@@ -227,19 +240,21 @@ __global__ __launch_bounds__(256) void emb_accumulate(T* __restrict__ demb, floa
     }
 }
 
-// The wave of the window in which a window-crossing id segment ENDS adds its fp32 rows in window
-// order and rounds dE[w,:] once.  The segment's first window is found by looking back, 64
-// windows per trip: window v is the first one if the entry before it has another key (or v = 0).
+// The workgroup of the (window, column block) in which a window-crossing id segment ENDS adds
+// the segment's fp32 rows and rounds dE[w,:] once.  The segment's first window is found by looking
+// back, 64 windows per trip: window v is the first one if the entry before it has another key
+// (or v = 0).  The four waves take every fourth row each, eight in flight, and their sums are
+// added in wave order: a fixed association, so the result does not depend on timing.
 template <typename T>
 __global__ __launch_bounds__(256) void emb_combine(T* __restrict__ demb, const float* __restrict__ win_rows,
-                                                   const int2* __restrict__ order, int64_t rows, int64_t nwin, int ncb,
-                                                   int ppr, float scale)
+                                                   const int2* __restrict__ order, int64_t rows, int ncb, int ppr,
+                                                   float scale)
 {
-    const int lane = threadIdx.x & 63;
-    const int64_t gw = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-    if (gw >= nwin * ncb) return;                                   // wave-uniform
-    const int64_t win = gw / ncb;
-    const int cp = static_cast<int>(gw % ncb) * 64 + lane;
+    __shared__ float sm[kEmbWaves - 1][8][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t win = blockIdx.x / ncb;
+    const int cp = static_cast<int>(blockIdx.x % ncb) * 64 + lane;
+    // every wave reads the same entries and takes the same decisions: the exits are workgroup-uniform
     const int2 e = emb_window(order, win, rows, lane);
     const int key = __builtin_amdgcn_readlane(e.y, 1);
     if (!emb_live_key(key) || __builtin_amdgcn_readlane(e.y, 0) != key) return;   // first run starts here: nothing to combine
@@ -264,47 +279,61 @@ __global__ __launch_bounds__(256) void emb_combine(T* __restrict__ demb, const f
             break;
         }
     }
-    if (cp >= ppr) return;
-    // the segment is the first run of its first window exactly if it starts at that window's first entry
-    float acc[8];
-    load8<float>(win_rows + ((2 * head + (head_first_key == key ? 0 : 1)) * ppr + cp) * kPack, acc);
-    int64_t v = head + 1;
-    for (; v + 4 <= win + 1; v += 4) {                              // four rows in flight, added in window order
-        float r[4][8];
+    const bool active = cp < ppr;
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (active) {
+        // the segment is the first run of its first window exactly if it starts at that window's first entry
+        if (wave == 0) load8<float>(win_rows + ((2 * head + (head_first_key == key ? 0 : 1)) * ppr + cp) * kPack, acc);
+        constexpr int U = 8;
+        for (int64_t v0 = head + 1 + wave; v0 <= win; v0 += U * kEmbWaves) {
+            float r[U][8];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) load8<float>(win_rows + (2 * (v + k) * ppr + cp) * kPack, r[k]);
+            for (int k = 0; k < U; ++k) {
+                const int64_t v = v0 + k * kEmbWaves;
+                if (v <= win) {
+                    load8<float>(win_rows + (2 * v * ppr + cp) * kPack, r[k]);
+                } else {
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
+                    for (int j = 0; j < 8; ++j) r[k][j] = 0.0f;
+                }
+            }
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j] += r[k][j];
+            for (int k = 0; k < U; ++k)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j] += r[k][j];
+        }
     }
-    for (; v <= win; ++v) {
-        float r[8];
-        load8<float>(win_rows + (2 * v * ppr + cp) * kPack, r);
+    if (wave > 0) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] += r[j];
+        for (int j = 0; j < 8; ++j) sm[wave - 1][j][lane] = acc[j];
     }
-    T* dst = demb + (static_cast<int64_t>(key) * ppr + cp) * kPack;
-    float o[8];
-    load8<T>(dst, o);
+    __syncthreads();
+    if (wave == 0 && active) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) o[j] = fmaf(scale, acc[j], o[j]);
-    store8<T>(dst, o);
+        for (int w = 0; w < kEmbWaves - 1; ++w)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] += sm[w][j][lane];
+        T* dst = demb + (static_cast<int64_t>(key) * ppr + cp) * kPack;
+        float o[8];
+        load8<T>(dst, o);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] = fmaf(scale, acc[j], o[j]);
+        store8<T>(dst, o);
+    }
 }
 
 // dP[l,:] += sum over the batch.  A workgroup owns 64 packs of one position; its four
 // waves take every fourth sentence each (four loads in flight per wave) and their
 // partial sums are added in wave order, so the result does not depend on timing.
 template <typename T, bool DROP>
-__global__ __launch_bounds__(256) void emb_dpos(T* __restrict__ dpos, const T* __restrict__ dy,
-                                                const int32_t* __restrict__ tokens, int batch, int len, int ppr,
-                                                int vocab, int pad_idx, DropoutParams d)
+__device__ __forceinline__ void emb_dpos_body(int cb, int l, T* __restrict__ dpos, const T* __restrict__ dy,
+                                              const int32_t* __restrict__ tokens, int batch, int len, int ppr,
+                                              int vocab, int pad_idx, const DropoutParams& d)
 {
     constexpr int U = 4;
     __shared__ float sm[kEmbWaves - 1][8][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int l = blockIdx.y;
-    const int cp = blockIdx.x * 64 + lane;
+    const int cp = cb * 64 + lane;
     const bool active = cp < ppr;
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if (active) {
@@ -356,6 +385,25 @@ __global__ __launch_bounds__(256) void emb_dpos(T* __restrict__ dpos, const T* _
 #pragma unroll
         for (int j = 0; j < 8; ++j) o[j] += acc[j];
         store8<T>(dst, o);
+    }
+}
+
+// The rank count is arithmetic out of LDS, the position gradient a stream over dy; neither
+// needs the other.  One launch holds the workgroups of both (the rank ones first, so that they
+// all start at once and the streaming ones fill the remaining wave slots): the two overlap
+// instead of running back to back.
+template <typename T, bool DROP>
+__global__ __launch_bounds__(256) void emb_rank_dpos(int32_t* __restrict__ partial, const int32_t* __restrict__ tokens,
+                                                     int64_t rows, int ntiles, int span_tiles, int rank_blocks,
+                                                     T* __restrict__ dpos, const T* __restrict__ dy, int batch, int len,
+                                                     int ppr, int ncb, int vocab, int pad_idx, DropoutParams d)
+{
+    static_assert(kTile == 256, "one block size for both bodies");
+    if (static_cast<int>(blockIdx.x) < rank_blocks) {            // workgroup-uniform
+        emb_rank_body(blockIdx.x % ntiles, blockIdx.x / ntiles, partial, tokens, rows, ntiles, span_tiles, vocab, pad_idx);
+    } else {
+        const int b = static_cast<int>(blockIdx.x) - rank_blocks;
+        emb_dpos_body<T, DROP>(b % ncb, b / ncb, dpos, dy, tokens, batch, len, ppr, vocab, pad_idx, d);
     }
 }
 
@@ -460,22 +508,29 @@ static lsq_status emb_bwd_dispatch(void* demb, void* dpos, const void* dy, const
     T* dp = static_cast<T*>(dpos);
     const T* g = static_cast<const T*>(dy);
     // the dropout scale 1/(1-p) is carried by the per-element factors; `scale` is the embedding scale
-    hipLaunchKernelGGL(emb_rank_partial, dim3(plan.ntiles, plan.nspans), dim3(kTile), 0, s, partial, tokens, rows,
-                       plan.ntiles, plan.span_tiles, vocab, pad_idx);
-    hipLaunchKernelGGL(emb_scatter, dim3(static_cast<unsigned>(ceil_div(rows, 256))), dim3(256), 0, s, order, partial,
+    const unsigned rank_blocks = static_cast<unsigned>(plan.ntiles) * static_cast<unsigned>(plan.nspans);
+    const bool packed = hidden % kPack == 0;
+    const int ppr = hidden / kPack;
+    const int ncb = static_cast<int>(ceil_div(ppr, 64));
+    if (packed && dp) {
+        // the position gradient rides along with the rank count
+        const dim3 rgrid(rank_blocks + static_cast<unsigned>(ncb) * static_cast<unsigned>(len));
+        if (d.t16) hipLaunchKernelGGL((emb_rank_dpos<T, true>), rgrid, dim3(256), 0, s, partial, tokens, rows, plan.ntiles, plan.span_tiles,
+                                      static_cast<int>(rank_blocks), dp, g, batch, len, ppr, ncb, vocab, pad_idx, d);
+        else hipLaunchKernelGGL((emb_rank_dpos<T, false>), rgrid, dim3(256), 0, s, partial, tokens, rows, plan.ntiles, plan.span_tiles,
+                                static_cast<int>(rank_blocks), dp, g, batch, len, ppr, ncb, vocab, pad_idx, d);
+    } else {
+        hipLaunchKernelGGL(emb_rank_partial, dim3(rank_blocks), dim3(kTile), 0, s, partial, tokens, rows, plan.ntiles,
+                           plan.span_tiles, vocab, pad_idx);
+    }
+    hipLaunchKernelGGL(emb_scatter, dim3(static_cast<unsigned>(ceil_div(rows, 64))), dim3(256), 0, s, order, partial,
                        tokens, rows, plan.nspans, vocab, pad_idx);
-    if (hidden % kPack == 0) {
-        const int ppr = hidden / kPack;
-        const int ncb = static_cast<int>(ceil_div(ppr, 64));
-        const dim3 grid(static_cast<unsigned>(ceil_div(plan.nwin * ncb, 4))), block(256);   // one wave per (window, column block)
+    if (packed) {
+        const unsigned pairs = static_cast<unsigned>(plan.nwin * ncb);      // (window, column block) pairs
+        const dim3 grid(static_cast<unsigned>(ceil_div(pairs, 4))), block(256);   // one wave per pair
         if (d.t16) hipLaunchKernelGGL((emb_accumulate<T, true>), grid, block, 0, s, de, win_rows, g, order, rows, plan.nwin, ncb, ppr, scale, d);
         else hipLaunchKernelGGL((emb_accumulate<T, false>), grid, block, 0, s, de, win_rows, g, order, rows, plan.nwin, ncb, ppr, scale, d);
-        hipLaunchKernelGGL((emb_combine<T>), grid, block, 0, s, de, win_rows, order, rows, plan.nwin, ncb, ppr, scale);
-        if (dp) {
-            const dim3 pgrid(static_cast<unsigned>(ceil_div(ppr, 64)), static_cast<unsigned>(len));
-            if (d.t16) hipLaunchKernelGGL((emb_dpos<T, true>), pgrid, dim3(256), 0, s, dp, g, tokens, batch, len, ppr, vocab, pad_idx, d);
-            else hipLaunchKernelGGL((emb_dpos<T, false>), pgrid, dim3(256), 0, s, dp, g, tokens, batch, len, ppr, vocab, pad_idx, d);
-        }
+        hipLaunchKernelGGL((emb_combine<T>), dim3(pairs), block, 0, s, de, win_rows, order, rows, ncb, ppr, scale);   // one workgroup per pair
     } else {
         hipLaunchKernelGGL((emb_accumulate_flat<T>), dim3(static_cast<unsigned>(rows)), dim3(256), 0, s, de, g, order, rows, hidden, scale, d);
         if (dp)
@@ -522,7 +577,8 @@ extern "C" lsq_status lsq_embedding_bwd(void* demb, void* dpos, const void* dy, 
     const int64_t rows = static_cast<int64_t>(batch) * len;
     if (rows == 0) return LSQ_OK;
     LSQ_REQUIRE(rows <= 0x7FFFFFFF / 2 && ceil_div(rows, kTile) <= 65535);
-    LSQ_REQUIRE(ceil_div(rows, kEmbWin) * ceil_div(hidden, 8 * 64) / 4 < 0x7FFFFFFF);   // one wave per (window, column block)
+    LSQ_REQUIRE(ceil_div(rows, kEmbWin) * ceil_div(hidden, 8 * 64) < 0x7FFFFFFF);   // one workgroup per (window, column block)
+    LSQ_REQUIRE(ceil_div(rows, kTile) * 64 + ceil_div(hidden, 8 * 64) * static_cast<int64_t>(len) < 0x7FFFFFFF);
     LSQ_REQUIRE(!dpos || len <= 65535);       // one grid row per position
     LSQ_REQUIRE(demb && dy && tokens);
     LSQ_ALIGNED(demb); LSQ_ALIGNED(dpos); LSQ_ALIGNED(dy); LSQ_ALIGNED(workspace);

@@ -139,7 +139,10 @@ inline int bdr_bwd_row_blocks(int64_t rows, int32_t /*hidden*/)
 //   rank counts [spans][rows] int32: token i against the tokens of span js (a span is a run
 //          of 256-token tiles, at most 64 spans)
 constexpr int kEmbTile = 256;
-constexpr int kEmbWin = 8;
+#ifndef LSQ_EMB_WIN
+#define LSQ_EMB_WIN 8
+#endif
+constexpr int kEmbWin = LSQ_EMB_WIN;
 struct EmbBwdPlan {
     int ntiles, span_tiles, nspans;
     int64_t nwin;
