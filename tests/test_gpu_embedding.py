@@ -14,7 +14,8 @@ PAD = 1
 # (batch, len, vocab, hidden, p)
 CASES = [(8, 64, 8000, 512, 0.1), (128, 32, 32768, 512, 0.1), (16, 128, 4096, 1024, 0.3), (4, 512, 30522, 1024, 0.1),
          (2, 1024, 50257, 1280, 0.1), (3, 50, 97, 768, 0.0), (5, 7, 11, 8, 0.25), (2, 9, 13, 257, 0.2), (1, 1, 3, 64, 0.1),
-         (4, 300, 5, 64, 0.1)]
+         (4, 300, 5, 64, 0.1),
+         (40, 520, 1000, 64, 0.1)]      # more than 64 rank tiles: several tiles per span
 
 
 def _tokens(B, Ln, V, rng):
