@@ -181,6 +181,10 @@ def main():
     def op_xent_bwd(i):
         L.lsq_ls_xent_bwd(logits, lse, target, cfg.alpha, IGNORE_INDEX, 1.0 / max(t_active, 1), dlogits=dlogits)
 
+    def op_xent_fwd_bwd(i):      # forward and backward in one pass over the logits
+        L.lsq_ls_xent_fwd_bwd(logits, target, cfg.alpha, IGNORE_INDEX, 1.0 / max(t_active, 1), loss=loss, nll=nll, lse=lse,
+                              sums=sums, dlogits=dlogits)
+
     def op_adam(i):
         state["step"] += 1
         L.lsq_adam_step(p, m, v, g, p_lp, step=state["step"], **ADAM_HYPER)
@@ -341,6 +345,7 @@ def main():
         "softmax_bwd": 4 * allowed + 2 * Es,
         "ls_xent_fwd": 2 * t_active * V + 16 * T,
         "ls_xent_bwd": 2 * t_active * V + 2 * T * V + 8 * T,
+        "ls_xent_fwd_bwd": 2 * t_active * V + 2 * T * V + 16 * T,
         "adam_step": 28 * n,
         "bias_act_dropout_fwd": 4 * EF + 2 * F, "bias_act_dropout_bwd": 6 * EF + 6 * F,
         "adam_step_lp": 22 * n, "sgd_step": 20 * n, "adam_step_blocked": 28 * n,
@@ -365,7 +370,7 @@ def main():
     ops.append(adam_main)
 
     all_nine = list(ops)
-    extra = [adam_other, ("bias_act_dropout_fwd", op_bad_fwd), ("bias_act_dropout_bwd", op_bad_bwd),
+    extra = [adam_other, ("ls_xent_fwd_bwd", op_xent_fwd_bwd), ("bias_act_dropout_fwd", op_bad_fwd), ("bias_act_dropout_bwd", op_bad_bwd),
              ("embedding_fwd", op_emb_fwd), ("embedding_bwd", op_emb_bwd),
              ("split_heads_fwd", op_split_fwd), ("split_heads_bwd", op_split_bwd), ("merge_heads_fwd", op_merge_fwd),
              ("layernorm_bwd_dres", op_ln_bwd_dres), ("bdr_layernorm_fwd", op_bdr_ln_fwd), ("bdr_layernorm_bwd", op_bdr_ln_bwd),
@@ -421,6 +426,14 @@ def main():
         other = {"entry_point": "lsq_" + adam_other[0], "value": round(step_bytes / (ms_o * 1e-3) / 1e9, 1),
                  "ms_per_step": round(ms_o, 4), "adam_avg_launch_ms": round(adam_ms_o, 4),
                  "adam_frac_of_peak": round(bts["adam_step"] / (adam_ms_o * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    one_pass = None
+    if not args.ops:      # and with the criterion's forward and backward replaced by the one-pass entry point
+        swapped = [o for o in ops if o[0] not in ("ls_xent_fwd", "ls_xent_bwd")]
+        swapped.insert(3, ("ls_xent_fwd_bwd", op_xent_fwd_bwd))
+        ms_f, _ = time_steps(swapped)
+        one_pass = {"entry_point": "lsq_ls_xent_fwd_bwd", "ms_per_step": round(ms_f, 4),
+                    "note": "same outputs; 2 B/elem fewer algorithmic bytes, so only the time is comparable"}
 
     # ------------------------------------------- per-operator table (cold, back to back)
     # `reps` launches of one operator are captured into a HIP graph and the graph is replayed
@@ -518,6 +531,10 @@ def main():
                                           "with query lengths (rows of padded queries neither read nor computed)"),
         "layer_us": {"encoder_layer_fwd_bwd_nongemm": round(enc, 1), "decoder_layer_fwd_bwd_nongemm": round(dec, 1)},
         "layer_us_with_residual_gradient": fused_layer,
+        "same_step_one_pass_criterion": one_pass,
+        "criterion_us": ({"separate": round(table["ls_xent_fwd"]["us"] + table["ls_xent_bwd"]["us"], 1),
+                          "one_pass": round(table["ls_xent_fwd_bwd"]["us"], 1)}
+                         if all(k in table for k in ("ls_xent_fwd", "ls_xent_bwd", "ls_xent_fwd_bwd")) else None),
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, dt)

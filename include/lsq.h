@@ -182,6 +182,23 @@ lsq_status lsq_ls_xent_bwd(void* dlogits, const void* logits, const float* lse,
                            float alpha, int32_t ignore_index, float grad_scale,
                            lsq_dtype dt, void* stream);
 
+/* Criterion forward and backward in ONE pass (Sec. IV-A, criterion layer: both formulas
+ * above).  The scale of the loss gradient is known before the criterion runs, so the
+ * gradient can be written while a token's row is still on chip: the logits are read
+ * once and dlogits written once, two passes over [tokens, vocab] instead of the three
+ * of the two calls (about a quarter less time when most tokens count; no gain on
+ * masked-LM batches where most rows are ignored and only zeros are written).
+ * Outputs as lsq_ls_xent_fwd (loss, nll nullable, lse, sums nullable) plus dlogits as
+ * lsq_ls_xent_bwd.  dlogits is evaluated as e_i * (grad_scale / S) - grad_scale*alpha/V
+ * with e_i = exp(h_i - max) rounded once to dt and S = sum_i e_i: it agrees with
+ * lsq_ls_xent_bwd to two roundings of dt.  dlogits may alias logits (in place).  Rows
+ * of up to 65528 elements are held in registers; longer rows run the two operators
+ * back to back. */
+lsq_status lsq_ls_xent_fwd_bwd(float* loss, float* nll, float* lse, float* sums, void* dlogits,
+                               const void* logits, const int32_t* target,
+                               int64_t tokens, int32_t vocab, float alpha, int32_t ignore_index,
+                               float grad_scale, lsq_dtype dt, void* stream);
+
 /* Mixed-precision Adam over one flat workspace, one launch (Sec. IV-C): the
  * low-precision gradient is converted on the fly, the update runs in fp32
  * registers, and each element is read and written once.

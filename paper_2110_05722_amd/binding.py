@@ -27,7 +27,7 @@ _DT = {torch.float16: LSQ_F16, torch.bfloat16: LSQ_BF16, torch.float32: LSQ_F32}
 EXPORTS = [
     "lsq_workspace_bytes", "lsq_status_string", "lsq_layernorm_fwd", "lsq_layernorm_bwd",
     "lsq_bias_dropout_residual_fwd", "lsq_bias_dropout_residual_bwd", "lsq_softmax_fwd", "lsq_softmax_bwd",
-    "lsq_ls_xent_fwd", "lsq_ls_xent_bwd", "lsq_adam_step",
+    "lsq_ls_xent_fwd", "lsq_ls_xent_bwd", "lsq_ls_xent_fwd_bwd", "lsq_adam_step",
     "lsq_bias_act_dropout_fwd", "lsq_bias_act_dropout_bwd", "lsq_adam_step_lp", "lsq_sgd_step",
     "lsq_split_heads_fwd", "lsq_split_heads_bwd", "lsq_merge_heads_fwd", "lsq_merge_heads_bwd",
     "lsq_embedding_fwd", "lsq_embedding_bwd",
@@ -68,6 +68,7 @@ def load():
         "lsq_softmax_bwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64, C.c_int, vp]),
         "lsq_ls_xent_fwd": (C.c_int, [vp, vp, vp, vp, vp, vp, i64, i32, f32, i32, C.c_int, vp]),
         "lsq_ls_xent_bwd": (C.c_int, [vp, vp, vp, vp, i64, i32, f32, i32, f32, C.c_int, vp]),
+        "lsq_ls_xent_fwd_bwd": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, i64, i32, f32, i32, f32, C.c_int, vp]),
         "lsq_adam_step": (C.c_int, [vp, vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, i32, i32, i32, f32,
                                     C.c_int, C.c_int, vp]),
         "lsq_bias_act_dropout_fwd": (C.c_int, [vp, vp, vp, i64, i32, i32, f32, u64, u64, C.c_int, vp]),
@@ -266,6 +267,29 @@ def lsq_ls_xent_bwd(logits, lse, target, alpha: float, ignore_index: int = -100,
     _check(load().lsq_ls_xent_bwd(_ptr(dlogits), _ptr(logits), _ptr(lse), _ptr(target), T, V, alpha, ignore_index,
                                   grad_scale, _dt(logits), _stream()), "lsq_ls_xent_bwd")
     return dlogits
+
+
+def lsq_ls_xent_fwd_bwd(logits, target, alpha: float, ignore_index: int = -100, grad_scale: float = 1.0,
+                        want_sums: bool = True, want_nll: bool = True, loss=None, nll=None, lse=None, sums=None,
+                        dlogits=None):
+    """Forward and backward in one pass -> (loss, nll or None, lse, sums or None, dlogits).  dlogits may be
+    `logits` itself (in place)."""
+    T, V = logits.shape
+    loss = torch.empty(T, dtype=torch.float32, device=logits.device) if loss is None else loss
+    lse = torch.empty(T, dtype=torch.float32, device=logits.device) if lse is None else lse
+    if want_nll and nll is None:
+        nll = torch.empty(T, dtype=torch.float32, device=logits.device)
+    if want_sums and sums is None:
+        sums = torch.empty(3, dtype=torch.float32, device=logits.device)
+    dlogits = torch.empty_like(logits) if dlogits is None else dlogits
+    _need("target", target, T, torch.int32)
+    for name, t, k in (("loss", loss, T), ("nll", nll, T), ("lse", lse, T), ("sums", sums, 3)):
+        _need(name, t, k, torch.float32)
+    _need("dlogits", dlogits, T * V, logits.dtype)
+    _check(load().lsq_ls_xent_fwd_bwd(_ptr(loss), _ptr(nll) if want_nll else None, _ptr(lse),
+                                      _ptr(sums) if want_sums else None, _ptr(dlogits), _ptr(logits), _ptr(target), T, V,
+                                      alpha, ignore_index, grad_scale, _dt(logits), _stream()), "lsq_ls_xent_fwd_bwd")
+    return loss, (nll if want_nll else None), lse, (sums if want_sums else None), dlogits
 
 
 def lsq_adam_step(p, m, v, g, p_lp=None, *, lr: float, beta1: float, beta2: float, eps: float, step: int,

@@ -130,6 +130,15 @@ __device__ __forceinline__ RawPack<T> zero_raw()
     return r;
 }
 
+// Hide a packed row from the optimiser: a kernel that walks the same packs in several passes
+// re-widens them in each pass instead of keeping 8 fp32 registers per pack alive in between.
+template <typename T>
+__device__ __forceinline__ void opaque(RawPack<T>& r)
+{
+    if constexpr (sizeof(T) == 2) asm volatile("" : "+v"(r.u));
+    else asm volatile("" : "+v"(r.a), "+v"(r.b));
+}
+
 template <typename T>
 __device__ __forceinline__ void unpack(const RawPack<T>& r, float (&f)[8])
 {

@@ -170,15 +170,6 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(T* __restrict__ y, float* _
     }
 }
 
-// Hide a value from the optimiser (the packed row is re-widened in pass 2 instead of
-// keeping 16 fp32 registers per pack alive across the row reduction).
-template <typename T>
-__device__ __forceinline__ void opaque(RawPack<T>& r)
-{
-    if constexpr (sizeof(T) == 2) asm volatile("" : "+v"(r.u));
-    else asm volatile("" : "+v"(r.a), "+v"(r.b));
-}
-
 #ifndef LSQ_LN_BWD_THREADS
 #define LSQ_LN_BWD_THREADS 256
 #endif

@@ -315,6 +315,212 @@ __global__ __launch_bounds__(256) void xent_bwd_flat_kernel(T* dlogits, const T*
     }
 }
 
+// ---- forward and backward in one pass over the logits.
+// The loss scale of a training step is known before the criterion runs, so the gradient can be
+// written while the row is still in registers: the logits are read once and dlogits written once
+// (two passes over [tokens, vocab] instead of the three of forward + backward).  One workgroup
+// per token holds the whole row as NP packs per thread.  Two exponentials per element would make
+// the pass ALU-bound (v_exp_f32 runs at a quarter of the vector rate), so there is one: pass 1
+// takes the maximum, pass 2 replaces each logit IN the registers by e = exp2(h log2e - max),
+// rounded to the storage type, while summing e and h, and pass 3 is one fma per element,
+// dlogits = e * (grad_scale / S) - grad_scale * alpha / V (- grad_scale (1 - alpha) at the target).
+// The extra rounding of e is of the size of the rounding of dlogits itself (fp32 storage: none).
+// Rows of odd vocabularies share their first and last pack of the flat tensor with the
+// neighbouring rows: those two packs are read and written element by element, everything else in
+// aligned 128-bit packs.  Every load of the row (and of the target logit) precedes every store,
+// and a workgroup writes only its own row's elements, so dlogits may be the logits buffer itself.
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+struct Half8 { half2v v[4]; };
+template <typename T> constexpr bool kIsF16 = false;
+template <> constexpr bool kIsF16<f16> = true;
+
+// which of the 8 elements of window pack i lie in [lo, hi) (element offsets from the window's first pack)
+__device__ __forceinline__ unsigned row_mask(int i, int lo, int hi)
+{
+    unsigned m = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) m |= (i * kPack + j >= lo && i * kPack + j < hi) ? (1u << j) : 0u;
+    return m;
+}
+
+template <typename T, int THREADS, int NP>
+__global__ __launch_bounds__(THREADS) void xent_fused_kernel(
+    float* __restrict__ loss, float* __restrict__ nll, float* __restrict__ lse, T* dlogits, const T* logits,
+    const int32_t* __restrict__ target, int vocab, float alpha, int ignore_index, float grad_scale)
+{
+    constexpr int NW = THREADS / 64;
+    __shared__ float lds[2][NW];
+    const int64_t t = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int64_t begin = t * vocab, end = begin + vocab;
+    const int64_t p0 = begin >> 3, p1 = (end - 1) >> 3;        // packs of the flat tensor that hold the row
+    const int np = static_cast<int>(p1 - p0) + 1;
+    const int lo = static_cast<int>(begin - p0 * kPack), hi = lo + vocab;   // the row inside its window of packs
+    // only the row's first and last pack can be shared with a neighbouring row (or overhang the tensor)
+    const int ragged_first = (begin & 7) != 0 || np == 1 ? 0 : -1;
+    const int ragged_last = (end & 7) != 0 || np == 1 ? np - 1 : -1;
+    const T* src = logits + p0 * kPack;
+    T* dst = dlogits + p0 * kPack;
+    const int k0 = target[t];
+    if (is_ignored(k0, vocab, ignore_index)) {                 // uniform over the workgroup: zeros, nothing is read
+        const float z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int k = 0; k < NP; ++k) {
+            const int i = tid + k * THREADS;
+            if (i >= np) continue;
+            if (i != ragged_first && i != ragged_last) {
+                store8<T, kBwdNTS>(dst + i * kPack, z);
+            } else {
+                const unsigned mask = row_mask(i, lo, hi);
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (mask >> j & 1u) dst[i * kPack + j] = from_f32<T>(0.0f);
+            }
+        }
+        if (tid == 0) {
+            loss[t] = 0.0f;
+            lse[t] = 0.0f;
+            if (nll) nll[t] = 0.0f;
+        }
+        return;
+    }
+    const float hk = tid == 0 ? to_f32<T>(logits[begin + k0]) : 0.0f;
+    // Elements of a ragged pack that belong to another row, and packs past the row, are held as
+    // -inf: neutral for the maximum and for the sum of exponentials, so the wide passes carry no
+    // per-element conditions; the sum of the logits skips them explicitly.
+    // Iterations whose packs all lie past the row are skipped as a whole.  That uniform test also keeps
+    // the compiler from interleaving the iterations: 16-bit rows of 8 packs per thread then fit 64
+    // registers, so two 1024-thread workgroups share a compute unit and one streams while the other
+    // computes (measured: 385 us with one workgroup per unit, 301 us with two, at 8192 x 50257).
+    RawPack<T> raw[NP];
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+        const int i = tid + k * THREADS;
+        if (k * THREADS >= np) {
+            raw[k] = zero_raw<T>();
+        } else if (i < np && i != ragged_first && i != ragged_last) {
+            raw[k] = load_raw<T, kNT>(src + i * kPack);
+        } else if (i < np) {
+            const unsigned mask = row_mask(i, lo, hi);
+            float h[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) h[j] = (mask >> j & 1u) ? to_f32<T>(src[i * kPack + j]) : -INFINITY;
+            raw[k] = pack_raw<T>(h);                           // exact: the values come from T, and -inf exists in T
+        } else {
+            float h[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) h[j] = -INFINITY;
+            raw[k] = pack_raw<T>(h);
+        }
+    }
+    // pass 1: the maximum (fp16: two elements per instruction, no widening)
+    float m = -INFINITY;
+    if constexpr (kIsF16<T>) {
+        half2v mm = {static_cast<_Float16>(-INFINITY), static_cast<_Float16>(-INFINITY)};
+#pragma unroll
+        for (int k = 0; k < NP; ++k) {
+            if (k * THREADS >= np) continue;
+            const Half8 h = __builtin_bit_cast(Half8, raw[k].u);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) mm = __builtin_elementwise_max(mm, h.v[c]);
+        }
+        m = fmaxf(static_cast<float>(mm.x), static_cast<float>(mm.y));
+    } else {
+#pragma unroll
+        for (int k = 0; k < NP; ++k) {
+            if (k * THREADS >= np) continue;
+            float h[8];
+            unpack<T>(raw[k], h);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) m = fmaxf(m, h[j]);
+        }
+    }
+    // the maximum of h * log2(e) is the maximum of h times log2(e): rounding is monotonic.  The
+    // exponentials are kept for pass 3 in the storage type, so fp16 shifts them up by 2^14: the
+    // largest is 16384 and relative precision holds down to 2^-28 of it.
+    constexpr float kShift = kIsF16<T> ? 14.0f : 0.0f;
+    const float Ms = block_allreduce<NW, OpMax>(m, lds[0]) * kLog2eX - kShift;
+    // pass 2: e = exp2(h log2e - Ms) replaces h in the registers; sums of e (before its rounding) and of h
+    float sx = 0.0f, sh = 0.0f;
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+        const int i = tid + k * THREADS;
+        if (k * THREADS >= np) continue;
+        opaque<T>(raw[k]);                                     // widened again in each pass: the row stays packed in between
+        const bool whole = i < np && i != ragged_first && i != ragged_last;
+        if constexpr (kIsF16<T>) {
+            if (whole) {                                       // sum of the logits: two per instruction, fp32 accumulator
+                const Half8 h2 = __builtin_bit_cast(Half8, raw[k].u);
+                const half2v ones = {static_cast<_Float16>(1.0f), static_cast<_Float16>(1.0f)};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) sh = __builtin_amdgcn_fdot2(h2.v[c], ones, sh, false);
+            }
+        }
+        float h[8];
+        unpack<T>(raw[k], h);
+        if (!kIsF16<T> && whole) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) sh += h[j];
+        }
+        if (!whole && i < np) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) sh += h[j] == -INFINITY ? 0.0f : h[j];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            h[j] = __builtin_amdgcn_exp2f(fmaf(h[j], kLog2eX, -Ms));     // exp2(-inf) = 0
+            sx += h[j];
+        }
+        raw[k] = pack_raw<T>(h);
+    }
+    // both sums through LDS in one exchange
+    sx = group_allreduce<64, OpSum>(sx);
+    sh = group_allreduce<64, OpSum>(sh);
+    __syncthreads();                                           // lds[0] was read by the maximum
+    if ((tid & 63) == 0) {
+        lds[0][tid >> 6] = sx;
+        lds[1][tid >> 6] = sh;
+    }
+    __syncthreads();
+    float S = lds[0][0], SH = lds[1][0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) { S += lds[0][w]; SH += lds[1][w]; }
+    const float l = (Ms + __builtin_amdgcn_logf(S)) * kLn2X;       // v_log_f32 is log2
+    if (tid == 0) {
+        lse[t] = l;
+        loss[t] = l - (1.0f - alpha) * hk - (alpha / static_cast<float>(vocab)) * SH;
+        if (nll) nll[t] = l - hk;
+    }
+    // pass 3: dlogits = grad_scale * (e / S - alpha/V) - grad_scale * (1 - alpha) [target], one fma per element
+    const float c1 = grad_scale / S;
+    const float c0 = -grad_scale * (alpha / static_cast<float>(vocab));
+    const float hit = grad_scale * (1.0f - alpha);
+    const int ki = static_cast<int>(((begin + k0) >> 3) - p0);  // the pack of the target logit, and its place there
+    const int kj = static_cast<int>((begin + k0) & 7);
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+        const int i = tid + k * THREADS;
+        if (i >= np) continue;
+        float h[8];
+        opaque<T>(raw[k]);
+        unpack<T>(raw[k], h);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) h[j] = fmaf(h[j], c1, c0);
+        if (i == ki) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) h[j] -= (j == kj) ? hit : 0.0f;
+        }
+        if (i != ragged_first && i != ragged_last) {
+            store8<T, kBwdNTS>(dst + i * kPack, h);
+        } else {
+            const unsigned mask = row_mask(i, lo, hi);
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (mask >> j & 1u) dst[i * kPack + j] = from_f32<T>(h[j]);
+        }
+    }
+}
+
 // sums = { sum loss, sum nll, count } over non-ignored tokens: one workgroup, double
 // accumulators, fixed strided order and a fixed LDS tree.  With the per-token nll at
 // hand every input is a contiguous array; without it the target logits are gathered
@@ -414,6 +620,37 @@ static lsq_status xent_bwd_dispatch(void* dlogits, const void* logits, const flo
     return launch_status();
 }
 
+// Rows of up to 1024 x 8 packs stay in registers; longer ones take the two operators back to back.
+template <typename T>
+static lsq_status xent_fused_dispatch(float* loss, float* nll, float* lse, float* sums, void* dlogits, const void* logits,
+                                      const int32_t* target, int64_t tokens, int32_t vocab, float alpha,
+                                      int32_t ignore_index, float grad_scale, hipStream_t s)
+{
+    const int64_t rp = (static_cast<int64_t>(vocab) + 7) / 8 + 1;       // packs a row can touch
+    T* dp = static_cast<T*>(dlogits);
+    const T* lp = static_cast<const T*>(logits);
+    const dim3 grid(static_cast<unsigned>(tokens));
+#define LSQ_XF(TH, NPK)                                                                                              \
+    hipLaunchKernelGGL((xent_fused_kernel<T, TH, NPK>), grid, dim3(TH), 0, s, loss, nll, lse, dp, lp, target, vocab, alpha, \
+                       ignore_index, grad_scale)
+    if (rp <= 256 * 2) LSQ_XF(256, 2);
+    else if (rp <= 256 * 4) LSQ_XF(256, 4);
+    else if (rp <= 256 * 8) LSQ_XF(256, 8);
+    else if (rp <= 1024 * 4) LSQ_XF(1024, 4);
+    else if (rp <= 1024 * 8) LSQ_XF(1024, 8);
+    else {
+        const lsq_status st = xent_fwd_dispatch<T>(loss, nll, lse, nullptr, logits, target, tokens, vocab, alpha, ignore_index, s);
+        if (st != LSQ_OK) return st;
+        const lsq_status sb = xent_bwd_dispatch<T>(dlogits, logits, lse, target, tokens, vocab, alpha, ignore_index, grad_scale, s);
+        if (sb != LSQ_OK) return sb;
+    }
+#undef LSQ_XF
+    if (sums)
+        hipLaunchKernelGGL((xent_sums_kernel<T>), dim3(1), dim3(1024), 0, s, sums, loss, nll, lse, lp, target, tokens,
+                           vocab, ignore_index);
+    return launch_status();
+}
+
 }  // namespace lsq
 
 extern "C" lsq_status lsq_ls_xent_fwd(float* loss, float* nll, float* lse, float* sums, const void* logits, const int32_t* target,
@@ -451,5 +688,24 @@ extern "C" lsq_status lsq_ls_xent_bwd(void* dlogits, const void* logits, const f
         case LSQ_F16: return xent_bwd_dispatch<f16>(dlogits, logits, lse, target, tokens, vocab, alpha, ignore_index, grad_scale, s);
         case LSQ_BF16: return xent_bwd_dispatch<bf16>(dlogits, logits, lse, target, tokens, vocab, alpha, ignore_index, grad_scale, s);
         default: return xent_bwd_dispatch<float>(dlogits, logits, lse, target, tokens, vocab, alpha, ignore_index, grad_scale, s);
+    }
+}
+
+extern "C" lsq_status lsq_ls_xent_fwd_bwd(float* loss, float* nll, float* lse, float* sums, void* dlogits, const void* logits,
+                                          const int32_t* target, int64_t tokens, int32_t vocab, float alpha,
+                                          int32_t ignore_index, float grad_scale, lsq_dtype dt, void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(tokens >= 0 && tokens <= 0x7FFFFFFF && vocab > 0);
+    LSQ_REQUIRE(alpha >= 0.0f && alpha <= 1.0f);
+    if (!valid_dtype(dt)) return LSQ_UNSUPPORTED_DTYPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (tokens == 0) return sums ? zero_fill(sums, 3, s) : LSQ_OK;
+    LSQ_REQUIRE(loss && lse && dlogits && logits && target);
+    LSQ_ALIGNED(dlogits); LSQ_ALIGNED(logits);
+    switch (dt) {
+        case LSQ_F16: return xent_fused_dispatch<f16>(loss, nll, lse, sums, dlogits, logits, target, tokens, vocab, alpha, ignore_index, grad_scale, s);
+        case LSQ_BF16: return xent_fused_dispatch<bf16>(loss, nll, lse, sums, dlogits, logits, target, tokens, vocab, alpha, ignore_index, grad_scale, s);
+        default: return xent_fused_dispatch<float>(loss, nll, lse, sums, dlogits, logits, target, tokens, vocab, alpha, ignore_index, grad_scale, s);
     }
 }

@@ -76,7 +76,8 @@ def test_layer_ops_replay_under_a_hip_graph():
 
 
 def test_newer_entry_points_replay_under_a_hip_graph():
-    say("[graph] capture + 3 replays: padding removal, fused boundary, query-length and unaligned softmax, blocked trainers")
+    say("[graph] capture + 3 replays: padding removal, fused boundary, query-length and unaligned softmax, blocked "
+        "trainers, one-pass criterion, embedding backward")
     d = dev()
     B, Ln, H, N = 6, 37, 256, 4                       # 37 keys: the LDS-staged softmax path
     T = B * Ln
@@ -101,8 +102,20 @@ def test_newer_entry_points_replay_under_a_hip_graph():
     ws = torch.empty(L.lsq_workspace_bytes(5, T, H), dtype=torch.uint8, device=d)
     sy, syd, sdx = (torch.empty_like(sx) for _ in range(3))
     state, sgd, p_lp = state0.clone(), sgd0.clone(), torch.empty(n, dtype=torch.float16, device=d)
+    V = 1003                                          # odd vocabulary: ragged first / last pack of every row
+    logits = rn(T, V)
+    target = torch.randint(0, V, (T,), generator=g0).to(torch.int32).to(d)
+    target[::5] = -100
+    xl, xn, xe, xs = torch.empty(T, device=d), torch.empty(T, device=d), torch.empty(T, device=d), torch.empty(3, device=d)
+    dlog = torch.empty_like(logits)
+    tokens = torch.randint(0, 50, (B, Ln), generator=g0).to(torch.int32).to(d)
+    demb0, dpos0 = rn(50, H), rn(Ln, H)
+    demb, dpos = demb0.clone(), dpos0.clone()
+    ews = torch.empty(L.lsq_workspace_bytes(4, T, H), dtype=torch.uint8, device=d)
 
     def run():
+        L.lsq_ls_xent_fwd_bwd(logits, target, 0.1, -100, 0.25, loss=xl, nll=xn, lse=xe, sums=xs, dlogits=dlog)
+        L.lsq_embedding_bwd(demb, dpos, dy, tokens, 1, 2.0, 0.1, 9, 3, workspace=ews)
         L.lsq_pad_offsets(lens, B, Ln, offsets=offsets)
         L.lsq_pad_remove(x.view(B, Ln, H), offsets, total, packed=packed)
         L.lsq_pad_restore(packed, offsets, B, Ln, padded=padded)
@@ -114,10 +127,11 @@ def test_newer_entry_points_replay_under_a_hip_graph():
         L.lsq_adam_step_blocked(state, gr, p_lp, step=2, **HY)
         L.lsq_sgd_step_blocked(sgd, gr, None, lr=0.1, momentum=0.9)
 
-    outputs = (offsets, packed, padded, h, y, mean, rstd, dh, dxp, dgm, dbt, dbi, sy, syd, sdx, state, sgd, p_lp)
+    outputs = (offsets, packed, padded, h, y, mean, rstd, dh, dxp, dgm, dbt, dbi, sy, syd, sdx, xl, xn, xe, xs, dlog,
+               demb, dpos, state, sgd, p_lp)
 
     def reset_state():
-        state.copy_(state0); sgd.copy_(sgd0)
+        state.copy_(state0); sgd.copy_(sgd0); demb.copy_(demb0); dpos.copy_(dpos0)
 
     reset_state()
     run()
@@ -128,7 +142,7 @@ def test_newer_entry_points_replay_under_a_hip_graph():
     with torch.cuda.graph(graph):
         run()
     for replay in range(3):
-        for o in outputs[:-3]:
+        for o in outputs[:-5]:
             o.fill_(float("nan")) if o.is_floating_point() else o.fill_(-7)
         reset_state()
         torch.cuda.synchronize()

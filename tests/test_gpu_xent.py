@@ -14,6 +14,7 @@ pytestmark = pytest.mark.gpu
 CASES = [
     (512, 8000, 0.1), (64, 32768, 0.1), (48, 30522, 0.0), (40, 50257, 0.1),
     (33, 8001, 0.1), (17, 257, 0.3), (9, 5, 0.1), (11, 8, 0.0), (7, 1, 0.5), (16, 13, 1.0), (5, 2051, 0.1),
+    (10, 12345, 0.1), (9, 70001, 0.1),      # the widest 256-thread row bucket of the one-pass kernel; a row beyond its buckets
 ]
 
 
@@ -43,6 +44,20 @@ def _run(t, T, V, alpha, dt, grad_scale=1.0):
     lc = logits.clone()
     dl2 = L.lsq_ls_xent_bwd(lc, lse, target, alpha, IGNORE_INDEX, grad_scale, dlogits=lc)
     assert torch.equal(dl, dl2)
+    # forward and backward in one pass: the same outputs to the same tolerances, ignored rows exact zeros,
+    # in place allowed
+    floss, fnll, flse, fsums, fdl = L.lsq_ls_xent_fwd_bwd(logits, target, alpha, IGNORE_INDEX, grad_scale)
+    assert_close_f32(flse, rlse, "one-pass lse", floor=1e-6)
+    assert_close_f32(floss, rloss, "one-pass loss", floor=2e-6)
+    assert_close_f32(fnll, rnll, "one-pass nll", floor=2e-6)
+    assert_close_f32(fsums, rsums, "one-pass sums", floor=1e-5)
+    assert_close_store(fdl, rdl, dt, "one-pass dlogits", f32_floor=1e-7)
+    assert not from_torch(fdl, dt)[ign].view(np.uint16 if dt != "f32" else np.uint32).any()
+    assert (floss.cpu().numpy()[ign] == 0).all() and (flse.cpu().numpy()[ign] == 0).all()
+    lc = logits.clone()
+    out = L.lsq_ls_xent_fwd_bwd(lc, target, alpha, IGNORE_INDEX, grad_scale, want_sums=False, want_nll=False, dlogits=lc)
+    assert out[1] is None and out[3] is None
+    assert torch.equal(out[4], fdl) and torch.equal(out[0], floss) and torch.equal(out[2], flse)
     return loss, lse, sums
 
 
@@ -114,3 +129,21 @@ def test_ls_xent_full_size(ci, dt):
     assert abs(sums[0].item() - loss.double().sum().item()) <= 1e-5 * loss.double().sum().item()
     assert abs(sums[1].item() - nll.double().sum().item()) <= 1e-5 * nll.double().sum().item()
     assert sums[2].item() == int((tgt != IGNORE_INDEX).sum())
+    # the one-pass entry point at the same size: sampled rows against the oracle, the whole gradient against the
+    # stand-alone backward (two roundings to the storage type apart at most), then in place over the logits
+    del dl
+    floss, fnll, flse, fsums, fdl = L.lsq_ls_xent_fwd_bwd(logits, target, cfg.alpha, IGNORE_INDEX, gs)
+    assert_close_f32(flse[idx], rlse, "one-pass lse", floor=1e-6)
+    assert_close_f32(floss[idx], rloss, "one-pass loss", floor=2e-6)
+    assert_close_f32(fnll[idx], rnll, "one-pass nll", floor=2e-6)
+    assert_close_store(fdl[idx], rdl, dt, "one-pass dlogits")
+    assert fsums[2].item() == sums[2].item() and abs(fsums[0].item() - sums[0].item()) <= 1e-5 * sums[0].item()
+    ref = L.lsq_ls_xent_bwd(logits, flse, target, cfg.alpha, IGNORE_INDEX, gs)
+    ulp = 2.0 ** -7 if dt == "bf16" else 2.0 ** -10
+    err = (fdl.float() - ref.float()).abs_()
+    err -= ref.float().abs_().mul_(2 * ulp)
+    assert err.max().item() <= (1e-7 if dt != "bf16" else 1e-6), err.max().item()
+    assert not fdl[ign].any()
+    del ref, err
+    L.lsq_ls_xent_fwd_bwd(logits, target, cfg.alpha, IGNORE_INDEX, gs, dlogits=logits)
+    assert torch.equal(logits, fdl)
