@@ -533,8 +533,8 @@ def main():
         "layer_us_with_residual_gradient": fused_layer,
         "same_step_one_pass_criterion": one_pass,
         "criterion_us": ({"separate": round(table["ls_xent_fwd"]["us"] + table["ls_xent_bwd"]["us"], 1),
-                          "one_pass": round(table["ls_xent_fwd_bwd"]["us"], 1)}
-                         if all(k in table for k in ("ls_xent_fwd", "ls_xent_bwd", "ls_xent_fwd_bwd")) else None),
+                          "one_pass": round(next_table["ls_xent_fwd_bwd"]["us"], 1)}
+                         if "ls_xent_fwd" in table and "ls_xent_bwd" in table and "ls_xent_fwd_bwd" in next_table else None),
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, dt)
