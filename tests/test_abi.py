@@ -96,6 +96,12 @@ def test_host_side_argument_errors(lib):
     f = lib.lsq_ls_xent_bwd
     assert f(A, A, None, A, 4, 8, 0.1, -100, 1.0, 0, None) == INVALID
     assert f(A, A, A, A, 4, 8, 0.1, -100, 1.0, 9, None) == DTYPE
+    f = lib.lsq_ls_xent_fwd_bwd
+    assert f(A, None, A, None, None, A, A, 4, 8, 0.1, -100, 1.0, 0, None) == INVALID      # no dlogits
+    assert f(A, None, A, None, A, A, A, 4, 8, -0.1, -100, 1.0, 0, None) == INVALID
+    assert f(A, None, A, None, U, A, A, 4, 8, 0.1, -100, 1.0, 0, None) == MISALIGNED
+    assert f(A, None, A, None, A, A, A, 4, 8, 0.1, -100, 1.0, 3, None) == DTYPE
+    assert f(None, None, None, None, None, None, None, 0, 8, 0.1, -100, 1.0, 0, None) == 0
 
 
 def test_host_side_argument_errors_of_the_next_rows(lib):
