@@ -123,7 +123,14 @@ def test_criterion_and_trainers_random(seed):
     assert_close_f32(nll, rnll, "nll", floor=4e-6)
     assert_close_f32(sums, rsums, "sums", floor=1e-5 * max(1, T))
     dl = L.lsq_ls_xent_bwd(logits, lse, target, alpha, IGNORE_INDEX, 0.5)
-    assert_close_store(dl, oracle.ls_xent_bwd(ls, tg, alpha, IGNORE_INDEX, 0.5, dt), dt, "dlogits", f32_floor=1e-6)
+    rdl = oracle.ls_xent_bwd(ls, tg, alpha, IGNORE_INDEX, 0.5, dt)
+    assert_close_store(dl, rdl, dt, "dlogits", f32_floor=1e-6)
+    floss, fnll, flse, fsums, fdl = L.lsq_ls_xent_fwd_bwd(logits, target, alpha, IGNORE_INDEX, 0.5)   # both in one pass
+    assert_close_f32(flse, rlse, "one-pass lse", floor=2e-6)
+    assert_close_f32(floss, rloss, "one-pass loss", floor=4e-6)
+    assert_close_f32(fnll, rnll, "one-pass nll", floor=4e-6)
+    assert_close_f32(fsums, rsums, "one-pass sums", floor=1e-5 * max(1, T))
+    assert_close_store(fdl, rdl, dt, "one-pass dlogits", f32_floor=1e-6)
     # Adam, both layouts, on a random length
     n = int(r.choice([int(r.integers(1, 64)), int(r.integers(64, 20000)), 8192 * int(r.integers(1, 4)) + int(r.integers(-2, 3))]))
     hp = (r.standard_normal(n) * 0.02).astype(np.float32)
