@@ -9,8 +9,8 @@
 // its two row sums (sum g, sum g*xhat) are independent given the saved mean and
 // rstd, and run side by side in the same DPP reduction steps.
 //
-// Layout: LPR lanes share a row (8..64 lanes of one wave, or a whole 256-thread
-// workgroup for very wide rows); each lane holds VPL packs of 8 columns, strided
+// Layout: LPR lanes share a row (8..64 lanes of one wave, or a whole 256- or 1024-thread
+// workgroup for rows of 2049..8192 and 8193..16384 columns); each lane holds VPL packs of 8 columns, strided
 // by LPR packs so that a wave's loads are contiguous.  gamma/beta stay in
 // registers while the workgroup walks down its rows.  dgamma/dbeta: every lane
 // accumulates its own columns over its rows, the row slots of a workgroup are
@@ -28,7 +28,7 @@ constexpr bool kNT = LSQ_NT != 0;   // nontemporal hint on the streamed tensors 
 template <int LPR>
 __device__ __forceinline__ float row_sum(float v, float* lds)
 {
-    if constexpr (LPR == 256) return block_allreduce<4, OpSum>(v, lds);
+    if constexpr (LPR >= 256) return block_allreduce<LPR / 64, OpSum>(v, lds);      // the row spans the workgroup
     else return group_sum<LPR>(v);
 }
 
@@ -59,13 +59,13 @@ struct BdrFuse {
 // two loads, stored once (the next residual) and normalised from its STORED (rounded) value, so the
 // result equals bias+dropout+residual followed by LayerNorm bit for bit while h is never re-read.
 template <typename T, int LPR, int VPL, bool FUSE = false, bool DROP = false>
-__global__ __launch_bounds__(256) void ln_fwd_kernel(T* __restrict__ y, float* __restrict__ mean,
+__global__ __launch_bounds__(LPR > 256 ? LPR : 256) void ln_fwd_kernel(T* __restrict__ y, float* __restrict__ mean,
                                                      float* __restrict__ rstd, const T* __restrict__ x,
                                                      const T* __restrict__ gamma, const T* __restrict__ beta,
                                                      int64_t rows, int hidden, float eps, BdrFuse<T> fz)
 {
-    __shared__ float lds[4];
-    constexpr int RPB = 256 / LPR;            // rows a workgroup handles at a time
+    __shared__ float lds[16];
+    constexpr int RPB = LPR > 256 ? 1 : 256 / LPR;     // rows a workgroup handles at a time
     const int sub = threadIdx.x % LPR;
     const int slot = threadIdx.x / LPR;
     const int nv = hidden / kPack;
@@ -187,7 +187,7 @@ constexpr int kLnBwdThreads = LSQ_LN_BWD_THREADS;
 template <int LPR, int VPL, int THREADS, int NACC>
 constexpr bool ln_bwd_slots_parallel()
 {
-    return LPR != 256 && static_cast<long>(THREADS / LPR) * NACC * 8 * ((LPR * VPL) | 1) * 4 <= 63 * 1024;
+    return LPR < 256 && static_cast<long>(THREADS / LPR) * NACC * 8 * ((LPR * VPL) | 1) * 4 <= 63 * 1024;
 }
 
 // partial: [gridDim.x][2][hidden] fp32 (dgamma row, then dbeta row).
@@ -198,7 +198,10 @@ constexpr bool ln_bwd_slots_parallel()
 // stored (the residual branch's gradient), then masked and scaled from its STORED value into
 // fz.out (the projection's gradient), whose column sums (dbias) join dgamma/dbeta as a third
 // partial row.  Equal to LayerNorm backward followed by bias+dropout+residual backward, one pass.
-template <typename T, int LPR, int VPL, bool HAS_RES, int THREADS, bool FUSE = false, bool DROP = false>
+// COLS = false: dx only (rows wider than 8192 columns, one 1024-thread workgroup per row: the
+// column accumulators would not fit the 128 registers a thread has there, so dgamma/dbeta come
+// from the two-stage column kernel instead, which reads dy and x once more).
+template <typename T, int LPR, int VPL, bool HAS_RES, int THREADS, bool FUSE = false, bool DROP = false, bool COLS = true>
 __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restrict__ partial, const T* dy,
                                                          const T* __restrict__ x, const T* __restrict__ gamma,
                                                          const float* __restrict__ mean, const float* __restrict__ rstd,
@@ -206,8 +209,9 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
 {
     constexpr int NACC = FUSE ? 3 : 2;        // column accumulators: dgamma, dbeta (, dbias)
     extern __shared__ float colbuf[];         // [NACC][8][packs | 1] when LPR < 256
-    __shared__ float lds[4];
-    static_assert(LPR != 256 || THREADS == 256, "a whole-workgroup row needs 256 threads");
+    __shared__ float lds[16];
+    static_assert(LPR < 256 || THREADS == LPR, "a whole-workgroup row takes the whole workgroup");
+    static_assert(COLS || !FUSE, "the fused boundary needs the column sums");
     constexpr int RPB = THREADS / LPR;
     const int sub = threadIdx.x % LPR;
     const int slot = threadIdx.x / LPR;
@@ -280,8 +284,10 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const float xhat = fmaf(xv[j], rs, nmr);
-                dg[k][j] = fmaf(gy[j], xhat, dg[k][j]);
-                db[k][j] += gy[j];
+                if constexpr (COLS) {
+                    dg[k][j] = fmaf(gy[j], xhat, dg[k][j]);
+                    db[k][j] += gy[j];
+                }
                 const float gg = gy[j] * g8[j];
                 s1 += gg;
                 s2 = fmaf(gg, xhat, s2);
@@ -353,8 +359,9 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
 #endif
     }
 
+    if constexpr (!COLS) return;
     float* prow = partial + static_cast<int64_t>(blockIdx.x) * NACC * hidden;
-    if constexpr (LPR == 256) {
+    if constexpr (LPR >= 256) {               // every thread owns its columns: nothing to combine
 #pragma unroll
         for (int k = 0; k < VPL; ++k) {
             const int idx = sub + k * LPR;
@@ -528,6 +535,48 @@ __global__ __launch_bounds__(256) void ln_dparams_generic(float* __restrict__ pa
     prow[hidden + c] = sb;
 }
 
+// The same first stage for rows of whole packs: one thread per PACK of 8 columns (128-bit
+// loads), four rows in flight.  Serves the rows that are too wide for the column
+// accumulators to stay in registers next to the row itself.
+template <typename T>
+__global__ __launch_bounds__(256) void ln_dparams_packed(float* __restrict__ partial,
+                                                         const T* __restrict__ dy, const T* __restrict__ x,
+                                                         const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                         int64_t rows, int hidden)
+{
+    const int idx = blockIdx.x * 256 + threadIdx.x;       // pack of the row
+    if (idx >= hidden / kPack) return;
+    float sg[8] = {0, 0, 0, 0, 0, 0, 0, 0}, sb[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const int64_t stride = gridDim.y;
+    for (int64_t r0 = blockIdx.y; r0 < rows; r0 += 4 * stride) {
+        RawPack<T> gy[4], xv[4];
+        float mu[4], rs[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t r = r0 + u * stride;
+            const bool ok = r < rows;
+            gy[u] = ok ? load_raw<T, false>(dy + r * hidden + idx * kPack) : zero_raw<T>();
+            xv[u] = ok ? load_raw<T, false>(x + r * hidden + idx * kPack) : zero_raw<T>();
+            mu[u] = ok ? mean[r] : 0.0f;
+            rs[u] = ok ? rstd[r] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float g8[8], x8[8];
+            unpack<T>(gy[u], g8);
+            unpack<T>(xv[u], x8);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                sg[j] = fmaf(g8[j], (x8[j] - mu[u]) * rs[u], sg[j]);
+                sb[j] += g8[j];
+            }
+        }
+    }
+    float* prow = partial + static_cast<int64_t>(blockIdx.y) * 2 * hidden;
+    store8<float>(prow + idx * kPack, sg);
+    store8<float>(prow + hidden + idx * kPack, sb);
+}
+
 // ------------------------------------------------------------------ dispatch
 // Shape buckets: lanes per row and packs per lane for a row of nv packs.
 struct LnShape { int lpr, vpl; };
@@ -545,19 +594,21 @@ inline LnShape ln_shape(int hidden)
     if (nv <= 256) return {64, 4};
     if (nv <= 512) return {256, 2};
     if (nv <= 1024) return {256, 4};
+    if (nv <= 2048) return {1024, 2};     // hidden up to 16384: one 1024-thread workgroup per row
     return {0, 0};
 }
 
 inline int ln_fwd_blocks(int64_t rows, int lpr)
 {
-    const int rpb = 256 / lpr;
+    const int rpb = lpr > 256 ? 1 : 256 / lpr;
     int64_t b = ceil_div(rows, static_cast<int64_t>(rpb) * 2);   // about two row groups per workgroup
     if (b > 8192) b = 8192;
     if (b < 1) b = 1;
     return static_cast<int>(b);
 }
 
-#define LSQ_LN_CASES(X) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 3) X(64, 4) X(256, 2) X(256, 4)
+#define LSQ_LN_CASES_BWD(X) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 3) X(64, 4) X(256, 2) X(256, 4)
+#define LSQ_LN_CASES(X) LSQ_LN_CASES_BWD(X) X(1024, 2)
 
 // fuse != nullptr: x is the projection output and *fuse carries h / residual / bias / dropout
 template <typename T>
@@ -575,7 +626,7 @@ static lsq_status ln_fwd_dispatch(void* y, float* mean, float* rstd, const void*
                            yp, mean, rstd, xp, gp, bp, rows, hidden, eps);
         return launch_status();
     }
-    const dim3 grid(ln_fwd_blocks(rows, sh.lpr)), block(256);
+    const dim3 grid(ln_fwd_blocks(rows, sh.lpr)), block(sh.lpr > 256 ? sh.lpr : 256);
     const BdrFuse<T> none{};
 #define X(L, V)                                                                                              \
     if (sh.lpr == L && sh.vpl == V) {                                                                        \
@@ -603,8 +654,12 @@ static lsq_status ln_bwd_dispatch(void* dx, float* dgamma, float* dbeta, const v
     if (sh.lpr == 0) {
         const int Pg = ln_bwd_blocks(rows, hidden);
         float* gpartial = static_cast<float*>(workspace);
-        hipLaunchKernelGGL((ln_dparams_generic<T>), dim3(static_cast<unsigned>(ceil_div(hidden, 256)), static_cast<unsigned>(Pg)),
-                           dim3(256), 0, s, gpartial, dyp, xp, mean, rstd, rows, hidden);
+        if (hidden % kPack == 0)
+            hipLaunchKernelGGL((ln_dparams_packed<T>), dim3(static_cast<unsigned>(ceil_div(hidden / kPack, 256)), static_cast<unsigned>(Pg)),
+                               dim3(256), 0, s, gpartial, dyp, xp, mean, rstd, rows, hidden);
+        else
+            hipLaunchKernelGGL((ln_dparams_generic<T>), dim3(static_cast<unsigned>(ceil_div(hidden, 256)), static_cast<unsigned>(Pg)),
+                               dim3(256), 0, s, gpartial, dyp, xp, mean, rstd, rows, hidden);
         launch_colsum_finalize(dgamma, dbeta, hidden, gpartial, Pg, 2 * hidden, s);
         hipLaunchKernelGGL((ln_bwd_generic<T>), dim3(static_cast<unsigned>(ceil_div(rows, 4))), dim3(256), 0, s,
                            dxp, dyp, xp, gp, mean, rstd, rp, rows, hidden);
@@ -612,12 +667,22 @@ static lsq_status ln_bwd_dispatch(void* dx, float* dgamma, float* dbeta, const v
     }
     const int P = ln_bwd_blocks(rows, hidden);
     float* partial = static_cast<float*>(workspace);
+    if (sh.lpr > 256) {       // 8193..16384 columns (never fused: the entry point splits such rows into its two operators)
+        hipLaunchKernelGGL((ln_dparams_packed<T>), dim3(static_cast<unsigned>(ceil_div(hidden / kPack, 256)), static_cast<unsigned>(P)),
+                           dim3(256), 0, s, partial, dyp, xp, mean, rstd, rows, hidden);
+        launch_colsum_finalize(dgamma, dbeta, hidden, partial, P, 2 * hidden, s);
+        const BdrFuse<T> nofuse{};
+        const dim3 wgrid(static_cast<unsigned>(rows < 2048 ? rows : 2048)), wblock(1024);
+        if (rp) hipLaunchKernelGGL((ln_bwd_kernel<T, 1024, 2, true, 1024, false, false, false>), wgrid, wblock, 0, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, nofuse);
+        else hipLaunchKernelGGL((ln_bwd_kernel<T, 1024, 2, false, 1024, false, false, false>), wgrid, wblock, 0, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, nofuse);
+        return launch_status();
+    }
     const int nacc = fuse ? 3 : 2;
-    const size_t one_copy = sh.lpr == 256 ? 0 : sizeof(float) * 8 * nacc * ((hidden / kPack) | 1);
+    const size_t one_copy = sh.lpr >= 256 ? 0 : sizeof(float) * 8 * nacc * ((hidden / kPack) | 1);
     const BdrFuse<T> none{};
 #define X(L, V)                                                                                              \
     if (sh.lpr == L && sh.vpl == V) {                                                                        \
-        constexpr int TH = L == 256 ? 256 : kLnBwdThreads;                                                   \
+        constexpr int TH = L >= 256 ? L : kLnBwdThreads;                                                   \
         const bool par = fuse ? ln_bwd_slots_parallel<L, V, TH, 3>() : ln_bwd_slots_parallel<L, V, TH, 2>(); \
         const size_t shmem = par ? one_copy * (TH / L) : one_copy;                                           \
         const dim3 grid(P), block(TH);                                                                       \
@@ -632,7 +697,7 @@ static lsq_status ln_bwd_dispatch(void* dx, float* dgamma, float* dbeta, const v
             else hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, false, TH, true, false>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, *fuse);   \
         }                                                                                                    \
     }
-    LSQ_LN_CASES(X)
+    LSQ_LN_CASES_BWD(X)
 #undef X
     if (fuse) launch_colsum_finalize(dgamma, dbeta, hidden, partial, P, 3 * hidden, s, dbias, 2 * hidden);
     else launch_colsum_finalize(dgamma, dbeta, hidden, partial, P, 2 * hidden, s);
@@ -758,7 +823,7 @@ extern "C" lsq_status lsq_bdr_layernorm_bwd(void* dh, void* dx, float* dgamma, f
     LSQ_REQUIRE(ceil_div(rows * hidden, 256) <= 0x7FFFFFFF);
     const size_t need = lsq_workspace_bytes(LSQ_OP_BDR_LAYERNORM_BWD, rows, hidden);
     if (need && (!workspace || workspace_bytes < need)) return LSQ_WORKSPACE_TOO_SMALL;
-    if (ln_shape(hidden).lpr == 0) {
+    if (ln_shape(hidden).lpr == 0 || ln_shape(hidden).lpr > 256) {      // no fused bucket: the two operators back to back
         const lsq_status st = lsq_layernorm_bwd(dh, dgamma, dbeta, dy, h, gamma, mean, rstd, dres_in, workspace,
                                                 workspace_bytes, rows, hidden, dt, stream);
         return st != LSQ_OK ? st : lsq_bias_dropout_residual_bwd(dx, dbias, dh, rows, hidden, p, seed, offset, workspace,
