@@ -68,3 +68,29 @@ def test_embedding_fwd_bwd(B, Ln, V, H, p, dt):
     demb2 = to_torch(d0, dt, d)
     L.lsq_embedding_bwd(demb2, None, dy, tokens, PAD, scale, p, seed, offset)
     assert torch.equal(demb, demb2)
+
+
+@pytest.mark.parametrize("kind", ["all padding", "one id everywhere", "all distinct"])
+def test_embedding_bwd_degenerate_batches(kind):
+    """Batches at the ends of the id distribution: nothing to accumulate, one segment that spans every window of the
+    sorted order, and no repeated id at all."""
+    say(f"[embedding] degenerate batch: {kind}")
+    d, dt = dev(), "f16"
+    B, Ln, V, H = 7, 41, 400, 64                   # 287 tokens: a ragged last rank tile and a ragged last window
+    rng = np.random.default_rng(17)
+    if kind == "all padding":
+        tok = np.full((B, Ln), PAD, np.int32)
+    elif kind == "one id everywhere":
+        tok = np.full((B, Ln), 9, np.int32)
+    else:
+        tok = (rng.permutation(V - 2)[:B * Ln] + 2).astype(np.int32).reshape(B, Ln)
+    dys = encode(rng.standard_normal((B * Ln, H), dtype=np.float32), dt)
+    d0 = encode(rng.standard_normal((V, H), dtype=np.float32) * 0.1, dt)
+    p0 = encode(rng.standard_normal((Ln, H), dtype=np.float32) * 0.1, dt)
+    demb, dpos = to_torch(d0, dt, d), to_torch(p0, dt, d)
+    L.lsq_embedding_bwd(demb, dpos, to_torch(dys, dt, d), torch.from_numpy(tok).to(d), PAD, 8.0, 0.1, 5, 2)
+    inc_e, inc_p = oracle.embedding_bwd(dys, tok, V, PAD, 8.0, 0.1, 5, 2, dt)
+    assert_close_store(demb, decode(d0, dt) + inc_e, dt, "demb", f32_floor=1e-3)
+    assert_close_store(dpos, decode(p0, dt) + inc_p, dt, "dpos", f32_floor=1e-4)
+    if kind == "all padding":
+        assert np.array_equal(from_torch(demb, dt), d0) and np.array_equal(from_torch(dpos, dt), p0)

@@ -147,3 +147,16 @@ def test_ls_xent_full_size(ci, dt):
     del ref, err
     L.lsq_ls_xent_fwd_bwd(logits, target, cfg.alpha, IGNORE_INDEX, gs, dlogits=logits)
     assert torch.equal(logits, fdl)
+
+
+def test_ls_xent_every_token_ignored():
+    say("[ls_xent] a batch whose every token is ignored: zeros everywhere, count 0, nothing read")
+    d, dt = dev(), "bf16"
+    T, V = 37, 1003
+    logits = torch.full((T, V), float("nan"), dtype=torch.bfloat16, device=d)      # must not be looked at
+    target = torch.full((T,), IGNORE_INDEX, dtype=torch.int32, device=d)
+    loss, nll, lse, sums = L.lsq_ls_xent_fwd(logits, target, 0.1, IGNORE_INDEX)
+    dl = L.lsq_ls_xent_bwd(logits, lse, target, 0.1, IGNORE_INDEX, 1.0)
+    floss, fnll, flse, fsums, fdl = L.lsq_ls_xent_fwd_bwd(logits, target, 0.1, IGNORE_INDEX, 1.0)
+    for t in (loss, nll, lse, sums, dl, floss, fnll, flse, fsums, fdl):
+        assert not t.float().ne(0).any()
