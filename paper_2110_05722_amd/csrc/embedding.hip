@@ -8,7 +8,8 @@
 //   1. rank: every token's position in the order sorted by (token id, position) is
 //      COUNTED — tile against tile, 256 x 256 comparisons per workgroup out of LDS, one
 //      compare per pair — rather than sorted: counting is order-free, so the result is
-//      deterministic;
+//      deterministic; beyond 16384 tokens (counting is quadratic) a stable radix sort of
+//      (position, id) by id produces the same order;
 //   2. scatter: order[rank[t]] = (t, id);
 //   3. accumulate: the sorted order is cut into windows of 8 entries; one wave per (window,
 //      64-pack column block) sums m (.) dy in ascending position in fp32, the eight rows and
@@ -142,6 +143,135 @@ __global__ __launch_bounds__(256) void emb_scatter(int2* __restrict__ order, con
     if (part == 0 && t < rows) {
         rank += sm[0][threadIdx.x] + sm[1][threadIdx.x] + sm[2][threadIdx.x];
         order[rank] = make_int2(static_cast<int>(t), static_cast<int>(emb_key(tokens[t], vocab, pad_idx)));
+    }
+}
+
+// ---- the same order for MANY tokens.  Counting pairs is quadratic in the tokens of a call (10 us at
+// 8192, 270 us at 65536); beyond 16384 tokens the (token, key) pairs go through a stable
+// least-significant-digit radix sort instead, 8 bits per pass over the bits an id can have (two
+// passes up to 65535 ids): a stable sort by key leaves equal ids in ascending position, which is the
+// order the accumulation wants.  A workgroup owns 2048 consecutive entries, striped over its 256
+// threads (entry j*256 + i is item j of thread i), so that "round j, wave w, lane l" is ascending
+// position.  Per pass: digit histogram per workgroup (integer LDS atomics: the counts do not depend
+// on arrival order), exclusive scan of the [digit][workgroup] table (its own kernel only for very
+// many workgroups), and the scatter, which hands out slots in position order: the lanes of a wave that hold the same digit find
+// each other with 8 ballots, and the four waves take their turns on the running LDS counters.
+constexpr int kRadixItems = 8;
+constexpr int kRadixBlock = 256 * kRadixItems;
+constexpr int kRadixFuseScan = 512;       // up to this many workgroups (2^20 tokens) the scatter scans its own offsets
+
+__device__ __forceinline__ int2 radix_item(const int2* __restrict__ src, const int32_t* __restrict__ tokens, int64_t i,
+                                           int vocab, int pad_idx)
+{
+    if (src) return src[i];
+    return make_int2(static_cast<int>(i), static_cast<int>(emb_key(tokens[i], vocab, pad_idx)));   // first pass: the ids themselves
+}
+
+__global__ __launch_bounds__(256) void emb_radix_hist(int32_t* __restrict__ hist, const int2* __restrict__ src,
+                                                      const int32_t* __restrict__ tokens, int64_t rows, int nblocks,
+                                                      int shift, int vocab, int pad_idx)
+{
+    __shared__ int cnt[256];
+    cnt[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t base = static_cast<int64_t>(blockIdx.x) * kRadixBlock;
+#pragma unroll
+    for (int j = 0; j < kRadixItems; ++j) {
+        const int64_t i = base + j * 256 + threadIdx.x;
+        if (i < rows) atomicAdd(&cnt[(radix_item(src, tokens, i, vocab, pad_idx).y >> shift) & 255], 1);
+    }
+    __syncthreads();
+    hist[static_cast<int64_t>(threadIdx.x) * nblocks + blockIdx.x] = cnt[threadIdx.x];      // digit-major
+}
+
+// exclusive scan of n counts in place, one workgroup: every thread owns a contiguous piece
+__global__ __launch_bounds__(1024) void emb_radix_scan(int32_t* __restrict__ hist, int64_t n)
+{
+    __shared__ int wave_sum[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t per = (n + 1023) / 1024;
+    const int64_t lo = min(n, tid * per), hi = min(n, lo + per);
+    int sum = 0;
+    for (int64_t i = lo; i < hi; ++i) sum += hist[i];
+    int incl = sum;                                              // inclusive scan over the wave
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int v = __shfl_up(incl, o);
+        if (lane >= o) incl += v;
+    }
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    int before = incl - sum;
+    for (int w = 0; w < wave; ++w) before += wave_sum[w];
+    for (int64_t i = lo; i < hi; ++i) {
+        const int c = hist[i];
+        hist[i] = before;
+        before += c;
+    }
+}
+
+// SCANNED: `offs` went through emb_radix_scan.  Otherwise it holds the raw counts and the workgroup
+// derives its own 256 offsets: thread = digit adds up its row of the table (all of it, and the part
+// before this workgroup), and an exclusive scan over the 256 row sums finishes it; one launch less per
+// pass, worth it while a row of the table is short.
+template <bool SCANNED>
+__global__ __launch_bounds__(256) void emb_radix_scatter(int2* __restrict__ dst, const int32_t* __restrict__ offs,
+                                                         const int2* __restrict__ src, const int32_t* __restrict__ tokens,
+                                                         int64_t rows, int nblocks, int shift, int vocab, int pad_idx)
+{
+    __shared__ int next[256];                  // next slot of each digit, for this workgroup's entries
+    __shared__ int wave_sum[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if constexpr (SCANNED) {
+        next[tid] = offs[static_cast<int64_t>(tid) * nblocks + blockIdx.x];
+    } else {
+        const int32_t* row = offs + static_cast<int64_t>(tid) * nblocks;
+        int total = 0, mine = 0;
+        const int me = blockIdx.x;
+#pragma unroll 8
+        for (int b = 0; b < nblocks; ++b) {
+            const int c = row[b];
+            total += c;
+            mine += b < me ? c : 0;
+        }
+        int incl = total;                                        // inclusive scan of the row sums over the wave
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int v = __shfl_up(incl, o);
+            if (lane >= o) incl += v;
+        }
+        if (lane == 63) wave_sum[wave] = incl;
+        __syncthreads();
+        int before = incl - total;
+        for (int w = 0; w < wave; ++w) before += wave_sum[w];
+        next[tid] = before + mine;
+    }
+    __syncthreads();
+    const int64_t base = static_cast<int64_t>(blockIdx.x) * kRadixBlock;
+    for (int j = 0; j < kRadixItems; ++j) {                      // uniform trip count: every thread reaches every barrier
+        const int64_t i = base + j * 256 + tid;
+        const bool valid = i < rows;
+        const int2 item = valid ? radix_item(src, tokens, i, vocab, pad_idx) : make_int2(0, 0);
+        const int digit = (item.y >> shift) & 255;
+        uint64_t same = __ballot(valid);                         // lanes of this wave with my digit
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const uint64_t has = __ballot((digit >> b) & 1);
+            same &= ((digit >> b) & 1) ? has : ~has;
+        }
+        if (!valid) same = 0;
+        const int below = __popcll(same & ((1ull << lane) - 1ull));
+        const int leader = same ? __builtin_ctzll(same) : lane;
+        int slot = 0;
+        for (int w = 0; w < 4; ++w) {                            // waves in order: ascending position
+            if (wave == w && valid && lane == leader) {          // one lane per digit present in the wave
+                slot = next[digit];
+                next[digit] = slot + __popcll(same);
+            }
+            __syncthreads();
+        }
+        slot = __shfl(slot, leader);
+        if (valid) dst[slot + below] = item;
     }
 }
 
@@ -508,23 +638,51 @@ static lsq_status emb_bwd_dispatch(void* demb, void* dpos, const void* dy, const
     T* dp = static_cast<T*>(dpos);
     const T* g = static_cast<const T*>(dy);
     // the dropout scale 1/(1-p) is carried by the per-element factors; `scale` is the embedding scale
-    const unsigned rank_blocks = static_cast<unsigned>(plan.ntiles) * static_cast<unsigned>(plan.nspans);
     const bool packed = hidden % kPack == 0;
     const int ppr = hidden / kPack;
     const int ncb = static_cast<int>(ceil_div(ppr, 64));
-    if (packed && dp) {
-        // the position gradient rides along with the rank count
-        const dim3 rgrid(rank_blocks + static_cast<unsigned>(ncb) * static_cast<unsigned>(len));
-        if (d.t16) hipLaunchKernelGGL((emb_rank_dpos<T, true>), rgrid, dim3(256), 0, s, partial, tokens, rows, plan.ntiles, plan.span_tiles,
-                                      static_cast<int>(rank_blocks), dp, g, batch, len, ppr, ncb, vocab, pad_idx, d);
-        else hipLaunchKernelGGL((emb_rank_dpos<T, false>), rgrid, dim3(256), 0, s, partial, tokens, rows, plan.ntiles, plan.span_tiles,
-                                static_cast<int>(rank_blocks), dp, g, batch, len, ppr, ncb, vocab, pad_idx, d);
+    if (rows <= kEmbCountMax) {
+        // few tokens: order[rank of t] = (t, key), the rank counted pair by pair
+        const unsigned rank_blocks = static_cast<unsigned>(plan.ntiles) * static_cast<unsigned>(plan.nspans);
+        if (packed && dp) {
+            // the position gradient rides along with the rank count
+            const dim3 rgrid(rank_blocks + static_cast<unsigned>(ncb) * static_cast<unsigned>(len));
+            if (d.t16) hipLaunchKernelGGL((emb_rank_dpos<T, true>), rgrid, dim3(256), 0, s, partial, tokens, rows, plan.ntiles, plan.span_tiles,
+                                          static_cast<int>(rank_blocks), dp, g, batch, len, ppr, ncb, vocab, pad_idx, d);
+            else hipLaunchKernelGGL((emb_rank_dpos<T, false>), rgrid, dim3(256), 0, s, partial, tokens, rows, plan.ntiles, plan.span_tiles,
+                                    static_cast<int>(rank_blocks), dp, g, batch, len, ppr, ncb, vocab, pad_idx, d);
+        } else {
+            hipLaunchKernelGGL(emb_rank_partial, dim3(rank_blocks), dim3(kTile), 0, s, partial, tokens, rows, plan.ntiles,
+                               plan.span_tiles, vocab, pad_idx);
+        }
+        hipLaunchKernelGGL(emb_scatter, dim3(static_cast<unsigned>(ceil_div(rows, 64))), dim3(256), 0, s, order, partial,
+                           tokens, rows, plan.nspans, vocab, pad_idx);
     } else {
-        hipLaunchKernelGGL(emb_rank_partial, dim3(rank_blocks), dim3(kTile), 0, s, partial, tokens, rows, plan.ntiles,
-                           plan.span_tiles, vocab, pad_idx);
+        // many tokens: stable radix sort of (t, key) by the bits an id can have; padding (all ones) comes last
+        int bits = 1;
+        while ((static_cast<int64_t>(1) << bits) <= vocab) ++bits;                 // 2^bits > vocab
+        const int passes = (bits + 7) / 8;
+        const int nblocks = plan.radix_blocks;
+        int32_t* hist = partial;                                                     // [256][nblocks]
+        int2* tmp = reinterpret_cast<int2*>(reinterpret_cast<char*>(partial) + plan.radix_hist_bytes);
+        const int2* src = nullptr;
+        for (int pass = 0; pass < passes; ++pass) {
+            int2* dst = (passes - pass) % 2 == 1 ? order : tmp;                      // the last pass lands in `order`
+            hipLaunchKernelGGL(emb_radix_hist, dim3(nblocks), dim3(256), 0, s, hist, src, tokens, rows, nblocks, 8 * pass, vocab, pad_idx);
+            if (nblocks <= kRadixFuseScan) {
+                hipLaunchKernelGGL((emb_radix_scatter<false>), dim3(nblocks), dim3(256), 0, s, dst, hist, src, tokens, rows, nblocks, 8 * pass, vocab, pad_idx);
+            } else {
+                hipLaunchKernelGGL(emb_radix_scan, dim3(1), dim3(1024), 0, s, hist, static_cast<int64_t>(256) * nblocks);
+                hipLaunchKernelGGL((emb_radix_scatter<true>), dim3(nblocks), dim3(256), 0, s, dst, hist, src, tokens, rows, nblocks, 8 * pass, vocab, pad_idx);
+            }
+            src = dst;
+        }
+        if (packed && dp) {            // the position gradient on its own (no rank workgroups in the launch)
+            const dim3 rgrid(static_cast<unsigned>(ncb) * static_cast<unsigned>(len));
+            if (d.t16) hipLaunchKernelGGL((emb_rank_dpos<T, true>), rgrid, dim3(256), 0, s, partial, tokens, rows, 1, 1, 0, dp, g, batch, len, ppr, ncb, vocab, pad_idx, d);
+            else hipLaunchKernelGGL((emb_rank_dpos<T, false>), rgrid, dim3(256), 0, s, partial, tokens, rows, 1, 1, 0, dp, g, batch, len, ppr, ncb, vocab, pad_idx, d);
+        }
     }
-    hipLaunchKernelGGL(emb_scatter, dim3(static_cast<unsigned>(ceil_div(rows, 64))), dim3(256), 0, s, order, partial,
-                       tokens, rows, plan.nspans, vocab, pad_idx);
     if (packed) {
         const unsigned pairs = static_cast<unsigned>(plan.nwin * ncb);      // (window, column block) pairs
         const dim3 grid(static_cast<unsigned>(ceil_div(pairs, 4))), block(256);   // one wave per pair

@@ -137,14 +137,17 @@ inline int bdr_bwd_row_blocks(int64_t rows, int32_t /*hidden*/)
 //   window rows [2 * windows][hidden rounded up to 8] fp32: the partial sums of id segments
 //          that cross a window of kEmbWin sorted entries (at most two per window)
 //   rank counts [spans][rows] int32: token i against the tokens of span js (a span is a run
-//          of 256-token tiles, at most 64 spans)
+//          of 256-token tiles, at most 64 spans); beyond kEmbCountMax tokens the same region holds
+//          the radix sort's [256][workgroups] digit counts and its second (token, key) buffer
 constexpr int kEmbTile = 256;
+constexpr int64_t kEmbCountMax = 16384;
 #ifndef LSQ_EMB_WIN
 #define LSQ_EMB_WIN 8
 #endif
 constexpr int kEmbWin = LSQ_EMB_WIN;
 struct EmbBwdPlan {
-    int ntiles, span_tiles, nspans;
+    int ntiles, span_tiles, nspans, radix_blocks;
+    size_t radix_hist_bytes;
     int64_t nwin;
     size_t order_bytes, win_bytes, rank_bytes;
     size_t total() const { return order_bytes + win_bytes + rank_bytes; }
@@ -160,6 +163,9 @@ inline EmbBwdPlan emb_bwd_plan(int64_t rows, int32_t hidden)
     p.order_bytes = (static_cast<size_t>(rows) * 8u + 15u) / 16u * 16u;
     p.win_bytes = 2u * static_cast<size_t>(p.nwin) * colsp * sizeof(float);
     p.rank_bytes = static_cast<size_t>(p.nspans) * static_cast<size_t>(rows) * sizeof(int32_t);
+    p.radix_blocks = static_cast<int>(ceil_div(rows, 2048));
+    p.radix_hist_bytes = (static_cast<size_t>(256) * static_cast<size_t>(p.radix_blocks) * sizeof(int32_t) + 15u) / 16u * 16u;
+    if (rows > kEmbCountMax) p.rank_bytes = p.radix_hist_bytes + static_cast<size_t>(rows) * 8u;
     return p;
 }
 

@@ -15,7 +15,10 @@ PAD = 1
 CASES = [(8, 64, 8000, 512, 0.1), (128, 32, 32768, 512, 0.1), (16, 128, 4096, 1024, 0.3), (4, 512, 30522, 1024, 0.1),
          (2, 1024, 50257, 1280, 0.1), (3, 50, 97, 768, 0.0), (5, 7, 11, 8, 0.25), (2, 9, 13, 257, 0.2), (1, 1, 3, 64, 0.1),
          (4, 300, 5, 64, 0.1),
-         (40, 520, 1000, 64, 0.1)]      # more than 64 rank tiles: several tiles per span
+         (40, 520, 1000, 64, 0.1),      # beyond 16384 tokens: the radix-sorted order, two passes
+         (36, 512, 100, 16, 0.1), (9, 2048, 70001, 16, 0.1),      # one pass (ids below 256) and three (above 65535)
+         (550, 2000, 3000, 8, 0.1),     # 1.1 M tokens: the radix passes with the stand-alone offset scan
+         (4, 4096, 50257, 8, 0.0)]      # exactly 16384 tokens: the last size whose ranks are counted, 64 one-tile spans
 
 
 def _tokens(B, Ln, V, rng):
