@@ -379,8 +379,7 @@ lsq_status lsq_embedding_fwd(void* out, const int32_t* tokens, const void* emb, 
  * demb [vocab, hidden] and dpos [len, hidden] are dt and are ACCUMULATED INTO (one
  * rounding per row and call; rows of tokens that do not occur are not touched).
  * Padding tokens receive nothing.  workspace: >= lsq_workspace_bytes(
- * LSQ_OP_EMBEDDING_BWD, batch*len, hidden) bytes.  Errors: batch*len beyond 2^30,
- * len > 65535 with dpos != NULL. */
+ * LSQ_OP_EMBEDDING_BWD, batch*len, hidden) bytes.  Errors: batch*len beyond 2^30. */
 lsq_status lsq_embedding_bwd(void* demb, void* dpos, const void* dy, const int32_t* tokens,
                              int32_t batch, int32_t len, int32_t hidden, int32_t vocab, int32_t pad_idx,
                              float scale, float p, uint64_t seed, uint64_t offset,

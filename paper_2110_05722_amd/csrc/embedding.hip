@@ -734,10 +734,9 @@ extern "C" lsq_status lsq_embedding_bwd(void* demb, void* dpos, const void* dy, 
     LSQ_REQUIRE(make_dropout(p, seed, offset, &d));
     const int64_t rows = static_cast<int64_t>(batch) * len;
     if (rows == 0) return LSQ_OK;
-    LSQ_REQUIRE(rows <= 0x7FFFFFFF / 2 && ceil_div(rows, kTile) <= 65535);
+    LSQ_REQUIRE(rows <= 0x7FFFFFFF / 2);
     LSQ_REQUIRE(ceil_div(rows, kEmbWin) * ceil_div(hidden, 8 * 64) < 0x7FFFFFFF);   // one workgroup per (window, column block)
     LSQ_REQUIRE(ceil_div(rows, kTile) * 64 + ceil_div(hidden, 8 * 64) * static_cast<int64_t>(len) < 0x7FFFFFFF);
-    LSQ_REQUIRE(!dpos || len <= 65535);       // one grid row per position
     LSQ_REQUIRE(demb && dy && tokens);
     LSQ_ALIGNED(demb); LSQ_ALIGNED(dpos); LSQ_ALIGNED(dy); LSQ_ALIGNED(workspace);
     const size_t need = lsq_workspace_bytes(LSQ_OP_EMBEDDING_BWD, rows, hidden);

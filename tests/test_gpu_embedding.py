@@ -18,6 +18,7 @@ CASES = [(8, 64, 8000, 512, 0.1), (128, 32, 32768, 512, 0.1), (16, 128, 4096, 10
          (40, 520, 1000, 64, 0.1),      # beyond 16384 tokens: the radix-sorted order, two passes
          (36, 512, 100, 16, 0.1), (9, 2048, 70001, 16, 0.1),      # one pass (ids below 256) and three (above 65535)
          (550, 2000, 3000, 8, 0.1),     # 1.1 M tokens: the radix passes with the stand-alone offset scan
+         (1, 70000, 500, 8, 0.1),       # one sentence longer than 65535 positions
          (4, 4096, 50257, 8, 0.0)]      # exactly 16384 tokens: the last size whose ranks are counted, 64 one-tile spans
 
 
