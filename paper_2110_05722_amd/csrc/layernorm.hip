@@ -198,9 +198,11 @@ constexpr bool ln_bwd_slots_parallel()
 // stored (the residual branch's gradient), then masked and scaled from its STORED value into
 // fz.out (the projection's gradient), whose column sums (dbias) join dgamma/dbeta as a third
 // partial row.  Equal to LayerNorm backward followed by bias+dropout+residual backward, one pass.
-// COLS = false: dx only (rows wider than 8192 columns, one 1024-thread workgroup per row: the
-// column accumulators would not fit the 128 registers a thread has there, so dgamma/dbeta come
-// from the two-stage column kernel instead, which reads dy and x once more).
+// Rows wider than 8192 columns take one 1024-thread workgroup per row, which leaves a thread 128
+// registers: too few for the row, its prefetched successor and the column accumulators.  There the
+// accumulators live in LDS instead, each thread reading and writing only its own columns' entries
+// (131 KB for 16384 columns: no barrier, no conflict, and the LDS traffic hides behind the row
+// stream).  COLS = false computes dx only.
 template <typename T, int LPR, int VPL, bool HAS_RES, int THREADS, bool FUSE = false, bool DROP = false, bool COLS = true>
 __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restrict__ partial, const T* dy,
                                                          const T* __restrict__ x, const T* __restrict__ gamma,
@@ -208,7 +210,8 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
                                                          const T* dres, int64_t rows, int hidden, BdrFuse<T> fz)
 {
     constexpr int NACC = FUSE ? 3 : 2;        // column accumulators: dgamma, dbeta (, dbias)
-    extern __shared__ float colbuf[];         // [NACC][8][packs | 1] when LPR < 256
+    constexpr bool kColsInRegs = COLS && LPR <= 256, kColsInLds = COLS && LPR > 256;
+    extern __shared__ float colbuf[];         // [NACC][8][packs | 1]: the slots' exchange when LPR < 256, the accumulators themselves when LPR > 256
     __shared__ float lds[16];
     static_assert(LPR < 256 || THREADS == LPR, "a whole-workgroup row takes the whole workgroup");
     static_assert(COLS || !FUSE, "the fused boundary needs the column sums");
@@ -231,6 +234,18 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
         for (int k = 0; k < VPL; ++k)
 #pragma unroll
             for (int j = 0; j < 8; ++j) dbi[k][j] = 0.0f;
+    }
+
+    const int cstride = nv | 1;               // odd: consecutive lanes fall in consecutive banks
+    if constexpr (kColsInLds) {
+#pragma unroll
+        for (int k = 0; k < VPL; ++k) {
+            const int idx = sub + k * LPR;
+            if (idx < nv) {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) colbuf[j * cstride + idx] = 0.0f;
+            }
+        }
     }
 
     int64_t base = static_cast<int64_t>(blockIdx.x) * RPB;
@@ -284,9 +299,15 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const float xhat = fmaf(xv[j], rs, nmr);
-                if constexpr (COLS) {
+                if constexpr (kColsInRegs) {
                     dg[k][j] = fmaf(gy[j], xhat, dg[k][j]);
                     db[k][j] += gy[j];
+                } else if constexpr (kColsInLds) {
+                    if (sub + k * LPR < nv) {              // rows that do not exist hold dy = 0 and add nothing
+                        float* a = colbuf + j * cstride + (sub + k * LPR);
+                        a[0] = fmaf(gy[j], xhat, a[0]);
+                        a[8 * cstride] += gy[j];
+                    }
                 }
                 const float gg = gy[j] * g8[j];
                 s1 += gg;
@@ -361,7 +382,19 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
 
     if constexpr (!COLS) return;
     float* prow = partial + static_cast<int64_t>(blockIdx.x) * NACC * hidden;
-    if constexpr (LPR >= 256) {               // every thread owns its columns: nothing to combine
+    if constexpr (kColsInLds) {
+#pragma unroll
+        for (int k = 0; k < VPL; ++k) {
+            const int idx = sub + k * LPR;
+            if (idx < nv) {
+                float a[8], b[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) { a[j] = colbuf[j * cstride + idx]; b[j] = colbuf[(8 + j) * cstride + idx]; }
+                store8<float>(prow + idx * kPack, a);
+                store8<float>(prow + hidden + idx * kPack, b);
+            }
+        }
+    } else if constexpr (LPR >= 256) {        // every thread owns its columns: nothing to combine
 #pragma unroll
         for (int k = 0; k < VPL; ++k) {
             const int idx = sub + k * LPR;
@@ -668,13 +701,23 @@ static lsq_status ln_bwd_dispatch(void* dx, float* dgamma, float* dbeta, const v
     const int P = ln_bwd_blocks(rows, hidden);
     float* partial = static_cast<float*>(workspace);
     if (sh.lpr > 256) {       // 8193..16384 columns (never fused: the entry point splits such rows into its two operators)
-        hipLaunchKernelGGL((ln_dparams_packed<T>), dim3(static_cast<unsigned>(ceil_div(hidden / kPack, 256)), static_cast<unsigned>(P)),
-                           dim3(256), 0, s, partial, dyp, xp, mean, rstd, rows, hidden);
-        launch_colsum_finalize(dgamma, dbeta, hidden, partial, P, 2 * hidden, s);
         const BdrFuse<T> nofuse{};
-        const dim3 wgrid(static_cast<unsigned>(rows < 2048 ? rows : 2048)), wblock(1024);
-        if (rp) hipLaunchKernelGGL((ln_bwd_kernel<T, 1024, 2, true, 1024, false, false, false>), wgrid, wblock, 0, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, nofuse);
-        else hipLaunchKernelGGL((ln_bwd_kernel<T, 1024, 2, false, 1024, false, false, false>), wgrid, wblock, 0, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, nofuse);
+        const size_t shmem = sizeof(float) * 16 * ((hidden / kPack) | 1);          // beyond the 64 KiB a kernel gets by default
+        const void* fn = rp ? reinterpret_cast<const void*>(&ln_bwd_kernel<T, 1024, 2, true, 1024, false, false, true>)
+                            : reinterpret_cast<const void*>(&ln_bwd_kernel<T, 1024, 2, false, 1024, false, false, true>);
+        static bool ready[2][64] = {};        // per residual variant and device: the attribute is set once
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return LSQ_LAUNCH_FAILED;
+        const bool known = dev >= 0 && dev < 64;
+        if (!known || !ready[rp ? 1 : 0][dev]) {
+            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) != hipSuccess)
+                return LSQ_LAUNCH_FAILED;
+            if (known) ready[rp ? 1 : 0][dev] = true;
+        }
+        const dim3 wgrid(P), wblock(1024);
+        if (rp) hipLaunchKernelGGL((ln_bwd_kernel<T, 1024, 2, true, 1024, false, false, true>), wgrid, wblock, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, nofuse);
+        else hipLaunchKernelGGL((ln_bwd_kernel<T, 1024, 2, false, 1024, false, false, true>), wgrid, wblock, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, nofuse);
+        launch_colsum_finalize(dgamma, dbeta, hidden, partial, P, 2 * hidden, s);
         return launch_status();
     }
     const int nacc = fuse ? 3 : 2;

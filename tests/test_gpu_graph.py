@@ -113,7 +113,14 @@ def test_newer_entry_points_replay_under_a_hip_graph():
     demb, dpos = demb0.clone(), dpos0.clone()
     ews = torch.empty(L.lsq_workspace_bytes(4, T, H), dtype=torch.uint8, device=d)
 
+    wx, wdy, wg, wb = rn(5, 8200), rn(5, 8200), rn(8200), rn(8200)      # rows wider than 8192: the 1024-lane bucket
+    wy, wdx, wmean, wrstd = torch.empty_like(wx), torch.empty_like(wx), torch.empty(5, device=d), torch.empty(5, device=d)
+    wdg, wdb = torch.empty(8200, device=d), torch.empty(8200, device=d)
+    wws = torch.empty(L.lsq_workspace_bytes(0, 5, 8200), dtype=torch.uint8, device=d)
+
     def run():
+        L.lsq_layernorm_fwd(wx, wg, wb, y=wy, mean=wmean, rstd=wrstd)
+        L.lsq_layernorm_bwd(wdy, wx, wg, wmean, wrstd, dx=wdx, dgamma=wdg, dbeta=wdb, workspace=wws)
         L.lsq_ls_xent_fwd_bwd(logits, target, 0.1, -100, 0.25, loss=xl, nll=xn, lse=xe, sums=xs, dlogits=dlog)
         L.lsq_embedding_bwd(demb, dpos, dy, tokens, 1, 2.0, 0.1, 9, 3, workspace=ews)
         L.lsq_pad_offsets(lens, B, Ln, offsets=offsets)
@@ -127,7 +134,7 @@ def test_newer_entry_points_replay_under_a_hip_graph():
         L.lsq_adam_step_blocked(state, gr, p_lp, step=2, **HY)
         L.lsq_sgd_step_blocked(sgd, gr, None, lr=0.1, momentum=0.9)
 
-    outputs = (offsets, packed, padded, h, y, mean, rstd, dh, dxp, dgm, dbt, dbi, sy, syd, sdx, xl, xn, xe, xs, dlog,
+    outputs = (wy, wdx, wmean, wrstd, wdg, wdb, offsets, packed, padded, h, y, mean, rstd, dh, dxp, dgm, dbt, dbi, sy, syd, sdx, xl, xn, xe, xs, dlog,
                demb, dpos, state, sgd, p_lp)
 
     def reset_state():
