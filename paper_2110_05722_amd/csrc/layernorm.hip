@@ -610,6 +610,11 @@ __global__ __launch_bounds__(256) void ln_dparams_packed(float* __restrict__ par
     store8<float>(prow + hidden + idx * kPack, sb);
 }
 
+#ifndef LSQ_LN_WIDE_LPR
+#define LSQ_LN_WIDE_LPR 1024
+#endif
+constexpr int kLnWideLpr = LSQ_LN_WIDE_LPR, kLnWideVpl = 2048 / LSQ_LN_WIDE_LPR;      // the bucket of rows with 1025..2048 packs
+
 // ------------------------------------------------------------------ dispatch
 // Shape buckets: lanes per row and packs per lane for a row of nv packs.
 struct LnShape { int lpr, vpl; };
@@ -627,7 +632,7 @@ inline LnShape ln_shape(int hidden)
     if (nv <= 256) return {64, 4};
     if (nv <= 512) return {256, 2};
     if (nv <= 1024) return {256, 4};
-    if (nv <= 2048) return {1024, 2};     // hidden up to 16384: one 1024-thread workgroup per row
+    if (nv <= 2048) return {kLnWideLpr, kLnWideVpl};     // hidden up to 16384: one large workgroup per row
     return {0, 0};
 }
 
@@ -641,7 +646,7 @@ inline int ln_fwd_blocks(int64_t rows, int lpr)
 }
 
 #define LSQ_LN_CASES_BWD(X) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 3) X(64, 4) X(256, 2) X(256, 4)
-#define LSQ_LN_CASES(X) LSQ_LN_CASES_BWD(X) X(1024, 2)
+#define LSQ_LN_CASES(X) LSQ_LN_CASES_BWD(X) X(kLnWideLpr, kLnWideVpl)
 
 // fuse != nullptr: x is the projection output and *fuse carries h / residual / bias / dropout
 template <typename T>
@@ -703,8 +708,8 @@ static lsq_status ln_bwd_dispatch(void* dx, float* dgamma, float* dbeta, const v
     if (sh.lpr > 256) {       // 8193..16384 columns (never fused: the entry point splits such rows into its two operators)
         const BdrFuse<T> nofuse{};
         const size_t shmem = sizeof(float) * 16 * ((hidden / kPack) | 1);          // beyond the 64 KiB a kernel gets by default
-        const void* fn = rp ? reinterpret_cast<const void*>(&ln_bwd_kernel<T, 1024, 2, true, 1024, false, false, true>)
-                            : reinterpret_cast<const void*>(&ln_bwd_kernel<T, 1024, 2, false, 1024, false, false, true>);
+        const void* fn = rp ? reinterpret_cast<const void*>(&ln_bwd_kernel<T, kLnWideLpr, kLnWideVpl, true, kLnWideLpr, false, false, true>)
+                            : reinterpret_cast<const void*>(&ln_bwd_kernel<T, kLnWideLpr, kLnWideVpl, false, kLnWideLpr, false, false, true>);
         static bool ready[2][64] = {};        // per residual variant and device: the attribute is set once
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess) return LSQ_LAUNCH_FAILED;
@@ -714,9 +719,9 @@ static lsq_status ln_bwd_dispatch(void* dx, float* dgamma, float* dbeta, const v
                 return LSQ_LAUNCH_FAILED;
             if (known) ready[rp ? 1 : 0][dev] = true;
         }
-        const dim3 wgrid(P), wblock(1024);
-        if (rp) hipLaunchKernelGGL((ln_bwd_kernel<T, 1024, 2, true, 1024, false, false, true>), wgrid, wblock, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, nofuse);
-        else hipLaunchKernelGGL((ln_bwd_kernel<T, 1024, 2, false, 1024, false, false, true>), wgrid, wblock, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, nofuse);
+        const dim3 wgrid(P), wblock(kLnWideLpr);
+        if (rp) hipLaunchKernelGGL((ln_bwd_kernel<T, kLnWideLpr, kLnWideVpl, true, kLnWideLpr, false, false, true>), wgrid, wblock, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, nofuse);
+        else hipLaunchKernelGGL((ln_bwd_kernel<T, kLnWideLpr, kLnWideVpl, false, kLnWideLpr, false, false, true>), wgrid, wblock, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, nofuse);
         launch_colsum_finalize(dgamma, dbeta, hidden, partial, P, 2 * hidden, s);
         return launch_status();
     }
