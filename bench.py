@@ -55,7 +55,127 @@ def parse():
     ap.add_argument("--skip-ops", default="", help="comma-separated operators left out of the per-op table "
                     "(profiling runs: rows that reuse a kernel at another size would blur its per-kernel average)")
     ap.add_argument("--ops", default="", help="comma-separated subset of operators (tuning runs; the default is all nine)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the JSON line: tables of operator time over tensor sizes (tokens x hidden, sequence "
+                         "length, vocabulary, parameter count), the way the paper evaluates its kernels one by one")
     return ap.parse_args()
+
+
+def sweep(args):
+    """Per-operator time and fraction of the HBM peak (algorithmic bytes) over sizes, fp16 or bf16 storage, cold
+    buffers, launches replayed from a HIP graph.  Prints markdown tables; not part of the JSON contract."""
+    import torch
+
+    import paper_2110_05722_amd as L
+    from workloads import ADAM_HYPER, device_normal, torch_dtype
+
+    L.load()
+    dev, dt, tdt = torch.device("cuda:0"), args.dtype, torch_dtype(args.dtype)
+    torch.cuda.set_device(dev)
+
+    def timed(fn, nbytes):
+        reps = max(3, min(40, int(1e10 // max(nbytes, 1)) + 3))
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(reps):
+                fn(i)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        graph.replay()
+        torch.cuda.synchronize()
+        a.record()
+        graph.replay()
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 1e3 / reps
+        return f"{us:.1f} us ({nbytes / us / 1e3 / HBM_PEAK_GBS:.2f})"
+
+    def nsets(per_set):
+        return int(max(1, min(8, COLD_FOOTPRINT // max(per_set, 1) + 1)))
+
+    print(f"storage {dt}; every cell: time per launch (fraction of the {HBM_PEAK_GBS / 1000:.0f} TB/s HBM peak on algorithmic bytes)\n")
+    print("| tokens x hidden | layernorm fwd | layernorm bwd | bias+dropout+residual fwd | bwd (+dbias) | fused boundary fwd | fused boundary bwd |")
+    print("|---|---|---|---|---|---|---|")
+    for T in (2048, 8192, 32768):
+        for H in (512, 1024, 1280, 2048, 4096, 8192, 12288):
+            E = T * H
+            k = nsets(12 * E)
+            bufs = [{n: device_normal((T, H), 1.0, dt, 7 * i + j, dev) for j, n in enumerate(("x", "res", "dy"))} for i in range(k)]
+            outs = [{n: torch.empty((T, H), dtype=tdt, device=dev) for n in ("y", "h", "dx", "dh")} for _ in range(k)]
+            gamma, beta, bias = (device_normal((H,), 1.0, dt, 90 + j, dev) for j in range(3))
+            mean, rstd = torch.zeros(T, device=dev), torch.ones(T, device=dev)
+            dg, db, dbi = (torch.empty(H, device=dev) for _ in range(3))
+            ws = torch.empty(max(L.lsq_workspace_bytes(5, T, H), 16), dtype=torch.uint8, device=dev)
+            cells = [
+                timed(lambda i: L.lsq_layernorm_fwd(bufs[i % k]["x"], gamma, beta, y=outs[i % k]["y"], mean=mean, rstd=rstd), 4 * E + 8 * T),
+                timed(lambda i: L.lsq_layernorm_bwd(bufs[i % k]["dy"], bufs[i % k]["x"], gamma, mean, rstd, dx=outs[i % k]["dx"],
+                                                    dgamma=dg, dbeta=db, workspace=ws), 6 * E + 8 * T),
+                timed(lambda i: L.lsq_bias_dropout_residual_fwd(bufs[i % k]["x"], bias, bufs[i % k]["res"], 0.1, 1, i, out=outs[i % k]["h"]), 6 * E),
+                timed(lambda i: L.lsq_bias_dropout_residual_bwd(bufs[i % k]["dy"], 0.1, 1, i, dx=outs[i % k]["dx"], dbias=dbi, workspace=ws), 4 * E),
+                timed(lambda i: L.lsq_bdr_layernorm_fwd(bufs[i % k]["x"], bias, bufs[i % k]["res"], gamma, beta, 0.1, 1, i, h=outs[i % k]["h"],
+                                                        y=outs[i % k]["y"], mean=mean, rstd=rstd), 8 * E + 8 * T),
+                timed(lambda i: L.lsq_bdr_layernorm_bwd(bufs[i % k]["dy"], bufs[i % k]["x"], gamma, mean, rstd, 0.1, 1, i, dres_in=bufs[i % k]["res"],
+                                                        dh=outs[i % k]["dh"], dx=outs[i % k]["dx"], dgamma=dg, dbeta=db, dbias=dbi, workspace=ws),
+                      10 * E + 8 * T),
+            ]
+            print(f"| {T} x {H} | " + " | ".join(cells) + " |", flush=True)
+            del bufs, outs
+
+    print("\n| batch*heads x length (keys = queries) | softmax fwd | softmax bwd | causal fwd | causal bwd | fwd with attention dropout |")
+    print("|---|---|---|---|---|---|")
+    for Ln in (64, 128, 256, 512, 1024, 2048, 4096):
+        BN = max(1, (1 << 27) // (Ln * Ln))
+        B, N = max(1, BN // 16), min(16, BN)
+        Es = B * N * Ln * Ln
+        k = nsets(8 * Es)
+        xs = [device_normal((B, N, Ln, Ln), 1.0, dt, 300 + i, dev) for i in range(k)]
+        ys = [torch.empty_like(xs[0]) for _ in range(k)]
+        yd = [torch.empty_like(xs[0]) for _ in range(k)]
+        causal_frac = (Ln + 1) / (2 * Ln)
+        cells = [
+            timed(lambda i: L.lsq_softmax_fwd(xs[i % k], None, False, 0.125, y=ys[i % k]), 4 * Es),
+            timed(lambda i: L.lsq_softmax_bwd(xs[i % k], ys[i % k], None, False, 0.125, dx=yd[i % k]), 6 * Es),
+            timed(lambda i: L.lsq_softmax_fwd(xs[i % k], None, True, 0.125, y=ys[i % k]), int(2 * Es * causal_frac) + 2 * Es),
+            timed(lambda i: L.lsq_softmax_bwd(xs[i % k], ys[i % k], None, True, 0.125, dx=yd[i % k]), int(4 * Es * causal_frac) + 2 * Es),
+            timed(lambda i: L.lsq_softmax_fwd(xs[i % k], None, False, 0.125, 0.1, 3, i, y=ys[i % k], y_drop=yd[i % k]), 6 * Es),
+        ]
+        print(f"| {B * N} x {Ln} | " + " | ".join(cells) + " |", flush=True)
+        del xs, ys, yd
+
+    print("\n| tokens x vocabulary | criterion fwd | criterion bwd | fwd + bwd in one pass |")
+    print("|---|---|---|---|")
+    for V in (1000, 8000, 32768, 50257, 128256):
+        T = max(64, (1 << 28) // V)
+        logits = device_normal((T, V), 2.0, dt, 500, dev)
+        dlog = torch.empty_like(logits)
+        target = torch.randint(0, V, (T,), device=dev, dtype=torch.int32)
+        loss, nll, lse, sums = torch.empty(T, device=dev), torch.empty(T, device=dev), torch.empty(T, device=dev), torch.empty(3, device=dev)
+        cells = [
+            timed(lambda i: L.lsq_ls_xent_fwd(logits, target, 0.1, -100, loss=loss, nll=nll, lse=lse, sums=sums), 2 * T * V),
+            timed(lambda i: L.lsq_ls_xent_bwd(logits, lse, target, 0.1, -100, 1.0 / T, dlogits=dlog), 4 * T * V),
+            timed(lambda i: L.lsq_ls_xent_fwd_bwd(logits, target, 0.1, -100, 1.0 / T, loss=loss, nll=nll, lse=lse, sums=sums, dlogits=dlog), 4 * T * V),
+        ]
+        print(f"| {T} x {V} | " + " | ".join(cells) + " |", flush=True)
+        del logits, dlog
+
+    print("\n| parameters | Adam, blocked state | Adam, separate arrays | SGD with momentum, blocked |")
+    print("|---|---|---|---|")
+    for n in (1 << 20, 1 << 24, 100_000_000, 774_000_000):
+        p = device_normal((n,), 0.02, "f32", 700, dev)
+        m, v = torch.zeros_like(p), torch.zeros_like(p)
+        g = device_normal((n,), 1e-3, dt, 701, dev)
+        p_lp = torch.empty(n, dtype=tdt, device=dev)
+        state = L.lsq_adam_state_pack(p)
+        sgd = L.lsq_trainer_state_pack([p, None])
+        cells = [
+            timed(lambda i: L.lsq_adam_step_blocked(state, g, p_lp, step=i + 1, **ADAM_HYPER), 28 * n),
+            timed(lambda i: L.lsq_adam_step(p, m, v, g, p_lp, step=i + 1, **ADAM_HYPER), 28 * n),
+            timed(lambda i: L.lsq_sgd_step_blocked(sgd, g, p_lp, lr=1e-3, momentum=0.9), 20 * n),
+        ]
+        print(f"| {n} | " + " | ".join(cells) + " |", flush=True)
+        del p, m, v, g, p_lp, state, sgd
 
 
 def main():
@@ -73,6 +193,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; there is no CPU path to time.", file=sys.stderr)
         sys.exit(2)
+    if args.sweep:
+        sweep(args)
+        return
     L.load()
     cfg = next(c for c in CONFIGS if c.name == args.config)
     dt = args.dtype

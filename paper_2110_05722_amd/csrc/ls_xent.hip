@@ -97,18 +97,24 @@ struct OnlineLse {
     }
 };
 
-template <typename T>
-__global__ __launch_bounds__(kXentThreads) void xent_fwd_kernel(float* __restrict__ loss, float* __restrict__ nll,
-                                                               float* __restrict__ lse,
-                                                               const T* __restrict__ logits,
-                                                               const int32_t* __restrict__ target, int vocab,
-                                                               float alpha, int ignore_index)
+// TH threads share a row and a workgroup holds R rows.  Long rows: TH = 256, R = 1.  Short rows
+// (up to 2048 logits): TH = 64, R = 4: every wave has its own token, its reductions stay inside the
+// wave (no barrier anywhere, so waves may leave on their own), and no thread idles on a row that
+// is shorter than the workgroup.
+template <typename T, int TH = kXentThreads, int R = 1>
+__global__ __launch_bounds__(TH * R) void xent_fwd_kernel(float* __restrict__ loss, float* __restrict__ nll,
+                                                          float* __restrict__ lse,
+                                                          const T* __restrict__ logits,
+                                                          const int32_t* __restrict__ target, int64_t tokens, int vocab,
+                                                          float alpha, int ignore_index)
 {
-    __shared__ float lds[kXentThreads / 64];
-    const int64_t t = blockIdx.x;
-    const int tid = threadIdx.x;
+    static_assert(R == 1 || TH == 64, "several rows per workgroup only with one wave per row");
+    __shared__ float lds[TH / 64];
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * R + threadIdx.x / TH;
+    const int tid = threadIdx.x % TH;
+    if (t >= tokens) return;                      // whole waves (R > 1 only)
     const int k0 = target[t];
-    if (is_ignored(k0, vocab, ignore_index)) {    // uniform over the workgroup: a padded token's row is not read
+    if (is_ignored(k0, vocab, ignore_index)) {    // uniform over the row's threads: a padded token's row is not read
         if (tid == 0) {
             loss[t] = 0.0f;
             lse[t] = 0.0f;
@@ -127,12 +133,12 @@ __global__ __launch_bounds__(kXentThreads) void xent_fwd_kernel(float* __restric
     // line-aligned.  (Started at the pack, each 1 KiB request straddles nine lines and,
     // with nontemporal loads, the shared line is fetched from HBM twice: +6 % traffic.)
     const int64_t base = r.pack_begin & ~static_cast<int64_t>(7);
-    for (int64_t p = base + tid; p < r.pack_end; p += kXentUnroll * kXentThreads) {
+    for (int64_t p = base + tid; p < r.pack_end; p += kXentUnroll * TH) {
         RawPack<T> raw[kXentUnroll];
         bool ok[kXentUnroll];
 #pragma unroll
         for (int u = 0; u < kXentUnroll; ++u) {
-            const int64_t q = p + u * kXentThreads;
+            const int64_t q = p + u * TH;
             ok[u] = q >= r.pack_begin && q < r.pack_end;
             if (ok[u]) raw[u] = load_raw<T, kNT>(logits + q * kPack);
             else raw[u] = zero_raw<T>();
@@ -146,9 +152,9 @@ __global__ __launch_bounds__(kXentThreads) void xent_fwd_kernel(float* __restric
             }
         }
     }
-    const float M = block_allreduce<kXentThreads / 64, OpMax>(st.m, lds);
-    const float S = block_allreduce<kXentThreads / 64, OpSum>(st.s * __builtin_amdgcn_exp2f(st.m - M), lds);
-    const float SH = block_allreduce<kXentThreads / 64, OpSum>(st.sh, lds);
+    const float M = block_allreduce<TH / 64, OpMax>(st.m, lds);
+    const float S = block_allreduce<TH / 64, OpSum>(st.s * __builtin_amdgcn_exp2f(st.m - M), lds);
+    const float SH = block_allreduce<TH / 64, OpSum>(st.sh, lds);
     if (tid == 0) {
         const float l = (M + __builtin_amdgcn_logf(S)) * kLn2X;     // v_log_f32 is log2
         lse[t] = l;
@@ -343,15 +349,17 @@ __device__ __forceinline__ unsigned row_mask(int i, int lo, int hi)
     return m;
 }
 
-template <typename T, int THREADS, int NP>
-__global__ __launch_bounds__(THREADS) void xent_fused_kernel(
+template <typename T, int THREADS, int NP, int R = 1>
+__global__ __launch_bounds__(THREADS * R) void xent_fused_kernel(
     float* __restrict__ loss, float* __restrict__ nll, float* __restrict__ lse, T* dlogits, const T* logits,
-    const int32_t* __restrict__ target, int vocab, float alpha, int ignore_index, float grad_scale)
+    const int32_t* __restrict__ target, int64_t tokens, int vocab, float alpha, int ignore_index, float grad_scale)
 {
+    static_assert(R == 1 || THREADS == 64, "several rows per workgroup only with one wave per row (no barriers then)");
     constexpr int NW = THREADS / 64;
     __shared__ float lds[2][NW];
-    const int64_t t = blockIdx.x;
-    const int tid = threadIdx.x;
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * R + threadIdx.x / THREADS;
+    const int tid = threadIdx.x % THREADS;
+    if (t >= tokens) return;                                   // whole waves (R > 1 only)
     const int64_t begin = t * vocab, end = begin + vocab;
     const int64_t p0 = begin >> 3, p1 = (end - 1) >> 3;        // packs of the flat tensor that hold the row
     const int np = static_cast<int>(p1 - p0) + 1;
@@ -473,18 +481,21 @@ __global__ __launch_bounds__(THREADS) void xent_fused_kernel(
         }
         raw[k] = pack_raw<T>(h);
     }
-    // both sums through LDS in one exchange
     sx = group_allreduce<64, OpSum>(sx);
     sh = group_allreduce<64, OpSum>(sh);
-    __syncthreads();                                           // lds[0] was read by the maximum
-    if ((tid & 63) == 0) {
-        lds[0][tid >> 6] = sx;
-        lds[1][tid >> 6] = sh;
-    }
-    __syncthreads();
-    float S = lds[0][0], SH = lds[1][0];
+    float S = sx, SH = sh;
+    if constexpr (NW > 1) {                                    // both sums through LDS in one exchange
+        __syncthreads();                                       // lds[0] was read by the maximum
+        if ((tid & 63) == 0) {
+            lds[0][tid >> 6] = sx;
+            lds[1][tid >> 6] = sh;
+        }
+        __syncthreads();
+        S = lds[0][0];
+        SH = lds[1][0];
 #pragma unroll
-    for (int w = 1; w < NW; ++w) { S += lds[0][w]; SH += lds[1][w]; }
+        for (int w = 1; w < NW; ++w) { S += lds[0][w]; SH += lds[1][w]; }
+    }
     const float l = (Ms + __builtin_amdgcn_logf(S)) * kLn2X;       // v_log_f32 is log2
     if (tid == 0) {
         lse[t] = l;
@@ -535,17 +546,28 @@ __global__ __launch_bounds__(1024) void xent_sums_kernel(float* __restrict__ sum
     __shared__ double sm[3][16];
     const int tid = threadIdx.x;
     double a = 0.0, b = 0.0, c = 0.0;
-    for (int64_t t0 = tid; t0 < tokens; t0 += 8 * 1024) {
-        int k[8];
-        float ls[8], lo[8], hk[8];
+    // One workgroup walks all tokens, 8 x 1024 per trip; the next trip's loads are issued before this
+    // trip's values are used (one compute unit alone is bound by latency, not bandwidth: without the
+    // prefetch a quarter of a million tokens took 120 us, four times the forward kernel's share).
+    int k[8], nk[8];
+    float ls[8], lo[8], nls[8], nlo[8];
+    auto fetch = [&](int64_t t0, int (&kk)[8], float (&llo)[8], float (&lls)[8]) {
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int64_t t = t0 + u * 1024;
-            k[u] = t < tokens ? target[t] : ignore_index;
-            lo[u] = t < tokens ? loss[t] : 0.0f;
-            if (nll) { ls[u] = t < tokens ? nll[t] : 0.0f; hk[u] = 0.0f; }
-            else ls[u] = t < tokens ? lse[t] : 0.0f;
+            kk[u] = t < tokens ? target[t] : ignore_index;
+            llo[u] = t < tokens ? loss[t] : 0.0f;
+            lls[u] = t < tokens ? (nll ? nll[t] : lse[t]) : 0.0f;
         }
+    };
+    fetch(tid, nk, nlo, nls);
+    for (int64_t t0 = tid; t0 < tokens; t0 += 8 * 1024) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { k[u] = nk[u]; lo[u] = nlo[u]; ls[u] = nls[u]; }
+        if (t0 + 8 * 1024 < tokens) fetch(t0 + 8 * 1024, nk, nlo, nls);
+        float hk[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) hk[u] = 0.0f;
         if (!nll) {
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
@@ -586,8 +608,12 @@ static lsq_status xent_fwd_dispatch(float* loss, float* nll, float* lse, float* 
                                     int64_t tokens, int32_t vocab, float alpha, int32_t ignore_index, hipStream_t s)
 {
     const T* lp = static_cast<const T*>(logits);
-    hipLaunchKernelGGL((xent_fwd_kernel<T>), dim3(static_cast<unsigned>(tokens)), dim3(kXentThreads), 0, s,
-                       loss, nll, lse, lp, target, vocab, alpha, ignore_index);
+    if (vocab <= 2048)
+        hipLaunchKernelGGL((xent_fwd_kernel<T, 64, 4>), dim3(static_cast<unsigned>(ceil_div(tokens, 4))), dim3(256), 0, s,
+                           loss, nll, lse, lp, target, tokens, vocab, alpha, ignore_index);
+    else
+        hipLaunchKernelGGL((xent_fwd_kernel<T>), dim3(static_cast<unsigned>(tokens)), dim3(kXentThreads), 0, s,
+                           loss, nll, lse, lp, target, tokens, vocab, alpha, ignore_index);
     if (sums)
         hipLaunchKernelGGL((xent_sums_kernel<T>), dim3(1), dim3(1024), 0, s, sums, loss, nll, lse, lp, target, tokens,
                            vocab, ignore_index);
@@ -629,15 +655,16 @@ static lsq_status xent_fused_dispatch(float* loss, float* nll, float* lse, float
     const int64_t rp = (static_cast<int64_t>(vocab) + 7) / 8 + 1;       // packs a row can touch
     T* dp = static_cast<T*>(dlogits);
     const T* lp = static_cast<const T*>(logits);
-    const dim3 grid(static_cast<unsigned>(tokens));
-#define LSQ_XF(TH, NPK)                                                                                              \
-    hipLaunchKernelGGL((xent_fused_kernel<T, TH, NPK>), grid, dim3(TH), 0, s, loss, nll, lse, dp, lp, target, vocab, alpha, \
-                       ignore_index, grad_scale)
-    if (rp <= 256 * 2) LSQ_XF(256, 2);
-    else if (rp <= 256 * 4) LSQ_XF(256, 4);
-    else if (rp <= 256 * 8) LSQ_XF(256, 8);
-    else if (rp <= 1024 * 4) LSQ_XF(1024, 4);
-    else if (rp <= 1024 * 8) LSQ_XF(1024, 8);
+#define LSQ_XF(TH, NPK, ROWS)                                                                                        \
+    hipLaunchKernelGGL((xent_fused_kernel<T, TH, NPK, ROWS>), dim3(static_cast<unsigned>(ceil_div(tokens, ROWS))), dim3(TH * ROWS), 0, s, \
+                       loss, nll, lse, dp, lp, target, tokens, vocab, alpha, ignore_index, grad_scale)
+    if (rp <= 64 * 2) LSQ_XF(64, 2, 4);         // short rows: one wave per token, four tokens per workgroup, no barriers
+    else if (rp <= 64 * 4) LSQ_XF(64, 4, 4);
+    else if (rp <= 256 * 2) LSQ_XF(256, 2, 1);
+    else if (rp <= 256 * 4) LSQ_XF(256, 4, 1);
+    else if (rp <= 256 * 8) LSQ_XF(256, 8, 1);
+    else if (rp <= 1024 * 4) LSQ_XF(1024, 4, 1);
+    else if (rp <= 1024 * 8) LSQ_XF(1024, 8, 1);
     else {
         const lsq_status st = xent_fwd_dispatch<T>(loss, nll, lse, nullptr, logits, target, tokens, vocab, alpha, ignore_index, s);
         if (st != LSQ_OK) return st;
