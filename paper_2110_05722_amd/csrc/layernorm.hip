@@ -659,7 +659,8 @@ static lsq_status ln_fwd_dispatch(void* y, float* mean, float* rstd, const void*
     const T* bp = static_cast<const T*>(beta);
     LnShape sh = ln_shape(hidden);
     // rows of 8193..16384 columns: the forward has the registers for 6 or 8 packs per lane of a 256-thread
-    // workgroup (0.70 of peak at 12288 columns against 0.53 with the backward's 1024 lanes x 2 packs)
+    // workgroup (0.70 of peak at 12288 columns against 0.53 with the backward's 1024 lanes x 2 packs).  The fused
+    // boundary follows (it would be 10 % faster on 1024 lanes, but then no longer bit-identical to the two calls).
     if (sh.lpr > 256) sh = hidden / kPack <= 1536 ? LnShape{256, 6} : LnShape{256, 8};
     if (sh.lpr == 0) {
         hipLaunchKernelGGL((ln_fwd_generic<T>), dim3(static_cast<unsigned>(ceil_div(rows, 4))), dim3(256), 0, s,
