@@ -149,3 +149,41 @@ def test_criterion_and_trainers_random(seed):
     assert_close_f32(v, rv, "v", rel=1e-6, floor=1e-30)
     floor_m = 2.0 ** -23 * (HY["beta1"] * np.abs(hm.astype(np.float64)) + (1 - HY["beta1"]) * np.abs(decode(hg, dt)))
     assert_close_f32(m, rm, "m", rel=1e-6, floor=floor_m)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_embedding_random(seed):
+    """Token counts on both sides of the switch from counted ranks to the radix sort, vocabularies that take one,
+    two or three radix passes, id distributions from all-distinct to a few ids only, random padding."""
+    r = np.random.default_rng(5000 + seed)
+    dt = DTS[seed % 3]
+    B = int(r.integers(1, 40))
+    Ln = int(r.choice([int(r.integers(1, 64)), int(r.integers(64, 700)), int(r.integers(700, 1200))]))
+    Ln = max(1, min(Ln, 36000 // B))
+    if seed % 3 == 1:                                        # beyond 16384 tokens: the radix-sorted order
+        B, Ln = int(r.integers(30, 40)), int(r.integers(560, 900))
+    H = int(r.choice([8, 16, 24, 64, 13]))
+    V = int(r.choice([int(r.integers(3, 250)), int(r.integers(300, 60000)), int(r.integers(66000, 90000))]))
+    p = float(r.choice([0.0, 0.1]))
+    pad = 1
+    say(f"[random embedding {seed}] B={B} L={Ln} ({B * Ln} tokens) hidden={H} vocab={V} p={p} dt={dt}")
+    d = dev()
+    spread = int(r.choice([3, 50, V]))                       # how many different ids the batch draws from
+    tok = (r.integers(0, min(spread, V - 2), size=(B, Ln)) + 2).astype(np.int32)
+    tok[r.random((B, Ln)) < float(r.choice([0.0, 0.3, 0.9]))] = pad
+    embs = encode(r.standard_normal((V, H), dtype=np.float32), dt)
+    poss = encode(r.standard_normal((Ln, H), dtype=np.float32) * 0.5, dt)
+    dys = encode(r.standard_normal((B * Ln, H), dtype=np.float32), dt)
+    scale = float(np.sqrt(H))
+    tokens = torch.from_numpy(tok).to(d)
+    out = L.lsq_embedding_fwd(tokens, to_torch(embs, dt, d), to_torch(poss, dt, d), pad, scale, p, 9, seed)
+    assert_close_store(out, oracle.embedding_fwd(tok, embs, poss, pad, scale, p, 9, seed, dt), dt, "out", f32_floor=1e-5)
+    d0 = encode(r.standard_normal((V, H), dtype=np.float32) * 0.1, dt)
+    p0 = encode(r.standard_normal((Ln, H), dtype=np.float32) * 0.1, dt)
+    demb, dpos = to_torch(d0, dt, d), to_torch(p0, dt, d)
+    L.lsq_embedding_bwd(demb, dpos, to_torch(dys, dt, d), tokens, pad, scale, p, 9, seed)
+    inc_e, inc_p = oracle.embedding_bwd(dys, tok, V, pad, scale, p, 9, seed, dt)
+    # a frequent id sums thousands of rows: the fp32 floor follows the square root of the longest segment
+    longest = max(1, int(np.bincount(tok.reshape(-1)[tok.reshape(-1) != pad], minlength=1).max())) if (tok != pad).any() else 1
+    assert_close_store(demb, decode(d0, dt) + inc_e, dt, "demb", f32_floor=2e-6 * scale * np.sqrt(longest) * 8)
+    assert_close_store(dpos, decode(p0, dt) + inc_p, dt, "dpos", f32_floor=1e-5 * np.sqrt(B))
