@@ -13,7 +13,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, os.environ.get("LSQ_LIB_NAME", "liblsq.so"))
+_LIB_PATH = os.path.join(_HERE, "liblsq.so")
 _lib = None
 
 LSQ_F16, LSQ_BF16, LSQ_F32 = 0, 1, 2

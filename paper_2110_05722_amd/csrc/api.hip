@@ -14,6 +14,10 @@ extern "C" size_t lsq_workspace_bytes(int32_t op, int64_t rows, int32_t cols)
             // two separate operators that serve row lengths without a register bucket
             return static_cast<size_t>(ln_bwd_blocks(rows, cols)) * 3u * static_cast<size_t>(cols) * sizeof(float);
         case LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD:
+            // one [cols] fp32 partial row (dbias) per row block
+            if (cols % kPack == 0)
+                return static_cast<size_t>(bdr_bwd_plan(rows, cols).row_blocks) * static_cast<size_t>(cols) * sizeof(float);
+            return 0;       // the generic path sums each column in one thread
         case LSQ_OP_BIAS_ACT_DROPOUT_BWD:
         case LSQ_OP_SPLIT_HEADS_BWD:
             // one [cols] fp32 partial row (dbias) per row block

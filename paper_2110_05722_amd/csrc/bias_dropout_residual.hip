@@ -1,110 +1,144 @@
 // Fused bias + dropout + residual, forward and backward (Sec. IV-A of the paper,
 // Transformer layers: "bias adding, dropout, and residual" in one launch).
 //
-// Layout of the fast path (hidden % 8 == 0): a wave owns 64 consecutive packs of
-// one row (512 columns, 1 KiB of fp16) and walks down the rows, so the bias pack
-// is loaded once into registers, every access is a 128-bit one, and in backward
-// each lane accumulates the column sums of its own 8 columns with no atomics.
+// Layout of the fast path (hidden % 8 == 0): W lanes of a wave (W = 64, 32 or 16, the widest
+// that divides the packs of a row, so no lane idles on a ragged last column block) own W
+// consecutive packs of one row and the wave covers 64 / W rows at a time; a workgroup's column
+// block is fixed, so the bias pack is loaded once into registers, every access is a 128-bit one,
+// and in backward each lane accumulates the column sums of its own 8 columns with no atomics.
 // The dropout mask is never stored: both directions rebuild it from the Philox
 // counter of the pack.  HBM traffic: forward 3 tensors, backward 2.
+//
+// Backward column sums (dbias): a workgroup adds up its lanes' sums through LDS in a fixed order and
+// writes one partial row of its column block to the workspace; a second small kernel sums the
+// partial rows in a fixed order (bit-reproducible; no atomics).
 #include "host.hpp"
 
 namespace lsq {
 
-#ifndef LSQ_NT
-#define LSQ_NT 1
-#endif
-constexpr bool kNT = LSQ_NT != 0;   // nontemporal hint on the streamed tensors (not on gamma/beta/bias)
+constexpr bool kNT = true;    // nontemporal hint on the streamed tensors (not on gamma/beta/bias)
 
-constexpr int kBdrWaves = 4;   // waves per workgroup; each takes its own rows
-#ifndef LSQ_BDR_UNROLL
-#define LSQ_BDR_UNROLL 4
-#endif
-constexpr int kBdrUnroll = LSQ_BDR_UNROLL;   // rows a wave has in flight in backward
+// A wave as 64 / W row segments of W packs: lane -> (row of the group, pack of the column block).
+template <int W> struct BdrLane {
+    static constexpr int SUB = 64 / W;
+    int col, sub;
+    __device__ __forceinline__ BdrLane() : col((threadIdx.x & 63) % W), sub((threadIdx.x & 63) / W) {}
+};
 
-template <typename T, bool HAS_BIAS, bool DROP>
-__global__ __launch_bounds__(256) void bdr_fwd_cols(T* out, const T* x,
-                                                    const T* __restrict__ bias, const T* res,
-                                                    int64_t rows, int ppr, DropoutParams d)
+template <typename T, bool HAS_BIAS, bool DROP, int W>
+__global__ __launch_bounds__(64 * kBdrFwdWaves) void bdr_fwd_cols(T* out, const T* x, const T* __restrict__ bias,
+                                                                  const T* res, int64_t rows, int ppr, DropoutParams d)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int cp = blockIdx.x * 64 + lane;
+    constexpr int SUB = 64 / W, U = kBdrFwdUnroll, RPI = kBdrFwdWaves * SUB * U;
+    const BdrLane<W> ln;
+    const int wave = threadIdx.x >> 6;
+    const int cp = blockIdx.x * W + ln.col;
     if (cp >= ppr) return;
-    float b[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    if constexpr (HAS_BIAS) load8<T>(bias + static_cast<int64_t>(cp) * kPack, b);
-    const int64_t stride = static_cast<int64_t>(gridDim.y) * kBdrWaves;
-    for (int64_t r = static_cast<int64_t>(blockIdx.y) * kBdrWaves + wave; r < rows; r += stride) {
-        const int64_t pack = r * ppr + cp;
-        float xf[8], rf[8], k[8];
-        load8<T, kNT>(x + pack * kPack, xf);
-        load8<T, kNT>(res + pack * kPack, rf);
-        if constexpr (DROP) dropout_factors8(d, static_cast<uint64_t>(pack), k);
+    // the bias stays packed and is widened where it is used: widening it here would make the
+    // row loads below wait for its arrival
+    RawPack<T> braw = zero_raw<T>();
+    if constexpr (HAS_BIAS) braw = load_raw<T>(bias + static_cast<int64_t>(cp) * kPack);
+    for (int64_t base = static_cast<int64_t>(blockIdx.y) * RPI; base < rows; base += static_cast<int64_t>(gridDim.y) * RPI) {
+        RawPack<T> xr[U], rr[U];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float z = xf[j] + b[j];
-            rf[j] = DROP ? fmaf(z, k[j], rf[j]) : rf[j] + z;
+        for (int u = 0; u < U; ++u) {
+            const int64_t r = base + (u * kBdrFwdWaves + wave) * SUB + ln.sub;
+            if (r < rows) {
+                xr[u] = load_raw<T, kNT>(x + (r * ppr + cp) * kPack);
+                rr[u] = load_raw<T, kNT>(res + (r * ppr + cp) * kPack);
+            } else {
+                xr[u] = zero_raw<T>();
+                rr[u] = zero_raw<T>();
+            }
         }
-        store8<T, kNT>(out + pack * kPack, rf);
+        // the dropout factors need no data: they are drawn while the loads are in flight
+        float k[DROP ? U : 1][8];
+        if constexpr (DROP) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t r = base + (u * kBdrFwdWaves + wave) * SUB + ln.sub;
+                dropout_factors8(d, static_cast<uint64_t>(r * ppr + cp), k[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t r = base + (u * kBdrFwdWaves + wave) * SUB + ln.sub;
+            if (r < rows) {
+                const int64_t pack = r * ppr + cp;
+                float xf[8], rf[8], b[8];
+                unpack<T>(xr[u], xf);
+                unpack<T>(rr[u], rf);
+                if constexpr (HAS_BIAS) opaque<T>(braw);
+                unpack<T>(braw, b);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float z = xf[j] + b[j];
+                    rf[j] = DROP ? fmaf(z, k[DROP ? u : 0][j], rf[j]) : rf[j] + z;
+                }
+                pin_f32(rf);                  // rounds like the kernel that fuses the LayerNorm behind it
+                store8<T, kNT>(out + pack * kPack, rf);
+            }
+        }
     }
 }
 
-// Backward.  partial: [gridDim.y][hidden] fp32 column sums of this workgroup's rows
-// (nullptr: dbias not wanted).
-template <typename T, bool DROP>
-__global__ __launch_bounds__(256) void bdr_bwd_cols(T* dx, float* __restrict__ partial,
-                                                    const T* dy, int64_t rows, int ppr,
-                                                    DropoutParams d)
+// Backward.  partial: [gridDim.y][hidden] fp32 column sums of the workgroups' rows (nullptr:
+// dbias not wanted), summed over the row blocks by colsum_finalize_kernel.
+template <typename T, bool DROP, int W>
+__global__ __launch_bounds__(64 * kBdrBwdWaves) void bdr_bwd_cols(T* dx, float* __restrict__ partial, const T* dy,
+                                                                  int64_t rows, int ppr, int trips, DropoutParams d)
 {
-    __shared__ float sm[kBdrWaves][8][64];
+    constexpr int SUB = 64 / W, NW = kBdrBwdWaves, THREADS = 64 * NW;
+    __shared__ float sm[NW * 8 * 64];      // the lanes' sums
+    const BdrLane<W> ln;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int cp = blockIdx.x * 64 + lane;
+    const int cp = blockIdx.x * W + ln.col;
     const bool active = cp < ppr;
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    const int64_t stride = static_cast<int64_t>(gridDim.y) * kBdrWaves;
     if (active) {
-        // kBdrUnroll rows per trip: their loads are issued before the first Philox call
-        for (int64_t r0 = static_cast<int64_t>(blockIdx.y) * kBdrWaves + wave; r0 < rows; r0 += stride * kBdrUnroll) {
-            RawPack<T> raw[kBdrUnroll];
+        // A workgroup walks `trips` consecutive groups of NW * SUB rows; the pack of the next trip is
+        // loaded before this trip's is used, and the dropout factors, which need no data, are
+        // drawn while the loads are in flight.
+        const int64_t first = static_cast<int64_t>(blockIdx.y) * trips * (NW * SUB) + wave * SUB + ln.sub;
+        RawPack<T> nxt = first < rows ? load_raw<T, kNT>(dy + (first * ppr + cp) * kPack) : zero_raw<T>();
+        for (int t = 0; t < trips; ++t) {
+            const int64_t r = first + static_cast<int64_t>(t) * (NW * SUB);
+            const RawPack<T> cur = nxt;
+            const int64_t rn = r + NW * SUB;
+            if (t + 1 < trips && rn < rows) nxt = load_raw<T, kNT>(dy + (rn * ppr + cp) * kPack);
+            if (r < rows) {
+                const int64_t pack = r * ppr + cp;
+                float g[8], k[8];
+                if constexpr (DROP) dropout_factors8(d, static_cast<uint64_t>(pack), k);
+                unpack<T>(cur, g);
+                if constexpr (DROP) {
 #pragma unroll
-            for (int u = 0; u < kBdrUnroll; ++u) {
-                const int64_t r = r0 + u * stride;
-                if (r < rows) raw[u] = load_raw<T, kNT>(dy + (r * ppr + cp) * kPack);
-                else raw[u] = zero_raw<T>();
-            }
-#pragma unroll
-            for (int u = 0; u < kBdrUnroll; ++u) {
-                const int64_t r = r0 + u * stride;
-                if (r < rows) {
-                    const int64_t pack = r * ppr + cp;
-                    float g[8], k[8];
-                    unpack<T>(raw[u], g);
-                    if constexpr (DROP) {
-                        dropout_factors8(d, static_cast<uint64_t>(pack), k);
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) g[j] *= k[j];
-                    }
-                    store8<T, kNT>(dx + pack * kPack, g);
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) acc[j] += g[j];
+                    for (int j = 0; j < 8; ++j) g[j] *= k[j];
                 }
+                pin_f32(g);
+                store8<T, kNT>(dx + pack * kPack, g);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j] += g[j];
             }
         }
     }
     if (partial == nullptr) return;        // uniform over the grid
+    // the workgroup's sums: wave by wave, row of the group by row of the group, in that order
 #pragma unroll
-    for (int j = 0; j < 8; ++j) sm[wave][j][lane] = acc[j];
+    for (int j = 0; j < 8; ++j) sm[(wave * 8 + j) * 64 + lane] = acc[j];
     __syncthreads();
-    if (wave == 0 && active) {
-        float* dst = partial + static_cast<int64_t>(blockIdx.y) * ppr * kPack + static_cast<int64_t>(cp) * kPack;
-        float s[8];
+    const int hidden = ppr * kPack;
+    const int c0 = blockIdx.x * W * kPack;                       // first column of the block
+    const int ncols = min(W * kPack, hidden - c0);
+    float* prow = partial + static_cast<int64_t>(blockIdx.y) * hidden + c0;
+    for (int c = threadIdx.x; c < W * kPack; c += THREADS) {
+        const int j = c / W, col = c % W;                        // consecutive threads read consecutive LDS words
+        float t = 0.0f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            float t = sm[0][j][lane];
+        for (int w = 0; w < NW; ++w)
 #pragma unroll
-            for (int w = 1; w < kBdrWaves; ++w) t += sm[w][j][lane];
-            s[j] = t;
-        }
-        store8<float>(dst, s);
+            for (int sb = 0; sb < SUB; ++sb) t += sm[(w * 8 + j) * 64 + sb * W + col];
+        if (col * kPack + j < ncols) prow[col * kPack + j] = t;
     }
 }
 
@@ -150,11 +184,6 @@ __global__ __launch_bounds__(256) void bdr_dbias_flat(float* __restrict__ dbias,
     dbias[c] = s;
 }
 
-inline dim3 bdr_grid(int64_t rows, int ppr, int row_blocks)
-{
-    return dim3(static_cast<unsigned>(ceil_div(ppr, 64)), static_cast<unsigned>(row_blocks));
-}
-
 template <typename T>
 static lsq_status bdr_fwd_dispatch(void* out, const void* x, const void* bias, const void* res, int64_t rows,
                                    int32_t hidden, const DropoutParams& d, hipStream_t s)
@@ -165,14 +194,21 @@ static lsq_status bdr_fwd_dispatch(void* out, const void* x, const void* bias, c
     const T* rp = static_cast<const T*>(res);
     if (hidden % kPack == 0) {
         const int ppr = hidden / kPack;
-        int64_t rb = ceil_div(rows, 4 * kBdrWaves);
-        if (rb > 4096) rb = 4096;
-        const dim3 grid = bdr_grid(rows, ppr, static_cast<int>(rb)), block(256);
+        const int w = bdr_lanes_per_row(ppr);
+        const int64_t rpi = static_cast<int64_t>(kBdrFwdWaves) * (64 / w) * kBdrFwdUnroll;     // rows of a workgroup's trip
+        int64_t rb = ceil_div(rows, rpi);
+        if (rb > 8192) rb = 8192;
+        const dim3 grid(static_cast<unsigned>(ceil_div(ppr, w)), static_cast<unsigned>(rb)), block(64 * kBdrFwdWaves);
         const bool drop = d.t16 != 0;
-        if (bp && drop) hipLaunchKernelGGL((bdr_fwd_cols<T, true, true>), grid, block, 0, s, o, xp, bp, rp, rows, ppr, d);
-        else if (bp) hipLaunchKernelGGL((bdr_fwd_cols<T, true, false>), grid, block, 0, s, o, xp, bp, rp, rows, ppr, d);
-        else if (drop) hipLaunchKernelGGL((bdr_fwd_cols<T, false, true>), grid, block, 0, s, o, xp, bp, rp, rows, ppr, d);
-        else hipLaunchKernelGGL((bdr_fwd_cols<T, false, false>), grid, block, 0, s, o, xp, bp, rp, rows, ppr, d);
+#define LSQ_BDR_FWD(W)                                                                                                  \
+        if (w == W) {                                                                                                   \
+            if (bp && drop) hipLaunchKernelGGL((bdr_fwd_cols<T, true, true, W>), grid, block, 0, s, o, xp, bp, rp, rows, ppr, d);    \
+            else if (bp) hipLaunchKernelGGL((bdr_fwd_cols<T, true, false, W>), grid, block, 0, s, o, xp, bp, rp, rows, ppr, d);     \
+            else if (drop) hipLaunchKernelGGL((bdr_fwd_cols<T, false, true, W>), grid, block, 0, s, o, xp, bp, rp, rows, ppr, d);   \
+            else hipLaunchKernelGGL((bdr_fwd_cols<T, false, false, W>), grid, block, 0, s, o, xp, bp, rp, rows, ppr, d);            \
+        }
+        LSQ_BDR_FWD(64) LSQ_BDR_FWD(32) LSQ_BDR_FWD(16)
+#undef LSQ_BDR_FWD
     } else {
         const int64_t total = rows * hidden;
         hipLaunchKernelGGL((bdr_fwd_flat<T>), dim3(static_cast<unsigned>(ceil_div(total, 256))), dim3(256), 0, s,
@@ -189,20 +225,25 @@ static lsq_status bdr_bwd_dispatch(void* dx, float* dbias, const void* dy, int64
     const T* g = static_cast<const T*>(dy);
     if (hidden % kPack == 0) {
         const int ppr = hidden / kPack;
-        const int rb = bdr_bwd_row_blocks(rows, hidden);
-        const dim3 grid = bdr_grid(rows, ppr, rb), block(256);
+        const BdrBwdPlan pl = bdr_bwd_plan(rows, hidden);
+        const dim3 grid(static_cast<unsigned>(pl.col_blocks), static_cast<unsigned>(pl.row_blocks)), block(64 * kBdrBwdWaves);
         float* partial = dbias ? static_cast<float*>(workspace) : nullptr;
-        if (d.t16) hipLaunchKernelGGL((bdr_bwd_cols<T, true>), grid, block, 0, s, o, partial, g, rows, ppr, d);
-        else hipLaunchKernelGGL((bdr_bwd_cols<T, false>), grid, block, 0, s, o, partial, g, rows, ppr, d);
-        if (dbias)
-            launch_colsum_finalize(dbias, dbias, hidden, partial, rb, hidden, s);
+#define LSQ_BDR_BWD(W)                                                                                                  \
+        if (pl.w == W) {                                                                                                \
+            if (d.t16) hipLaunchKernelGGL((bdr_bwd_cols<T, true, W>), grid, block, 0, s, o, partial, g, rows, ppr, pl.trips, d);    \
+            else hipLaunchKernelGGL((bdr_bwd_cols<T, false, W>), grid, block, 0, s, o, partial, g, rows, ppr, pl.trips, d);         \
+        }
+        LSQ_BDR_BWD(64) LSQ_BDR_BWD(32) LSQ_BDR_BWD(16)
+        if (dbias) launch_colsum_finalize(dbias, dbias, hidden, partial, pl.row_blocks, hidden, s);
+#undef LSQ_BDR_BWD
     } else {
         const int64_t total = rows * hidden;
-        hipLaunchKernelGGL((bdr_bwd_flat<T>), dim3(static_cast<unsigned>(ceil_div(total, 256))), dim3(256), 0, s,
-                           o, g, total, d);
+        // the column sums read dy, so they run first: dx may be the dy buffer itself
         if (dbias)
             hipLaunchKernelGGL((bdr_dbias_flat<T>), dim3(static_cast<unsigned>(ceil_div(hidden, 256))), dim3(256), 0, s,
                                dbias, g, rows, hidden, d);
+        hipLaunchKernelGGL((bdr_bwd_flat<T>), dim3(static_cast<unsigned>(ceil_div(total, 256))), dim3(256), 0, s,
+                           o, g, total, d);
     }
     return launch_status();
 }

@@ -169,6 +169,15 @@ __device__ __forceinline__ RawPack<T> pack_raw(const float (&f)[8])
     return r;
 }
 
+// Make eight fp32 values exist as fp32 before they are narrowed: without it the compiler may fold
+// a final fma into the conversion (v_fma_mixlo_f16: one rounding instead of two), and it takes
+// that decision instantiation by instantiation, so two kernels that must agree bit for bit would not.
+__device__ __forceinline__ void pin_f32(float (&f)[8])
+{
+#pragma unroll
+    for (int j = 0; j < 8; ++j) asm volatile("" : "+v"(f[j]));
+}
+
 // 4 consecutive elements (one 128-bit access of fp32, one 64-bit access of fp16/bf16).
 template <typename T> struct alignas(sizeof(T) * 4 > 16 ? 16 : sizeof(T) * 4) Raw4 { T v[4]; };
 

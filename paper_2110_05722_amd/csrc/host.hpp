@@ -112,13 +112,59 @@ inline void launch_colsum_finalize(float* out0, float* out1, int split, const fl
 // while the partials stay a small fraction of the tensor traffic.
 inline int ln_bwd_blocks(int64_t rows, int32_t /*hidden*/)
 {
-#ifndef LSQ_LN_BWD_BLOCKS
-#define LSQ_LN_BWD_BLOCKS 256
-#endif
     int64_t b = ceil_div(rows, 8);       // at least 8 rows per workgroup
-    if (b > LSQ_LN_BWD_BLOCKS) b = LSQ_LN_BWD_BLOCKS;   // one workgroup per compute unit: measured best at 8192 rows
+    if (b > 256) b = 256;   // one workgroup per compute unit: measured best at 8192 rows
     if (b < 1) b = 1;
     return static_cast<int>(b);
+}
+
+// ---- bias + dropout + residual: launch shapes (shared with the workspace sizing)
+#ifndef LSQ_X_BDR_FWD_U
+#define LSQ_X_BDR_FWD_U 1
+#endif
+#ifndef LSQ_X_BDR_BWD_NW
+#define LSQ_X_BDR_BWD_NW 4
+#endif
+#ifndef LSQ_X_BDR_W
+#define LSQ_X_BDR_W 32
+#endif
+constexpr int kBdrFwdWaves = 4;                   // waves per forward workgroup; each takes its own rows
+constexpr int kBdrFwdUnroll = LSQ_X_BDR_FWD_U;    // rows a lane has in flight in forward
+constexpr int kBdrBwdWaves = LSQ_X_BDR_BWD_NW;    // waves per backward workgroup
+
+// Lanes of a wave that share a row: the widest of 64 / 32 / 16 (at most LSQ_X_BDR_W) that divides the
+// packs of a row; 16 with a ragged last column block if none does.
+inline int bdr_lanes_per_row(int ppr)
+{
+    for (int w = LSQ_X_BDR_W; w >= 16; w >>= 1)
+        if (ppr % w == 0) return w;
+    return 16;
+}
+
+// Backward launch shape: column blocks of w packs; row blocks (= partial rows of the column sums) of
+// `trips` consecutive groups of waves * 64 / w rows.
+#ifndef LSQ_X_BDR_WGS
+#define LSQ_X_BDR_WGS 1280
+#endif
+#ifndef LSQ_X_BDR_PMAX
+#define LSQ_X_BDR_PMAX 256
+#endif
+struct BdrBwdPlan { int w, col_blocks, row_blocks, trips; };
+inline BdrBwdPlan bdr_bwd_plan(int64_t rows, int32_t hidden)
+{
+    BdrBwdPlan p;
+    const int ppr = hidden / kPack;
+    p.w = bdr_lanes_per_row(ppr);
+    p.col_blocks = static_cast<int>(ceil_div(ppr, p.w));
+    const int64_t units = ceil_div(rows, static_cast<int64_t>(kBdrBwdWaves) * (64 / p.w));     // row groups of one trip
+    int64_t rb_max = LSQ_X_BDR_WGS / p.col_blocks;
+    if (rb_max > LSQ_X_BDR_PMAX) rb_max = LSQ_X_BDR_PMAX;
+    if (rb_max < 1) rb_max = 1;
+    const int64_t trips = ceil_div(units, rb_max);
+    p.trips = static_cast<int>(trips < 1 ? 1 : trips);
+    const int64_t rb = ceil_div(units, p.trips);
+    p.row_blocks = static_cast<int>(rb < 1 ? 1 : rb);
+    return p;
 }
 
 inline int bdr_bwd_row_blocks(int64_t rows, int32_t /*hidden*/)

@@ -20,10 +20,7 @@
 
 namespace lsq {
 
-#ifndef LSQ_NT
-#define LSQ_NT 1
-#endif
-constexpr bool kNT = LSQ_NT != 0;   // nontemporal hint on the streamed tensors (not on gamma/beta/bias)
+constexpr bool kNT = true;    // nontemporal hint on the streamed tensors (not on gamma/beta/bias)
 
 template <int LPR>
 __device__ __forceinline__ float row_sum(float v, float* lds)
@@ -121,6 +118,7 @@ __global__ __launch_bounds__(LPR > 256 ? LPR : 256) void ln_fwd_kernel(T* __rest
                         const float z = xf[j] + b8[j];
                         rf[j] = DROP ? fmaf(z, kf[j], rf[j]) : rf[j] + z;
                     }
+                    pin_f32(rf);              // rounds like the stand-alone bias+dropout+residual kernel
                     cur[k] = pack_raw<T>(rf);
                     store_raw<T, kNT>(fz.out + r * hidden + idx * kPack, cur[k]);
                 }
@@ -164,22 +162,14 @@ __global__ __launch_bounds__(LPR > 256 ? LPR : 256) void ln_fwd_kernel(T* __rest
                 unpack<T>(bt[k], b8);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) o[j] = fmaf(xv[k][j] * rs, g8[j], b8[j]);
+                pin_f32(o);                   // the fused and the plain kernel round alike
                 store8<T, kNT>(yr + idx * kPack, o);
             }
         }
     }
 }
 
-#ifndef LSQ_LN_BWD_THREADS
-#define LSQ_LN_BWD_THREADS 256
-#endif
-#ifndef LSQ_LN_BWD_RECOMPUTE
-#define LSQ_LN_BWD_RECOMPUTE 1
-#endif
-#ifndef LSQ_LN_BWD_PREFETCH
-#define LSQ_LN_BWD_PREFETCH 1
-#endif
-constexpr int kLnBwdThreads = LSQ_LN_BWD_THREADS;
+constexpr int kLnBwdThreads = 256;
 
 // Whether every row slot of a workgroup gets its own LDS copy of the column accumulators
 // (one barrier in the epilogue) or the slots take turns on one copy: decided by the LDS
@@ -271,7 +261,6 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
             for (int k = 0; k < VPL; ++k) cres[k] = nres[k];
         }
         const float mu = nmu, rs = nrs;
-#if LSQ_LN_BWD_PREFETCH
         if (base + gstride < rows) {          // prefetch the next row group
             const int64_t rn = r + gstride;
             const bool rnv = rn < rows;
@@ -281,15 +270,11 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
             nmu = 0.0f; nrs = 0.0f;
             if (rnv) { nmu = mean[rn]; nrs = rstd[rn]; }
         }
-#endif
 
         // pass 1 over registers: the two row sums and the column accumulators.  Absent packs
         // hold dy = 0, so they add nothing to any of the sums.  xhat = x*rstd - mean*rstd.
         const float nmr = -mu * rs;
         float s1 = 0.0f, s2 = 0.0f;
-#if !LSQ_LN_BWD_RECOMPUTE
-        float gk[VPL][8], xk[VPL][8];
-#endif
 #pragma unroll
         for (int k = 0; k < VPL; ++k) {
             float gy[8], xv[8], g8[8];
@@ -312,9 +297,6 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
                 const float gg = gy[j] * g8[j];
                 s1 += gg;
                 s2 = fmaf(gg, xhat, s2);
-#if !LSQ_LN_BWD_RECOMPUTE
-                gk[k][j] = gg; xk[k][j] = xhat;
-#endif
             }
         }
         s1 = row_sum<LPR>(s1, lds);
@@ -327,7 +309,6 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
             if (rv && idx < nv) {
                 float o[8];
                 if constexpr (HAS_RES) unpack<T>(cres[k], o);
-#if LSQ_LN_BWD_RECOMPUTE
                 // xhat and gamma*dy are rebuilt from the packed row (a few flops) rather than kept
                 // in 16 more registers per pack across the reduction
                 opaque<T>(cdy[k]);
@@ -341,13 +322,7 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
                     const float v = fmaf(gy[j] * g8[j], rs, fmaf(fmaf(xv[j], rs, nmr), c1, c0));
                     o[j] = HAS_RES ? o[j] + v : v;
                 }
-#else
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const float v = fmaf(gk[k][j], rs, fmaf(xk[k][j], c1, c0));
-                    o[j] = HAS_RES ? o[j] + v : v;
-                }
-#endif
+                pin_f32(o);               // the fused and the plain kernel round alike
                 if constexpr (!FUSE) {
                     store8<T, kNT>(dx + ro + idx * kPack, o);
                 } else {
@@ -361,23 +336,13 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
 #pragma unroll
                         for (int j = 0; j < 8; ++j) gq[j] *= kf[j];
                     }
+                    pin_f32(gq);
                     store8<T, kNT>(fz.out + ro + idx * kPack, gq);
 #pragma unroll
                     for (int j = 0; j < 8; ++j) dbi[k][j] += gq[j];
                 }
             }
         }
-#if !LSQ_LN_BWD_PREFETCH
-        if (base + gstride < rows) {          // no prefetch: occupancy hides the latency instead
-            const int64_t rn = r + gstride;
-            const bool rnv = rn < rows;
-            ln_load_row<T, LPR, VPL>(ndy, dy, rn, rnv, hidden, nv, sub);
-            ln_load_row<T, LPR, VPL>(nx, x, rn, rnv, hidden, nv, sub);
-            if constexpr (HAS_RES) ln_load_row<T, LPR, VPL>(nres, dres, rn, rnv, hidden, nv, sub);
-            nmu = 0.0f; nrs = 0.0f;
-            if (rnv) { nmu = mean[rn]; nrs = rstd[rn]; }
-        }
-#endif
     }
 
     if constexpr (!COLS) return;
@@ -610,10 +575,7 @@ __global__ __launch_bounds__(256) void ln_dparams_packed(float* __restrict__ par
     store8<float>(prow + hidden + idx * kPack, sb);
 }
 
-#ifndef LSQ_LN_WIDE_LPR
-#define LSQ_LN_WIDE_LPR 1024
-#endif
-constexpr int kLnWideLpr = LSQ_LN_WIDE_LPR, kLnWideVpl = 2048 / LSQ_LN_WIDE_LPR;      // the bucket of rows with 1025..2048 packs
+constexpr int kLnWideLpr = 1024, kLnWideVpl = 2;      // the bucket of rows with 1025..2048 packs
 
 // ------------------------------------------------------------------ dispatch
 // Shape buckets: lanes per row and packs per lane for a row of nv packs.
@@ -623,29 +585,43 @@ inline LnShape ln_shape(int hidden)
 {
     if (hidden % kPack != 0) return {0, 0};
     const int nv = hidden / kPack;
-    if (nv <= 8) return {8, 1};
-    if (nv <= 16) return {16, 1};
-    if (nv <= 32) return {32, 1};
-    if (nv <= 64) return {64, 1};
-    if (nv <= 128) return {64, 2};
-    if (nv <= 192) return {64, 3};
-    if (nv <= 256) return {64, 4};
+    // rows of up to 384 packs: lanes of one wave, the shape with the fewest idle lane slots (the first
+    // of equals: more lanes per row before more packs per lane).  768, 1280, 2560 and 3072 columns
+    // fit 32 x 3, 32 x 5, 64 x 5 and 64 x 6 exactly.
+    static const LnShape wave_shapes[] = {{64, 1}, {64, 2}, {64, 3}, {64, 4}, {64, 5}, {64, 6}, {32, 1}, {32, 3}, {32, 5},
+                                          {16, 1}, {8, 1}};
+    if (nv <= 384) {
+        LnShape best{0, 0};
+        for (const LnShape& c : wave_shapes)
+            if (c.lpr * c.vpl >= nv && (best.lpr == 0 || c.lpr * c.vpl < best.lpr * best.vpl)) best = c;
+        return best;
+    }
     if (nv <= 512) return {256, 2};
     if (nv <= 1024) return {256, 4};
     if (nv <= 2048) return {kLnWideLpr, kLnWideVpl};     // hidden up to 16384: one large workgroup per row
     return {0, 0};
 }
 
+// Backward keeps 2 (3 when fused) fp32 column accumulators per element of a lane next to the rows in
+// flight and sums the row slots of a workgroup through LDS: there 64 lanes per row with an idle
+// tail beat the exact fit (hidden 1280: 18.9 against 20.7 us with 32 lanes x 5 packs).
+inline LnShape ln_bwd_shape(int hidden)
+{
+    const LnShape f = ln_shape(hidden);
+    if (f.lpr != 32 || f.vpl == 1) return f;
+    return {64, (hidden / kPack + 63) / 64};
+}
+
 inline int ln_fwd_blocks(int64_t rows, int lpr)
 {
     const int rpb = lpr > 256 ? 1 : 256 / lpr;
-    int64_t b = ceil_div(rows, static_cast<int64_t>(rpb) * 2);   // about two row groups per workgroup
+    int64_t b = ceil_div(rows, static_cast<int64_t>(rpb) * 2);   // two row groups per workgroup (one: 11.1, two: 9.2, four: 10.4 us at 8192 x 1280)
     if (b > 8192) b = 8192;
     if (b < 1) b = 1;
     return static_cast<int>(b);
 }
 
-#define LSQ_LN_CASES_COMMON(X) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 3) X(64, 4) X(256, 2) X(256, 4)
+#define LSQ_LN_CASES_COMMON(X) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 3) X(64, 4) X(64, 5) X(64, 6) X(256, 2) X(256, 4)
 
 // fuse != nullptr: x is the projection output and *fuse carries h / residual / bias / dropout
 template <typename T>
@@ -675,7 +651,7 @@ static lsq_status ln_fwd_dispatch(void* y, float* mean, float* rstd, const void*
         else if (fuse->d.t16) hipLaunchKernelGGL((ln_fwd_kernel<T, L, V, true, true>), grid, block, 0, s, yp, mean, rstd, xp, gp, bp, rows, hidden, eps, *fuse); \
         else hipLaunchKernelGGL((ln_fwd_kernel<T, L, V, true, false>), grid, block, 0, s, yp, mean, rstd, xp, gp, bp, rows, hidden, eps, *fuse); \
     }
-    LSQ_LN_CASES_COMMON(X) X(256, 6) X(256, 8)
+    LSQ_LN_CASES_COMMON(X) X(32, 3) X(32, 5) X(256, 6) X(256, 8)
 #undef X
     return launch_status();
 }
@@ -717,7 +693,7 @@ static lsq_status ln_bwd_dispatch(void* dx, float* dgamma, float* dbeta, const v
     const T* xp = static_cast<const T*>(x);
     const T* gp = static_cast<const T*>(gamma);
     const T* rp = static_cast<const T*>(dres);
-    const LnShape sh = ln_shape(hidden);
+    const LnShape sh = ln_bwd_shape(hidden);
     if (sh.lpr == 0) {
         const int Pg = ln_bwd_blocks(rows, hidden);
         float* gpartial = static_cast<float*>(workspace);
