@@ -110,6 +110,22 @@ lsq_status lsq_layernorm_bwd(void* dx, float* dgamma, float* dbeta,
                              void* workspace, size_t workspace_bytes,
                              int64_t rows, int32_t hidden, lsq_dtype dt, void* stream);
 
+/* lsq_layernorm_bwd for callers that cannot allocate device memory or own no workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same
+ * arguments (minus the workspace), same kernels and therefore the same bits as lsq_layernorm_bwd.
+ * The partial rows of the dgamma / dbeta column sums go to an 8 MiB device array that the library
+ * itself holds (one copy per GPU the library runs on, until the process ends); the call allocates
+ * and frees nothing.  Limit: lsq_workspace_bytes(LSQ_OP_LAYERNORM_BWD, rows, hidden) <= 8 MiB
+ * (hidden <= 4096 for any number of rows); beyond it the call returns LSQ_WORKSPACE_TOO_SMALL and
+ * launches nothing.  Every call on a GPU uses that GPU's one array: calls that may overlap in time on
+ * one GPU (different streams, concurrent graph launches) race and must be serialised by the caller.
+ * Nothing in the array needs to start at zero (each launch overwrites what it later reads).
+ * LSQ_LAUNCH_FAILED if the array's device address cannot be obtained. */
+lsq_status lsq_layernorm_bwd_noalloc(void* dx, float* dgamma, float* dbeta,
+                                     const void* dy, const void* x, const void* gamma,
+                                     const float* mean, const float* rstd, const void* dres_in,
+                                     int64_t rows, int32_t hidden, lsq_dtype dt, void* stream);
+
 /* Fused bias + dropout + residual, forward (Sec. IV-A, Transformer layers: the
  * last kernel of the self-attention block):
  *   out[r,i] = residual[r,i] + keep[r,i] * (x[r,i] + bias[i]) / (1 - p)

@@ -25,7 +25,7 @@ LSQ_ACT = {"relu": 0, "gelu": 1, "gelu_tanh": 2}
 _DT = {torch.float16: LSQ_F16, torch.bfloat16: LSQ_BF16, torch.float32: LSQ_F32}
 
 EXPORTS = [
-    "lsq_workspace_bytes", "lsq_status_string", "lsq_layernorm_fwd", "lsq_layernorm_bwd",
+    "lsq_workspace_bytes", "lsq_status_string", "lsq_layernorm_fwd", "lsq_layernorm_bwd", "lsq_layernorm_bwd_noalloc",
     "lsq_bias_dropout_residual_fwd", "lsq_bias_dropout_residual_bwd", "lsq_softmax_fwd", "lsq_softmax_bwd",
     "lsq_ls_xent_fwd", "lsq_ls_xent_bwd", "lsq_ls_xent_fwd_bwd", "lsq_adam_step",
     "lsq_bias_act_dropout_fwd", "lsq_bias_act_dropout_bwd", "lsq_adam_step_lp", "lsq_sgd_step",
@@ -62,6 +62,7 @@ def load():
         "lsq_status_string": (C.c_char_p, [C.c_int]),
         "lsq_layernorm_fwd": (C.c_int, [vp, vp, vp, vp, vp, vp, i64, i32, f32, C.c_int, vp]),
         "lsq_layernorm_bwd": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, i64, i32, C.c_int, vp]),
+        "lsq_layernorm_bwd_noalloc": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, C.c_int, vp]),
         "lsq_bias_dropout_residual_fwd": (C.c_int, [vp, vp, vp, vp, i64, i32, f32, u64, u64, C.c_int, vp]),
         "lsq_bias_dropout_residual_bwd": (C.c_int, [vp, vp, vp, i64, i32, f32, u64, u64, vp, sz, C.c_int, vp]),
         "lsq_softmax_fwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64, C.c_int, vp]),
@@ -186,6 +187,20 @@ def lsq_layernorm_bwd(dy, x, gamma, mean, rstd, dres_in=None, dx=None, dgamma=No
     _check(load().lsq_layernorm_bwd(_ptr(dx), _ptr(dgamma), _ptr(dbeta), _ptr(dy), _ptr(x), _ptr(gamma), _ptr(mean),
                                     _ptr(rstd), _ptr(dres_in), _ptr(ws), ws.numel() * ws.element_size(), rows, hidden,
                                     _dt(x), _stream()), "lsq_layernorm_bwd")
+    return dx, dgamma, dbeta
+
+
+def lsq_layernorm_bwd_noalloc(dy, x, gamma, mean, rstd, dx, dgamma, dbeta, dres_in=None):
+    """LayerNorm backward into caller-supplied outputs, scratch held by the library: the call allocates nothing."""
+    rows, hidden = x.shape
+    for name, t in (("dy", dy), ("dx", dx), ("dres_in", dres_in)):
+        _need(name, t, rows * hidden, x.dtype)
+    _need("gamma", gamma, hidden, x.dtype)
+    for name, t, k in (("mean", mean, rows), ("rstd", rstd, rows), ("dgamma", dgamma, hidden), ("dbeta", dbeta, hidden)):
+        _need(name, t, k, torch.float32)
+    _check(load().lsq_layernorm_bwd_noalloc(_ptr(dx), _ptr(dgamma), _ptr(dbeta), _ptr(dy), _ptr(x), _ptr(gamma), _ptr(mean),
+                                            _ptr(rstd), _ptr(dres_in), rows, hidden, _dt(x), _stream()),
+           "lsq_layernorm_bwd_noalloc")
     return dx, dgamma, dbeta
 
 

@@ -16,6 +16,8 @@
 // accumulates its own columns over its rows, the row slots of a workgroup are
 // summed in a fixed order through LDS, one partial row per workgroup goes to the
 // workspace and a second small kernel sums the partial rows in order.  No atomics.
+#include <mutex>
+
 #include "host.hpp"
 
 namespace lsq {
@@ -790,6 +792,47 @@ extern "C" lsq_status lsq_layernorm_bwd(void* dx, float* dgamma, float* dbeta, c
         case LSQ_BF16: return ln_bwd_dispatch<bf16>(dx, dgamma, dbeta, dy, x, gamma, mean, rstd, dres_in, workspace, rows, hidden, s);
         default: return ln_bwd_dispatch<float>(dx, dgamma, dbeta, dy, x, gamma, mean, rstd, dres_in, workspace, rows, hidden, s);
     }
+}
+
+// ---- LayerNorm backward for callers that may not allocate: the partial rows of the column sums go to
+// device memory the library itself holds, one copy per GPU, for as long as the process lives.
+namespace lsq {
+constexpr size_t kLnScratchBytes = 8u << 20;
+static __device__ __align__(256) unsigned char scratch[kLnScratchBytes];
+
+// The array's address on the current device.  `scratch` itself is only a host-side handle: the
+// address is asked for once per device (each GPU holds its own copy at its own address) and kept.
+static void* ln_scratch_on_current_device()
+{
+    static std::mutex mu;
+    static void* ptr[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        ptr[dev] = p;
+    }
+    return ptr[dev];
+}
+}  // namespace lsq
+
+extern "C" lsq_status lsq_layernorm_bwd_noalloc(void* dx, float* dgamma, float* dbeta, const void* dy, const void* x,
+                                                const void* gamma, const float* mean, const float* rstd,
+                                                const void* dres_in, int64_t rows, int32_t hidden, lsq_dtype dt,
+                                                void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(rows >= 0 && hidden > 0);
+    if (lsq_workspace_bytes(LSQ_OP_LAYERNORM_BWD, rows, hidden) > kLnScratchBytes) return LSQ_WORKSPACE_TOO_SMALL;
+    void* ws = nullptr;
+    if (rows > 0) {
+        ws = ln_scratch_on_current_device();
+        if (!ws) return LSQ_LAUNCH_FAILED;
+    }
+    return lsq_layernorm_bwd(dx, dgamma, dbeta, dy, x, gamma, mean, rstd, dres_in, ws, kLnScratchBytes, rows, hidden, dt,
+                             stream);
 }
 
 // ---- fused sub-layer boundary of a pre-LN Transformer

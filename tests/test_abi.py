@@ -69,6 +69,9 @@ def test_host_side_argument_errors(lib):
     assert f(A, A, A, A, A, A, A, A, None, A, 16, 64, 512, 0, None) == WS
     assert f(A, A, A, A, A, A, A, A, None, None, 0, 64, 512, 0, None) == WS
     assert f(A, None, A, A, A, A, A, A, None, A, 1 << 30, 64, 512, 0, None) == INVALID
+    f = lib.lsq_layernorm_bwd_noalloc
+    assert f(A, A, A, A, A, A, A, A, None, 4096, 8192, 0, None) == WS          # 16 MiB of partial rows > the 8 MiB held
+    assert f(A, A, A, A, A, A, A, A, None, -1, 64, 0, None) == INVALID
     # bias + dropout + residual: p outside [0, 1)
     f = lib.lsq_bias_dropout_residual_fwd
     assert f(A, A, A, A, 4, 8, 1.0, 1, 0, 0, None) == INVALID
