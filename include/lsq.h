@@ -8,7 +8,14 @@
  *
  * Conventions that hold for every entry point
  *   - Every data pointer is a DEVICE pointer owned by the caller; the library
- *     allocates nothing, frees nothing and never synchronises.  Work is
+ *     allocates nothing, frees nothing and never synchronises.  It keeps no state
+ *     between calls except two host-side "done once per device" notes, both
+ *     guarded for concurrent host threads: the raised dynamic-LDS limit of the
+ *     LayerNorm backward kernel for rows of 8193..16384 columns
+ *     (hipFuncSetAttribute on its first use on a device) and the device address
+ *     of the array behind lsq_layernorm_bwd_noalloc.  Neither is a stream
+ *     operation; a caller that captures such a call into a HIP graph should
+ *     have made one eager call of it on that device before.  Work is
  *     enqueued on `stream` (a hipStream_t passed as void*; NULL = the null
  *     stream) and the call returns as soon as the launches are queued.
  *   - Tensors are dense, row-major, innermost dimension contiguous.  Base
@@ -34,7 +41,8 @@
  *   r16 = (w[(e%8)/2] >> (16*(e%2))) & 0xFFFF.  With T16 = round(p * 65536)
  *   (host double arithmetic, clamped to [0, 65535]) the element is KEPT iff
  *   r16 >= T16, and kept values are scaled by 1/(1-p) (inverted dropout, the
- *   nominal p).  p == 0 keeps everything and draws nothing.  Nothing is stored:
+ *   nominal p).  p == 0 keeps everything and draws nothing; a p > 0 so small that T16 is 0
+ *   (p < 2^-17) keeps everything too and still scales by 1/(1-p).  Nothing is stored:
  *   the backward entry points regenerate the mask from (seed, offset).
  */
 #ifndef LSQ_H_
@@ -210,7 +218,9 @@ lsq_status lsq_ls_xent_bwd(void* dlogits, const void* logits, const float* lse,
  * Outputs as lsq_ls_xent_fwd (loss, nll nullable, lse, sums nullable) plus dlogits as
  * lsq_ls_xent_bwd.  dlogits is evaluated as e_i * (grad_scale / S) - grad_scale*alpha/V
  * with e_i = exp(h_i - max) rounded once to dt and S = sum_i e_i: it agrees with
- * lsq_ls_xent_bwd to two roundings of dt.  dlogits may alias logits (in place).  Rows
+ * lsq_ls_xent_bwd to two roundings of dt.  dlogits may alias logits (in place); in place,
+ * `sums` needs `nll` (LSQ_INVALID_ARG if sums != NULL, nll == NULL and dlogits == logits:
+ * the logits the sum of nll would be gathered from are overwritten by then).  Rows
  * of up to 65528 elements are held in registers; longer rows run the two operators
  * back to back. */
 lsq_status lsq_ls_xent_fwd_bwd(float* loss, float* nll, float* lse, float* sums, void* dlogits,
@@ -274,7 +284,9 @@ lsq_status lsq_adam_step_lp(void* p_lp, float* m, float* v, const void* g, int64
  *   y, mean, rstd = LayerNorm(h; gamma, beta)   (from the STORED, rounded h)
  * Bit for bit the result of lsq_bias_dropout_residual_fwd followed by
  * lsq_layernorm_fwd on its output; 8 instead of 10 bytes per element, one launch.
- * Arguments as in those two calls (h: [rows, hidden] dt, written). */
+ * Arguments as in those two calls (h: [rows, hidden] dt, written), except that h and y must
+ * not alias x or residual (the next rows of x and residual are being read while h is
+ * written). */
 lsq_status lsq_bdr_layernorm_fwd(void* h, void* y, float* mean, float* rstd, const void* x,
                                  const void* bias, const void* residual, const void* gamma,
                                  const void* beta, int64_t rows, int32_t hidden, float p,

@@ -181,7 +181,7 @@ __global__ __launch_bounds__(256) void bad_fwd_flat(T* out, const T* x, const T*
     float z = to_f32<T>(x[e]);
     if (bias) z += to_f32<T>(bias[e % hidden]);
     float a = act_value<ACT>(z);
-    if (d.t16) a *= dropout_factor1(d, static_cast<uint64_t>(e));
+    if (d.on) a *= dropout_factor1(d, static_cast<uint64_t>(e));
     out[e] = from_f32<T>(a);
 }
 
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(256) void bad_bwd_flat(T* dx, const T* dy, const T*
     float z = to_f32<T>(x[e]);
     if (bias) z += to_f32<T>(bias[e % hidden]);
     float g = to_f32<T>(dy[e]) * act_slope<ACT>(z);
-    if (d.t16) g *= dropout_factor1(d, static_cast<uint64_t>(e));
+    if (d.on) g *= dropout_factor1(d, static_cast<uint64_t>(e));
     dx[e] = from_f32<T>(g);
 }
 
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(256) void bad_dbias_flat(float* __restrict__ dbias,
     for (int64_t r = 0; r < rows; ++r) {
         const int64_t e = r * hidden + c;
         float g = to_f32<T>(dy[e]) * act_slope<ACT>(to_f32<T>(x[e]) + b);
-        if (d.t16) g *= dropout_factor1(d, static_cast<uint64_t>(e));
+        if (d.on) g *= dropout_factor1(d, static_cast<uint64_t>(e));
         s += g;
     }
     dbias[c] = s;
@@ -229,7 +229,7 @@ static lsq_status bad_fwd_dispatch(void* out, const void* x, const void* bias, i
         int64_t rb = ceil_div(rows, 4 * kBadWaves);
         if (rb > 4096) rb = 4096;
         const dim3 grid(static_cast<unsigned>(ceil_div(ppr, 64)), static_cast<unsigned>(rb)), block(256);
-        const bool drop = d.t16 != 0;
+        const bool drop = d.on != 0;
         if (bp && drop) hipLaunchKernelGGL((bad_fwd_cols<T, ACT, true, true>), grid, block, 0, s, o, xp, bp, rows, ppr, d);
         else if (bp) hipLaunchKernelGGL((bad_fwd_cols<T, ACT, true, false>), grid, block, 0, s, o, xp, bp, rows, ppr, d);
         else if (drop) hipLaunchKernelGGL((bad_fwd_cols<T, ACT, false, true>), grid, block, 0, s, o, xp, bp, rows, ppr, d);
@@ -255,7 +255,7 @@ static lsq_status bad_bwd_dispatch(void* dx, float* dbias, const void* dy, const
         const int rb = bdr_bwd_row_blocks(rows, hidden);
         const dim3 grid(static_cast<unsigned>(ceil_div(ppr, 64)), static_cast<unsigned>(rb)), block(256);
         float* partial = dbias ? static_cast<float*>(workspace) : nullptr;
-        const bool drop = d.t16 != 0;
+        const bool drop = d.on != 0;
         if (bp && drop) hipLaunchKernelGGL((bad_bwd_cols<T, ACT, true, true>), grid, block, 0, s, o, partial, g, xp, bp, rows, ppr, d);
         else if (bp) hipLaunchKernelGGL((bad_bwd_cols<T, ACT, true, false>), grid, block, 0, s, o, partial, g, xp, bp, rows, ppr, d);
         else if (drop) hipLaunchKernelGGL((bad_bwd_cols<T, ACT, false, true>), grid, block, 0, s, o, partial, g, xp, bp, rows, ppr, d);

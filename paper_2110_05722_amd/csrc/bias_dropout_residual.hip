@@ -152,8 +152,8 @@ __global__ __launch_bounds__(256) void bdr_fwd_flat(T* out, const T* x,
     if (e >= total) return;
     float z = to_f32<T>(x[e]);
     if (bias) z += to_f32<T>(bias[e % hidden]);
-    const float k = d.t16 ? dropout_factor1(d, static_cast<uint64_t>(e)) : 1.0f;
-    out[e] = from_f32<T>(d.t16 ? fmaf(z, k, to_f32<T>(res[e])) : to_f32<T>(res[e]) + z);
+    const float k = d.on ? dropout_factor1(d, static_cast<uint64_t>(e)) : 1.0f;
+    out[e] = from_f32<T>(d.on ? fmaf(z, k, to_f32<T>(res[e])) : to_f32<T>(res[e]) + z);
 }
 
 template <typename T>
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256) void bdr_bwd_flat(T* dx, const T* dy,
     const int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     if (e >= total) return;
     float g = to_f32<T>(dy[e]);
-    if (d.t16) g *= dropout_factor1(d, static_cast<uint64_t>(e));
+    if (d.on) g *= dropout_factor1(d, static_cast<uint64_t>(e));
     dx[e] = from_f32<T>(g);
 }
 
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(256) void bdr_dbias_flat(float* __restrict__ dbias,
     for (int64_t r = 0; r < rows; ++r) {
         const int64_t e = r * hidden + c;
         float g = to_f32<T>(dy[e]);
-        if (d.t16) g *= dropout_factor1(d, static_cast<uint64_t>(e));
+        if (d.on) g *= dropout_factor1(d, static_cast<uint64_t>(e));
         s += g;
     }
     dbias[c] = s;
@@ -199,7 +199,7 @@ static lsq_status bdr_fwd_dispatch(void* out, const void* x, const void* bias, c
         int64_t rb = ceil_div(rows, rpi);
         if (rb > 8192) rb = 8192;
         const dim3 grid(static_cast<unsigned>(ceil_div(ppr, w)), static_cast<unsigned>(rb)), block(64 * kBdrFwdWaves);
-        const bool drop = d.t16 != 0;
+        const bool drop = d.on != 0;
 #define LSQ_BDR_FWD(W)                                                                                                  \
         if (w == W) {                                                                                                   \
             if (bp && drop) hipLaunchKernelGGL((bdr_fwd_cols<T, true, true, W>), grid, block, 0, s, o, xp, bp, rp, rows, ppr, d);    \
@@ -230,7 +230,7 @@ static lsq_status bdr_bwd_dispatch(void* dx, float* dbias, const void* dy, int64
         float* partial = dbias ? static_cast<float*>(workspace) : nullptr;
 #define LSQ_BDR_BWD(W)                                                                                                  \
         if (pl.w == W) {                                                                                                \
-            if (d.t16) hipLaunchKernelGGL((bdr_bwd_cols<T, true, W>), grid, block, 0, s, o, partial, g, rows, ppr, pl.trips, d);    \
+            if (d.on) hipLaunchKernelGGL((bdr_bwd_cols<T, true, W>), grid, block, 0, s, o, partial, g, rows, ppr, pl.trips, d);    \
             else hipLaunchKernelGGL((bdr_bwd_cols<T, false, W>), grid, block, 0, s, o, partial, g, rows, ppr, pl.trips, d);         \
         }
         LSQ_BDR_BWD(64) LSQ_BDR_BWD(32) LSQ_BDR_BWD(16)

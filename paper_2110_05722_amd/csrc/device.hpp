@@ -272,7 +272,8 @@ __device__ __forceinline__ float block_allreduce(float v, float* scratch)
 struct DropoutParams {
     uint32_t key0, key1;      // seed
     uint32_t ctr2, ctr3;      // offset
-    uint32_t t16;             // keep iff r16 >= t16; 0 means "no dropout, draw nothing"
+    uint32_t t16;             // keep iff r16 >= t16
+    uint32_t on;              // p > 0: draw and scale (a p so small that t16 rounds to 0 keeps everything, still scaled)
     float scale;              // 1 / (1 - p)
 };
 

@@ -552,7 +552,7 @@ __global__ __launch_bounds__(256) void emb_fwd_flat(T* __restrict__ out, const i
     float v = 0.0f;
     if (!emb_is_pad(w, vocab, pad_idx)) {
         v = fmaf(scale, to_f32<T>(emb[static_cast<int64_t>(w) * hidden + i]), to_f32<T>(pos[(t % len) * hidden + i]));
-        if (d.t16) v *= dropout_factor1(d, static_cast<uint64_t>(e));
+        if (d.on) v *= dropout_factor1(d, static_cast<uint64_t>(e));
     }
     out[e] = from_f32<T>(v);
 }
@@ -573,7 +573,7 @@ __global__ __launch_bounds__(256) void emb_accumulate_flat(T* __restrict__ demb,
             if (o.y != key) break;
             const int64_t e = static_cast<int64_t>(o.x) * hidden + i;
             float g = to_f32<T>(dy[e]);
-            if (d.t16) g *= dropout_factor1(d, static_cast<uint64_t>(e));
+            if (d.on) g *= dropout_factor1(d, static_cast<uint64_t>(e));
             acc += g;
         }
         T* dst = demb + static_cast<int64_t>(key) * hidden + i;
@@ -594,7 +594,7 @@ __global__ __launch_bounds__(256) void emb_dpos_flat(T* __restrict__ dpos, const
             if (emb_is_pad(tokens[t], vocab, pad_idx)) continue;
             const int64_t e = t * hidden + i;
             float g = to_f32<T>(dy[e]);
-            if (d.t16) g *= dropout_factor1(d, static_cast<uint64_t>(e));
+            if (d.on) g *= dropout_factor1(d, static_cast<uint64_t>(e));
             acc += g;
         }
         T* dst = dpos + static_cast<int64_t>(l) * hidden + i;
@@ -615,7 +615,7 @@ static lsq_status emb_fwd_dispatch(void* out, const int32_t* tokens, const void*
         int64_t rb = ceil_div(rows, 4 * kEmbWaves);
         if (rb > 4096) rb = 4096;
         const dim3 grid(static_cast<unsigned>(ceil_div(ppr, 64)), static_cast<unsigned>(rb)), block(256);
-        if (d.t16) hipLaunchKernelGGL((emb_fwd_cols<T, true>), grid, block, 0, s, o, tokens, e, p, rows, len, ppr, vocab, pad_idx, scale, d);
+        if (d.on) hipLaunchKernelGGL((emb_fwd_cols<T, true>), grid, block, 0, s, o, tokens, e, p, rows, len, ppr, vocab, pad_idx, scale, d);
         else hipLaunchKernelGGL((emb_fwd_cols<T, false>), grid, block, 0, s, o, tokens, e, p, rows, len, ppr, vocab, pad_idx, scale, d);
     } else {
         hipLaunchKernelGGL((emb_fwd_flat<T>), dim3(static_cast<unsigned>(ceil_div(rows * hidden, 256))), dim3(256), 0, s,
@@ -647,7 +647,7 @@ static lsq_status emb_bwd_dispatch(void* demb, void* dpos, const void* dy, const
         if (packed && dp) {
             // the position gradient rides along with the rank count
             const dim3 rgrid(rank_blocks + static_cast<unsigned>(ncb) * static_cast<unsigned>(len));
-            if (d.t16) hipLaunchKernelGGL((emb_rank_dpos<T, true>), rgrid, dim3(256), 0, s, partial, tokens, rows, plan.ntiles, plan.span_tiles,
+            if (d.on) hipLaunchKernelGGL((emb_rank_dpos<T, true>), rgrid, dim3(256), 0, s, partial, tokens, rows, plan.ntiles, plan.span_tiles,
                                           static_cast<int>(rank_blocks), dp, g, batch, len, ppr, ncb, vocab, pad_idx, d);
             else hipLaunchKernelGGL((emb_rank_dpos<T, false>), rgrid, dim3(256), 0, s, partial, tokens, rows, plan.ntiles, plan.span_tiles,
                                     static_cast<int>(rank_blocks), dp, g, batch, len, ppr, ncb, vocab, pad_idx, d);
@@ -679,14 +679,14 @@ static lsq_status emb_bwd_dispatch(void* demb, void* dpos, const void* dy, const
         }
         if (packed && dp) {            // the position gradient on its own (no rank workgroups in the launch)
             const dim3 rgrid(static_cast<unsigned>(ncb) * static_cast<unsigned>(len));
-            if (d.t16) hipLaunchKernelGGL((emb_rank_dpos<T, true>), rgrid, dim3(256), 0, s, partial, tokens, rows, 1, 1, 0, dp, g, batch, len, ppr, ncb, vocab, pad_idx, d);
+            if (d.on) hipLaunchKernelGGL((emb_rank_dpos<T, true>), rgrid, dim3(256), 0, s, partial, tokens, rows, 1, 1, 0, dp, g, batch, len, ppr, ncb, vocab, pad_idx, d);
             else hipLaunchKernelGGL((emb_rank_dpos<T, false>), rgrid, dim3(256), 0, s, partial, tokens, rows, 1, 1, 0, dp, g, batch, len, ppr, ncb, vocab, pad_idx, d);
         }
     }
     if (packed) {
         const unsigned pairs = static_cast<unsigned>(plan.nwin * ncb);      // (window, column block) pairs
         const dim3 grid(static_cast<unsigned>(ceil_div(pairs, 4))), block(256);   // one wave per pair
-        if (d.t16) hipLaunchKernelGGL((emb_accumulate<T, true>), grid, block, 0, s, de, win_rows, g, order, rows, plan.nwin, ncb, ppr, scale, d);
+        if (d.on) hipLaunchKernelGGL((emb_accumulate<T, true>), grid, block, 0, s, de, win_rows, g, order, rows, plan.nwin, ncb, ppr, scale, d);
         else hipLaunchKernelGGL((emb_accumulate<T, false>), grid, block, 0, s, de, win_rows, g, order, rows, plan.nwin, ncb, ppr, scale, d);
         hipLaunchKernelGGL((emb_combine<T>), dim3(pairs), block, 0, s, de, win_rows, order, rows, ncb, ppr, scale);   // one workgroup per pair
     } else {

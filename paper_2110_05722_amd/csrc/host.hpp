@@ -29,6 +29,7 @@ inline bool make_dropout(float p, uint64_t seed, uint64_t offset, DropoutParams*
     d->ctr2 = static_cast<uint32_t>(offset);
     d->ctr3 = static_cast<uint32_t>(offset >> 32);
     d->t16 = p == 0.0f ? 0u : static_cast<uint32_t>(t);
+    d->on = p > 0.0f ? 1u : 0u;
     d->scale = static_cast<float>(1.0 / (1.0 - static_cast<double>(p)));
     return true;
 }

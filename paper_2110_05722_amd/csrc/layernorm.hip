@@ -650,7 +650,7 @@ static lsq_status ln_fwd_dispatch(void* y, float* mean, float* rstd, const void*
 #define X(L, V)                                                                                              \
     if (sh.lpr == L && sh.vpl == V) {                                                                        \
         if (!fuse) hipLaunchKernelGGL((ln_fwd_kernel<T, L, V>), grid, block, 0, s, yp, mean, rstd, xp, gp, bp, rows, hidden, eps, none); \
-        else if (fuse->d.t16) hipLaunchKernelGGL((ln_fwd_kernel<T, L, V, true, true>), grid, block, 0, s, yp, mean, rstd, xp, gp, bp, rows, hidden, eps, *fuse); \
+        else if (fuse->d.on) hipLaunchKernelGGL((ln_fwd_kernel<T, L, V, true, true>), grid, block, 0, s, yp, mean, rstd, xp, gp, bp, rows, hidden, eps, *fuse); \
         else hipLaunchKernelGGL((ln_fwd_kernel<T, L, V, true, false>), grid, block, 0, s, yp, mean, rstd, xp, gp, bp, rows, hidden, eps, *fuse); \
     }
     LSQ_LN_CASES_COMMON(X) X(32, 3) X(32, 5) X(256, 6) X(256, 8)
@@ -669,15 +669,20 @@ static lsq_status ln_bwd_wide(T* dxp, float* partial, const T* dyp, const T* xp,
     const size_t shmem = sizeof(float) * 16 * ((hidden / kPack) | 1);
     auto* kres = &ln_bwd_kernel<T, L, V, true, TH, false, false, true>;
     auto* kplain = &ln_bwd_kernel<T, L, V, false, TH, false, false, true>;
-    static bool ready[2][64] = {};            // per residual variant and device
+    // once per residual variant and device (a host-side note, guarded for concurrent host threads)
+    static std::mutex mu;
+    static bool ready[2][64] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return LSQ_LAUNCH_FAILED;
     const bool known = dev >= 0 && dev < 64;
-    if (!known || !ready[rp ? 1 : 0][dev]) {
-        if (hipFuncSetAttribute(rp ? reinterpret_cast<const void*>(kres) : reinterpret_cast<const void*>(kplain),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) != hipSuccess)
-            return LSQ_LAUNCH_FAILED;
-        if (known) ready[rp ? 1 : 0][dev] = true;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (!known || !ready[rp ? 1 : 0][dev]) {
+            if (hipFuncSetAttribute(rp ? reinterpret_cast<const void*>(kres) : reinterpret_cast<const void*>(kplain),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) != hipSuccess)
+                return LSQ_LAUNCH_FAILED;
+            if (known) ready[rp ? 1 : 0][dev] = true;
+        }
     }
     if (rp) hipLaunchKernelGGL(kres, dim3(P), dim3(TH), shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, nofuse);
     else hipLaunchKernelGGL(kplain, dim3(P), dim3(TH), shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, nofuse);
@@ -732,7 +737,7 @@ static lsq_status ln_bwd_dispatch(void* dx, float* dgamma, float* dbeta, const v
         if (!fuse) {                                                                                         \
             if (rp) hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, true, TH>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, none); \
             else hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, false, TH>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, none);   \
-        } else if (fuse->d.t16) {                                                                            \
+        } else if (fuse->d.on) {                                                                            \
             if (rp) hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, true, TH, true, true>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, *fuse); \
             else hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, false, TH, true, true>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, *fuse);   \
         } else {                                                                                             \

@@ -730,6 +730,9 @@ extern "C" lsq_status lsq_ls_xent_fwd_bwd(float* loss, float* nll, float* lse, f
     if (tokens == 0) return sums ? zero_fill(sums, 3, s) : LSQ_OK;
     LSQ_REQUIRE(loss && lse && dlogits && logits && target);
     LSQ_ALIGNED(dlogits); LSQ_ALIGNED(logits);
+    // in place, the logits are gone by the time the sums are taken: the sum of nll then has to come
+    // from the per-token nll, which the caller must ask for
+    LSQ_REQUIRE(!(sums && !nll && dlogits == logits));
     switch (dt) {
         case LSQ_F16: return xent_fused_dispatch<f16>(loss, nll, lse, sums, dlogits, logits, target, tokens, vocab, alpha, ignore_index, grad_scale, s);
         case LSQ_BF16: return xent_fused_dispatch<bf16>(loss, nll, lse, sums, dlogits, logits, target, tokens, vocab, alpha, ignore_index, grad_scale, s);

@@ -598,7 +598,7 @@ __global__ __launch_bounds__(256) void softmax_bwd_generic(T* dx, const T* dy, c
     float dot = 0.0f;
     for (int j = lane; j < limit; j += 64) {
         float gg = to_f32<T>(dy[ro + j]);
-        if (d.t16) gg *= dropout_factor1(d, static_cast<uint64_t>(ro + j));
+        if (d.on) gg *= dropout_factor1(d, static_cast<uint64_t>(ro + j));
         dot = fmaf(gg, to_f32<T>(y[ro + j]), dot);
     }
     dot = group_sum<64>(dot);
@@ -606,7 +606,7 @@ __global__ __launch_bounds__(256) void softmax_bwd_generic(T* dx, const T* dy, c
         float o = 0.0f;
         if (j < limit) {
             float gg = to_f32<T>(dy[ro + j]);
-            if (d.t16) gg *= dropout_factor1(d, static_cast<uint64_t>(ro + j));
+            if (d.on) gg *= dropout_factor1(d, static_cast<uint64_t>(ro + j));
             o = g.scale * to_f32<T>(y[ro + j]) * (gg - dot);
         }
         dx[ro + j] = from_f32<T>(o);
@@ -673,7 +673,7 @@ static lsq_status softmax_fwd_dispatch(void* y, void* yd, const void* x, Softmax
     const T* xp = static_cast<const T*>(x);
     const bool packs_ok = g.k_len % kPack == 0 && aligned16(y) && aligned16(yd) && aligned16(x);
     const SmShape sh = packs_ok ? softmax_shape(g.k_len) : SmShape{0, 0};
-    const bool drop = d.t16 != 0;
+    const bool drop = d.on != 0;
     const SmShape es = softmax_elem_shape(g.k_len);
     if (sh.lpr == 0 && es.lpr != 0) {
         const dim3 egrid(static_cast<unsigned>(ceil_div(g.nrows, 256 / es.lpr)));
@@ -728,7 +728,7 @@ static lsq_status softmax_bwd_dispatch(void* dx, const void* dy, const void* y, 
     const T* yp = static_cast<const T*>(y);
     const bool packs_ok = g.k_len % kPack == 0 && aligned16(dx) && aligned16(dy) && aligned16(y);
     const SmShape sh = packs_ok ? softmax_shape(g.k_len) : SmShape{0, 0};
-    const bool drop = d.t16 != 0;
+    const bool drop = d.on != 0;
     const SmShape es = softmax_elem_shape(g.k_len);
     if (sh.lpr == 0 && es.lpr != 0) {
         const dim3 egrid(static_cast<unsigned>(ceil_div(g.nrows, 256 / es.lpr)));
@@ -808,7 +808,7 @@ extern "C" lsq_status lsq_softmax_varlen_fwd(void* y, void* y_drop, const void* 
     g.causal = causal != 0;
     DropoutParams d;
     LSQ_REQUIRE(make_dropout(p_attn, seed, offset, &d));
-    LSQ_REQUIRE((d.t16 != 0) == (y_drop != nullptr));
+    LSQ_REQUIRE((d.on != 0) == (y_drop != nullptr));
     if (g.nrows == 0 || k_len == 0) return LSQ_OK;
     LSQ_REQUIRE(y && x);
     LSQ_ALIGNED(y); LSQ_ALIGNED(y_drop); LSQ_ALIGNED(x);

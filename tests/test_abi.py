@@ -105,6 +105,7 @@ def test_host_side_argument_errors(lib):
     assert f(A, None, A, None, U, A, A, 4, 8, 0.1, -100, 1.0, 0, None) == MISALIGNED
     assert f(A, None, A, None, A, A, A, 4, 8, 0.1, -100, 1.0, 3, None) == DTYPE
     assert f(None, None, None, None, None, None, None, 0, 8, 0.1, -100, 1.0, 0, None) == 0
+    assert f(A, None, A, A, A, A, A, 4, 8, 0.1, -100, 1.0, 0, None) == INVALID        # in place + sums without nll
 
 
 def test_host_side_argument_errors_of_the_next_rows(lib):

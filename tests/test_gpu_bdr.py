@@ -66,6 +66,37 @@ def test_dropout_mask_is_bit_exact_and_shared_by_fwd_and_bwd(rows, hidden, p):
     assert torch.all((fwd == 0) | (fwd == scale))
 
 
+def test_dropout_rate_below_the_16_bit_grid_keeps_everything_and_still_scales():
+    """p < 2^-17 rounds to T16 = 0: every element is kept, the nominal 1/(1-p) is still applied (oracle: same)."""
+    say("[bias_dropout_residual] p = 2^-18")
+    dt, d, p = "f32", dev(), 2.0 ** -18
+    t = _case(64, 264, dt)
+    x, bias, res, dy = (to_torch(t[k], dt, d) for k in ("x", "bias", "residual", "dy"))
+    out = L.lsq_bias_dropout_residual_fwd(x, bias, res, p, 5, 0)
+    assert_close_store(out, oracle.bias_dropout_residual_fwd(t["x"], t["bias"], t["residual"], p, 5, 0, dt), dt, "out")
+    dx, dbias = L.lsq_bias_dropout_residual_bwd(dy, p, 5, 0)
+    rdx, rdb = oracle.bias_dropout_residual_bwd(t["dy"], p, 5, 0, dt)
+    assert_close_store(dx, rdx, dt, "dx")
+    scale = torch.tensor(1.0 / (1.0 - p), dtype=torch.float32, device=d)
+    assert torch.equal(dx, dy * scale)                       # all kept, all scaled
+    # the softmax takes y_drop for any p > 0
+    sx = torch.randn((2, 2, 8, 16), device=d).half()
+    y, yd = L.lsq_softmax_fwd(sx, None, False, 1.0, p, 5, 0)
+    assert torch.allclose(yd.float(), y.float() * scale, rtol=2e-3, atol=1e-6) and bool((yd > 0).all())
+
+
+def test_bdr_generic_in_place_sums_columns_before_it_overwrites_dy():
+    say("[bias_dropout_residual] in place, hidden 257 (generic path)")
+    dt, d = "f16", dev()
+    t = _case(300, 257, dt)
+    dy = to_torch(t["dy"], dt, d)
+    dyc = dy.clone()
+    dx, dbias = L.lsq_bias_dropout_residual_bwd(dyc, 0.25, 11, 3, dx=dyc)
+    rdx, rdb = oracle.bias_dropout_residual_bwd(t["dy"], 0.25, 11, 3, dt)
+    assert_close_store(dx, rdx, dt, "dx in place")
+    assert_close_f32(dbias, rdb, "dbias in place", floor=4e-6 * np.sqrt(300) * 8)
+
+
 def test_bdr_in_place_and_reproducible():
     say("[bias_dropout_residual] in place / reproducible")
     dt, d = "f16", dev()

@@ -58,6 +58,17 @@ def _run(t, T, V, alpha, dt, grad_scale=1.0):
     out = L.lsq_ls_xent_fwd_bwd(lc, target, alpha, IGNORE_INDEX, grad_scale, want_sums=False, want_nll=False, dlogits=lc)
     assert out[1] is None and out[3] is None
     assert torch.equal(out[4], fdl) and torch.equal(out[0], floss) and torch.equal(out[2], flse)
+    # in place WITH sums: the sum of nll must come from the per-token nll (the logits are gone by then);
+    # without nll the call is refused
+    lc = logits.clone()
+    out = L.lsq_ls_xent_fwd_bwd(lc, target, alpha, IGNORE_INDEX, grad_scale, want_sums=True, want_nll=True, dlogits=lc)
+    assert torch.equal(out[3], fsums) and torch.equal(out[4], fdl)
+    lc = logits.clone()
+    with pytest.raises(L.LsqError, match="INVALID_ARG"):
+        L.lsq_ls_xent_fwd_bwd(lc, target, alpha, IGNORE_INDEX, grad_scale, want_sums=True, want_nll=False, dlogits=lc)
+    assert torch.equal(lc, logits)                                              # refused before any launch
+    out = L.lsq_ls_xent_fwd_bwd(logits, target, alpha, IGNORE_INDEX, grad_scale, want_sums=True, want_nll=False)
+    assert_close_f32(out[3], rsums, "one-pass sums without nll, out of place", floor=1e-5)
     return loss, lse, sums
 
 
