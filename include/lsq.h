@@ -454,6 +454,14 @@ lsq_status lsq_softmax_varlen_bwd(void* dx, const void* dy, const void* y, const
                                   int32_t k_len, int32_t causal, float scale, float p_attn,
                                   uint64_t seed, uint64_t offset, lsq_dtype dt, void* stream);
 
+/* Measurement aid, not an operator: a plain memory stream in the operators' launch style (128-bit
+ * nontemporal accesses, one pack per thread), which the benchmark times beside the operators at the
+ * operators' tensor sizes (the calibration ceiling).  kind 0: copy `bytes` from src to dst;
+ * kind 1: read `bytes` of src (dst: 4 bytes that are written only if a pack of src equals an
+ * unlikely constant); kind 2: write `bytes` of a constant to dst; kind 3: an empty kernel (launch
+ * cost).  bytes: a multiple of 16. */
+lsq_status lsq_calib_stream(int32_t kind, void* dst, const void* src, int64_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

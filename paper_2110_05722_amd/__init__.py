@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     lsq_trainer_state_unpack,
     lsq_adam_step_lp,
     lsq_bdr_layernorm_bwd,
+    lsq_calib_stream,
     lsq_bdr_layernorm_fwd,
     lsq_bias_act_dropout_bwd,
     lsq_bias_act_dropout_fwd,
@@ -55,7 +56,7 @@ from .binding import (  # noqa: F401
 __all__ = [
     "LsqError", "lib_path", "load", "lsq_adam_state_bytes", "lsq_adam_state_pack", "lsq_adam_state_unpack", "lsq_adam_step",
     "lsq_adam_step_blocked", "lsq_adam_step_lp", "lsq_adam_step_lp_blocked", "lsq_sgd_step_blocked",
-    "lsq_trainer_state_bytes", "lsq_trainer_state_pack", "lsq_trainer_state_unpack", "lsq_bdr_layernorm_bwd", "lsq_bdr_layernorm_fwd", "lsq_bias_act_dropout_bwd",
+    "lsq_trainer_state_bytes", "lsq_trainer_state_pack", "lsq_trainer_state_unpack", "lsq_bdr_layernorm_bwd", "lsq_bdr_layernorm_fwd", "lsq_calib_stream", "lsq_bias_act_dropout_bwd",
     "lsq_bias_act_dropout_fwd", "lsq_sgd_step", "lsq_bias_dropout_residual_bwd",
     "lsq_bias_dropout_residual_fwd", "lsq_embedding_bwd", "lsq_embedding_fwd", "lsq_layernorm_bwd", "lsq_layernorm_bwd_noalloc", "lsq_layernorm_fwd", "lsq_ls_xent_bwd",
     "lsq_ls_xent_fwd_bwd",    "lsq_ls_xent_fwd", "lsq_merge_heads_bwd", "lsq_merge_heads_fwd", "lsq_split_heads_bwd", "lsq_split_heads_fwd",

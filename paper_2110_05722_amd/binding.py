@@ -36,6 +36,7 @@ EXPORTS = [
     "lsq_trainer_state_bytes", "lsq_trainer_state_pack", "lsq_trainer_state_unpack", "lsq_sgd_step_blocked",
     "lsq_adam_step_lp_blocked",
     "lsq_pad_offsets", "lsq_pad_remove", "lsq_pad_restore", "lsq_softmax_varlen_fwd", "lsq_softmax_varlen_bwd",
+    "lsq_calib_stream",
 ]
 
 
@@ -63,6 +64,7 @@ def load():
         "lsq_layernorm_fwd": (C.c_int, [vp, vp, vp, vp, vp, vp, i64, i32, f32, C.c_int, vp]),
         "lsq_layernorm_bwd": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, i64, i32, C.c_int, vp]),
         "lsq_layernorm_bwd_noalloc": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, C.c_int, vp]),
+        "lsq_calib_stream": (C.c_int, [i32, vp, vp, i64, vp]),
         "lsq_bias_dropout_residual_fwd": (C.c_int, [vp, vp, vp, vp, i64, i32, f32, u64, u64, C.c_int, vp]),
         "lsq_bias_dropout_residual_bwd": (C.c_int, [vp, vp, vp, i64, i32, f32, u64, u64, vp, sz, C.c_int, vp]),
         "lsq_softmax_fwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64, C.c_int, vp]),
@@ -655,3 +657,9 @@ def lsq_softmax_varlen_bwd(dy, y, key_len=None, query_len=None, causal: bool = F
                                          int(causal), scale, p_attn, seed, offset, _dt(y), _stream()),
            "lsq_softmax_varlen_bwd")
     return dx
+
+
+def lsq_calib_stream(kind: str, dst, src=None, nbytes: int = 0):
+    """A plain memory stream (measurement aid): kind = "copy" | "read" | "write" | "empty"."""
+    k = {"copy": 0, "read": 1, "write": 2, "empty": 3}[kind]
+    _check(load().lsq_calib_stream(k, _ptr(dst), _ptr(src), nbytes, _stream()), "lsq_calib_stream")

@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblsq.so")
 OBJ_DIR = os.path.join(HERE, "_build", "liblsq.so")
-SOURCES = ["api", "adam", "bias_dropout_residual", "bias_act_dropout", "heads", "embedding", "pad", "layernorm", "softmax",
+SOURCES = ["api", "calibrate", "adam", "bias_dropout_residual", "bias_act_dropout", "heads", "embedding", "pad", "layernorm", "softmax",
            "ls_xent"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -1,0 +1,53 @@
+// Plain memory streams in the launch style of the operators (128-bit nontemporal accesses, one
+// pack per thread, 256-thread workgroups): what the machine gives a kernel that does nothing but
+// move bytes.  The benchmark times them next to the operators, at the operators' tensor sizes.
+#include "host.hpp"
+
+namespace lsq {
+
+__global__ __launch_bounds__(256) void calib_copy_kernel(uvec4* __restrict__ dst, const uvec4* __restrict__ src, int64_t n)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < n) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+// Reads everything, writes (practically) nothing: a pack whose four words all equal an unlikely
+// constant would be reported to `sink`, which keeps the loads alive.
+__global__ __launch_bounds__(256) void calib_read_kernel(const uvec4* __restrict__ src, int64_t n, uint32_t* sink)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= n) return;
+    const uvec4 v = __builtin_nontemporal_load(src + i);
+    if (v.x == 0x9E3779B9u && v.y == 0x7F4A7C15u && v.z == 0xF39CC060u && v.w == 0x5CEDC834u) *sink = 1u;
+}
+
+__global__ __launch_bounds__(256) void calib_write_kernel(uvec4* __restrict__ dst, int64_t n, uint32_t word)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < n) __builtin_nontemporal_store(uvec4{word, word, word, word}, dst + i);
+}
+
+__global__ void calib_empty_kernel() {}
+
+}  // namespace lsq
+
+extern "C" lsq_status lsq_calib_stream(int32_t kind, void* dst, const void* src, int64_t bytes, void* stream)
+{
+    using namespace lsq;
+    LSQ_REQUIRE(kind >= 0 && kind <= 3 && bytes >= 0 && bytes % 16 == 0);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (kind == 3) {
+        hipLaunchKernelGGL(calib_empty_kernel, dim3(1), dim3(64), 0, s);
+        return launch_status();
+    }
+    if (bytes == 0) return LSQ_OK;
+    LSQ_REQUIRE(dst && (kind == 2 || src));
+    LSQ_ALIGNED(dst); LSQ_ALIGNED(src);
+    const int64_t n = bytes / 16;
+    LSQ_REQUIRE(ceil_div(n, 256) <= 0x7FFFFFFF);
+    const dim3 grid(static_cast<unsigned>(ceil_div(n, 256))), block(256);
+    if (kind == 0) hipLaunchKernelGGL(calib_copy_kernel, grid, block, 0, s, static_cast<uvec4*>(dst), static_cast<const uvec4*>(src), n);
+    else if (kind == 1) hipLaunchKernelGGL(calib_read_kernel, grid, block, 0, s, static_cast<const uvec4*>(src), n, static_cast<uint32_t*>(dst));
+    else hipLaunchKernelGGL(calib_write_kernel, grid, block, 0, s, static_cast<uvec4*>(dst), n, 0x3C003C00u);
+    return launch_status();
+}
