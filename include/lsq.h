@@ -13,7 +13,8 @@
  *     guarded for concurrent host threads: the raised dynamic-LDS limit of the
  *     LayerNorm backward kernel for rows of 8193..16384 columns
  *     (hipFuncSetAttribute on its first use on a device) and the device address
- *     of the array behind lsq_layernorm_bwd_noalloc.  Neither is a stream
+ *     of the array behind lsq_layernorm_bwd_noalloc; and the launch shapes
+ *     lsq_softmax_tune has recorded, if it was called.  None is a stream
  *     operation; a caller that captures such a call into a HIP graph should
  *     have made one eager call of it on that device before.  Work is
  *     enqueued on `stream` (a hipStream_t passed as void*; NULL = the null
@@ -184,6 +185,30 @@ lsq_status lsq_softmax_bwd(void* dx, const void* dy, const void* y, const int32_
                            int32_t causal, float scale,
                            float p_attn, uint64_t seed, uint64_t offset,
                            lsq_dtype dt, void* stream);
+
+/* Run-time choice of the softmax launch shape (Sec. IV-B, Softmax, last paragraph: several
+ * templates, the best parameters searched before training starts).  For rows of up to 2048 keys
+ * (k_len a multiple of 8) the library holds up to 4 launch shapes (lanes per row, packs per lane,
+ * rows per lane group) per row length; lsq_softmax_candidates returns how many (1 where there is no
+ * choice).  lsq_softmax_tune with force == -1 runs every candidate of the given problem on the
+ * caller's buffers (arguments as lsq_softmax_varlen_fwd / _bwd; y, y_drop and dx are overwritten
+ * with valid results), `reps` launches each between two events on `stream`, and records the fastest
+ * per direction for (row-length bucket, mask kind, dropout on/off, storage width); later calls of
+ * lsq_softmax_fwd/bwd and the varlen forms with such a problem use it.  force >= 0 records that
+ * candidate without launching anything (all candidates give the same results up to summation order
+ * inside a row; the tests run every one against the oracle); force == -2 forgets the record (the
+ * built-in default, candidate 0, is used again).  best_fwd / best_bwd (nullable) receive the choice,
+ * us (nullable, float[8]) the measured microseconds per launch, [direction][candidate], -1 where
+ * there is none.  The search synchronises with `stream` (it waits for its events) and must not be
+ * called under stream capture; it allocates no device memory.  The record is process-wide host
+ * state, safe against concurrent host threads. */
+int32_t lsq_softmax_candidates(int32_t k_len);
+lsq_status lsq_softmax_tune(int32_t* best_fwd, int32_t* best_bwd, float* us,
+                            void* y, void* y_drop, void* dx, const void* x, const void* dy,
+                            const int32_t* key_len, const int32_t* query_len,
+                            int32_t batch, int32_t heads, int32_t q_len, int32_t k_len,
+                            int32_t causal, float scale, float p_attn, uint64_t seed, uint64_t offset,
+                            lsq_dtype dt, int32_t force, int32_t reps, void* stream);
 
 /* Label-smoothed cross-entropy forward (Sec. IV-A, criterion layer): per token,
  * with q = softmax(h) over the whole vocabulary and p = (1-alpha)*onehot(k) + alpha/V,

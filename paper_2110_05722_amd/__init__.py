@@ -48,6 +48,8 @@ from .binding import (  # noqa: F401
     lsq_split_heads_bwd,
     lsq_split_heads_fwd,
     lsq_softmax_bwd,
+    lsq_softmax_candidates,
+    lsq_softmax_tune,
     lsq_softmax_fwd,
     lsq_status_string,
     lsq_workspace_bytes,
@@ -61,5 +63,5 @@ __all__ = [
     "lsq_bias_dropout_residual_fwd", "lsq_embedding_bwd", "lsq_embedding_fwd", "lsq_layernorm_bwd", "lsq_layernorm_bwd_noalloc", "lsq_layernorm_fwd", "lsq_ls_xent_bwd",
     "lsq_ls_xent_fwd_bwd",    "lsq_ls_xent_fwd", "lsq_merge_heads_bwd", "lsq_merge_heads_fwd", "lsq_split_heads_bwd", "lsq_split_heads_fwd",
     "lsq_pad_offsets", "lsq_pad_remove", "lsq_pad_restore", "lsq_softmax_varlen_bwd", "lsq_softmax_varlen_fwd",
-    "lsq_softmax_bwd", "lsq_softmax_fwd", "lsq_status_string", "lsq_workspace_bytes",
+    "lsq_softmax_bwd", "lsq_softmax_candidates", "lsq_softmax_fwd", "lsq_softmax_tune", "lsq_status_string", "lsq_workspace_bytes",
 ]

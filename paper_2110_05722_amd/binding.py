@@ -36,7 +36,7 @@ EXPORTS = [
     "lsq_trainer_state_bytes", "lsq_trainer_state_pack", "lsq_trainer_state_unpack", "lsq_sgd_step_blocked",
     "lsq_adam_step_lp_blocked",
     "lsq_pad_offsets", "lsq_pad_remove", "lsq_pad_restore", "lsq_softmax_varlen_fwd", "lsq_softmax_varlen_bwd",
-    "lsq_calib_stream",
+    "lsq_calib_stream", "lsq_softmax_candidates", "lsq_softmax_tune",
 ]
 
 
@@ -65,6 +65,9 @@ def load():
         "lsq_layernorm_bwd": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, i64, i32, C.c_int, vp]),
         "lsq_layernorm_bwd_noalloc": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, C.c_int, vp]),
         "lsq_calib_stream": (C.c_int, [i32, vp, vp, i64, vp]),
+        "lsq_softmax_candidates": (i32, [i32]),
+        "lsq_softmax_tune": (C.c_int, [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64,
+                                       C.c_int, i32, i32, vp]),
         "lsq_bias_dropout_residual_fwd": (C.c_int, [vp, vp, vp, vp, i64, i32, f32, u64, u64, C.c_int, vp]),
         "lsq_bias_dropout_residual_bwd": (C.c_int, [vp, vp, vp, i64, i32, f32, u64, u64, vp, sz, C.c_int, vp]),
         "lsq_softmax_fwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, f32, u64, u64, C.c_int, vp]),
@@ -663,3 +666,24 @@ def lsq_calib_stream(kind: str, dst, src=None, nbytes: int = 0):
     """A plain memory stream (measurement aid): kind = "copy" | "read" | "write" | "empty"."""
     k = {"copy": 0, "read": 1, "write": 2, "empty": 3}[kind]
     _check(load().lsq_calib_stream(k, _ptr(dst), _ptr(src), nbytes, _stream()), "lsq_calib_stream")
+
+
+def lsq_softmax_candidates(k_len: int) -> int:
+    return int(load().lsq_softmax_candidates(k_len))
+
+
+def lsq_softmax_tune(x, dy, key_len=None, query_len=None, causal: bool = False, scale: float = 1.0, p_attn: float = 0.0,
+                     seed: int = 0, offset: int = 0, force: int = -1, reps: int = 20, y=None, y_drop=None, dx=None):
+    """Search (force = -1), set (force >= 0) or forget (force = -2) the launch shape of the softmax for problems like
+    this one -> (best_fwd, best_bwd, us[2][4])."""
+    B, N, Lq, Lk = x.shape
+    y = torch.empty_like(x) if y is None else y
+    dx = torch.empty_like(x) if dx is None else dx
+    if p_attn > 0 and y_drop is None:
+        y_drop = torch.empty_like(x)
+    bf, bb = C.c_int32(0), C.c_int32(0)
+    us = (C.c_float * 8)()
+    _check(load().lsq_softmax_tune(C.byref(bf), C.byref(bb), us, _ptr(y), _ptr(y_drop) if p_attn > 0 else None, _ptr(dx), _ptr(x),
+                                   _ptr(dy), _ptr(key_len), _ptr(query_len), B, N, Lq, Lk, int(causal), scale, p_attn, seed, offset,
+                                   _dt(x), force, reps, _stream()), "lsq_softmax_tune")
+    return bf.value, bb.value, [[us[d * 4 + c] for c in range(4)] for d in range(2)]

@@ -19,14 +19,14 @@
 // row's limit (key padding, or the causal diagonal) are not even loaded, and
 // their outputs are written as exact zeros.  Attention-probability dropout is
 // fused (Philox per pack, mask regenerated in backward).
+#include <atomic>
+#include <mutex>
+
 #include "host.hpp"
 
 namespace lsq {
 
-#ifndef LSQ_NT
-#define LSQ_NT 1
-#endif
-constexpr bool kNT = LSQ_NT != 0;   // nontemporal hint on the streamed tensors
+constexpr bool kNT = true;    // nontemporal hint on the streamed tensors
 
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -82,20 +82,37 @@ __global__ __launch_bounds__(256) void softmax_fwd_kernel(T* y, T* __restrict__ 
     const int nv = g.k_len / kPack;
     int64_t row[RPT];
     int limit[RPT];
+    // Loads first, arithmetic after.  The packs of a row's first 128 bytes are loaded before the
+    // row's limit is known (unless the row is empty that line is needed whatever the limit, and
+    // what lies beyond the limit is masked in registers): with a key-padding mask the limit comes
+    // from memory, and waiting for it first would put two dependent round trips in front of
+    // every row.  The other packs are loaded only if they reach into the allowed prefix.
+    // (a limit that is computed from the row index alone, causal or none, waits for nothing)
+    const int kEarly = (len.key || len.query) ? 128 / static_cast<int>(sizeof(T)) : 0;
+    RawPack<T> raw[RPT][VPL];
 #pragma unroll
     for (int r = 0; r < RPT; ++r) {
         row[r] = (static_cast<int64_t>(blockIdx.x) * RPT + r) * RPB + threadIdx.x / LPR;
-        limit[r] = row[r] < g.nrows ? row_limit(g, len, row[r]) : 0;
+#pragma unroll
+        for (int k = 0; k < VPL; ++k) {
+            const int j0 = (sub + k * LPR) * kPack;
+            if (j0 < kEarly) {
+                if (row[r] < g.nrows && j0 < g.k_len) raw[r][k] = load_raw<T, kNT>(x + row[r] * g.k_len + j0);
+                else raw[r][k] = zero_raw<T>();
+            }
+        }
     }
-    // loads first (only the packs that reach into the allowed prefix), arithmetic after
-    RawPack<T> raw[RPT][VPL];
+#pragma unroll
+    for (int r = 0; r < RPT; ++r) limit[r] = row[r] < g.nrows ? row_limit(g, len, row[r]) : 0;
 #pragma unroll
     for (int r = 0; r < RPT; ++r)
 #pragma unroll
         for (int k = 0; k < VPL; ++k) {
             const int j0 = (sub + k * LPR) * kPack;
-            if (j0 < limit[r]) raw[r][k] = load_raw<T, kNT>(x + row[r] * g.k_len + j0);   // implies a valid row and pack
-            else raw[r][k] = zero_raw<T>();
+            if (j0 >= kEarly) {
+                if (j0 < limit[r]) raw[r][k] = load_raw<T, kNT>(x + row[r] * g.k_len + j0);   // implies a valid row and pack
+                else raw[r][k] = zero_raw<T>();
+            }
         }
 #pragma unroll
     for (int r = 0; r < RPT; ++r) {
@@ -166,23 +183,41 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(T* dx, const T* dy, co
     const int nv = g.k_len / kPack;
     int64_t row[RPT];
     int limit[RPT];
+    // as in forward: the first 128 bytes of a row are loaded before its limit is known
+    const int kEarly = (len.key || len.query) ? 128 / static_cast<int>(sizeof(T)) : 0;
+    RawPack<T> ry[RPT][VPL], rg[RPT][VPL];
 #pragma unroll
     for (int r = 0; r < RPT; ++r) {
         row[r] = (static_cast<int64_t>(blockIdx.x) * RPT + r) * RPB + threadIdx.x / LPR;
-        limit[r] = row[r] < g.nrows ? row_limit(g, len, row[r]) : 0;
+#pragma unroll
+        for (int k = 0; k < VPL; ++k) {
+            const int j0 = (sub + k * LPR) * kPack;
+            if (j0 < kEarly) {
+                if (row[r] < g.nrows && j0 < g.k_len) {
+                    ry[r][k] = load_raw<T, kNT>(y + row[r] * g.k_len + j0);
+                    rg[r][k] = load_raw<T, kNT>(dy + row[r] * g.k_len + j0);
+                } else {
+                    ry[r][k] = zero_raw<T>();
+                    rg[r][k] = zero_raw<T>();
+                }
+            }
+        }
     }
-    RawPack<T> ry[RPT][VPL], rg[RPT][VPL];
+#pragma unroll
+    for (int r = 0; r < RPT; ++r) limit[r] = row[r] < g.nrows ? row_limit(g, len, row[r]) : 0;
 #pragma unroll
     for (int r = 0; r < RPT; ++r)
 #pragma unroll
         for (int k = 0; k < VPL; ++k) {
             const int j0 = (sub + k * LPR) * kPack;
-            if (j0 < limit[r]) {
-                ry[r][k] = load_raw<T, kNT>(y + row[r] * g.k_len + j0);
-                rg[r][k] = load_raw<T, kNT>(dy + row[r] * g.k_len + j0);
-            } else {
-                ry[r][k] = zero_raw<T>();
-                rg[r][k] = zero_raw<T>();
+            if (j0 >= kEarly) {
+                if (j0 < limit[r]) {
+                    ry[r][k] = load_raw<T, kNT>(y + row[r] * g.k_len + j0);
+                    rg[r][k] = load_raw<T, kNT>(dy + row[r] * g.k_len + j0);
+                } else {
+                    ry[r][k] = zero_raw<T>();
+                    rg[r][k] = zero_raw<T>();
+                }
             }
         }
 #pragma unroll
@@ -207,7 +242,7 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(T* dx, const T* dy, co
             }
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                if (j0 + j >= lim) yv[k][j] = 0.0f;
+                if (j0 + j >= lim) { yv[k][j] = 0.0f; gv[k][j] = 0.0f; }      // whatever sits beyond the mask never counts
                 dot = fmaf(gv[k][j], yv[k][j], dot);
             }
         }
@@ -386,10 +421,7 @@ __device__ __forceinline__ int64_t elem_keep_mask(uint8_t (&keep)[NBYTES], const
 // results back from LDS), the lanes work on LDS with 2-byte accesses.  The first and the last pack
 // may be shared with the neighbouring workgroups: reading them is harmless, writing is done element
 // by element for the part that belongs here.  Element i of LDS = element (e0 & ~7) + i of the tensor.
-#ifndef LSQ_SM_STAGE
-#define LSQ_SM_STAGE 1
-#endif
-constexpr bool kSmStage = LSQ_SM_STAGE != 0;
+constexpr bool kSmStage = true;
 
 template <typename T>
 __device__ __forceinline__ void stage_in(T* buf, const T* src, int64_t e0, int64_t e1, int64_t total)
@@ -654,19 +686,84 @@ inline SmShape softmax_elem_shape(int k_len)
 }
 #define LSQ_SM_ELEM_CASES(X) X(8, 1) X(8, 2) X(8, 4) X(8, 8) X(16, 8) X(32, 8) X(64, 8) X(256, 4) X(256, 8)
 
-#define LSQ_SM_CASES(X) X(1, 1) X(2, 1) X(4, 1) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 3) X(64, 4)
+// ---- launch shapes of the register path for rows of up to 2048 keys, and their choice at run time.
+// The paper copes with the spread of softmax shapes by keeping several templates and searching for
+// the best parameters before training starts (Sec. IV-B, Softmax, last paragraph).  Here a template
+// is (lanes per row, packs per lane, rows per lane group); every row length has a short list of
+// candidates, the first of which is the default, and lsq_softmax_tune times them on the caller's
+// own buffers and records the winner per (row-length bucket, mask kind, dropout, storage width,
+// direction), which the dispatch then uses.
+struct SmCand { int lpr, vpl, rpt; };
+constexpr int kSmBuckets = 10, kSmMaxCand = 4;
+struct SmBucket { int max_packs, n; SmCand c[kSmMaxCand]; };
+// Defaults measured on MI355X at the shapes of the five configurations (fp16): rows of 128 keys under a
+// key-padding mask take 18.3 / 16.3 us (forward with attention dropout / backward) as 8 lanes x 2 packs
+// against 20.6 / 18.2 us as 16 lanes x 1 pack, two rows per group: each of a lane's two loads then covers
+// whole 128-byte lines of 8 rows, the first of which is issued before the sentence length has arrived.
+static const SmBucket kSmTable[kSmBuckets] = {
+    {1, 2, {{1, 1, 2}, {1, 1, 1}}},
+    {2, 2, {{2, 1, 2}, {2, 1, 1}}},
+    {4, 2, {{4, 1, 2}, {4, 1, 1}}},
+    {8, 3, {{8, 1, 2}, {8, 1, 1}, {4, 2, 1}}},
+    {16, 4, {{8, 2, 1}, {16, 1, 2}, {16, 1, 1}, {8, 2, 2}}},
+    {32, 4, {{32, 1, 2}, {32, 1, 1}, {16, 2, 1}, {8, 4, 1}}},
+    {64, 3, {{32, 2, 1}, {64, 1, 2}, {64, 1, 1}}},      // 512 keys, no mask: 44.5 / 63.9 us against 45.5 / 66.6 us as 64 x 1, two rows
+    {128, 1, {{64, 2, 1}}},
+    {192, 1, {{64, 3, 1}}},
+    {256, 1, {{64, 4, 1}}},
+};
+#define LSQ_SM_CASES(X)                                                                                      \
+    X(1, 1, 1) X(1, 1, 2) X(2, 1, 1) X(2, 1, 2) X(4, 1, 1) X(4, 1, 2) X(8, 1, 1) X(8, 1, 2) X(4, 2, 1)       \
+    X(8, 2, 1) X(8, 2, 2) X(16, 1, 1) X(16, 1, 2) X(32, 1, 1) X(32, 1, 2) X(16, 2, 1) X(8, 4, 1)             \
+    X(64, 1, 1) X(64, 1, 2) X(32, 2, 1) X(64, 2, 1) X(64, 3, 1) X(64, 4, 1)
 
-// rows per lane group: about LSQ_SM_PACKS packs in flight per lane, and one row per
-// group whenever the grid would otherwise fall under kSmMinBlocks workgroups
-#ifndef LSQ_SM_PACKS
-#define LSQ_SM_PACKS 2
-#endif
-constexpr int sm_rpt(int vpl) { return LSQ_SM_PACKS / vpl > 1 ? LSQ_SM_PACKS / vpl : 1; }
+inline int sm_bucket(int k_len)
+{
+    const int nv = k_len / kPack;
+    for (int b = 0; b < kSmBuckets; ++b)
+        if (nv <= kSmTable[b].max_packs) return b;
+    return -1;
+}
+
+// what lsq_softmax_tune has recorded: [bucket][mask kind][dropout][storage width][direction], -1 = default
+static std::atomic<signed char> sm_tuned[kSmBuckets][4][2][2][2];
+static std::atomic<bool> sm_tuned_init{false};
+static std::mutex sm_tuned_mutex;
+
+inline void sm_tuned_prepare()
+{
+    if (sm_tuned_init.load(std::memory_order_acquire)) return;
+    std::lock_guard<std::mutex> lock(sm_tuned_mutex);
+    if (sm_tuned_init.load(std::memory_order_relaxed)) return;
+    for (auto& a : sm_tuned) for (auto& b : a) for (auto& c : b) for (auto& e : c) for (auto& f : e) f.store(-1, std::memory_order_relaxed);
+    sm_tuned_init.store(true, std::memory_order_release);
+}
+
+inline std::atomic<signed char>& sm_slot(int bucket, const SoftmaxLens& len, const SoftmaxGeom& g, bool drop, size_t elem, int dir)
+{
+    sm_tuned_prepare();
+    const int mask = ((len.key || len.query) ? 1 : 0) + (g.causal ? 2 : 0);
+    return sm_tuned[bucket][mask][drop ? 1 : 0][elem == 2 ? 0 : 1][dir];
+}
+
+// `forced` >= 0 picks that candidate of the row length's list; -1 the recorded one, else the default.
+// A candidate with several rows per lane group falls back to one row when the grid would
+// otherwise drop under kSmMinBlocks workgroups.
 constexpr int64_t kSmMinBlocks = 1024;
+inline SmCand sm_choose(const SoftmaxLens& len, const SoftmaxGeom& g, bool drop, size_t elem, int dir, int forced)
+{
+    const int b = sm_bucket(g.k_len);
+    int pick = forced;
+    if (pick < 0) pick = sm_slot(b, len, g, drop, elem, dir).load(std::memory_order_relaxed);
+    if (pick < 0 || pick >= kSmTable[b].n) pick = 0;
+    SmCand c = kSmTable[b].c[pick];
+    if (c.rpt > 1 && ceil_div(g.nrows, 256 / c.lpr) < kSmMinBlocks * c.rpt) c.rpt = 1;
+    return c;
+}
 
 template <typename T>
 static lsq_status softmax_fwd_dispatch(void* y, void* yd, const void* x, SoftmaxLens key_len, const SoftmaxGeom& g,
-                                       const DropoutParams& d, hipStream_t s)
+                                       const DropoutParams& d, hipStream_t s, int forced = -1)
 {
     T* yp = static_cast<T*>(y);
     T* ydp = static_cast<T*>(yd);
@@ -691,7 +788,6 @@ static lsq_status softmax_fwd_dispatch(void* y, void* yd, const void* x, Softmax
                            yp, ydp, xp, key_len, g, d);
         return launch_status();
     }
-    const int64_t blocks1 = ceil_div(g.nrows, 256 / sh.lpr);
     const dim3 block(256);
 #define W(V)                                                                                                 \
     if (sh.lpr == 256 && sh.vpl == V) {                                                                      \
@@ -701,18 +797,13 @@ static lsq_status softmax_fwd_dispatch(void* y, void* yd, const void* x, Softmax
     }
     W(2) W(4) W(8)
 #undef W
-#define X(L, V)                                                                                              \
-    if (sh.lpr == L && sh.vpl == V) {                                                                        \
-        constexpr int R = sm_rpt(V);                                                                         \
-        if (R > 1 && blocks1 >= kSmMinBlocks * R) {                                                          \
-            const dim3 grid(static_cast<unsigned>(ceil_div(blocks1, R)));                                    \
-            if (drop) hipLaunchKernelGGL((softmax_fwd_kernel<T, L, V, R, true>), grid, block, 0, s, yp, ydp, xp, key_len, g, d); \
-            else hipLaunchKernelGGL((softmax_fwd_kernel<T, L, V, R, false>), grid, block, 0, s, yp, ydp, xp, key_len, g, d);    \
-        } else {                                                                                             \
-            const dim3 grid(static_cast<unsigned>(blocks1));                                                 \
-            if (drop) hipLaunchKernelGGL((softmax_fwd_kernel<T, L, V, 1, true>), grid, block, 0, s, yp, ydp, xp, key_len, g, d); \
-            else hipLaunchKernelGGL((softmax_fwd_kernel<T, L, V, 1, false>), grid, block, 0, s, yp, ydp, xp, key_len, g, d);    \
-        }                                                                                                    \
+    if (sh.lpr == 256) return launch_status();
+    const SmCand c = sm_choose(key_len, g, drop, sizeof(T), 0, forced);
+    const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(g.nrows, 256 / c.lpr), c.rpt)));
+#define X(L, V, R)                                                                                           \
+    if (c.lpr == L && c.vpl == V && c.rpt == R) {                                                            \
+        if (drop) hipLaunchKernelGGL((softmax_fwd_kernel<T, L, V, R, true>), grid, block, 0, s, yp, ydp, xp, key_len, g, d); \
+        else hipLaunchKernelGGL((softmax_fwd_kernel<T, L, V, R, false>), grid, block, 0, s, yp, ydp, xp, key_len, g, d);    \
     }
     LSQ_SM_CASES(X)
 #undef X
@@ -721,7 +812,7 @@ static lsq_status softmax_fwd_dispatch(void* y, void* yd, const void* x, Softmax
 
 template <typename T>
 static lsq_status softmax_bwd_dispatch(void* dx, const void* dy, const void* y, SoftmaxLens key_len,
-                                       const SoftmaxGeom& g, const DropoutParams& d, hipStream_t s)
+                                       const SoftmaxGeom& g, const DropoutParams& d, hipStream_t s, int forced = -1)
 {
     T* dxp = static_cast<T*>(dx);
     const T* dyp = static_cast<const T*>(dy);
@@ -746,7 +837,6 @@ static lsq_status softmax_bwd_dispatch(void* dx, const void* dy, const void* y, 
                            dxp, dyp, yp, key_len, g, d);
         return launch_status();
     }
-    const int64_t blocks1 = ceil_div(g.nrows, 256 / sh.lpr);
     const dim3 block(256);
 #define W(V)                                                                                                 \
     if (sh.lpr == 256 && sh.vpl == V) {                                                                      \
@@ -756,18 +846,13 @@ static lsq_status softmax_bwd_dispatch(void* dx, const void* dy, const void* y, 
     }
     W(2) W(4) W(8)
 #undef W
-#define X(L, V)                                                                                              \
-    if (sh.lpr == L && sh.vpl == V) {                                                                        \
-        constexpr int R = sm_rpt(V);                                                                         \
-        if (R > 1 && blocks1 >= kSmMinBlocks * R) {                                                          \
-            const dim3 grid(static_cast<unsigned>(ceil_div(blocks1, R)));                                    \
-            if (drop) hipLaunchKernelGGL((softmax_bwd_kernel<T, L, V, R, true>), grid, block, 0, s, dxp, dyp, yp, key_len, g, d); \
-            else hipLaunchKernelGGL((softmax_bwd_kernel<T, L, V, R, false>), grid, block, 0, s, dxp, dyp, yp, key_len, g, d);    \
-        } else {                                                                                             \
-            const dim3 grid(static_cast<unsigned>(blocks1));                                                 \
-            if (drop) hipLaunchKernelGGL((softmax_bwd_kernel<T, L, V, 1, true>), grid, block, 0, s, dxp, dyp, yp, key_len, g, d); \
-            else hipLaunchKernelGGL((softmax_bwd_kernel<T, L, V, 1, false>), grid, block, 0, s, dxp, dyp, yp, key_len, g, d);    \
-        }                                                                                                    \
+    if (sh.lpr == 256) return launch_status();
+    const SmCand c = sm_choose(key_len, g, drop, sizeof(T), 1, forced);
+    const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(g.nrows, 256 / c.lpr), c.rpt)));
+#define X(L, V, R)                                                                                           \
+    if (c.lpr == L && c.vpl == V && c.rpt == R) {                                                            \
+        if (drop) hipLaunchKernelGGL((softmax_bwd_kernel<T, L, V, R, true>), grid, block, 0, s, dxp, dyp, yp, key_len, g, d); \
+        else hipLaunchKernelGGL((softmax_bwd_kernel<T, L, V, R, false>), grid, block, 0, s, dxp, dyp, yp, key_len, g, d);    \
     }
     LSQ_SM_CASES(X)
 #undef X
@@ -858,4 +943,96 @@ extern "C" lsq_status lsq_softmax_bwd(void* dx, const void* dy, const void* y, c
 {
     return lsq_softmax_varlen_bwd(dx, dy, y, key_len, nullptr, batch, heads, q_len, k_len, causal, scale, p_attn, seed,
                                   offset, dt, stream);
+}
+
+// ---- run-time choice of the launch shape (Sec. IV-B, Softmax: templates + parameter search before training)
+extern "C" int32_t lsq_softmax_candidates(int32_t k_len)
+{
+    using namespace lsq;
+    if (k_len <= 0 || k_len % kPack != 0) return 1;
+    const int b = sm_bucket(k_len);
+    return b < 0 ? 1 : kSmTable[b].n;
+}
+
+extern "C" lsq_status lsq_softmax_tune(int32_t* best_fwd, int32_t* best_bwd, float* us, void* y, void* y_drop, void* dx,
+                                       const void* x, const void* dy, const int32_t* key_len, const int32_t* query_len,
+                                       int32_t batch, int32_t heads, int32_t q_len, int32_t k_len, int32_t causal,
+                                       float scale, float p_attn, uint64_t seed, uint64_t offset, lsq_dtype dt,
+                                       int32_t force, int32_t reps, void* stream)
+{
+    using namespace lsq;
+    const SoftmaxLens len{key_len, query_len};
+    SoftmaxGeom g;
+    lsq_status st = softmax_check(y, x, batch, heads, q_len, k_len, scale, dt, &g);
+    if (st != LSQ_OK) return st;
+    g.causal = causal != 0;
+    DropoutParams d;
+    LSQ_REQUIRE(make_dropout(p_attn, seed, offset, &d));
+    LSQ_REQUIRE(force >= -2 && reps >= 1 && reps <= 10000);
+    if (best_fwd) *best_fwd = 0;
+    if (best_bwd) *best_bwd = 0;
+    if (us)
+        for (int i = 0; i < 2 * kSmMaxCand; ++i) us[i] = -1.0f;
+    const int ncand = lsq_softmax_candidates(k_len);
+    const size_t elem = dt == LSQ_F32 ? 4 : 2;
+    const bool drop = d.on != 0;
+    const int b = sm_bucket(k_len);
+    if (force != -1) {                       // set (>= 0) or forget (-2): nothing is launched
+        LSQ_REQUIRE(force < ncand);
+        if (ncand > 1) {
+            sm_slot(b, len, g, drop, elem, 0).store(static_cast<signed char>(force < 0 ? -1 : force));
+            sm_slot(b, len, g, drop, elem, 1).store(static_cast<signed char>(force < 0 ? -1 : force));
+        }
+        if (best_fwd) *best_fwd = force < 0 ? 0 : force;
+        if (best_bwd) *best_bwd = force < 0 ? 0 : force;
+        return LSQ_OK;
+    }
+    if (g.nrows == 0 || k_len == 0 || ncand <= 1) return LSQ_OK;
+    LSQ_REQUIRE(y && x && dx && dy);
+    LSQ_REQUIRE(drop == (y_drop != nullptr));
+    LSQ_ALIGNED(y); LSQ_ALIGNED(y_drop); LSQ_ALIGNED(x); LSQ_ALIGNED(dx); LSQ_ALIGNED(dy);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return LSQ_LAUNCH_FAILED;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return LSQ_LAUNCH_FAILED; }
+    auto launch = [&](int dir, int cand) -> lsq_status {
+        if (dir == 0) {
+            switch (dt) {
+                case LSQ_F16: return softmax_fwd_dispatch<f16>(y, y_drop, x, len, g, d, s, cand);
+                case LSQ_BF16: return softmax_fwd_dispatch<bf16>(y, y_drop, x, len, g, d, s, cand);
+                default: return softmax_fwd_dispatch<float>(y, y_drop, x, len, g, d, s, cand);
+            }
+        }
+        switch (dt) {
+            case LSQ_F16: return softmax_bwd_dispatch<f16>(dx, dy, y, len, g, d, s, cand);
+            case LSQ_BF16: return softmax_bwd_dispatch<bf16>(dx, dy, y, len, g, d, s, cand);
+            default: return softmax_bwd_dispatch<float>(dx, dy, y, len, g, d, s, cand);
+        }
+    };
+    st = LSQ_OK;
+    for (int dir = 0; dir < 2 && st == LSQ_OK; ++dir) {
+        int best = 0;
+        float best_ms = 0.0f;
+        for (int c = 0; c < ncand && st == LSQ_OK; ++c) {
+            for (int i = 0; i < 2 && st == LSQ_OK; ++i) st = launch(dir, c);          // warm-up
+            if (st != LSQ_OK) break;
+            float ms = 0.0f;
+            bool ok = hipEventRecord(e0, s) == hipSuccess;
+            for (int i = 0; i < reps && st == LSQ_OK; ++i) st = launch(dir, c);
+            ok = ok && hipEventRecord(e1, s) == hipSuccess && hipEventSynchronize(e1) == hipSuccess &&
+                 hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+            if (!ok) st = LSQ_LAUNCH_FAILED;
+            if (st != LSQ_OK) break;
+            if (us) us[dir * kSmMaxCand + c] = ms * 1000.0f / static_cast<float>(reps);
+            if (c == 0 || ms < best_ms) { best = c; best_ms = ms; }
+        }
+        if (st == LSQ_OK) {
+            sm_slot(b, len, g, drop, elem, dir).store(static_cast<signed char>(best));
+            if (dir == 0 && best_fwd) *best_fwd = best;
+            if (dir == 1 && best_bwd) *best_bwd = best;
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return st;
 }
