@@ -13,16 +13,10 @@
 
 namespace lsq {
 
-#ifndef LSQ_NT
-#define LSQ_NT 1
-#endif
-constexpr bool kNT = LSQ_NT != 0;
+constexpr bool kNT = true;
 
 constexpr int kBadWaves = 4;
-#ifndef LSQ_BAD_UNROLL
-#define LSQ_BAD_UNROLL 1
-#endif
-constexpr int kBadUnroll = LSQ_BAD_UNROLL;   // rows a wave has in flight in backward
+constexpr int kBadUnroll = 1;   // rows a wave has in flight in backward
 enum { ACT_RELU = 0, ACT_GELU = 1, ACT_GELU_TANH = 2 };
 
 // sigmoid(t) = 1/(1 + 2^(-t*log2 e)): one v_exp_f32 and one v_rcp_f32 (1 ulp; an IEEE

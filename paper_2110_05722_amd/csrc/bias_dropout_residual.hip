@@ -1,7 +1,7 @@
 // Fused bias + dropout + residual, forward and backward (Sec. IV-A of the paper,
 // Transformer layers: "bias adding, dropout, and residual" in one launch).
 //
-// Layout of the fast path (hidden % 8 == 0): W lanes of a wave (W = 64, 32 or 16, the widest
+// Layout of the fast path (hidden % 8 == 0): W lanes of a wave (W = 32 or 16, the wider
 // that divides the packs of a row, so no lane idles on a ragged last column block) own W
 // consecutive packs of one row and the wave covers 64 / W rows at a time; a workgroup's column
 // block is fixed, so the bias pack is loaded once into registers, every access is a 128-bit one,
@@ -207,7 +207,7 @@ static lsq_status bdr_fwd_dispatch(void* out, const void* x, const void* bias, c
             else if (drop) hipLaunchKernelGGL((bdr_fwd_cols<T, false, true, W>), grid, block, 0, s, o, xp, bp, rp, rows, ppr, d);   \
             else hipLaunchKernelGGL((bdr_fwd_cols<T, false, false, W>), grid, block, 0, s, o, xp, bp, rp, rows, ppr, d);            \
         }
-        LSQ_BDR_FWD(64) LSQ_BDR_FWD(32) LSQ_BDR_FWD(16)
+        LSQ_BDR_FWD(32) LSQ_BDR_FWD(16)
 #undef LSQ_BDR_FWD
     } else {
         const int64_t total = rows * hidden;
@@ -233,7 +233,7 @@ static lsq_status bdr_bwd_dispatch(void* dx, float* dbias, const void* dy, int64
             if (d.on) hipLaunchKernelGGL((bdr_bwd_cols<T, true, W>), grid, block, 0, s, o, partial, g, rows, ppr, pl.trips, d);    \
             else hipLaunchKernelGGL((bdr_bwd_cols<T, false, W>), grid, block, 0, s, o, partial, g, rows, ppr, pl.trips, d);         \
         }
-        LSQ_BDR_BWD(64) LSQ_BDR_BWD(32) LSQ_BDR_BWD(16)
+        LSQ_BDR_BWD(32) LSQ_BDR_BWD(16)
         if (dbias) launch_colsum_finalize(dbias, dbias, hidden, partial, pl.row_blocks, hidden, s);
 #undef LSQ_BDR_BWD
     } else {

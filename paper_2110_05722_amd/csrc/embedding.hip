@@ -23,10 +23,7 @@
 
 namespace lsq {
 
-#ifndef LSQ_NT
-#define LSQ_NT 1
-#endif
-constexpr bool kNT = LSQ_NT != 0;
+constexpr bool kNT = true;
 constexpr int kEmbWaves = 4;
 constexpr int kTile = kEmbTile;
 

@@ -14,10 +14,7 @@
 
 namespace lsq {
 
-#ifndef LSQ_NT
-#define LSQ_NT 1
-#endif
-constexpr bool kNT = LSQ_NT != 0;
+constexpr bool kNT = true;
 constexpr int kHeadWaves = 4;
 
 struct HeadGeom {

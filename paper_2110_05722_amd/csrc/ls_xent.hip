@@ -16,28 +16,15 @@
 
 namespace lsq {
 
-#ifndef LSQ_NT
-#define LSQ_NT 1
-#endif
-constexpr bool kNT = LSQ_NT != 0;   // nontemporal hint on the streamed tensors
-#ifndef LSQ_XB_NTL
-#define LSQ_XB_NTL 1
-#endif
-#ifndef LSQ_XB_NTS
-#define LSQ_XB_NTS 1
-#endif
-constexpr bool kBwdNTL = LSQ_XB_NTL != 0, kBwdNTS = LSQ_XB_NTS != 0;
+constexpr bool kNT = true;   // nontemporal hint on the streamed tensors
+constexpr bool kBwdNTL = true, kBwdNTS = true;
 
 constexpr float kLog2eX = 1.4426950408889634f;
 constexpr float kLn2X = 0.6931471805599453f;
-#ifndef LSQ_XENT_THREADS
-#define LSQ_XENT_THREADS 256
-#endif
-#ifndef LSQ_XENT_UNROLL
-#define LSQ_XENT_UNROLL 4
-#endif
-constexpr int kXentThreads = LSQ_XENT_THREADS;
-constexpr int kXentUnroll = LSQ_XENT_UNROLL;
+// measured at 8192 x 30522 / 32768 / 50257 logits: 512 or 1024 threads per row and 8 packs in flight per thread are
+// no faster (within 2 %) or slower (1024 threads: -10 %)
+constexpr int kXentThreads = 256;
+constexpr int kXentUnroll = 4;
 
 struct RowSplit {
     int64_t begin, head_end, pack_begin, pack_end, tail_begin, end;

@@ -14,10 +14,7 @@
 
 namespace lsq {
 
-#ifndef LSQ_NT
-#define LSQ_NT 1
-#endif
-constexpr bool kNT = LSQ_NT != 0;
+constexpr bool kNT = true;
 constexpr int kPadWaves = 4;    // waves per workgroup
 constexpr int kPadRows = 4;     // rows a wave has in flight
 
