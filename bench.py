@@ -26,8 +26,9 @@ Prints ONE JSON line:
   layer_us             non-GEMM microseconds of one layer, forward + backward
   cpu_baseline         the CPU oracle timed on a bounded sample: per operator, one thread and OpenMP
 
---profile: only the step and the nine-operator table of ONE configuration plus a 1 GiB calibration copy
-(for rocprofv3 runs: per-kernel averages stay clean and counters can be scaled by the copy).
+--profile: only the step and the per-operator tables of ONE configuration plus three 1 GiB calibration copies
+(for rocprofv3 runs: per-kernel averages stay clean and counters can be scaled by the copy); --no-graph times
+the tables with eager launches (counter collection serialises dispatches anyway).
 """
 from __future__ import annotations
 
@@ -63,11 +64,16 @@ def parse():
     ap.add_argument("--op-reps", type=int, default=40, help="back-to-back launches per operator in the per-op table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile", action="store_true",
-                    help="one configuration, the step and the nine-operator table only, plus a 1 GiB calibration copy")
+                    help="for rocprofv3 runs: one configuration, the step and the per-operator tables only (no calibration sweep, no other "
+                         "configuration, no warm table, no CPU baseline), plus three 1 GiB calibration copies for scaling the counters")
+    ap.add_argument("--no-graph", action="store_true", help="per-operator tables from eager launches (counter collection)")
     return ap.parse_args()
 
 
 # ------------------------------------------------------------------------------------------- timing helpers
+EAGER = False      # --no-graph
+
+
 def graph_time_us(torch, fn, reps):
     """Average microseconds of one call of fn(i) when `reps` calls are captured into a HIP graph and the graph is
     replayed between two events: what is timed is the GPU running the kernels back to back, not the interpreter
@@ -76,6 +82,13 @@ def graph_time_us(torch, fn, reps):
         fn(i)
     torch.cuda.synchronize()
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if EAGER:
+        a.record()
+        for i in range(reps):
+            fn(3 + i)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / reps
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         for i in range(reps):
@@ -561,6 +574,8 @@ def main():
         print("bench.py: no GPU visible; there is no CPU path to time.", file=sys.stderr)
         sys.exit(2)
     L.load()
+    global EAGER
+    EAGER = args.no_graph
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     cfg = next(c for c in CONFIGS if c.name == args.config)
@@ -570,7 +585,7 @@ def main():
     calib = None if args.profile else Calibration(torch, L, dev, args.op_reps)
 
     # ------------------------------------------------------------------ the headline configuration
-    ops, bts, meta = make_workload(torch, L, cfg, dt, dev, extras=not args.profile, adam=adam)
+    ops, bts, meta = make_workload(torch, L, cfg, dt, dev, extras=True, adam=adam)
     del adam
     ms_per_step, adam_ms = time_steps(torch, ops, NINE, args.steps, args.warmup)
     step_bytes = sum(bts[k] for k in NINE)
@@ -590,12 +605,14 @@ def main():
         "config": {"workload": meta["workload"],
                    "buffers": f"cold (layer tensors rotate over {meta['sets']} sets, softmax over {meta['soft_sets']})"},
         "roofline": roofline,
-        "ops": table, "ops_timing": "hipgraph", "softmax_tune": meta["softmax_tune"],
+        "ops": table, "ops_timing": "eager" if EAGER else "hipgraph", "softmax_tune": meta["softmax_tune"],
         "family_frac": family_frac(table),
         "layer_us": layer_us(table),
     }
 
     if args.profile:
+        extra = [k for k in ops if k not in NINE]
+        out["ops_next"] = dict(op_table(torch, ops, bts, extra, args.op_reps), note=meta["next_note"])
         # known traffic for scaling FETCH_SIZE / WRITE_SIZE: reads 2^30 bytes, writes 2^30 bytes per launch
         src = torch.ones(1 << 29, dtype=torch.float16, device=dev)
         dst = torch.empty_like(src)
