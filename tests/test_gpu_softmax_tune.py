@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 # (batch, heads, q_len, k_len): one row length per bucket that has a choice, rows enough for several workgroups
 # (so that candidates with two rows per lane group are not folded to one) and a ragged last workgroup
 SHAPES = [(70, 4, 37, 8), (36, 4, 37, 16), (20, 4, 37, 32), (12, 4, 37, 64), (6, 4, 37, 128), (3, 4, 37, 256), (2, 4, 37, 512),
-          (700, 4, 40, 128)]
+          (1, 4, 37, 1024), (700, 4, 40, 128)]
 
 
 def _run_and_check(t, dt, kl_np, causal, p, tag):
@@ -81,8 +81,8 @@ def test_search_records_a_valid_choice_and_results_stay_right():
     finally:
         L.lsq_softmax_tune(x, dy, kl, None, False, 0.125, 0.1, force=-2)
     # a row length with one shape only: nothing to search, nothing launched
-    assert L.lsq_softmax_candidates(1024) == 1 and L.lsq_softmax_candidates(100) == 1
-    x2 = torch.zeros((1, 1, 2, 1024), dtype=torch.float16, device=d)
+    assert L.lsq_softmax_candidates(2048) == 1 and L.lsq_softmax_candidates(100) == 1
+    x2 = torch.zeros((1, 1, 2, 2048), dtype=torch.float16, device=d)
     assert L.lsq_softmax_tune(x2, x2, force=-1)[:2] == (0, 0)
     with pytest.raises(L.LsqError, match="INVALID_ARG"):
         L.lsq_softmax_tune(x, dy, kl, None, False, 0.125, 0.1, force=7)
