@@ -12,13 +12,19 @@ extern "C" size_t lsq_workspace_bytes(int32_t op, int64_t rows, int32_t cols)
         case LSQ_OP_BDR_LAYERNORM_BWD:
             // one [3][cols] fp32 partial row (dgamma, dbeta, dbias) per workgroup; also enough for the
             // two separate operators that serve row lengths without a register bucket
-            return static_cast<size_t>(ln_bwd_blocks(rows, cols)) * 3u * static_cast<size_t>(cols) * sizeof(float);
+            {
+                const size_t fused = static_cast<size_t>(ln_bwd_blocks(rows, cols)) * 3u * static_cast<size_t>(cols) * sizeof(float);
+                const size_t apart = lsq_workspace_bytes(LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD, rows, cols);
+                return fused > apart ? fused : apart;
+            }
         case LSQ_OP_BIAS_DROPOUT_RESIDUAL_BWD:
             // one [cols] fp32 partial row (dbias) per row block
             if (cols % kPack == 0)
                 return static_cast<size_t>(bdr_bwd_plan(rows, cols).row_blocks) * static_cast<size_t>(cols) * sizeof(float);
-            return 0;       // the generic path sums each column in one thread
+            return flat_workspace_bytes(rows, cols);        // one per workgroup of the flat walk
         case LSQ_OP_BIAS_ACT_DROPOUT_BWD:
+            if (cols % kPack != 0) return flat_workspace_bytes(rows, cols);
+            return static_cast<size_t>(bdr_bwd_row_blocks(rows, cols)) * static_cast<size_t>(cols) * sizeof(float);
         case LSQ_OP_SPLIT_HEADS_BWD:
             // one [cols] fp32 partial row (dbias) per row block
             return static_cast<size_t>(bdr_bwd_row_blocks(rows, cols)) * static_cast<size_t>(cols) * sizeof(float);

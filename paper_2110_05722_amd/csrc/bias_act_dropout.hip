@@ -165,51 +165,77 @@ __global__ __launch_bounds__(256) void bad_bwd_cols(T* dx, float* __restrict__ p
     }
 }
 
-// ---- generic paths: any hidden, one element per thread
+// ---- any hidden (rows are not a whole number of packs): the operators for flat_packs_kernel
 template <typename T, int ACT>
-__global__ __launch_bounds__(256) void bad_fwd_flat(T* out, const T* x, const T* __restrict__ bias, int64_t total,
-                                                    int hidden, DropoutParams d)
-{
-    const int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (e >= total) return;
-    float z = to_f32<T>(x[e]);
-    if (bias) z += to_f32<T>(bias[e % hidden]);
-    float a = act_value<ACT>(z);
-    if (d.on) a *= dropout_factor1(d, static_cast<uint64_t>(e));
-    out[e] = from_f32<T>(a);
-}
-
-template <typename T, int ACT>
-__global__ __launch_bounds__(256) void bad_bwd_flat(T* dx, const T* dy, const T* x, const T* __restrict__ bias,
-                                                    int64_t total, int hidden, DropoutParams d)
-{
-    const int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (e >= total) return;
-    float z = to_f32<T>(x[e]);
-    if (bias) z += to_f32<T>(bias[e % hidden]);
-    float g = to_f32<T>(dy[e]) * act_slope<ACT>(z);
-    if (d.on) g *= dropout_factor1(d, static_cast<uint64_t>(e));
-    dx[e] = from_f32<T>(g);
-}
-
-// dbias for the generic path; runs BEFORE bad_bwd_flat so that dx may alias dy
-template <typename T, int ACT>
-__global__ __launch_bounds__(256) void bad_dbias_flat(float* __restrict__ dbias, const T* __restrict__ dy,
-                                                      const T* __restrict__ x, const T* __restrict__ bias, int64_t rows,
-                                                      int hidden, DropoutParams d)
-{
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= hidden) return;
-    const float b = bias ? to_f32<T>(bias[c]) : 0.0f;
-    float s = 0.0f;
-    for (int64_t r = 0; r < rows; ++r) {
-        const int64_t e = r * hidden + c;
-        float g = to_f32<T>(dy[e]) * act_slope<ACT>(to_f32<T>(x[e]) + b);
-        if (d.on) g *= dropout_factor1(d, static_cast<uint64_t>(e));
-        s += g;
+struct BadFwdFlat {
+    T* out;
+    const T* x;
+    const T* bias;
+    int hidden;
+    DropoutParams d;
+    __device__ __forceinline__ void pack(int64_t e0, int c0, float (&g)[8]) const
+    {
+        const RawPack<T> xr = load_raw<T, kNT>(x + e0);
+        float k[8];
+        if (d.on) dropout_factors8(d, static_cast<uint64_t>(e0 >> 3), k);
+        unpack<T>(xr, g);
+        int c = c0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float z = bias ? g[j] + to_f32<T>(bias[c]) : g[j];
+            const float a = act_value<ACT>(z);
+            g[j] = d.on ? a * k[j] : a;
+            c = c + 1 == hidden ? 0 : c + 1;
+        }
+        store8<T, kNT>(out + e0, g);
     }
-    dbias[c] = s;
-}
+    __device__ __forceinline__ float one(int64_t e, int c) const
+    {
+        float z = to_f32<T>(x[e]);
+        if (bias) z += to_f32<T>(bias[c]);
+        float a = act_value<ACT>(z);
+        if (d.on) a *= dropout_factor1(d, static_cast<uint64_t>(e));
+        out[e] = from_f32<T>(a);
+        return a;
+    }
+};
+
+template <typename T, int ACT>
+struct BadBwdFlat {
+    T* dx;
+    const T* dy;
+    const T* x;
+    const T* bias;
+    int hidden;
+    DropoutParams d;
+    __device__ __forceinline__ void pack(int64_t e0, int c0, float (&g)[8]) const
+    {
+        const RawPack<T> gr = load_raw<T, kNT>(dy + e0), xr = load_raw<T, kNT>(x + e0);
+        float k[8];
+        if (d.on) dropout_factors8(d, static_cast<uint64_t>(e0 >> 3), k);
+        float xf[8];
+        unpack<T>(gr, g);
+        unpack<T>(xr, xf);
+        int c = c0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float z = bias ? xf[j] + to_f32<T>(bias[c]) : xf[j];
+            const float v = g[j] * act_slope<ACT>(z);
+            g[j] = d.on ? v * k[j] : v;
+            c = c + 1 == hidden ? 0 : c + 1;
+        }
+        store8<T, kNT>(dx + e0, g);
+    }
+    __device__ __forceinline__ float one(int64_t e, int c) const
+    {
+        float z = to_f32<T>(x[e]);
+        if (bias) z += to_f32<T>(bias[c]);
+        float v = to_f32<T>(dy[e]) * act_slope<ACT>(z);
+        if (d.on) v *= dropout_factor1(d, static_cast<uint64_t>(e));
+        dx[e] = from_f32<T>(v);
+        return v;
+    }
+};
 
 template <typename T, int ACT>
 static lsq_status bad_fwd_dispatch(void* out, const void* x, const void* bias, int64_t rows, int32_t hidden,
@@ -229,9 +255,7 @@ static lsq_status bad_fwd_dispatch(void* out, const void* x, const void* bias, i
         else if (drop) hipLaunchKernelGGL((bad_fwd_cols<T, ACT, false, true>), grid, block, 0, s, o, xp, bp, rows, ppr, d);
         else hipLaunchKernelGGL((bad_fwd_cols<T, ACT, false, false>), grid, block, 0, s, o, xp, bp, rows, ppr, d);
     } else {
-        const int64_t total = rows * hidden;
-        hipLaunchKernelGGL((bad_fwd_flat<T, ACT>), dim3(static_cast<unsigned>(ceil_div(total, 256))), dim3(256), 0, s,
-                           o, xp, bp, total, hidden, d);
+        launch_flat_packs(BadFwdFlat<T, ACT>{o, xp, bp, hidden, d}, nullptr, nullptr, rows, hidden, s);
     }
     return launch_status();
 }
@@ -256,12 +280,7 @@ static lsq_status bad_bwd_dispatch(void* dx, float* dbias, const void* dy, const
         else hipLaunchKernelGGL((bad_bwd_cols<T, ACT, false, false>), grid, block, 0, s, o, partial, g, xp, bp, rows, ppr, d);
         if (dbias) launch_colsum_finalize(dbias, dbias, hidden, partial, rb, hidden, s);
     } else {
-        const int64_t total = rows * hidden;
-        if (dbias)
-            hipLaunchKernelGGL((bad_dbias_flat<T, ACT>), dim3(static_cast<unsigned>(ceil_div(hidden, 256))), dim3(256), 0, s,
-                               dbias, g, xp, bp, rows, hidden, d);
-        hipLaunchKernelGGL((bad_bwd_flat<T, ACT>), dim3(static_cast<unsigned>(ceil_div(total, 256))), dim3(256), 0, s,
-                           o, g, xp, bp, total, hidden, d);
+        launch_flat_packs(BadBwdFlat<T, ACT>{o, g, xp, bp, hidden, d}, dbias, workspace, rows, hidden, s);
     }
     return launch_status();
 }

@@ -142,47 +142,70 @@ __global__ __launch_bounds__(64 * kBdrBwdWaves) void bdr_bwd_cols(T* dx, float* 
     }
 }
 
-// ---- generic paths: any hidden (rows are not 16-byte aligned), one element per thread
+// ---- any hidden (rows are not a whole number of packs): the operators for flat_packs_kernel
 template <typename T>
-__global__ __launch_bounds__(256) void bdr_fwd_flat(T* out, const T* x,
-                                                    const T* __restrict__ bias, const T* res,
-                                                    int64_t total, int hidden, DropoutParams d)
-{
-    const int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (e >= total) return;
-    float z = to_f32<T>(x[e]);
-    if (bias) z += to_f32<T>(bias[e % hidden]);
-    const float k = d.on ? dropout_factor1(d, static_cast<uint64_t>(e)) : 1.0f;
-    out[e] = from_f32<T>(d.on ? fmaf(z, k, to_f32<T>(res[e])) : to_f32<T>(res[e]) + z);
-}
+struct BdrFwdFlat {
+    T* out;
+    const T* x;
+    const T* bias;
+    const T* res;
+    int hidden;
+    DropoutParams d;
+    __device__ __forceinline__ void pack(int64_t e0, int c0, float (&g)[8]) const
+    {
+        const RawPack<T> xr = load_raw<T, kNT>(x + e0), rr = load_raw<T, kNT>(res + e0);
+        float k[8];
+        if (d.on) dropout_factors8(d, static_cast<uint64_t>(e0 >> 3), k);
+        float xf[8];
+        unpack<T>(xr, xf);
+        unpack<T>(rr, g);
+        int c = c0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float z = bias ? xf[j] + to_f32<T>(bias[c]) : xf[j];
+            g[j] = d.on ? fmaf(z, k[j], g[j]) : g[j] + z;
+            c = c + 1 == hidden ? 0 : c + 1;
+        }
+        pin_f32(g);
+        store8<T, kNT>(out + e0, g);
+    }
+    __device__ __forceinline__ float one(int64_t e, int c) const
+    {
+        float z = to_f32<T>(x[e]);
+        if (bias) z += to_f32<T>(bias[c]);
+        const float r = to_f32<T>(res[e]);
+        const float v = d.on ? fmaf(z, dropout_factor1(d, static_cast<uint64_t>(e)), r) : r + z;
+        out[e] = from_f32<T>(v);
+        return v;
+    }
+};
 
 template <typename T>
-__global__ __launch_bounds__(256) void bdr_bwd_flat(T* dx, const T* dy,
-                                                    int64_t total, DropoutParams d)
-{
-    const int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (e >= total) return;
-    float g = to_f32<T>(dy[e]);
-    if (d.on) g *= dropout_factor1(d, static_cast<uint64_t>(e));
-    dx[e] = from_f32<T>(g);
-}
-
-// one thread per column walks down the rows (coalesced across the wave)
-template <typename T>
-__global__ __launch_bounds__(256) void bdr_dbias_flat(float* __restrict__ dbias, const T* __restrict__ dy,
-                                                      int64_t rows, int hidden, DropoutParams d)
-{
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= hidden) return;
-    float s = 0.0f;
-    for (int64_t r = 0; r < rows; ++r) {
-        const int64_t e = r * hidden + c;
+struct BdrBwdFlat {
+    T* dx;
+    const T* dy;
+    DropoutParams d;
+    __device__ __forceinline__ void pack(int64_t e0, int, float (&g)[8]) const
+    {
+        const RawPack<T> cur = load_raw<T, kNT>(dy + e0);
+        float k[8];
+        if (d.on) dropout_factors8(d, static_cast<uint64_t>(e0 >> 3), k);
+        unpack<T>(cur, g);
+        if (d.on) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) g[j] *= k[j];
+        }
+        pin_f32(g);
+        store8<T, kNT>(dx + e0, g);
+    }
+    __device__ __forceinline__ float one(int64_t e, int) const
+    {
         float g = to_f32<T>(dy[e]);
         if (d.on) g *= dropout_factor1(d, static_cast<uint64_t>(e));
-        s += g;
+        dx[e] = from_f32<T>(g);
+        return g;
     }
-    dbias[c] = s;
-}
+};
 
 template <typename T>
 static lsq_status bdr_fwd_dispatch(void* out, const void* x, const void* bias, const void* res, int64_t rows,
@@ -210,9 +233,7 @@ static lsq_status bdr_fwd_dispatch(void* out, const void* x, const void* bias, c
         LSQ_BDR_FWD(32) LSQ_BDR_FWD(16)
 #undef LSQ_BDR_FWD
     } else {
-        const int64_t total = rows * hidden;
-        hipLaunchKernelGGL((bdr_fwd_flat<T>), dim3(static_cast<unsigned>(ceil_div(total, 256))), dim3(256), 0, s,
-                           o, xp, bp, rp, total, hidden, d);
+        launch_flat_packs(BdrFwdFlat<T>{o, xp, bp, rp, hidden, d}, nullptr, nullptr, rows, hidden, s);
     }
     return launch_status();
 }
@@ -237,13 +258,8 @@ static lsq_status bdr_bwd_dispatch(void* dx, float* dbias, const void* dy, int64
         if (dbias) launch_colsum_finalize(dbias, dbias, hidden, partial, pl.row_blocks, hidden, s);
 #undef LSQ_BDR_BWD
     } else {
-        const int64_t total = rows * hidden;
-        // the column sums read dy, so they run first: dx may be the dy buffer itself
-        if (dbias)
-            hipLaunchKernelGGL((bdr_dbias_flat<T>), dim3(static_cast<unsigned>(ceil_div(hidden, 256))), dim3(256), 0, s,
-                               dbias, g, rows, hidden, d);
-        hipLaunchKernelGGL((bdr_bwd_flat<T>), dim3(static_cast<unsigned>(ceil_div(total, 256))), dim3(256), 0, s,
-                           o, g, total, d);
+        // every pack is read and written by one thread, which also hands its fp32 results to the column sums: in place is fine
+        launch_flat_packs(BdrBwdFlat<T>{o, g, d}, dbias, workspace, rows, hidden, s);
     }
     return launch_status();
 }

@@ -145,15 +145,21 @@ __global__ __launch_bounds__(256) void merge_heads_flat(T* __restrict__ out, con
     out[e] = pick(i0, i1, i2, part)[head_offset(g, t, col - part * g.hidden)];
 }
 
+// Column sums when rows are not a whole number of packs: one thread per column and row block walks its
+// rows (a wave reads 64 consecutive elements per row), the row blocks' partial rows are summed by
+// colsum_finalize_kernel.
 template <typename T>
-__global__ __launch_bounds__(256) void colsum_flat(float* __restrict__ dbias, const T* __restrict__ x, int64_t rows,
-                                                   int cols)
+__global__ __launch_bounds__(256) void colsum_rows_flat(float* __restrict__ partial, const T* __restrict__ x, int64_t rows,
+                                                        int cols, int rows_per_block)
 {
     const int c = blockIdx.x * 256 + threadIdx.x;
     if (c >= cols) return;
+    const int64_t r0 = static_cast<int64_t>(blockIdx.y) * rows_per_block;
+    const int64_t r1 = r0 + rows_per_block < rows ? r0 + rows_per_block : rows;
     float s = 0.0f;
-    for (int64_t r = 0; r < rows; ++r) s += to_f32<T>(x[r * cols + c]);
-    dbias[c] = s;
+#pragma unroll 4
+    for (int64_t r = r0; r < r1; ++r) s += to_f32<T>(x[r * cols + c]);
+    partial[static_cast<int64_t>(blockIdx.y) * cols + c] = s;
 }
 
 inline int head_row_blocks(int64_t rows)
@@ -199,9 +205,13 @@ static lsq_status merge_dispatch(void* out, float* dbias, const void* i0, const 
         const int64_t total = g.rows * cols;
         hipLaunchKernelGGL((merge_heads_flat<T>), dim3(static_cast<unsigned>(ceil_div(total, 256))), dim3(256), 0, s,
                            o, a, b, c, g);
-        if (dbias)
-            hipLaunchKernelGGL((colsum_flat<T>), dim3(static_cast<unsigned>(ceil_div(cols, 256))), dim3(256), 0, s,
-                               dbias, static_cast<const T*>(o), g.rows, cols);
+        if (dbias) {
+            const int rb = bdr_bwd_row_blocks(g.rows, cols);
+            float* partial = static_cast<float*>(workspace);
+            hipLaunchKernelGGL((colsum_rows_flat<T>), dim3(static_cast<unsigned>(ceil_div(cols, 256)), static_cast<unsigned>(rb)), dim3(256), 0, s,
+                               partial, static_cast<const T*>(o), g.rows, cols, static_cast<int>(ceil_div(g.rows, rb)));
+            launch_colsum_finalize(dbias, dbias, cols, partial, rb, cols, s);
+        }
     }
     return launch_status();
 }
@@ -253,7 +263,7 @@ extern "C" lsq_status lsq_split_heads_bwd(void* din, float* dbias, const void* d
     if (g.rows == 0) return dbias ? zero_fill(dbias, static_cast<int64_t>(parts) * g.hidden, s) : LSQ_OK;
     LSQ_REQUIRE(din && d0 && (parts < 2 || d1) && (parts < 3 || d2));
     LSQ_ALIGNED(din); LSQ_ALIGNED(d0); LSQ_ALIGNED(d1); LSQ_ALIGNED(d2); LSQ_ALIGNED(dbias); LSQ_ALIGNED(workspace);
-    if (dbias && head_dim % kPack == 0) {
+    if (dbias) {
         const size_t need = lsq_workspace_bytes(LSQ_OP_SPLIT_HEADS_BWD, g.rows, parts * g.hidden);
         if (need && (!workspace || workspace_bytes < need)) return LSQ_WORKSPACE_TOO_SMALL;
     }

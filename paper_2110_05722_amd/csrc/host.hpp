@@ -108,6 +108,114 @@ inline void launch_colsum_finalize(float* out0, float* out1, int split, const fl
                        out0, out1, out2, split, split2, partial, P, C);
 }
 
+// ---- rows that are not a whole number of packs (hidden % 8 != 0): element-wise operators
+// The tensor is walked as ONE flat array in aligned packs (a pack may straddle two rows), so every
+// access stays a 128-bit one and a pack still costs one Philox call (the dropout contract counts
+// packs over the flat tensor).  F supplies the operator:
+//   void  pack(int64_t e0, int c0, float (&g)[8])   loads, computes and stores the pack at element e0,
+//                                                   whose first column is c0; g = the fp32 results
+//   float one(int64_t e, int c)                      the same for one element of the ragged last pack
+// With COLS the fp32 results also feed column sums (a bias gradient): a workgroup parks the
+// results of a trip (256 threads x 4 packs, consecutive) in LDS, then every thread adds up, in
+// ascending element order, the entries of the columns it owns (c = thread, thread + 256, ...); the
+// owner alone touches a column's accumulator (in LDS up to 8192 columns, else straight in the
+// workgroup's partial row), so no atomics and a fixed order.  One partial row per workgroup, summed
+// by colsum_finalize_kernel.
+constexpr int kFlatPacks = 4;                                    // packs per thread and trip
+constexpr int kFlatChunk = 256 * kFlatPacks * kPack;             // elements per trip
+constexpr int kFlatMaxBlocks = 512;                              // partial rows at most
+constexpr int kFlatLdsColumns = 8192;                            // accumulators in LDS up to this row length
+
+struct FlatPlan { int blocks, trips; };
+inline FlatPlan flat_plan(int64_t total, bool cols)
+{
+    const int64_t chunks = ceil_div(total, kFlatChunk);
+    FlatPlan p;
+    if (!cols) { p.blocks = static_cast<int>(chunks); p.trips = 1; return p; }
+    p.trips = static_cast<int>(ceil_div(chunks, kFlatMaxBlocks));
+    if (p.trips < 1) p.trips = 1;
+    p.blocks = static_cast<int>(ceil_div(chunks, p.trips));
+    if (p.blocks < 1) p.blocks = 1;
+    return p;
+}
+
+template <typename F, bool COLS, bool ACC_LDS>
+__global__ __launch_bounds__(256) void flat_packs_kernel(F f, float* __restrict__ partial, int64_t total, int hidden, int trips)
+{
+    extern __shared__ float flat_lds[];        // COLS: [kFlatChunk] results of the trip (, [hidden] accumulators)
+    const int tid = threadIdx.x;
+    float* acc = nullptr;
+    if constexpr (COLS) {
+        acc = ACC_LDS ? flat_lds + kFlatChunk : partial + static_cast<int64_t>(blockIdx.x) * hidden;
+        for (int c = tid; c < hidden; c += 256) acc[c] = 0.0f;     // read again by this thread only
+    }
+    for (int t = 0; t < trips; ++t) {
+        const int64_t base = (static_cast<int64_t>(blockIdx.x) * trips + t) * kFlatChunk;
+        if (base >= total) break;                                  // uniform over the workgroup
+        const int cb = static_cast<int>(base % hidden);            // column of the trip's first element
+#pragma unroll
+        for (int u = 0; u < kFlatPacks; ++u) {
+            const int off = (u * 256 + tid) * kPack;
+            const int64_t e0 = base + off;
+            float g[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (e0 + kPack <= total) {
+                f.pack(e0, static_cast<int>(static_cast<uint32_t>(cb + off) % static_cast<uint32_t>(hidden)), g);
+            } else if (e0 < total) {
+                int c = static_cast<int>(static_cast<uint32_t>(cb + off) % static_cast<uint32_t>(hidden));
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    if (e0 + j < total) g[j] = f.one(e0 + j, c);
+                    c = c + 1 == hidden ? 0 : c + 1;
+                }
+            }
+            if constexpr (COLS) store8<float>(flat_lds + off, g);
+        }
+        if constexpr (COLS) {
+            __syncthreads();
+            const int64_t left = total - base;
+            const int n = left < kFlatChunk ? static_cast<int>(left) : kFlatChunk;
+            for (int c = tid; c < hidden; c += 256) {
+                int i = c - cb;
+                if (i < 0) i += hidden;
+                float a = acc[c];
+                for (; i < n; i += hidden) a += flat_lds[i];
+                acc[c] = a;
+            }
+            __syncthreads();                                       // the next trip overwrites the results
+        }
+    }
+    if constexpr (COLS && ACC_LDS) {
+        float* prow = partial + static_cast<int64_t>(blockIdx.x) * hidden;
+        for (int c = tid; c < hidden; c += 256) prow[c] = acc[c];
+    }
+}
+
+// dbias == nullptr: the element-wise part only.  workspace: flat_plan(total, true).blocks rows of hidden floats.
+template <typename F>
+inline void launch_flat_packs(const F& f, float* dbias, void* workspace, int64_t rows, int hidden, hipStream_t s)
+{
+    const int64_t total = rows * hidden;
+    const FlatPlan pl = flat_plan(total, dbias != nullptr);
+    const dim3 grid(static_cast<unsigned>(pl.blocks)), block(256);
+    if (!dbias) {
+        hipLaunchKernelGGL((flat_packs_kernel<F, false, false>), grid, block, 0, s, f, nullptr, total, hidden, 1);
+        return;
+    }
+    float* partial = static_cast<float*>(workspace);
+    if (hidden <= kFlatLdsColumns)
+        hipLaunchKernelGGL((flat_packs_kernel<F, true, true>), grid, block, (kFlatChunk + hidden) * sizeof(float), s, f, partial,
+                           total, hidden, pl.trips);
+    else
+        hipLaunchKernelGGL((flat_packs_kernel<F, true, false>), grid, block, kFlatChunk * sizeof(float), s, f, partial, total,
+                           hidden, pl.trips);
+    launch_colsum_finalize(dbias, dbias, hidden, partial, pl.blocks, hidden, s);
+}
+
+inline size_t flat_workspace_bytes(int64_t rows, int32_t hidden)
+{
+    return static_cast<size_t>(flat_plan(rows * hidden, true).blocks) * static_cast<size_t>(hidden) * sizeof(float);
+}
+
 // Number of partial-sum rows the column reductions write to the workspace.
 // One per workgroup; sized so the grid fills 256 compute units a few times over
 // while the partials stay a small fraction of the tensor traffic.

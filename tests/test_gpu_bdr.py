@@ -14,6 +14,9 @@ SHAPES = [
     (512, 512, 0.1), (4096, 512, 0.1), (8192, 1024, 0.3), (8192, 1280, 0.1),
     (4096, 256, 0.1), (1000, 768, 0.5), (37, 64, 0.1), (5, 8, 0.25), (3, 1536, 0.1), (2, 8192, 0.1),
     (1, 1024, 0.1), (7, 257, 0.2), (33, 50, 0.1), (9, 1, 0.5), (131, 520, 0.0),
+    # hidden not a multiple of 8 (the flat walk in packs): a ragged last pack, rows shorter than a pack, two trips per
+    # workgroup (more than 512 x 8192 elements), column accumulators outside LDS (more than 8192 columns), no dropout
+    (3, 13, 0.1), (1031, 3, 0.2), (4100, 1031, 0.1), (9, 8197, 0.1), (700, 1281, 0.0),
 ]
 
 

@@ -12,7 +12,9 @@ pytestmark = pytest.mark.gpu
 
 # (rows, ffn width, p): the FFN widths of the configurations, then buckets, ragged and generic shapes
 SHAPES = [(512, 2048, 0.1), (2048, 4096, 0.1), (1024, 5120, 0.1), (1000, 768, 0.3), (37, 64, 0.0), (5, 8, 0.25),
-          (3, 1536, 0.1), (7, 257, 0.2), (33, 50, 0.1), (1, 4096, 0.1)]
+          (3, 1536, 0.1), (7, 257, 0.2), (33, 50, 0.1), (1, 4096, 0.1),
+          # hidden not a multiple of 8 (the flat walk in packs): ragged last pack, two trips, accumulators outside LDS
+          (3, 13, 0.1), (4100, 1031, 0.1), (9, 8197, 0.1), (300, 5124, 0.0)]
 
 
 @pytest.mark.parametrize("act", ["relu", "gelu", "gelu_tanh"])
