@@ -590,26 +590,31 @@ __global__ __launch_bounds__(256) void softmax_bwd_elem(T* dx, const T* dy, cons
     }
 }
 
-// ---- generic path: any k_len; one wave per row, element-strided, row re-read from cache
-template <typename T>
+// ---- generic path: any k_len; TH = 64 (one wave per row) or 256 lanes (one workgroup per row), element-strided,
+// row re-read from cache
+template <typename T, int TH>
 __global__ __launch_bounds__(256) void softmax_fwd_generic(T* y, T* __restrict__ yd, const T* x,
                                                            SoftmaxLens key_len, SoftmaxGeom g,
                                                            DropoutParams d)
 {
-    const int lane = threadIdx.x & 63;
-    const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-    if (row >= g.nrows) return;               // whole waves leave together
+    __shared__ float lds[4];
+    constexpr int R = 256 / TH;
+    const int lane = threadIdx.x % TH;
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * R + threadIdx.x / TH;
+    if (row >= g.nrows) return;               // whole waves (TH = 64) or the whole workgroup (TH = 256) leave together
     const int limit = row_limit(g, key_len, row);
     const int64_t ro = row * g.k_len;
     float mx = -INFINITY;
-    for (int j = lane; j < limit; j += 64) mx = fmaxf(mx, to_f32<T>(x[ro + j]) * g.scale);
-    mx = group_max<64>(mx);
+    for (int j = lane; j < limit; j += TH) mx = fmaxf(mx, to_f32<T>(x[ro + j]) * g.scale);
+    if constexpr (TH == 64) mx = group_max<64>(mx);
+    else mx = block_allreduce<4, OpMax>(mx, lds);
     const float mxs = (limit > 0 ? mx : 0.0f) * kLog2e;
     float z = 0.0f;
-    for (int j = lane; j < limit; j += 64) z += __builtin_amdgcn_exp2f(fmaf(to_f32<T>(x[ro + j]) * g.scale, kLog2e, -mxs));
-    z = group_sum<64>(z);
+    for (int j = lane; j < limit; j += TH) z += __builtin_amdgcn_exp2f(fmaf(to_f32<T>(x[ro + j]) * g.scale, kLog2e, -mxs));
+    if constexpr (TH == 64) z = group_sum<64>(z);
+    else z = block_allreduce<4, OpSum>(z, lds);
     const float inv = limit > 0 ? 1.0f / z : 0.0f;
-    for (int j = lane; j < g.k_len; j += 64) {
+    for (int j = lane; j < g.k_len; j += TH) {
         float o = 0.0f;
         if (j < limit) o = __builtin_amdgcn_exp2f(fmaf(to_f32<T>(x[ro + j]) * g.scale, kLog2e, -mxs)) * inv;
         y[ro + j] = from_f32<T>(o);
@@ -617,24 +622,27 @@ __global__ __launch_bounds__(256) void softmax_fwd_generic(T* y, T* __restrict__
     }
 }
 
-template <typename T>
+template <typename T, int TH>
 __global__ __launch_bounds__(256) void softmax_bwd_generic(T* dx, const T* dy, const T* __restrict__ y,
                                                            SoftmaxLens key_len, SoftmaxGeom g,
                                                            DropoutParams d)
 {
-    const int lane = threadIdx.x & 63;
-    const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    __shared__ float lds[4];
+    constexpr int R = 256 / TH;
+    const int lane = threadIdx.x % TH;
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * R + threadIdx.x / TH;
     if (row >= g.nrows) return;
     const int limit = row_limit(g, key_len, row);
     const int64_t ro = row * g.k_len;
     float dot = 0.0f;
-    for (int j = lane; j < limit; j += 64) {
+    for (int j = lane; j < limit; j += TH) {
         float gg = to_f32<T>(dy[ro + j]);
         if (d.on) gg *= dropout_factor1(d, static_cast<uint64_t>(ro + j));
         dot = fmaf(gg, to_f32<T>(y[ro + j]), dot);
     }
-    dot = group_sum<64>(dot);
-    for (int j = lane; j < g.k_len; j += 64) {
+    if constexpr (TH == 64) dot = group_sum<64>(dot);
+    else dot = block_allreduce<4, OpSum>(dot, lds);
+    for (int j = lane; j < g.k_len; j += TH) {
         float o = 0.0f;
         if (j < limit) {
             float gg = to_f32<T>(dy[ro + j]);
@@ -784,8 +792,13 @@ static lsq_status softmax_fwd_dispatch(void* y, void* yd, const void* x, Softmax
         return launch_status();
     }
     if (sh.lpr == 0) {
-        hipLaunchKernelGGL((softmax_fwd_generic<T>), dim3(static_cast<unsigned>(ceil_div(g.nrows, 4))), dim3(256), 0, s,
-                           yp, ydp, xp, key_len, g, d);
+        // long rows: a whole workgroup per row (four times the lanes, and rows of this length come in small numbers)
+        if (g.k_len > 2048)
+            hipLaunchKernelGGL((softmax_fwd_generic<T, 256>), dim3(static_cast<unsigned>(g.nrows)), dim3(256), 0, s,
+                               yp, ydp, xp, key_len, g, d);
+        else
+            hipLaunchKernelGGL((softmax_fwd_generic<T, 64>), dim3(static_cast<unsigned>(ceil_div(g.nrows, 4))), dim3(256), 0, s,
+                               yp, ydp, xp, key_len, g, d);
         return launch_status();
     }
     const dim3 block(256);
@@ -833,8 +846,12 @@ static lsq_status softmax_bwd_dispatch(void* dx, const void* dy, const void* y, 
         return launch_status();
     }
     if (sh.lpr == 0) {
-        hipLaunchKernelGGL((softmax_bwd_generic<T>), dim3(static_cast<unsigned>(ceil_div(g.nrows, 4))), dim3(256), 0, s,
-                           dxp, dyp, yp, key_len, g, d);
+        if (g.k_len > 2048)
+            hipLaunchKernelGGL((softmax_bwd_generic<T, 256>), dim3(static_cast<unsigned>(g.nrows)), dim3(256), 0, s,
+                               dxp, dyp, yp, key_len, g, d);
+        else
+            hipLaunchKernelGGL((softmax_bwd_generic<T, 64>), dim3(static_cast<unsigned>(ceil_div(g.nrows, 4))), dim3(256), 0, s,
+                               dxp, dyp, yp, key_len, g, d);
         return launch_status();
     }
     const dim3 block(256);

@@ -24,7 +24,7 @@ CASES = [
     (1, 2, 3, 2048, "pad", 0.1), (1, 1, 3, 4096, "pad", 0.1), (1, 1, 2, 1, "none", 0.0),
     # long rows: one workgroup per row (2048 < k_len <= 16384), and the fallback beyond
     (2, 1, 4, 2056, "pad", 0.1), (1, 2, 3, 8192, "pad+causal", 0.1), (1, 1, 2, 16384, "pad", 0.0),
-    (1, 1, 2, 16392, "pad", 0.1),
+    (1, 1, 2, 16392, "pad", 0.1), (2, 1, 5, 4099, "pad+causal", 0.1),
     # lengths that are not a multiple of 8: element-granular lanes (every bucket, both sides of each edge)
     (3, 2, 5, 7, "pad", 0.25), (3, 2, 9, 9, "pad+causal", 0.1), (4, 2, 17, 17, "pad", 0.1), (2, 2, 31, 33, "pad+causal", 0.0),
     (2, 2, 63, 63, "pad", 0.1), (2, 2, 65, 65, "causal", 0.1), (64, 4, 100, 100, "pad", 0.1), (2, 3, 127, 127, "pad+causal", 0.1),
