@@ -215,7 +215,7 @@ static lsq_status bdr_fwd_dispatch(void* out, const void* x, const void* bias, c
     const T* xp = static_cast<const T*>(x);
     const T* bp = static_cast<const T*>(bias);
     const T* rp = static_cast<const T*>(res);
-    if (hidden % kPack == 0) {
+    if (!bdr_fwd_is_flat(hidden)) {
         const int ppr = hidden / kPack;
         const int w = bdr_lanes_per_row(ppr);
         const int64_t rpi = static_cast<int64_t>(kBdrFwdWaves) * (64 / w) * kBdrFwdUnroll;     // rows of a workgroup's trip
@@ -244,7 +244,7 @@ static lsq_status bdr_bwd_dispatch(void* dx, float* dbias, const void* dy, int64
 {
     T* o = static_cast<T*>(dx);
     const T* g = static_cast<const T*>(dy);
-    if (hidden % kPack == 0) {
+    if (!bdr_bwd_is_flat(hidden)) {
         const int ppr = hidden / kPack;
         const BdrBwdPlan pl = bdr_bwd_plan(rows, hidden);
         const dim3 grid(static_cast<unsigned>(pl.col_blocks), static_cast<unsigned>(pl.row_blocks)), block(64 * kBdrBwdWaves);
