@@ -244,7 +244,7 @@ static lsq_status bad_fwd_dispatch(void* out, const void* x, const void* bias, i
     T* o = static_cast<T*>(out);
     const T* xp = static_cast<const T*>(x);
     const T* bp = static_cast<const T*>(bias);
-    if (hidden % kPack == 0) {
+    if (!bad_is_flat(hidden)) {
         const int ppr = hidden / kPack;
         int64_t rb = ceil_div(rows, 4 * kBadWaves);
         if (rb > 4096) rb = 4096;
@@ -268,7 +268,7 @@ static lsq_status bad_bwd_dispatch(void* dx, float* dbias, const void* dy, const
     const T* g = static_cast<const T*>(dy);
     const T* xp = static_cast<const T*>(x);
     const T* bp = static_cast<const T*>(bias);
-    if (hidden % kPack == 0) {
+    if (!bad_is_flat(hidden)) {
         const int ppr = hidden / kPack;
         const int rb = bdr_bwd_row_blocks(rows, hidden);
         const dim3 grid(static_cast<unsigned>(ceil_div(ppr, 64)), static_cast<unsigned>(rb)), block(256);

@@ -250,6 +250,9 @@ inline int bdr_lanes_per_row(int ppr)
 // ~55 us flat; backward 860 / 439 / 175 / 83 us at 8 / 16 / 24 / 64 columns against ~57 us flat).
 inline bool bdr_fwd_is_flat(int hidden) { return hidden % kPack != 0 || hidden <= 16; }
 inline bool bdr_bwd_is_flat(int hidden) { return hidden % kPack != 0 || hidden <= 64; }
+// bias + activation + dropout works in column blocks of 64 packs: rows of fewer than 32 packs take the flat walk
+// (8 columns: 1629 / 10103 us in column blocks at 32 Mi elements).
+inline bool bad_is_flat(int hidden) { return hidden % kPack != 0 || hidden < 256; }
 
 // Backward launch shape: column blocks of w packs; row blocks (= partial rows of the column sums) of
 // `trips` consecutive groups of waves * 64 / w rows.
