@@ -174,14 +174,35 @@ __global__ __launch_bounds__(256) void flat_packs_kernel(F f, float* __restrict_
             __syncthreads();
             const int64_t left = total - base;
             const int n = left < kFlatChunk ? static_cast<int>(left) : kFlatChunk;
-            for (int c = tid; c < hidden; c += 256) {
-                int i = c - cb;
-                if (i < 0) i += hidden;
-                float a = acc[c];
-                for (; i < n; i += hidden) a += flat_lds[i];
-                acc[c] = a;
+            if (hidden >= 256) {
+                for (int c = tid; c < hidden; c += 256) {
+                    int i = c - cb;
+                    if (i < 0) i += hidden;
+                    float a = acc[c];
+                    for (; i < n; i += hidden) a += flat_lds[i];
+                    acc[c] = a;
+                }
+                __syncthreads();                                   // the next trip overwrites the results
+            } else {
+                // short rows: 256 / hidden threads share a column (every slices-th entry each, ascending), their
+                // sums are added in slice order by the column's owner
+                const int slices = 256 / hidden, c = tid % hidden, sl = tid / hidden;
+                float a = 0.0f;
+                if (sl < slices) {
+                    int i = c - cb;
+                    if (i < 0) i += hidden;
+                    for (i += sl * hidden; i < n; i += slices * hidden) a += flat_lds[i];
+                }
+                __syncthreads();                                   // all entries read: the results' place is reused
+                if (sl < slices) flat_lds[sl * hidden + c] = a;
+                __syncthreads();
+                if (tid < hidden) {
+                    float tsum = acc[tid];
+                    for (int k = 0; k < slices; ++k) tsum += flat_lds[k * hidden + tid];
+                    acc[tid] = tsum;
+                }
+                __syncthreads();
             }
-            __syncthreads();                                       // the next trip overwrites the results
         }
     }
     if constexpr (COLS && ACC_LDS) {
@@ -246,13 +267,13 @@ inline int bdr_lanes_per_row(int ppr)
 }
 
 // Rows of very few packs leave most lanes of a 16-lane row segment idle; they take the flat walk like the
-// rows that are not whole packs (measured at 32 Mi elements: forward 187 / 94 us at 8 / 16 columns against
-// ~55 us flat; backward 860 / 439 / 175 / 83 us at 8 / 16 / 24 / 64 columns against ~57 us flat).
-inline bool bdr_fwd_is_flat(int hidden) { return hidden % kPack != 0 || hidden <= 16; }
-inline bool bdr_bwd_is_flat(int hidden) { return hidden % kPack != 0 || hidden <= 64; }
-// bias + activation + dropout works in column blocks of 64 packs: rows of fewer than 32 packs take the flat walk
-// (8 columns: 1629 / 10103 us in column blocks at 32 Mi elements).
-inline bool bad_is_flat(int hidden) { return hidden % kPack != 0 || hidden < 256; }
+// rows that are not whole packs (measured at 32 Mi elements: forward 187 / 94 / 63 us at 8 / 16 / 24 columns
+// against 47 us flat; backward 860 / 439 / 175 / 83 / 80 us at 8 / 16 / 24 / 64 / 72 columns against 48 us flat).
+inline bool bdr_fwd_is_flat(int hidden) { return hidden % kPack != 0 || hidden <= 32; }
+inline bool bdr_bwd_is_flat(int hidden) { return hidden % kPack != 0 || hidden < 128; }
+// bias + activation + dropout works in column blocks of 64 packs: rows of up to 32 packs take the flat walk
+// (8 columns: 1629 / 10103 us in column blocks at 32 Mi elements, 51 / 95 us flat; 256 columns: 56 / 138 us).
+inline bool bad_is_flat(int hidden) { return hidden % kPack != 0 || hidden <= 256; }
 
 // Backward launch shape: column blocks of w packs; row blocks (= partial rows of the column sums) of
 // `trips` consecutive groups of waves * 64 / w rows.
