@@ -655,6 +655,7 @@ inline LnShape ln_shape(int hidden)
         return best;
     }
     if (nv <= 512) return {256, 2};
+    if (nv <= 768) return {256, 3};       // 5120 columns: 640 of 768 pack slots in use (of 1024 as 256 x 4); 6144 fit exactly
     if (nv <= 1024) return {256, 4};
     if (nv <= 2048) return {kLnWideLpr, kLnWideVpl};     // hidden up to 16384: one large workgroup per row
     return {0, 0};
@@ -679,7 +680,7 @@ inline int ln_fwd_blocks(int64_t rows, int lpr)
     return static_cast<int>(b);
 }
 
-#define LSQ_LN_CASES_COMMON(X) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 3) X(64, 4) X(64, 5) X(64, 6) X(256, 2) X(256, 4)
+#define LSQ_LN_CASES_COMMON(X) X(8, 1) X(16, 1) X(32, 1) X(64, 1) X(64, 2) X(64, 3) X(64, 4) X(64, 5) X(64, 6) X(256, 2) X(256, 3) X(256, 4)
 
 // fuse != nullptr: x is the projection output and *fuse carries h / residual / bias / dropout
 template <typename T>

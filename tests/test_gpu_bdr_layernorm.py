@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 
 # (rows, hidden): the five workload shapes, every register bucket, ragged tails, the no-bucket fallback
 SHAPES = [(512, 512), (4096, 512), (8192, 1024), (8192, 1280), (37, 64), (19, 128), (5, 256), (33, 768), (9, 1536),
-          (7, 2048), (3, 4096), (2, 8192), (1, 8), (50, 257), (3, 16384),
+          (7, 2048), (3, 4096), (2, 8192), (1, 8), (50, 257), (3, 16384), (6, 5120), (3, 6144),
           (300, 12288), (11, 8200), (7, 16392)]
 
 

@@ -16,6 +16,7 @@ SHAPES = [
     (512, 512), (4096, 512), (8192, 1024), (8192, 1280),
     (4096, 256), (1000, 768), (37, 64), (5, 8), (129, 128), (3, 1536), (67, 2048),
     (9, 4096), (5, 8192), (1, 1024), (7, 257), (33, 50), (3, 16384), (2, 1),
+    (11, 5120), (6, 6144), (5, 4104),         # 256 lanes x 3 packs: ragged, exact, first past 256 x 2
     (300, 12288), (11, 8200), (7, 16392),     # the 1024-lane row bucket (up to 16384), ragged inside it, and beyond it
     (13, 2051), (6, 20001), (5, 20480),       # rows off the pack grid: one wave per row up to 2048 columns, a workgroup per row beyond; whole packs beyond 16384
 ]
