@@ -29,7 +29,9 @@
  *     single-precision computation).  Results are rounded once, to nearest
  *     even, when stored.
  *   - Outputs must not alias inputs except where a comment says they may.
- *   - Results are bit-reproducible from run to run: no floating-point atomics.
+ *   - Results are bit-reproducible from run to run: no floating-point atomics.  (A launch
+ *     shape recorded by lsq_softmax_tune sums a row in another order than the default: the
+ *     last bit of a few softmax outputs may differ from the default's, reproducibly.)
  *   - Return value: LSQ_OK, or an error code; on error nothing was launched.
  *     Sizes of zero (rows == 0, n == 0, ...) are valid and launch nothing.
  *
