@@ -17,8 +17,9 @@ Prints ONE JSON line:
                        inside the timed region; the blocked-state variant beside it
   calibration          plain copy / read / write streams in the operators' launch style at the
                        operators' tensor sizes: what this machine gives a kernel that only moves bytes
-  ops                  per-operator table: us (HIP-graph replay of back-to-back launches), GB/s, fraction
-                       of the 8 TB/s peak, and fraction of the calibrated copy of the same byte count
+  ops                  per-operator table: us (median of five HIP-graph replays of back-to-back launches; us_min the
+                       fastest), GB/s, fraction of the 8 TB/s peak, and fraction of the calibrated copy of the same
+                       byte count; the masked softmax also at 128-byte-line granularity and with every position counted
   ops_warm             the layer-sized operators again on one buffer set (cache-warm)
   ops_next             rows beyond the nine
   ops_by_config        the nine-operator table of the other target shape (transformer-big, fp16) and of the
@@ -73,6 +74,7 @@ def parse():
 
 # ------------------------------------------------------------------------------------------- timing helpers
 EAGER = False      # --no-graph
+LAST_MIN_US = [0.0]     # graph_time_us: the fastest of the replays of its last call (the return value is their median)
 
 
 def graph_time_us(torch, fn, reps):
@@ -89,7 +91,8 @@ def graph_time_us(torch, fn, reps):
             fn(3 + i)
         b.record()
         torch.cuda.synchronize()
-        return a.elapsed_time(b) * 1e3 / reps
+        LAST_MIN_US[0] = a.elapsed_time(b) * 1e3 / reps
+        return LAST_MIN_US[0]
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         for i in range(reps):
@@ -97,13 +100,14 @@ def graph_time_us(torch, fn, reps):
     graph.replay()
     torch.cuda.synchronize()
     best = []
-    for _ in range(3):
+    for _ in range(5):
         a.record()
         graph.replay()
         b.record()
         torch.cuda.synchronize()
         best.append(a.elapsed_time(b) * 1e3 / reps)
     del graph
+    LAST_MIN_US[0] = float(np.min(best))
     return float(np.median(best))
 
 
@@ -320,7 +324,8 @@ def make_workload(torch, L, cfg, dt, dev, extras=True, warm=False, adam=None):
     }
     meta = dict(sets=sets, soft_sets=soft_sets, t_active=t_active, allowed=allowed, softmax_tune=softmax_tune,
                 softmax_line_bytes={"softmax_fwd": allowed_lines + 2 * Es + (2 * Es if pa > 0 else 0),
-                                    "softmax_bwd": 2 * allowed_lines + 2 * Es},
+                                    "softmax_bwd": 2 * allowed_lines + 2 * Es,
+                                    "softmax_fwd_full": 4 * Es + (2 * Es if pa > 0 else 0), "softmax_bwd_full": 6 * Es},
                 workload=f"{cfg.name}: {B}x{Lq} tokens, hidden {H}, heads {N}, vocab {V}, Adam n={n}, "
                          f"{'causal' if causal else 'key-padding'} softmax, storage {dt}")
     if not extras:
@@ -525,19 +530,29 @@ def time_steps(torch, ops, names, steps, warmup):
     return (t1 - t0) * 1e3 / steps, float(np.mean([a.elapsed_time(b) for a, b in ev]))
 
 
+def device_info(torch, dev):
+    """What the runtime says the device is (the peak the fractions refer to is the datasheet's 8 TB/s)."""
+    pr = torch.cuda.get_device_properties(dev)
+    return {"name": pr.name, "compute_units": int(pr.multi_processor_count), "memory_GiB": round(pr.total_memory / 2**30, 1),
+            "arch": getattr(pr, "gcnArchName", "")}
+
+
 def op_table(torch, ops, bts, names, max_reps, calib=None, line_bytes=None):
     table = {}
     for name in names:
         reps = max(3, min(max_reps, int(2e10 // max(bts[name], 1)) + 3))
         us = graph_time_us(torch, ops[name], reps)
         gbs = bts[name] / (us * 1e-6) / 1e9
-        row = {"us": round(us, 2), "GBps": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4), "bytes": int(bts[name]),
-               "launches": reps}
+        row = {"us": round(us, 2), "us_min": round(LAST_MIN_US[0], 2), "GBps": round(gbs, 1),
+               "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4), "bytes": int(bts[name]), "launches": reps}
         if calib is not None:
             row["frac_of_copy"] = round(calib.copy_us(bts[name]) / us, 4)
         if line_bytes and name in line_bytes:      # the masked softmax at 128-byte line granularity
             row["bytes_line_granular"] = int(line_bytes[name])
             row["frac_of_peak_line_granular"] = round(line_bytes[name] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
+            full = line_bytes[name + "_full"]          # every position counted as if no mask let the kernel skip it
+            row["bytes_full_tensor"] = int(full)
+            row["frac_of_peak_full_tensor"] = round(full / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
         table[name] = row
     return table
 
@@ -603,7 +618,7 @@ def main():
                   "(per-op GB/s, % of peak and us per layer in 'ops' / 'layer_us')",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "storage_dtype": dt, "data": "synthetic",
+        "dtype": "f32", "storage_dtype": dt, "data": "synthetic", "device": device_info(torch, dev),
         "config": {"workload": meta["workload"],
                    "buffers": f"cold (layer tensors rotate over {meta['sets']} sets, softmax over {meta['soft_sets']})"},
         "roofline": roofline,
