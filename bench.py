@@ -189,7 +189,7 @@ def _line_bytes_softmax(cfg, key_len, elem_bytes=2):
 
 def adam_arrays(torch, cfg, dt, dev):
     """The trainer's arrays: fp32 p, m, v, low-precision g and p_lp.  Allocated first, as a training program does
-    when it builds its model: where the five arrays land decides 0.66-0.73 of peak for the kernel that walks them
+    when it builds its model: where the five arrays land decides 0.66-0.80 of peak for the kernel that walks them
     as five streams (the blocked optimizer state does not care)."""
     from workloads import device_normal, torch_dtype
     n, seed = cfg.adam_n, cfg.seed * 1000
@@ -198,6 +198,61 @@ def adam_arrays(torch, cfg, dt, dev):
     g = device_normal((n,), 1e-3, dt, seed + 401, dev)
     p_lp = torch.empty(n, dtype=torch_dtype(dt), device=dev)
     return p, g, m, v, p_lp
+
+
+def adam_placement_spread(torch, L, cfg, dt, dev):
+    """lsq_adam_step on three more allocations of its five arrays (fresh; behind 2 GiB of other allocations; as slices
+    of one slab): the same kernel on the same sizes, only the physical pages differ.  The separate-array trainer is
+    sensitive to them; the blocked state, measured beside it on a fresh allocation, is not."""
+    from workloads import ADAM_HYPER, torch_dtype
+    n, tdt = cfg.adam_n, torch_dtype(dt)
+    res = {}
+    st = dict(step=0)
+
+    def run(p, m, v, g, p_lp):
+        def f(i):
+            st["step"] += 1
+            L.lsq_adam_step(p, m, v, g, p_lp, step=st["step"], **ADAM_HYPER)
+        return round(28 * n / graph_time_us(torch, f, 3) / 1e3 / HBM_PEAK_GBS, 4)
+
+    def fresh():
+        return (torch.zeros(n, dtype=torch.float32, device=dev), torch.zeros(n, dtype=torch.float32, device=dev),
+                torch.zeros(n, dtype=torch.float32, device=dev), torch.zeros(n, dtype=tdt, device=dev),
+                torch.empty(n, dtype=tdt, device=dev))
+
+    arrs = fresh()
+    res["fresh"] = run(*arrs)
+    del arrs
+    gc.collect()
+    torch.cuda.empty_cache()
+    junk = [torch.empty(64 << 20, dtype=torch.uint8, device=dev) for _ in range(64)]
+    junk = junk[::2]
+    arrs = fresh()
+    res["behind_other_allocations"] = run(*arrs)
+    del arrs, junk
+    gc.collect()
+    torch.cuda.empty_cache()
+    a4 = -(-4 * n // 4096) * 4096
+    a2 = -(-2 * n // 4096) * 4096
+    slab = torch.zeros(3 * a4 + 2 * a2, dtype=torch.uint8, device=dev)
+    cut = lambda off, nb, t: slab[off:off + nb].view(t)
+    res["one_slab"] = run(cut(0, 4 * n, torch.float32), cut(a4, 4 * n, torch.float32), cut(2 * a4, 4 * n, torch.float32),
+                          cut(3 * a4, 2 * n, tdt), cut(3 * a4 + a2, 2 * n, tdt))
+    del slab
+    gc.collect()
+    torch.cuda.empty_cache()
+    state = torch.zeros(L.lsq_adam_state_bytes(n) // 4, dtype=torch.float32, device=dev)
+    g, p_lp = torch.zeros(n, dtype=tdt, device=dev), torch.empty(n, dtype=tdt, device=dev)
+
+    def fb(i):
+        st["step"] += 1
+        L.lsq_adam_step_blocked(state, g, p_lp, step=st["step"], **ADAM_HYPER)
+    res["blocked_state_fresh"] = round(28 * n / graph_time_us(torch, fb, 3) / 1e3 / HBM_PEAK_GBS, 4)
+    del state, g, p_lp
+    gc.collect()
+    torch.cuda.empty_cache()
+    return dict(res, what="fraction of the 8 TB/s peak of lsq_adam_step on other allocations of the same arrays "
+                          "(the roofline entry above is the allocation made first in this process)")
 
 
 def make_workload(torch, L, cfg, dt, dev, extras=True, warm=False, adam=None):
@@ -699,6 +754,7 @@ def main():
         gc.collect()
         torch.cuda.empty_cache()
 
+    out["adam_placement_spread"] = adam_placement_spread(torch, L, cfg, dt, dev)
     out["calibration"] = calib.as_json()
     out["cpu_baseline"] = None if args.no_cpu_baseline else cpu_baseline(cfg, dt)
     print(json.dumps(out))
