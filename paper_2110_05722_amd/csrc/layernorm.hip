@@ -665,12 +665,13 @@ inline LnShape ln_shape(int hidden)
 }
 
 // Backward keeps 2 (3 when fused) fp32 column accumulators per element of a lane next to the rows in
-// flight and sums the row slots of a workgroup through LDS: there 64 lanes per row with an idle
-// tail beat the exact fit (hidden 1280: 18.9 against 20.7 us with 32 lanes x 5 packs).
+// flight and sums the row slots of a workgroup through LDS: from three packs per lane on, 64 lanes per
+// row with an idle tail beat the exact fit on 32 (8192 rows: 1280 columns 18.9 against 20.7 us as 32 x 5,
+// 1024 columns 16.9 against 20.0 us as 32 x 4); 512 columns stay on 32 x 2 (11.5 against 12.9 us as 64 x 1).
 inline LnShape ln_bwd_shape(int hidden)
 {
     const LnShape f = ln_shape(hidden);
-    if (f.lpr != 32 || f.vpl == 1) return f;
+    if (f.lpr != 32 || f.vpl <= 2) return f;
     return {64, (hidden / kPack + 63) / 64};
 }
 
@@ -820,7 +821,7 @@ static lsq_status ln_bwd_dispatch(void* dx, float* dgamma, float* dbeta, const v
             else hipLaunchKernelGGL((ln_bwd_kernel<T, L, V, false, TH, true, false>), grid, block, shmem, s, dxp, partial, dyp, xp, gp, mean, rstd, rp, rows, hidden, *fuse);   \
         }                                                                                                    \
     }
-    LSQ_LN_CASES_COMMON(X)
+    LSQ_LN_CASES_COMMON(X) X(32, 2)
 #undef X
     if (fuse) launch_colsum_finalize(dgamma, dbeta, hidden, partial, P, 3 * hidden, s, dbias, 2 * hidden);
     else launch_colsum_finalize(dgamma, dbeta, hidden, partial, P, 2 * hidden, s);
