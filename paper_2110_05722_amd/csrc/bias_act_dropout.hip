@@ -16,7 +16,6 @@ namespace lsq {
 constexpr bool kNT = true;
 
 constexpr int kBadWaves = 4;
-constexpr int kBadUnroll = 1;   // rows a wave has in flight in backward
 enum { ACT_RELU = 0, ACT_GELU = 1, ACT_GELU_TANH = 2 };
 
 // sigmoid(t) = 1/(1 + 2^(-t*log2 e)): one v_exp_f32 and one v_rcp_f32 (1 ulp; an IEEE
@@ -86,11 +85,16 @@ __global__ __launch_bounds__(256) void bad_fwd_cols(T* out, const T* x, const T*
     float b[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if constexpr (HAS_BIAS) load8<T>(bias + static_cast<int64_t>(cp) * kPack, b);
     const int64_t stride = static_cast<int64_t>(gridDim.y) * kBadWaves;
-    for (int64_t r = static_cast<int64_t>(blockIdx.y) * kBadWaves + wave; r < rows; r += stride) {
+    // the pack of the next row is loaded before this row's is used
+    int64_t r = static_cast<int64_t>(blockIdx.y) * kBadWaves + wave;
+    RawPack<T> nx = r < rows ? load_raw<T, kNT>(x + (r * ppr + cp) * kPack) : zero_raw<T>();
+    for (; r < rows; r += stride) {
+        const RawPack<T> cx = nx;
+        if (r + stride < rows) nx = load_raw<T, kNT>(x + ((r + stride) * ppr + cp) * kPack);
         const int64_t pack = r * ppr + cp;
         float xf[8], k[8];
-        load8<T, kNT>(x + pack * kPack, xf);
         if constexpr (DROP) dropout_factors8(d, static_cast<uint64_t>(pack), k);
+        unpack<T>(cx, xf);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const float a = act_value<ACT>(xf[j] + b[j]);
@@ -113,38 +117,33 @@ __global__ __launch_bounds__(256) void bad_bwd_cols(T* dx, float* __restrict__ p
     if (active) {
         float b[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         if constexpr (HAS_BIAS) load8<T>(bias + static_cast<int64_t>(cp) * kPack, b);
-        // kBadUnroll rows per trip: all their loads are issued before the first Philox call
-        for (int64_t r0 = static_cast<int64_t>(blockIdx.y) * kBadWaves + wave; r0 < rows; r0 += stride * kBadUnroll) {
-            RawPack<T> rg[kBadUnroll], rx[kBadUnroll];
-#pragma unroll
-            for (int u = 0; u < kBadUnroll; ++u) {
-                const int64_t r = r0 + u * stride;
-                if (r < rows) {
-                    rg[u] = load_raw<T, kNT>(dy + (r * ppr + cp) * kPack);
-                    rx[u] = load_raw<T, kNT>(x + (r * ppr + cp) * kPack);
-                } else {
-                    rg[u] = zero_raw<T>();
-                    rx[u] = zero_raw<T>();
-                }
+        // the packs of the next row are loaded before this row's are used, and the dropout factors, which need
+        // no data, are drawn while the loads are in flight
+        int64_t r = static_cast<int64_t>(blockIdx.y) * kBadWaves + wave;
+        RawPack<T> ng = zero_raw<T>(), nx = zero_raw<T>();
+        if (r < rows) {
+            ng = load_raw<T, kNT>(dy + (r * ppr + cp) * kPack);
+            nx = load_raw<T, kNT>(x + (r * ppr + cp) * kPack);
+        }
+        for (; r < rows; r += stride) {
+            const RawPack<T> cg = ng, cx = nx;
+            const int64_t rn = r + stride;
+            if (rn < rows) {
+                ng = load_raw<T, kNT>(dy + (rn * ppr + cp) * kPack);
+                nx = load_raw<T, kNT>(x + (rn * ppr + cp) * kPack);
             }
+            const int64_t pack = r * ppr + cp;
+            float g[8], xf[8], k[8];
+            if constexpr (DROP) dropout_factors8(d, static_cast<uint64_t>(pack), k);
+            unpack<T>(cg, g);
+            unpack<T>(cx, xf);
 #pragma unroll
-            for (int u = 0; u < kBadUnroll; ++u) {
-                const int64_t r = r0 + u * stride;
-                if (r < rows) {
-                    const int64_t pack = r * ppr + cp;
-                    float g[8], xf[8], k[8];
-                    unpack<T>(rg[u], g);
-                    unpack<T>(rx[u], xf);
-                    if constexpr (DROP) dropout_factors8(d, static_cast<uint64_t>(pack), k);
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        const float s = act_slope<ACT>(xf[j] + b[j]);
-                        g[j] = DROP ? g[j] * k[j] * s : g[j] * s;
-                        acc[j] += g[j];
-                    }
-                    store8<T, kNT>(dx + pack * kPack, g);
-                }
+            for (int j = 0; j < 8; ++j) {
+                const float s = act_slope<ACT>(xf[j] + b[j]);
+                g[j] = DROP ? g[j] * k[j] * s : g[j] * s;
+                acc[j] += g[j];
             }
+            store8<T, kNT>(dx + pack * kPack, g);
         }
     }
     if (partial == nullptr) return;        // uniform over the grid
