@@ -52,17 +52,20 @@ __global__ __launch_bounds__(256) void split_heads_kernel(T* __restrict__ o0, T*
     float b[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if constexpr (HAS_BIAS) load8<T>(bias + col, b);
     const int64_t stride = static_cast<int64_t>(gridDim.y) * kHeadWaves;
-    for (int64_t t = static_cast<int64_t>(blockIdx.y) * kHeadWaves + wave; t < g.rows; t += stride) {
-        const T* src = in + (t * g.ppr + cp) * kPack;
+    // the pack of the next token is loaded before this token's is stored
+    int64_t t = static_cast<int64_t>(blockIdx.y) * kHeadWaves + wave;
+    RawPack<T> nxt = t < g.rows ? load_raw<T, kNT>(in + (t * g.ppr + cp) * kPack) : zero_raw<T>();
+    for (; t < g.rows; t += stride) {
+        const RawPack<T> r = nxt;
+        if (t + stride < g.rows) nxt = load_raw<T, kNT>(in + ((t + stride) * g.ppr + cp) * kPack);
         T* dst = out + head_offset(g, t, within);
         if constexpr (HAS_BIAS) {
             float f[8];
-            load8<T, kNT>(src, f);
+            unpack<T>(r, f);
 #pragma unroll
             for (int j = 0; j < 8; ++j) f[j] += b[j];
             store8<T, kNT>(dst, f);
-        } else {
-            const RawPack<T> r = load_raw<T, kNT>(src);          // a pure move: bit-exact
+        } else {                                                 // a pure move: bit-exact
             if constexpr (sizeof(T) == 2) st_u4<kNT>(dst, r.u);
             else { st_f4<kNT>(reinterpret_cast<float*>(dst), r.a); st_f4<kNT>(reinterpret_cast<float*>(dst) + 4, r.b); }
         }
