@@ -54,6 +54,11 @@ __device__ __forceinline__ bool is_ignored(int k, int vocab, int ignore_index)
     return k == ignore_index || k < 0 || k >= vocab;
 }
 
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+struct Half8 { half2v v[4]; };
+template <typename T> constexpr bool kIsF16 = false;
+template <> constexpr bool kIsF16<f16> = true;
+
 struct OnlineLse {
     float m = -INFINITY;   // running maximum of h*log2(e)
     float s = 0.0f;        // sum of exp2(h*log2e - m)
@@ -81,6 +86,27 @@ struct OnlineLse {
         s = acc;
         m = mn;
         sh += hsum;
+    }
+    // The same for a pack of fp16 logits, on the packed halves: the maximum two elements per instruction (exact,
+    // and max(h) * log2e = max(h * log2e) because rounding is monotonic), the sum of the logits by dot products
+    // with ones, the exponent by one fma that reads the half directly.  A quarter fewer vector instructions per
+    // element than add8, on a kernel whose vector ALU is 85 % busy.
+    __device__ __forceinline__ void add_pack_f16(const Half8& h)
+    {
+        const half2v m01 = __builtin_elementwise_max(h.v[0], h.v[1]), m23 = __builtin_elementwise_max(h.v[2], h.v[3]);
+        const half2v mm = __builtin_elementwise_max(m01, m23);
+        const float vm = fmaxf(static_cast<float>(mm.x), static_cast<float>(mm.y)) * kLog2eX;
+        const float mn = fmaxf(m, vm);
+        float acc = s * __builtin_amdgcn_exp2f(m - mn);
+        const half2v ones = {static_cast<_Float16>(1.0f), static_cast<_Float16>(1.0f)};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            acc += __builtin_amdgcn_exp2f(fmaf(static_cast<float>(h.v[c].x), kLog2eX, -mn));
+            acc += __builtin_amdgcn_exp2f(fmaf(static_cast<float>(h.v[c].y), kLog2eX, -mn));
+            sh = __builtin_amdgcn_fdot2(h.v[c], ones, sh, false);
+        }
+        s = acc;
+        m = mn;
     }
 };
 
@@ -133,9 +159,13 @@ __global__ __launch_bounds__(TH * R) void xent_fwd_kernel(float* __restrict__ lo
 #pragma unroll
         for (int u = 0; u < kXentUnroll; ++u) {
             if (ok[u]) {
-                float h[8];
-                unpack<T>(raw[u], h);
-                st.add8(h);
+                if constexpr (kIsF16<T>) {
+                    st.add_pack_f16(__builtin_bit_cast(Half8, raw[u].u));
+                } else {
+                    float h[8];
+                    unpack<T>(raw[u], h);
+                    st.add8(h);
+                }
             }
         }
     }
@@ -322,10 +352,6 @@ __global__ __launch_bounds__(256) void xent_bwd_flat_kernel(T* dlogits, const T*
 // neighbouring rows: those two packs are read and written element by element, everything else in
 // aligned 128-bit packs.  Every load of the row (and of the target logit) precedes every store,
 // and a workgroup writes only its own row's elements, so dlogits may be the logits buffer itself.
-typedef _Float16 half2v __attribute__((ext_vector_type(2)));
-struct Half8 { half2v v[4]; };
-template <typename T> constexpr bool kIsF16 = false;
-template <> constexpr bool kIsF16<f16> = true;
 
 // which of the 8 elements of window pack i lie in [lo, hi) (element offsets from the window's first pack)
 __device__ __forceinline__ unsigned row_mask(int i, int lo, int hi)
