@@ -23,7 +23,7 @@ Prints ONE JSON line:
   ops_warm             the layer-sized operators again on one buffer set (cache-warm)
   ops_next             rows beyond the nine
   ops_by_config        the nine-operator table of the other target shape (transformer-big, fp16) and of the
-                       other storage type (gpt2-large, bf16)
+                       other storage type (gpt2-large, bf16), and of the masked-LM workload (bert-large, bf16)
   family_frac          bytes / time per operator family and the minimum over the five
   layer_us             non-GEMM microseconds of one layer, forward + backward
   cpu_baseline         the CPU oracle timed on a bounded sample: per operator, one thread and OpenMP
@@ -738,7 +738,7 @@ def main():
 
     # ---- the other target shape and the other storage type: the nine-operator table and the step
     out["ops_by_config"] = {}
-    for cname, cdt in (("transformer-big", "f16"), ("gpt2-large", "bf16")):
+    for cname, cdt in (("transformer-big", "f16"), ("gpt2-large", "bf16"), ("bert-large", "bf16")):
         if cname == cfg.name and cdt == dt:
             continue
         c2 = next(c for c in CONFIGS if c.name == cname)
