@@ -3,12 +3,13 @@
 // dropout — fused into one launch).  The paper names ReLU; the BERT and GPT-2
 // models of its Sec. VI use GELU (erf form and tanh approximation).
 //
-// Same layout as the bias+dropout+residual kernels: a wave owns 64 consecutive
-// packs of one row and walks down the rows with the bias pack in registers; the
+// A wave owns 64 consecutive packs of one row and walks down the rows with the bias
+// pack in registers, the next row's packs loaded before this row's are used; the
 // dropout mask is rebuilt from the Philox counter of the pack in both directions;
 // backward recomputes the activation slope from the saved pre-activation input
 // and accumulates dbias per lane (no atomics; partial rows + ordered second stage).
-// HBM traffic: forward 2 tensors, backward 3.
+// HBM traffic: forward 2 tensors, backward 3.  Rows of up to 32 packs, and rows that are not whole
+// packs, take the flat walk of host.hpp instead.
 #include "host.hpp"
 
 namespace lsq {

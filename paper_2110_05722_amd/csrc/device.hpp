@@ -326,7 +326,7 @@ __device__ __forceinline__ uint32_t dropout_keep_bits8(const DropoutParams& d, u
     return bits;
 }
 
-// The factor for one element (generic, unaligned paths: one Philox call per element).
+// The factor for one element (element-strided paths and the ragged last pack of a flat walk: one Philox call per element).
 __device__ __forceinline__ float dropout_factor1(const DropoutParams& d, uint64_t e)
 {
     uint32_t w[4];

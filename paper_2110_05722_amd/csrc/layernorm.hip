@@ -447,7 +447,8 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_kernel(T* dx, float* __restric
     }
 }
 
-// ---- generic path: any hidden; one wave per row, element-strided, rows re-read from cache
+// ---- generic path: any hidden; TH = 64 (one wave per row) or 256 lanes (one workgroup per row: rows beyond the
+// register buckets), rows re-read from cache
 // PACKS: the row is a whole number of packs (rows beyond 16384 columns), walked in 128-bit accesses.
 template <typename T, int TH, bool PACKS>
 __global__ __launch_bounds__(256) void ln_fwd_generic(T* __restrict__ y, float* __restrict__ mean,
