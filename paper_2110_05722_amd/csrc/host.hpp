@@ -58,11 +58,13 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Second stage of the column reductions: out[c] = sum over the P partial rows of
 // partial[y][c], C columns, in a fixed order (reproducible).  Columns below `split`
-// go to out0, those below `split2` to out1, the rest to out2.  A workgroup owns 32 columns; its 32 row slices each
-// sum a contiguous chunk of rows with the loads of 8 rows in flight at a time (a
-// plain loop would pay one memory latency per row), then the slices are combined in
-// slice order through LDS.
-constexpr int kFinalizeSlices = 32;
+// go to out0, those below `split2` to out1, the rest to out2.  A workgroup owns 32 columns; its 8 row slices each
+// sum a contiguous chunk of rows with the loads of 32 rows in flight at a time (a
+// plain loop would pay one memory latency per row; 256 partial rows are one batch per thread), then the
+// slices are combined in slice order through LDS.  Measured behind a 21 MB producer kernel, 256 x 2560
+// partials: 2.5 us against 2.7 us as 32 slices x 8 loads in a 1024-thread workgroup (an empty dependent
+// kernel: 1.4 us).
+constexpr int kFinalizeSlices = 8, kFinalizeLoads = 32;
 
 template <int = 0>
 __global__ __launch_bounds__(32 * kFinalizeSlices) void colsum_finalize_kernel(float* __restrict__ out0,
@@ -80,6 +82,13 @@ __global__ __launch_bounds__(32 * kFinalizeSlices) void colsum_finalize_kernel(f
     float s = 0.0f;
     if (c < C) {
         int y = y0;
+        for (; y + kFinalizeLoads <= y1; y += kFinalizeLoads) {
+            float t[kFinalizeLoads];
+#pragma unroll
+            for (int k = 0; k < kFinalizeLoads; ++k) t[k] = partial[static_cast<int64_t>(y + k) * C + c];
+#pragma unroll
+            for (int k = 0; k < kFinalizeLoads; ++k) s += t[k];
+        }
         for (; y + 8 <= y1; y += 8) {
             float t[8];
 #pragma unroll
