@@ -24,10 +24,10 @@ extern "C" size_t lsq_workspace_bytes(int32_t op, int64_t rows, int32_t cols)
             return flat_workspace_bytes(rows, cols);        // one per workgroup of the flat walk
         case LSQ_OP_BIAS_ACT_DROPOUT_BWD:
             if (bad_is_flat(cols)) return flat_workspace_bytes(rows, cols);
-            return static_cast<size_t>(bdr_bwd_row_blocks(rows, cols)) * static_cast<size_t>(cols) * sizeof(float);
+            return static_cast<size_t>(bad_bwd_row_blocks(rows, cols)) * static_cast<size_t>(cols) * sizeof(float);
         case LSQ_OP_SPLIT_HEADS_BWD:
             // one [cols] fp32 partial row (dbias) per row block
-            return static_cast<size_t>(bdr_bwd_row_blocks(rows, cols)) * static_cast<size_t>(cols) * sizeof(float);
+            return static_cast<size_t>(heads_bwd_row_blocks(rows, cols)) * static_cast<size_t>(cols) * sizeof(float);
         case LSQ_OP_EMBEDDING_BWD:
             // sorted order, fp32 rows of the id segments that cross a window, rank counts
             return emb_bwd_plan(rows, cols).total();

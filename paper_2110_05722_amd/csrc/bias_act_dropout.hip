@@ -19,15 +19,19 @@ constexpr bool kNT = true;
 constexpr int kBadWaves = 4;
 enum { ACT_RELU = 0, ACT_GELU = 1, ACT_GELU_TANH = 2 };
 
-// sigmoid(t) = 1/(1 + 2^(-t*log2 e)): one v_exp_f32 and one v_rcp_f32 (1 ulp; an IEEE
-// division costs ten instructions and this kernel is close to ALU-bound)
-__device__ __forceinline__ float sigmoidf_fast(float t)
+// sigmoid(2u) for the tanh form of GELU, 2u = 2 sqrt(2/pi) (z + 0.044715 z^3), with the constants of the
+// argument and of the base-2 exponential folded into one cubic: z * (c1 + c3 z^2) = -2u log2(e)
+// (the kernels that call this are bound by vector-ALU issue slots: every instruction counts).  One v_exp_f32 and
+// one v_rcp_f32 (1 ulp; an IEEE division costs ten instructions).
+__device__ __forceinline__ float sigmoid_2u(float z, float z2)
 {
-    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * t));
+    constexpr float c1 = -1.5957691216057308f * 1.4426950408889634f;
+    constexpr float c3 = c1 * 0.044715f;
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(z * fmaf(c3, z2, c1)));
 }
 
 // Standard normal CDF Phi(z).  erfc(u / sqrt 2) = 2 Phi(-u), u >= 0, is evaluated as
-// 2^q(u) with q a degree-10 least-squares fit (fit_normal_cdf.py) of log2 erfc(u / sqrt 2) on Chebyshev nodes
+// 2^q(u) with q a degree-10 least-squares fit of log2 erfc(u / sqrt 2) on Chebyshev nodes
 // of [0, 6.5] (relative error 5e-7 in exact arithmetic, 5e-6 in fp32 Horner form; beyond
 // 6.5 the tail is held at 8e-11).  The lower tail comes out with that RELATIVE accuracy
 // (no 1 + erf cancellation), the upper one as 1 - tail.  Branch-free, one v_exp_f32:
@@ -45,8 +49,8 @@ __device__ __forceinline__ float normal_cdf(float z)
     q = fmaf(q, u, -5.288341269e-02f);
     q = fmaf(q, u, -4.590395689e-01f);
     q = fmaf(q, u, -1.151132941e+00f);
-    q = fmaf(q, u, 7.463755196e-07f);
-    const float tail = 0.5f * __builtin_amdgcn_exp2f(q);        // Phi(-|z|)
+    q = fmaf(q, u, 7.463755196e-07f - 1.0f);                    // the factor 1/2 of Phi(-u) = erfc(u / sqrt 2) / 2
+    const float tail = __builtin_amdgcn_exp2f(q);               // Phi(-|z|)
     return z < 0.0f ? tail : 1.0f - tail;
 }
 
@@ -56,8 +60,7 @@ template <int ACT> __device__ __forceinline__ float act_value(float z)
     else if constexpr (ACT == ACT_GELU) return z * normal_cdf(z);
     else {
         // 0.5*(1 + tanh(u)) == sigmoid(2u): no cancellation in the negative tail, no tanh call
-        const float u2 = 1.5957691216057308f * fmaf(0.044715f * z * z, z, z);
-        return z * sigmoidf_fast(u2);
+        return z * sigmoid_2u(z, z * z);
     }
 }
 
@@ -70,9 +73,9 @@ template <int ACT> __device__ __forceinline__ float act_slope(float z)
     else {
         // d/dz [z*sigmoid(2u)] = s + z*s*(1-s)*d(2u)/dz
         const float z2 = z * z;
-        const float s = sigmoidf_fast(1.5957691216057308f * fmaf(0.044715f * z2, z, z));
-        const float du2 = 1.5957691216057308f * fmaf(3.0f * 0.044715f, z2, 1.0f);
-        return fmaf(z * s * (1.0f - s), du2, s);
+        const float s = sigmoid_2u(z, z2);
+        const float du2 = fmaf(3.0f * 0.044715f * 1.5957691216057308f, z2, 1.5957691216057308f);
+        return fmaf(z * du2, fmaf(-s, s, s), s);
     }
 }
 
@@ -270,7 +273,7 @@ static lsq_status bad_bwd_dispatch(void* dx, float* dbias, const void* dy, const
     const T* bp = static_cast<const T*>(bias);
     if (!bad_is_flat(hidden)) {
         const int ppr = hidden / kPack;
-        const int rb = bdr_bwd_row_blocks(rows, hidden);
+        const int rb = bad_bwd_row_blocks(rows, hidden);
         const dim3 grid(static_cast<unsigned>(ceil_div(ppr, 64)), static_cast<unsigned>(rb)), block(256);
         float* partial = dbias ? static_cast<float*>(workspace) : nullptr;
         const bool drop = d.on != 0;

@@ -199,7 +199,7 @@ static lsq_status merge_dispatch(void* out, float* dbias, const void* i0, const 
     const T* a = static_cast<const T*>(i0); const T* b = static_cast<const T*>(i1); const T* c = static_cast<const T*>(i2);
     const int cols = g.parts * g.hidden;
     if (g.head_dim % kPack == 0) {
-        const int rb = bdr_bwd_row_blocks(g.rows, cols);
+        const int rb = heads_bwd_row_blocks(g.rows, cols);
         const dim3 grid(static_cast<unsigned>(ceil_div(g.ppr, 64)), static_cast<unsigned>(dbias ? rb : head_row_blocks(g.rows))), block(256);
         float* partial = dbias ? static_cast<float*>(workspace) : nullptr;
         hipLaunchKernelGGL((merge_heads_kernel<T>), grid, block, 0, s, o, partial, a, b, c, g);
@@ -209,7 +209,7 @@ static lsq_status merge_dispatch(void* out, float* dbias, const void* i0, const 
         hipLaunchKernelGGL((merge_heads_flat<T>), dim3(static_cast<unsigned>(ceil_div(total, 256))), dim3(256), 0, s,
                            o, a, b, c, g);
         if (dbias) {
-            const int rb = bdr_bwd_row_blocks(g.rows, cols);
+            const int rb = heads_bwd_row_blocks(g.rows, cols);
             float* partial = static_cast<float*>(workspace);
             hipLaunchKernelGGL((colsum_rows_flat<T>), dim3(static_cast<unsigned>(ceil_div(cols, 256)), static_cast<unsigned>(rb)), dim3(256), 0, s,
                                partial, static_cast<const T*>(o), g.rows, cols, static_cast<int>(ceil_div(g.rows, rb)));

@@ -306,13 +306,25 @@ inline BdrBwdPlan bdr_bwd_plan(int64_t rows, int32_t hidden)
     return p;
 }
 
-inline int bdr_bwd_row_blocks(int64_t rows, int32_t /*hidden*/)
+// Row blocks of the column-blocked backward kernels that leave one partial row of column sums per row block
+// (feed-forward bias+activation+dropout, head merge): as many as give about `target` workgroups over the
+// hidden / 512 column blocks.  Measured at 8192 x 5120 (GELU, dropout) and 4096 x 4096 (ReLU): 512 workgroups, two per
+// compute unit, 45.2 / 35.2 us; 384: 49.8 / 40.7; 640: 47.5 / 37.9; 1024: 46.9 / 36.8; 2560 (one row block per
+// 32 rows, the earlier choice): 49.8 / 38.4 -- totals that are not a multiple of the 256 compute units leave some
+// of them with one workgroup more, and fewer, longer workgroups pay prologue, LDS epilogue and partial row less often.
+// The head merge (no arithmetic, 128-byte pieces) wants more loads in flight: 1024 workgroups 26.5 us at
+// 8192 x 3840, 768: 28.4, 1536: 27.6, 2048: 29.2, 512: 34.
+constexpr int kBadBwdWorkgroups = 512, kHeadsBwdWorkgroups = 1024;
+inline int colsum_row_blocks(int64_t rows, int32_t hidden, int target)
 {
-    int64_t b = ceil_div(rows, 16);
-    if (b > 256) b = 256;
-    if (b < 1) b = 1;
-    return static_cast<int>(b);
+    const int64_t col_blocks = ceil_div(hidden, 64 * kPack);
+    int64_t b = target / col_blocks;
+    const int64_t most = ceil_div(rows, 16);
+    if (b > most) b = most;
+    return static_cast<int>(b < 1 ? 1 : b);
 }
+inline int bad_bwd_row_blocks(int64_t rows, int32_t hidden) { return colsum_row_blocks(rows, hidden, kBadBwdWorkgroups); }
+inline int heads_bwd_row_blocks(int64_t rows, int32_t hidden) { return colsum_row_blocks(rows, hidden, kHeadsBwdWorkgroups); }
 
 // Workspace of the embedding backward:
 //   order  [rows] (token position, sort key), 8 bytes each
