@@ -32,6 +32,20 @@ __device__ __forceinline__ void adam_update(float& p, float& m, float& v, float 
 
 constexpr int kAdamPack = 4;
 
+// Workgroup -> tile of 1024 elements (xcd_chunked in device.hpp): with separate arrays each XCD takes runs of
+// kAdamXcdChunk consecutive tiles (1 MB of each fp32 array).  Measured on the same buffers in one process, six
+// processes: 0.720-0.735 of the HBM peak in every one of them against 0.69-0.72 with tile = workgroup (where the
+// five arrays land decides which); runs of 128 and 512 tiles are within 1 %, 32 and 1024 lose the gain, and
+// rotating which XCD takes which tile of eight changes nothing.  Through the library (graph replay, six processes
+// each): 0.719-0.730 against 0.693-0.733.  The blocked state, one stream already, loses 1 % with it and keeps
+// tile = workgroup.
+constexpr int kAdamXcdChunk = 256;
+template <bool BLOCKED>
+__device__ __forceinline__ int64_t adam_tile()
+{
+    return xcd_chunked<BLOCKED ? 1 : kAdamXcdChunk>(blockIdx.x, gridDim.x);
+}
+
 // Blocked optimizer state: the three fp32 arrays that only the trainer reads are kept
 // as blocks of kAdamBlock elements, [p block | m block | v block] back to back, instead
 // of three arrays a gigabyte apart.  The bytes moved are the same; the read-modify-write
@@ -53,7 +67,7 @@ __global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ p, float*
                                                    float* __restrict__ v, const G* __restrict__ g,
                                                    PL* __restrict__ plp, int64_t n, AdamParams a)
 {
-    const int64_t e = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * kAdamPack;
+    const int64_t e = (adam_tile<BLOCKED>() * 256 + threadIdx.x) * kAdamPack;
     if constexpr (BLOCKED) {        // p is the state; this thread's pack sits at one offset in all three blocks
         const int64_t so = adam_state_offset(e) - e;
         p += so;
@@ -145,7 +159,7 @@ template <typename T, bool BLOCKED>
 __global__ __launch_bounds__(256) void adam_lp_kernel(T* __restrict__ p, float* __restrict__ m, float* __restrict__ v,
                                                       const T* __restrict__ g, int64_t n, AdamParams a)
 {
-    const int64_t e = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * kAdamPack;
+    const int64_t e = (adam_tile<BLOCKED>() * 256 + threadIdx.x) * kAdamPack;
     if constexpr (BLOCKED) {        // m is the [m | v] state
         m += adam_state_offset(e, 2) - e;
         v = m + kAdamBlock;
@@ -190,7 +204,7 @@ template <typename G, typename PL, bool HAS_PL, bool MOM, bool BLOCKED>
 __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ p, float* __restrict__ buf,
                                                   const G* __restrict__ g, PL* __restrict__ plp, int64_t n, SgdParams a)
 {
-    const int64_t e = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * kAdamPack;
+    const int64_t e = (adam_tile<BLOCKED>() * 256 + threadIdx.x) * kAdamPack;
     if constexpr (BLOCKED) {        // p is the [p | momentum buffer] state
         p += adam_state_offset(e, 2) - e;
         buf = p + kAdamBlock;

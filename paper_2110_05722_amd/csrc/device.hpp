@@ -299,6 +299,22 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
+// Workgroup -> tile for kernels that stream large tensors one tile per workgroup.  Consecutive workgroups of a
+// launch go to the eight XCDs in turn, each with its own L2 and address-translation cache; with tile = workgroup
+// every XCD walks every small piece of every tensor.  Here an XCD takes a run of CHUNK consecutive tiles out of
+// every eight runs, so that it streams about a megabyte of each tensor at a stretch.  The last, partial group of
+// eight runs keeps its order; the map is a permutation of 0..nb-1.
+template <int CHUNK>
+__device__ __forceinline__ int64_t xcd_chunked(int64_t b, int64_t nb)
+{
+    if constexpr (CHUNK <= 1) return b;
+    constexpr int64_t kGroup = 8 * static_cast<int64_t>(CHUNK);
+    const int64_t first = b / kGroup * kGroup;
+    if (first + kGroup > nb) return b;
+    const int64_t r = b - first;
+    return first + (r % 8) * CHUNK + r / 8;
+}
+
 // keep[j] (as 0.0f / scale) for the 8 elements of pack `g` (flat element index / 8).
 __device__ __forceinline__ void dropout_factors8(const DropoutParams& d, uint64_t g, float (&k)[8])
 {
