@@ -189,7 +189,7 @@ def _line_bytes_softmax(cfg, key_len, elem_bytes=2):
 
 def adam_arrays(torch, cfg, dt, dev):
     """The trainer's arrays: fp32 p, m, v, low-precision g and p_lp.  Allocated first, as a training program does
-    when it builds its model: where the five arrays land decides 0.66-0.80 of peak for the kernel that walks them
+    when it builds its model: where the five arrays land decides 0.70-0.80 of peak for the kernel that walks them
     as five streams (the blocked optimizer state does not care)."""
     from workloads import device_normal, torch_dtype
     n, seed = cfg.adam_n, cfg.seed * 1000
