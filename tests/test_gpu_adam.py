@@ -23,7 +23,8 @@ def _check(p, m, v, rp, rm, rv, m_old, g64, b1=HY["beta1"], extra=0.0):
 
 
 @pytest.mark.parametrize("g_dt,lp_dt", [("f16", "f16"), ("bf16", "bf16"), ("f32", "f16"), ("f16", None)])
-@pytest.mark.parametrize("n", [1 << 20, 1000003, 8, 7, 1, 2049])
+# 4199427 = two full groups of XCD runs (2 x 2048 tiles of 1024 elements), five more tiles and a ragged end
+@pytest.mark.parametrize("n", [1 << 20, 1000003, 8, 7, 1, 2049, 4199427])
 def test_adam_four_steps(n, g_dt, lp_dt):
     """Config 1: state from zero moments, step 1 then three more, fresh gradient each step."""
     say(f"[adam] n={n} g={g_dt} p_lp={lp_dt}")

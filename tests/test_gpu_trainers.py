@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("dt", ["f16", "bf16"])
-@pytest.mark.parametrize("n", [1 << 20, 1000003, 5, 2049])
+@pytest.mark.parametrize("n", [1 << 20, 1000003, 5, 2049, 4199427])
 def test_adam_lp_three_steps(n, dt):
     say(f"[adam_lp] n={n} dt={dt}")
     d = dev()
@@ -40,7 +40,7 @@ def test_adam_lp_three_steps(n, dt):
 @pytest.mark.parametrize("kw", [dict(momentum=0.0), dict(momentum=0.9), dict(momentum=0.9, nesterov=True),
                                 dict(momentum=0.5, weight_decay=0.01, inv_grad_scale=0.25)])
 @pytest.mark.parametrize("g_dt,lp_dt", [("f16", "f16"), ("bf16", "bf16"), ("f32", None)])
-@pytest.mark.parametrize("n", [1 << 20, 1000003, 3])
+@pytest.mark.parametrize("n", [1 << 20, 1000003, 3, 4199427])
 def test_sgd_three_steps(n, g_dt, lp_dt, kw):
     say(f"[sgd] n={n} g={g_dt} p_lp={lp_dt} {kw}")
     d = dev()
