@@ -315,6 +315,20 @@ __device__ __forceinline__ int64_t xcd_chunked(int64_t b, int64_t nb)
     return first + (r % 8) * CHUNK + r / 8;
 }
 
+// (column block, row block) of a workgroup of a [column blocks, row blocks] grid.
+// ORDER 0: as launched (column blocks fastest); 1: row blocks fastest.
+struct GridBlock { int col; int row; };
+template <int ORDER>
+__device__ __forceinline__ GridBlock grid_block()
+{
+    if constexpr (ORDER == 1) {
+        const unsigned lin = blockIdx.x + gridDim.x * blockIdx.y;
+        return {static_cast<int>(lin / gridDim.y), static_cast<int>(lin % gridDim.y)};
+    } else {
+        return {static_cast<int>(blockIdx.x), static_cast<int>(blockIdx.y)};
+    }
+}
+
 // keep[j] (as 0.0f / scale) for the 8 elements of pack `g` (flat element index / 8).
 __device__ __forceinline__ void dropout_factors8(const DropoutParams& d, uint64_t g, float (&k)[8])
 {

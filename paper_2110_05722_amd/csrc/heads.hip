@@ -43,7 +43,10 @@ __global__ __launch_bounds__(256) void split_heads_kernel(T* __restrict__ o0, T*
                                                           HeadGeom g)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int cp = blockIdx.x * 64 + lane;
+    // row blocks fastest: consecutive workgroups (consecutive XCDs) take consecutive row blocks of one column block;
+    // 18.5 against 19.5 us at 4096 x 3072 and 23.7 against 24.4 us at 8192 x 3840 (the merge is 1-3 % slower that way)
+    const GridBlock gb = grid_block<1>();
+    const int cp = gb.col * 64 + lane;
     if (cp >= g.ppr) return;
     const int col = cp * kPack;
     const int part = col / g.hidden;
@@ -53,7 +56,7 @@ __global__ __launch_bounds__(256) void split_heads_kernel(T* __restrict__ o0, T*
     if constexpr (HAS_BIAS) load8<T>(bias + col, b);
     const int64_t stride = static_cast<int64_t>(gridDim.y) * kHeadWaves;
     // the pack of the next token is loaded before this token's is stored
-    int64_t t = static_cast<int64_t>(blockIdx.y) * kHeadWaves + wave;
+    int64_t t = static_cast<int64_t>(gb.row) * kHeadWaves + wave;
     RawPack<T> nxt = t < g.rows ? load_raw<T, kNT>(in + (t * g.ppr + cp) * kPack) : zero_raw<T>();
     for (; t < g.rows; t += stride) {
         const RawPack<T> r = nxt;
@@ -80,7 +83,8 @@ __global__ __launch_bounds__(256) void merge_heads_kernel(T* __restrict__ out, f
 {
     __shared__ float sm[kHeadWaves][8][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int cp = blockIdx.x * 64 + lane;
+    const GridBlock gb = grid_block<0>();
+    const int cp = gb.col * 64 + lane;
     const bool active = cp < g.ppr;
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if (active) {
@@ -89,7 +93,7 @@ __global__ __launch_bounds__(256) void merge_heads_kernel(T* __restrict__ out, f
         const int within = col - part * g.hidden;
         const T* in = pick(i0, i1, i2, part);
         const int64_t stride = static_cast<int64_t>(gridDim.y) * kHeadWaves;
-        for (int64_t t = static_cast<int64_t>(blockIdx.y) * kHeadWaves + wave; t < g.rows; t += stride) {
+        for (int64_t t = static_cast<int64_t>(gb.row) * kHeadWaves + wave; t < g.rows; t += stride) {
             const RawPack<T> r = load_raw<T, kNT>(in + head_offset(g, t, within));
             T* dst = out + (t * g.ppr + cp) * kPack;
             if constexpr (sizeof(T) == 2) st_u4<kNT>(dst, r.u);
@@ -115,7 +119,7 @@ __global__ __launch_bounds__(256) void merge_heads_kernel(T* __restrict__ out, f
             for (int w = 1; w < kHeadWaves; ++w) t += sm[w][j][lane];
             s[j] = t;
         }
-        store8<float>(partial + (static_cast<int64_t>(blockIdx.y) * g.ppr + cp) * kPack, s);
+        store8<float>(partial + (static_cast<int64_t>(gb.row) * g.ppr + cp) * kPack, s);
     }
 }
 
