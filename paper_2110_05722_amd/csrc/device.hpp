@@ -315,6 +315,21 @@ __device__ __forceinline__ int64_t xcd_chunked(int64_t b, int64_t nb)
     return first + (r % 8) * CHUNK + r / 8;
 }
 
+// The same with the runs of a group handed to the XCDs in an order that rotates from group to group: XCDs receive
+// their workgroups in strict rotation whatever their load, so when the cost of a tile depends on its position
+// in a period that the group length divides (padded sentence tails in a criterion batch), fixed runs would give
+// one XCD all the cheap tiles.
+template <int CHUNK>
+__device__ __forceinline__ int64_t xcd_chunked_rotating(int64_t b, int64_t nb)
+{
+    if constexpr (CHUNK <= 1) return b;
+    constexpr int64_t kGroup = 8 * static_cast<int64_t>(CHUNK);
+    const int64_t grp = b / kGroup, first = grp * kGroup;
+    if (first + kGroup > nb) return b;
+    const int64_t r = b - first;
+    return first + ((r + grp) % 8) * CHUNK + r / 8;
+}
+
 // (column block, row block) of a workgroup of a [column blocks, row blocks] grid.
 // ORDER 0: as launched (column blocks fastest); 1: row blocks fastest.
 struct GridBlock { int col; int row; };
