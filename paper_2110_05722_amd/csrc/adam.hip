@@ -32,18 +32,23 @@ __device__ __forceinline__ void adam_update(float& p, float& m, float& v, float 
 
 constexpr int kAdamPack = 4;
 
-// Workgroup -> tile of 1024 elements (xcd_chunked in device.hpp): with separate arrays each XCD takes runs of
-// kAdamXcdChunk consecutive tiles (1 MB of each fp32 array).  Measured on the same buffers in one process, six
-// processes: 0.720-0.735 of the HBM peak in every one of them against 0.69-0.72 with tile = workgroup (where the
-// five arrays land decides which); runs of 128 and 512 tiles are within 1 %, 32 and 1024 lose the gain, and
-// rotating which XCD takes which tile of eight changes nothing.  Through the library (graph replay, six processes
-// each): 0.719-0.730 against 0.693-0.733.  The blocked state, one stream already, loses 1 % with it and keeps
-// tile = workgroup.
-constexpr int kAdamXcdChunk = 256;
+// Launch shape of the trainers.  With separate arrays: one-wave workgroups (a tile of 256 elements, 1 KB of each
+// fp32 array), and each XCD takes runs of 1 MB of consecutive tiles (xcd_chunked in device.hpp).  Measured on the
+// same buffers in one process, three to six processes each (fraction of the 8 TB/s peak, 774 M parameters):
+//   256 threads, tile = workgroup   0.68-0.72   (where the five arrays land decides which)
+//   256 threads, runs of 1 MB       0.71-0.735
+//   128 threads, runs of 1 MB       0.72-0.75
+//    64 threads, tile = workgroup   0.72-0.75
+//    64 threads, runs of 1 MB       0.755-0.77  in every process (runs of 512 KB..4 MB alike; 128-256 KB less steady)
+// 512 / 1024 threads, or two / four packs per thread, are slower than 256 x 1; rotating which XCD takes which of
+// eight tiles changes nothing.  The blocked state, one address stream already, also gains from one-wave workgroups
+// (0.81 against 0.79 with 256 threads; 128 threads: 0.71) but not from runs (0.78-0.81 with runs of 4-1024 tiles).
+constexpr int kAdamThreads = 64;
+constexpr int kAdamRunBytes = 1 << 20;
 template <bool BLOCKED>
 __device__ __forceinline__ int64_t adam_tile()
 {
-    return xcd_chunked<BLOCKED ? 1 : kAdamXcdChunk>(blockIdx.x, gridDim.x);
+    return xcd_chunked<BLOCKED ? 1 : kAdamRunBytes / (kAdamThreads * 16)>(blockIdx.x, gridDim.x);
 }
 
 // Blocked optimizer state: the three fp32 arrays that only the trainer reads are kept
@@ -53,7 +58,7 @@ __device__ __forceinline__ int64_t adam_tile()
 // memory system rewards: 6.3 TB/s against 5.5-5.85 TB/s measured at 774 M parameters.
 // Swept 1 Ki .. 1 Mi elements per block: 8 Ki is the optimum, 64 Ki+ gives back half of it.
 constexpr int kAdamBlock = LSQ_ADAM_BLOCK;
-static_assert(kAdamBlock % (256 * kAdamPack) == 0, "a workgroup must not straddle a block");
+static_assert(kAdamBlock % (kAdamThreads * kAdamPack) == 0, "a workgroup must not straddle a block");
 
 // offset of element e of the first array inside a blocked state of `arrays` arrays; the other
 // arrays follow at +1 and +2 blocks
@@ -63,11 +68,11 @@ __device__ __host__ __forceinline__ int64_t adam_state_offset(int64_t e, int arr
 }
 
 template <typename G, typename PL, bool HAS_PL, bool BLOCKED>
-__global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ p, float* __restrict__ m,
+__global__ __launch_bounds__(kAdamThreads) void adam_kernel(float* __restrict__ p, float* __restrict__ m,
                                                    float* __restrict__ v, const G* __restrict__ g,
                                                    PL* __restrict__ plp, int64_t n, AdamParams a)
 {
-    const int64_t e = (adam_tile<BLOCKED>() * 256 + threadIdx.x) * kAdamPack;
+    const int64_t e = (adam_tile<BLOCKED>() * kAdamThreads + threadIdx.x) * kAdamPack;
     if constexpr (BLOCKED) {        // p is the state; this thread's pack sits at one offset in all three blocks
         const int64_t so = adam_state_offset(e) - e;
         p += so;
@@ -108,7 +113,7 @@ static lsq_status adam_dispatch(float* p, float* m, float* v, const void* g, voi
                                 const AdamParams& a, int p_lp_dt, hipStream_t s)
 {
     const int64_t packs = ceil_div(n, kAdamPack);
-    const dim3 grid(static_cast<unsigned>(ceil_div(packs, 256))), block(256);
+    const dim3 grid(static_cast<unsigned>(ceil_div(packs, kAdamThreads))), block(kAdamThreads);
     const G* gp = static_cast<const G*>(g);
     if (!plp)
         hipLaunchKernelGGL((adam_kernel<G, f16, false, BLOCKED>), grid, block, 0, s, p, m, v, gp, static_cast<f16*>(nullptr), n, a);
@@ -156,10 +161,10 @@ __global__ __launch_bounds__(256) void adam_state_move(float* state, float* p, f
 // ---- the paper's own layout: the workspace holds the parameter in low precision and
 // it is updated in place (Sec. IV-C, "on-the-fly conversion"): 22 bytes per parameter.
 template <typename T, bool BLOCKED>
-__global__ __launch_bounds__(256) void adam_lp_kernel(T* __restrict__ p, float* __restrict__ m, float* __restrict__ v,
+__global__ __launch_bounds__(kAdamThreads) void adam_lp_kernel(T* __restrict__ p, float* __restrict__ m, float* __restrict__ v,
                                                       const T* __restrict__ g, int64_t n, AdamParams a)
 {
-    const int64_t e = (adam_tile<BLOCKED>() * 256 + threadIdx.x) * kAdamPack;
+    const int64_t e = (adam_tile<BLOCKED>() * kAdamThreads + threadIdx.x) * kAdamPack;
     if constexpr (BLOCKED) {        // m is the [m | v] state
         m += adam_state_offset(e, 2) - e;
         v = m + kAdamBlock;
@@ -201,10 +206,10 @@ __device__ __forceinline__ void sgd_update(float& p, float& b, float g, const Sg
 }
 
 template <typename G, typename PL, bool HAS_PL, bool MOM, bool BLOCKED>
-__global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ p, float* __restrict__ buf,
+__global__ __launch_bounds__(kAdamThreads) void sgd_kernel(float* __restrict__ p, float* __restrict__ buf,
                                                   const G* __restrict__ g, PL* __restrict__ plp, int64_t n, SgdParams a)
 {
-    const int64_t e = (adam_tile<BLOCKED>() * 256 + threadIdx.x) * kAdamPack;
+    const int64_t e = (adam_tile<BLOCKED>() * kAdamThreads + threadIdx.x) * kAdamPack;
     if constexpr (BLOCKED) {        // p is the [p | momentum buffer] state
         p += adam_state_offset(e, 2) - e;
         buf = p + kAdamBlock;
@@ -238,7 +243,7 @@ template <typename G, bool MOM, bool BLOCKED = false>
 static lsq_status sgd_dispatch(float* p, float* buf, const void* g, void* plp, int64_t n, const SgdParams& a,
                                int p_lp_dt, hipStream_t s)
 {
-    const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(n, kAdamPack), 256))), block(256);
+    const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(n, kAdamPack), kAdamThreads))), block(kAdamThreads);
     const G* gp = static_cast<const G*>(g);
     if (!plp)
         hipLaunchKernelGGL((sgd_kernel<G, f16, false, MOM, BLOCKED>), grid, block, 0, s, p, buf, gp, static_cast<f16*>(nullptr), n, a);
@@ -283,7 +288,7 @@ extern "C" lsq_status lsq_adam_step(float* p, float* m, float* v, const void* g,
     if (n == 0) return LSQ_OK;
     LSQ_REQUIRE(p && m && v && g);
     LSQ_ALIGNED(p); LSQ_ALIGNED(m); LSQ_ALIGNED(v); LSQ_ALIGNED(g); LSQ_ALIGNED(p_lp);
-    LSQ_REQUIRE(ceil_div(ceil_div(n, kAdamPack), 256) <= 0x7FFFFFFF);
+    LSQ_REQUIRE(ceil_div(ceil_div(n, kAdamPack), kAdamThreads) <= 0x7FFFFFFF);
 
     AdamParams a;
     LSQ_REQUIRE(make_adam_params(&a, lr, beta1, beta2, eps, weight_decay, step, adamw, bias_correction, inv_grad_scale));
@@ -360,7 +365,7 @@ extern "C" lsq_status lsq_adam_step_blocked(float* state, const void* g, void* p
     if (n == 0) return LSQ_OK;
     LSQ_REQUIRE(state && g);
     LSQ_ALIGNED(state); LSQ_ALIGNED(g); LSQ_ALIGNED(p_lp);
-    LSQ_REQUIRE(ceil_div(ceil_div(n, kAdamPack), 256) <= 0x7FFFFFFF);
+    LSQ_REQUIRE(ceil_div(ceil_div(n, kAdamPack), kAdamThreads) <= 0x7FFFFFFF);
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (g_dt) {
         case LSQ_F16: return adam_dispatch<f16, true>(state, nullptr, nullptr, g, p_lp, n, a, p_lp_dt, s);
@@ -382,9 +387,9 @@ static lsq_status adam_lp_entry(void* p_lp, float* m, float* v, const void* g, i
     if (n == 0) return LSQ_OK;
     LSQ_REQUIRE(p_lp && m && (BLOCKED || v) && g);
     LSQ_ALIGNED(p_lp); LSQ_ALIGNED(m); LSQ_ALIGNED(v); LSQ_ALIGNED(g);
-    LSQ_REQUIRE(ceil_div(ceil_div(n, kAdamPack), 256) <= 0x7FFFFFFF);
+    LSQ_REQUIRE(ceil_div(ceil_div(n, kAdamPack), kAdamThreads) <= 0x7FFFFFFF);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(n, kAdamPack), 256))), block(256);
+    const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(n, kAdamPack), kAdamThreads))), block(kAdamThreads);
     if (dt == LSQ_F16)
         hipLaunchKernelGGL((adam_lp_kernel<f16, BLOCKED>), grid, block, 0, s, static_cast<f16*>(p_lp), m, v, static_cast<const f16*>(g), n, a);
     else
@@ -422,7 +427,7 @@ static lsq_status sgd_entry(float* p, float* momentum_buf, const void* g, void* 
     if (n == 0) return LSQ_OK;
     LSQ_REQUIRE(p && g && (BLOCKED || momentum == 0.0f || momentum_buf));
     LSQ_ALIGNED(p); LSQ_ALIGNED(momentum_buf); LSQ_ALIGNED(g); LSQ_ALIGNED(p_lp);
-    LSQ_REQUIRE(ceil_div(ceil_div(n, kAdamPack), 256) <= 0x7FFFFFFF);
+    LSQ_REQUIRE(ceil_div(ceil_div(n, kAdamPack), kAdamThreads) <= 0x7FFFFFFF);
     SgdParams a{lr, momentum, weight_decay, inv_grad_scale, nesterov != 0};
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool mom = momentum != 0.0f;
