@@ -1,31 +1,36 @@
-// Plain memory streams in the launch style of the operators (128-bit nontemporal accesses, one
-// pack per thread, 256-thread workgroups, each XCD on runs of 256 consecutive 4 KB tiles): what the
-// machine gives a kernel that does nothing but move bytes.  The benchmark times them next to the
-// operators, at the operators' tensor sizes.  (The runs are worth 1.5-2 % from 300 MB up: 6.63 against
-// 6.51 TB/s for the 1 GiB copy; below 200 MB they change nothing.)
+// Plain memory streams in the launch style of the trainers (128-bit nontemporal accesses, one pack per
+// thread, each XCD on runs of 1 MB of consecutive tiles): what the machine gives a kernel that does nothing
+// but move bytes.  The benchmark times them next to the operators, at the operators' tensor sizes.
+// The copy runs as one-wave workgroups: 3-7 % faster than 256-thread ones at every size from 40 MB to 1 GiB
+// (8.15 against 8.7 us at 42 MB, 6.6-6.75 against 6.52 TB/s at 1 GiB).  The read-only and write-only streams
+// keep 256 threads: with a million one-wave workgroups per GiB and half the bytes per workgroup they are bound
+// by the rate at which workgroups start (4.8 TB/s against 7.37 / 6.75); there the runs are worth 6 % to the read.
 #include "host.hpp"
 
 namespace lsq {
 
-__global__ __launch_bounds__(256) void calib_copy_kernel(uvec4* __restrict__ dst, const uvec4* __restrict__ src, int64_t n)
+constexpr int kCalibCopyThreads = 64, kCalibThreads = 256;
+constexpr int calib_run(int threads) { return (1 << 20) / (threads * 16); }      // tiles per run of 1 MB
+
+__global__ __launch_bounds__(kCalibCopyThreads) void calib_copy_kernel(uvec4* __restrict__ dst, const uvec4* __restrict__ src, int64_t n)
 {
-    const int64_t i = xcd_chunked<256>(blockIdx.x, gridDim.x) * 256 + threadIdx.x;
+    const int64_t i = xcd_chunked<calib_run(kCalibCopyThreads)>(blockIdx.x, gridDim.x) * kCalibCopyThreads + threadIdx.x;
     if (i < n) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 // Reads everything, writes (practically) nothing: a pack whose four words all equal an unlikely
 // constant would be reported to `sink`, which keeps the loads alive.
-__global__ __launch_bounds__(256) void calib_read_kernel(const uvec4* __restrict__ src, int64_t n, uint32_t* sink)
+__global__ __launch_bounds__(kCalibThreads) void calib_read_kernel(const uvec4* __restrict__ src, int64_t n, uint32_t* sink)
 {
-    const int64_t i = xcd_chunked<256>(blockIdx.x, gridDim.x) * 256 + threadIdx.x;
+    const int64_t i = xcd_chunked<calib_run(kCalibThreads)>(blockIdx.x, gridDim.x) * kCalibThreads + threadIdx.x;
     if (i >= n) return;
     const uvec4 v = __builtin_nontemporal_load(src + i);
     if (v.x == 0x9E3779B9u && v.y == 0x7F4A7C15u && v.z == 0xF39CC060u && v.w == 0x5CEDC834u) *sink = 1u;
 }
 
-__global__ __launch_bounds__(256) void calib_write_kernel(uvec4* __restrict__ dst, int64_t n, uint32_t word)
+__global__ __launch_bounds__(kCalibThreads) void calib_write_kernel(uvec4* __restrict__ dst, int64_t n, uint32_t word)
 {
-    const int64_t i = xcd_chunked<256>(blockIdx.x, gridDim.x) * 256 + threadIdx.x;
+    const int64_t i = xcd_chunked<calib_run(kCalibThreads)>(blockIdx.x, gridDim.x) * kCalibThreads + threadIdx.x;
     if (i < n) __builtin_nontemporal_store(uvec4{word, word, word, word}, dst + i);
 }
 
@@ -46,9 +51,11 @@ extern "C" lsq_status lsq_calib_stream(int32_t kind, void* dst, const void* src,
     LSQ_REQUIRE(dst && (kind == 2 || src));
     LSQ_ALIGNED(dst); LSQ_ALIGNED(src);
     const int64_t n = bytes / 16;
-    LSQ_REQUIRE(ceil_div(n, 256) <= 0x7FFFFFFF);
-    const dim3 grid(static_cast<unsigned>(ceil_div(n, 256))), block(256);
-    if (kind == 0) hipLaunchKernelGGL(calib_copy_kernel, grid, block, 0, s, static_cast<uvec4*>(dst), static_cast<const uvec4*>(src), n);
+    LSQ_REQUIRE(ceil_div(n, kCalibCopyThreads) <= 0x7FFFFFFF);
+    const dim3 grid(static_cast<unsigned>(ceil_div(n, kCalibThreads))), block(kCalibThreads);
+    if (kind == 0)
+        hipLaunchKernelGGL(calib_copy_kernel, dim3(static_cast<unsigned>(ceil_div(n, kCalibCopyThreads))), dim3(kCalibCopyThreads), 0, s,
+                           static_cast<uvec4*>(dst), static_cast<const uvec4*>(src), n);
     else if (kind == 1) hipLaunchKernelGGL(calib_read_kernel, grid, block, 0, s, static_cast<const uvec4*>(src), n, static_cast<uint32_t*>(dst));
     else hipLaunchKernelGGL(calib_write_kernel, grid, block, 0, s, static_cast<uvec4*>(dst), n, 0x3C003C00u);
     return launch_status();

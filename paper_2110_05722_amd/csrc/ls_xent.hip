@@ -24,6 +24,9 @@ constexpr float kLn2X = 0.6931471805599453f;
 // measured at 8192 x 30522 / 32768 / 50257 logits: 512 or 1024 threads per row and 8 packs in flight per thread are
 // no faster (within 2 %) or slower (1024 threads: -10 %)
 constexpr int kXentThreads = 256;
+// the flat backward runs as one-wave workgroups: 259 against 263 us at 8192 x 50257, 134 against 137 us at the
+// transformer-big shape, 103 against 109 us on a masked-LM batch (256 threads per workgroup; 128: 266 / 136 / 102)
+constexpr int kXbThreads = 64;
 constexpr int kXentUnroll = 4;
 
 struct RowSplit {
@@ -236,7 +239,7 @@ __global__ __launch_bounds__(kXentThreads) void xent_bwd_kernel(T* dlogits, cons
 }
 
 // Backward over the FLAT [tokens*vocab] tensor: a workgroup owns a contiguous chunk
-// of U*256 aligned packs whatever rows they fall in, so the access pattern is that
+// of U*64 aligned packs whatever rows they fall in, so the access pattern is that
 // of a plain copy (few DRAM pages open at a time, every access 128-bit and aligned,
 // no scalar head/tail per row).  Measured on MI355X a copy laid out one row per
 // workgroup reaches 4.8 TB/s at vocab 50257, the flat one 6.6 TB/s.  The chunk is
@@ -245,14 +248,14 @@ __global__ __launch_bounds__(kXentThreads) void xent_bwd_kernel(T* dlogits, cons
 // straddles the boundary (vocab % 8 != 0) selects per element.  Packs of ignored
 // rows are not read at all.
 template <typename T, int U>
-__global__ __launch_bounds__(256) void xent_bwd_flat_kernel(T* dlogits, const T* logits,
+__global__ __launch_bounds__(kXbThreads) void xent_bwd_flat_kernel(T* dlogits, const T* logits,
                                                             const float* __restrict__ lse,
                                                             const int32_t* __restrict__ target, int64_t tokens,
                                                             int vocab, float alpha, int ignore_index, float grad_scale)
 {
     const int64_t total = tokens * vocab;
     const int64_t npacks = total / kPack;                     // full packs; the ragged end is handled below
-    const int64_t pb = static_cast<int64_t>(blockIdx.x) * (U * 256);
+    const int64_t pb = static_cast<int64_t>(blockIdx.x) * (U * kXbThreads);
     const int64_t tA = (pb * kPack) / vocab;                  // row of the chunk's first element (uniform)
     const int64_t baseA = tA * vocab;
     const int64_t bnd = baseA + vocab;                        // first element of row B
@@ -272,7 +275,7 @@ __global__ __launch_bounds__(256) void xent_bwd_flat_kernel(T* dlogits, const T*
         const float zero[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t q = pb + u * 256 + threadIdx.x;
+            const int64_t q = pb + u * kXbThreads + threadIdx.x;
             if (q < npacks) store8<T, kBwdNTS>(dlogits + q * kPack, zero);
         }
         return;
@@ -281,7 +284,7 @@ __global__ __launch_bounds__(256) void xent_bwd_flat_kernel(T* dlogits, const T*
     float h[U][8];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int64_t q = pb + u * 256 + threadIdx.x;
+        const int64_t q = pb + u * kXbThreads + threadIdx.x;
         const int64_t e0 = q * kPack;
         const bool need = q < npacks && ((e0 < bnd && liveA) || (e0 + kPack > bnd && liveB));
         if (need) {
@@ -293,7 +296,7 @@ __global__ __launch_bounds__(256) void xent_bwd_flat_kernel(T* dlogits, const T*
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int64_t q = pb + u * 256 + threadIdx.x;
+        const int64_t q = pb + u * kXbThreads + threadIdx.x;
         if (q >= npacks) continue;
         const int64_t e0 = q * kPack;
         float o[8];
@@ -644,18 +647,18 @@ static lsq_status xent_bwd_dispatch(void* dlogits, const void* logits, const flo
 {
     // the flat kernel needs chunk <= vocab (a chunk touches at most two rows): pick the unroll by vocab
     const int64_t npacks = tokens * vocab / kPack;
-    const int U = vocab >= 4 * 256 * kPack ? 4 : vocab >= 2 * 256 * kPack ? 2 : vocab >= 256 * kPack ? 1 : 0;
-    const int64_t blocks = U ? ceil_div(npacks, U * 256) : 0;
+    const int U = vocab >= 4 * kXbThreads * kPack ? 4 : vocab >= 2 * kXbThreads * kPack ? 2 : vocab >= kXbThreads * kPack ? 1 : 0;
+    const int64_t blocks = U ? ceil_div(npacks, U * kXbThreads) : 0;
     T* dp = static_cast<T*>(dlogits);
     const T* lp = static_cast<const T*>(logits);
     if (U == 4 && blocks <= 0x7FFFFFFF)
-        hipLaunchKernelGGL((xent_bwd_flat_kernel<T, 4>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, dp, lp, lse,
+        hipLaunchKernelGGL((xent_bwd_flat_kernel<T, 4>), dim3(static_cast<unsigned>(blocks)), dim3(kXbThreads), 0, s, dp, lp, lse,
                            target, tokens, vocab, alpha, ignore_index, grad_scale);
     else if (U == 2 && blocks <= 0x7FFFFFFF)
-        hipLaunchKernelGGL((xent_bwd_flat_kernel<T, 2>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, dp, lp, lse,
+        hipLaunchKernelGGL((xent_bwd_flat_kernel<T, 2>), dim3(static_cast<unsigned>(blocks)), dim3(kXbThreads), 0, s, dp, lp, lse,
                            target, tokens, vocab, alpha, ignore_index, grad_scale);
     else if (U == 1 && blocks <= 0x7FFFFFFF)
-        hipLaunchKernelGGL((xent_bwd_flat_kernel<T, 1>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, dp, lp, lse,
+        hipLaunchKernelGGL((xent_bwd_flat_kernel<T, 1>), dim3(static_cast<unsigned>(blocks)), dim3(kXbThreads), 0, s, dp, lp, lse,
                            target, tokens, vocab, alpha, ignore_index, grad_scale);
     else
         hipLaunchKernelGGL((xent_bwd_kernel<T>), dim3(static_cast<unsigned>(tokens)), dim3(kXentThreads), 0, s, dp, lp,

@@ -25,6 +25,10 @@
 #include "host.hpp"
 
 namespace lsq {
+// Threads per workgroup of the packed kernels (lanes per row <= 64: the waves of a workgroup share nothing).  The
+// backward is 2-3 % faster as one-wave workgroups (106 against 109 us at 8 x 20 x 1024 x 1024 causal, 62.6 against 64 us
+// with key padding at 512 keys, 16.8 against 17.1 us at 256 keys), the forward 3-4 % slower at 256 keys and equal elsewhere.
+constexpr int kSmWgFwd = 256, kSmWgBwd = 64;
 
 constexpr bool kNT = true;    // nontemporal hint on the streamed tensors
 
@@ -74,10 +78,10 @@ __device__ __forceinline__ int row_limit(const SoftmaxGeom& g, const SoftmaxLens
 // reduction, so a wave has RPT*VPL packs per lane in flight and the two dependent
 // round trips (lengths, then scores) are paid once per RPT rows.
 template <typename T, int LPR, int VPL, int RPT, bool DROP>
-__global__ __launch_bounds__(256) void softmax_fwd_kernel(T* y, T* __restrict__ yd, const T* x,
+__global__ __launch_bounds__(kSmWgFwd) void softmax_fwd_kernel(T* y, T* __restrict__ yd, const T* x,
                                                           SoftmaxLens len, SoftmaxGeom g, DropoutParams d)
 {
-    constexpr int RPB = 256 / LPR;
+    constexpr int RPB = kSmWgFwd / LPR;
     const int sub = threadIdx.x % LPR;
     const int nv = g.k_len / kPack;
     int64_t row[RPT];
@@ -175,10 +179,10 @@ __global__ __launch_bounds__(256) void softmax_fwd_kernel(T* y, T* __restrict__ 
 }
 
 template <typename T, int LPR, int VPL, int RPT, bool DROP>
-__global__ __launch_bounds__(256) void softmax_bwd_kernel(T* dx, const T* dy, const T* __restrict__ y,
+__global__ __launch_bounds__(kSmWgBwd) void softmax_bwd_kernel(T* dx, const T* dy, const T* __restrict__ y,
                                                           SoftmaxLens len, SoftmaxGeom g, DropoutParams d)
 {
-    constexpr int RPB = 256 / LPR;
+    constexpr int RPB = kSmWgBwd / LPR;
     const int sub = threadIdx.x % LPR;
     const int nv = g.k_len / kPack;
     int64_t row[RPT];
@@ -812,11 +816,11 @@ static lsq_status softmax_fwd_dispatch(void* y, void* yd, const void* x, Softmax
 #undef W
     if (sh.lpr == 256) return launch_status();
     const SmCand c = sm_choose(key_len, g, drop, sizeof(T), 0, forced);
-    const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(g.nrows, 256 / c.lpr), c.rpt)));
+    const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(g.nrows, kSmWgFwd / c.lpr), c.rpt)));
 #define X(L, V, R)                                                                                           \
     if (c.lpr == L && c.vpl == V && c.rpt == R) {                                                            \
-        if (drop) hipLaunchKernelGGL((softmax_fwd_kernel<T, L, V, R, true>), grid, block, 0, s, yp, ydp, xp, key_len, g, d); \
-        else hipLaunchKernelGGL((softmax_fwd_kernel<T, L, V, R, false>), grid, block, 0, s, yp, ydp, xp, key_len, g, d);    \
+        if (drop) hipLaunchKernelGGL((softmax_fwd_kernel<T, L, V, R, true>), grid, dim3(kSmWgFwd), 0, s, yp, ydp, xp, key_len, g, d); \
+        else hipLaunchKernelGGL((softmax_fwd_kernel<T, L, V, R, false>), grid, dim3(kSmWgFwd), 0, s, yp, ydp, xp, key_len, g, d);    \
     }
     LSQ_SM_CASES(X)
 #undef X
@@ -865,11 +869,11 @@ static lsq_status softmax_bwd_dispatch(void* dx, const void* dy, const void* y, 
 #undef W
     if (sh.lpr == 256) return launch_status();
     const SmCand c = sm_choose(key_len, g, drop, sizeof(T), 1, forced);
-    const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(g.nrows, 256 / c.lpr), c.rpt)));
+    const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(g.nrows, kSmWgBwd / c.lpr), c.rpt)));
 #define X(L, V, R)                                                                                           \
     if (c.lpr == L && c.vpl == V && c.rpt == R) {                                                            \
-        if (drop) hipLaunchKernelGGL((softmax_bwd_kernel<T, L, V, R, true>), grid, block, 0, s, dxp, dyp, yp, key_len, g, d); \
-        else hipLaunchKernelGGL((softmax_bwd_kernel<T, L, V, R, false>), grid, block, 0, s, dxp, dyp, yp, key_len, g, d);    \
+        if (drop) hipLaunchKernelGGL((softmax_bwd_kernel<T, L, V, R, true>), grid, dim3(kSmWgBwd), 0, s, dxp, dyp, yp, key_len, g, d); \
+        else hipLaunchKernelGGL((softmax_bwd_kernel<T, L, V, R, false>), grid, dim3(kSmWgBwd), 0, s, dxp, dyp, yp, key_len, g, d);    \
     }
     LSQ_SM_CASES(X)
 #undef X

@@ -9,8 +9,8 @@ from tests._util import dev, say
 
 pytestmark = pytest.mark.gpu
 
-TILE = 4096                       # bytes per workgroup
-GROUP = 8 * 256 * TILE            # bytes per group of eight runs of 256 tiles
+TILE = 1024                       # bytes per workgroup
+GROUP = 8 * 1024 * TILE           # bytes per group of eight runs of 1024 tiles
 
 
 @pytest.mark.parametrize("nbytes", [16, TILE, 3 * TILE + 48, GROUP, 2 * GROUP, 2 * GROUP + 5 * TILE + 16])
