@@ -131,22 +131,27 @@ __global__ __launch_bounds__(kSmWgFwd) void softmax_fwd_kernel(T* y, T* __restri
             live[k] = __ballot(j0 < lim) != 0;
             if (live[k]) {    // a pack that is masked for the whole wave costs no arithmetic
                 unpack<T>(raw[r][k], v[k]);
+                const int allowed = lim - j0;             // of this pack's 8 elements (<= 0: none, >= 8: all)
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    v[k][j] = (j0 + j < lim) ? v[k][j] * g.scale : -INFINITY;
+                    v[k][j] = (j < allowed) ? v[k][j] : -INFINITY;
                     mx = fmaxf(mx, v[k][j]);
                 }
             }
         }
+        // The scale is positive here (the dispatch sends other scales to the element kernels), so the maximum of the
+        // scaled scores is the scaled maximum and the scale folds into the exponent's fma: one multiplication per
+        // element less in a kernel that is bound by vector-ALU issue slots.
         mx = group_max<LPR>(mx);
-        const float mxs = (lim > 0 ? mx : 0.0f) * kLog2e;
+        const float c = g.scale * kLog2e;
+        const float mxs = (lim > 0 ? mx : 0.0f) * c;
         float z = 0.0f;
 #pragma unroll
         for (int k = 0; k < VPL; ++k) {
             if (live[k]) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const float e = __builtin_amdgcn_exp2f(fmaf(v[k][j], kLog2e, -mxs));   // exp2(-inf) = 0 on masked lanes
+                    const float e = __builtin_amdgcn_exp2f(fmaf(v[k][j], c, -mxs));   // exp2(-inf) = 0 on masked lanes
                     v[k][j] = e;
                     z += e;
                 }
@@ -781,7 +786,10 @@ static lsq_status softmax_fwd_dispatch(void* y, void* yd, const void* x, Softmax
     T* ydp = static_cast<T*>(yd);
     const T* xp = static_cast<const T*>(x);
     const bool packs_ok = g.k_len % kPack == 0 && aligned16(y) && aligned16(yd) && aligned16(x);
-    const SmShape sh = packs_ok ? softmax_shape(g.k_len) : SmShape{0, 0};
+    SmShape sh = packs_ok ? softmax_shape(g.k_len) : SmShape{0, 0};
+    // the packed kernel of rows up to 2048 keys folds the scale into its exponent and needs it positive;
+    // other scales (never an attention scale) take the element kernels, which multiply first
+    if (sh.lpr != 0 && sh.lpr <= 64 && !(g.scale > 0.0f)) sh = SmShape{0, 0};
     const bool drop = d.on != 0;
     const SmShape es = softmax_elem_shape(g.k_len);
     if (sh.lpr == 0 && es.lpr != 0) {

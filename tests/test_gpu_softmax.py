@@ -72,6 +72,30 @@ def test_softmax_fwd_bwd(B, N, Lq, Lk, mask, p, dt):
     assert torch.equal(dx, dx2)
 
 
+@pytest.mark.parametrize("scale", [-0.125, 0.0, 3.0])
+@pytest.mark.parametrize("B,N,Lq,Lk,mask,p", [(2, 2, 9, 128, "pad", 0.1), (1, 2, 5, 1024, "causal", 0.0), (2, 1, 3, 2048, "pad+causal", 0.1),
+                                              (1, 1, 3, 4096, "pad", 0.1)])
+def test_softmax_other_scales(B, N, Lq, Lk, mask, p, scale):
+    """The scale is any float by contract: negative and zero scales (rows of whole packs up to 2048 keys take
+    another kernel for them), and a large one that spreads the exponents."""
+    say(f"[softmax] scale={scale} B={B} N={N} Lq={Lq} Lk={Lk} mask={mask} p={p}")
+    dt = "f16"
+    t = attention_tensors(CONFIGS[0], dt, batch=B, heads=N, q_len=Lq, k_len=Lk, stream=900 + Lk)
+    key_len = t["key_len"] if "pad" in mask else None
+    causal = "causal" in mask
+    d = dev()
+    x, dy = to_torch(t["x"], dt, d), to_torch(t["dy"], dt, d)
+    kl = None if key_len is None else torch.from_numpy(key_len).to(d)
+    y, yd = L.lsq_softmax_fwd(x, kl, causal, scale, p, 77, 5)
+    ry, ryd = oracle.softmax_fwd(t["x"], key_len, causal, scale, dt, p, 77, 5)
+    assert_close_store(y, ry, dt, "y", f32_floor=1e-7)
+    if p > 0:
+        assert_close_store(yd, ryd, dt, "y_drop", f32_floor=1e-7)
+    dx = L.lsq_softmax_bwd(dy, y, kl, causal, scale, p, 77, 5)
+    rdx = oracle.softmax_bwd(t["dy"], from_torch(y, dt), key_len, causal, scale, dt, p, 77, 5)
+    assert_close_store(dx, rdx, dt, "dx", f32_floor=1e-7)
+
+
 def test_softmax_key_len_edge_values():
     say("[softmax] key_len 0, 1, beyond k_len, negative")
     d, dt = dev(), "f16"
