@@ -249,9 +249,10 @@ __global__ __launch_bounds__(kSmWgBwd) void softmax_bwd_kernel(T* dx, const T* d
                     for (int j = 0; j < 8; ++j) gv[k][j] *= kf[j];
                 }
             }
+            const int allowed = lim - j0;                 // of this pack's 8 elements (<= 0: none, >= 8: all)
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                if (j0 + j >= lim) { yv[k][j] = 0.0f; gv[k][j] = 0.0f; }      // whatever sits beyond the mask never counts
+                if (j >= allowed) { yv[k][j] = 0.0f; gv[k][j] = 0.0f; }       // whatever sits beyond the mask never counts
                 dot = fmaf(gv[k][j], yv[k][j], dot);
             }
         }
@@ -262,8 +263,8 @@ __global__ __launch_bounds__(kSmWgBwd) void softmax_bwd_kernel(T* dx, const T* d
             if (row[r] < g.nrows && idx < nv) {
                 float o[8];
 #pragma unroll
-                for (int j = 0; j < 8; ++j)      // outside the allowed set: +0, not the -0 a product could give
-                    o[j] = (idx * kPack + j < lim) ? g.scale * yv[k][j] * (gv[k][j] - dot) : 0.0f;
+                for (int j = 0; j < 8; ++j)      // outside the allowed set y and dy are zero here: the sum with +0 turns the product's -0 into +0
+                    o[j] = g.scale * yv[k][j] * (gv[k][j] - dot) + 0.0f;
                 store8<T, kNT>(dx + ro + idx * kPack, o);
             }
         }
