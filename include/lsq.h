@@ -401,7 +401,8 @@ lsq_status lsq_sgd_step(float* p, float* momentum_buf, const void* g, void* p_lp
  * an optional bias [parts*hidden], is written as `parts` tensors
  * out_k[batch, heads, len, head_dim] (k < parts; parts in 1..3: 3 for a fused QKV
  * projection).  hidden = heads*head_dim.  Unused out pointers may be NULL.
- * Without a bias the move is bit-exact. */
+ * Without a bias the move is bit-exact.  batch*len must be below 2^31 (LSQ_INVALID_ARG beyond;
+ * the same holds for the three calls that follow). */
 lsq_status lsq_split_heads_fwd(void* out0, void* out1, void* out2, const void* in, const void* bias,
                                int32_t batch, int32_t len, int32_t heads, int32_t head_dim,
                                int32_t parts, lsq_dtype dt, void* stream);

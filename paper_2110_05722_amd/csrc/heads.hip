@@ -22,6 +22,7 @@ struct HeadGeom {
     int len, heads, head_dim, parts;
     int hidden;            // heads * head_dim
     int ppr;               // packs per [T, parts*hidden] row
+    FastDiv by_len;        // token index -> sentence
 };
 
 template <typename T>
@@ -30,7 +31,8 @@ __device__ __forceinline__ T* pick(T* a, T* b, T* c, int part) { return part == 
 // element offset inside a [batch, heads, len, head_dim] tensor of column `within` (< hidden) of row t
 __device__ __forceinline__ int64_t head_offset(const HeadGeom& g, int64_t t, int within)
 {
-    const int64_t b = t / g.len;
+    // tokens of a call are below 2^31 (checked at the entry): the batch index comes from a reciprocal
+    const int64_t b = fastdiv(static_cast<uint32_t>(t), g.by_len);
     const int l = static_cast<int>(t - b * g.len);
     const int n = within / g.head_dim;
     const int dd = within - n * g.head_dim;
@@ -232,6 +234,8 @@ static lsq_status head_geom(HeadGeom* g, int32_t batch, int32_t len, int32_t hea
     const int64_t hidden = static_cast<int64_t>(heads) * head_dim;
     if (hidden * parts > 0x3FFFFFFF) return LSQ_INVALID_ARG;
     g->rows = static_cast<int64_t>(batch) * len;
+    if (g->rows > 0x7FFFFFFF) return LSQ_INVALID_ARG;
+    g->by_len = make_fastdiv(static_cast<uint32_t>(len));
     g->len = len; g->heads = heads; g->head_dim = head_dim; g->parts = parts;
     g->hidden = static_cast<int>(hidden);
     g->ppr = static_cast<int>(hidden * parts / kPack);

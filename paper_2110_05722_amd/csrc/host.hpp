@@ -56,6 +56,30 @@ inline lsq_status zero_fill(float* p, int64_t n, hipStream_t s)
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// Division of a row index (below 2^32) by a launch constant: multiply-high by a host-made reciprocal, two shifts
+// (Granlund and Montgomery's round-up form) -- 5 integer instructions where the 64-bit division the compiler emits
+// for an int64 row index takes about 40 per row (a tenth of a short softmax row's vector-ALU work).
+struct FastDiv {
+    uint32_t m;
+    int sh1, sh2;
+};
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    if (d == 0) d = 1;
+    int l = 0;
+    while ((1ull << l) < d) ++l;                                   // ceil(log2 d)
+    FastDiv f;
+    f.m = static_cast<uint32_t>(((1ull << 32) * ((1ull << l) - d)) / d + 1);
+    f.sh1 = l < 1 ? l : 1;
+    f.sh2 = l - f.sh1;
+    return f;
+}
+__device__ __forceinline__ uint32_t fastdiv(uint32_t n, const FastDiv& f)
+{
+    const uint32_t t = __umulhi(f.m, n);
+    return (t + ((n - t) >> f.sh1)) >> f.sh2;
+}
+
 // Second stage of the column reductions: out[c] = sum over the P partial rows of
 // partial[y][c], C columns, in a fixed order (reproducible).  Columns below `split`
 // go to out0, those below `split2` to out1, the rest to out2.  A workgroup owns 32 columns; its 8 row slices each

@@ -34,30 +34,6 @@ constexpr bool kNT = true;    // nontemporal hint on the streamed tensors
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-// Division of a row index (below 2^32) by a launch constant: multiply-high by a host-made reciprocal, two shifts
-// (Granlund and Montgomery's round-up form) -- 5 integer instructions where the 64-bit division the compiler emits
-// for `row / heads*q_len` and `row % q_len` took about 40 per row, a tenth of a short row's vector-ALU work.
-struct FastDiv {
-    uint32_t m;
-    int sh1, sh2;
-};
-inline FastDiv make_fastdiv(uint32_t d)
-{
-    if (d == 0) d = 1;
-    int l = 0;
-    while ((1ull << l) < d) ++l;                                   // ceil(log2 d)
-    FastDiv f;
-    f.m = static_cast<uint32_t>(((1ull << 32) * ((1ull << l) - d)) / d + 1);
-    f.sh1 = l < 1 ? l : 1;
-    f.sh2 = l - f.sh1;
-    return f;
-}
-__device__ __forceinline__ uint32_t fastdiv(uint32_t n, const FastDiv& f)
-{
-    const uint32_t t = __umulhi(f.m, n);
-    return (t + ((n - t) >> f.sh1)) >> f.sh2;
-}
-
 struct SoftmaxGeom {
     int64_t nrows;        // batch * heads * q_len (below 2^31)
     int rows_per_batch;   // heads * q_len
