@@ -33,7 +33,7 @@ template <typename T, bool DROP>
 __global__ __launch_bounds__(256) void emb_fwd_cols(T* __restrict__ out, const int32_t* __restrict__ tokens,
                                                     const T* __restrict__ emb, const T* __restrict__ pos, int64_t rows,
                                                     int len, int ppr, int vocab, int pad_idx, float scale,
-                                                    DropoutParams d)
+                                                    DropoutParams d, FastDiv by_len)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int cp = blockIdx.x * 64 + lane;
@@ -44,7 +44,8 @@ __global__ __launch_bounds__(256) void emb_fwd_cols(T* __restrict__ out, const i
         const int64_t pack = t * ppr + cp;
         float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         if (!emb_is_pad(w, vocab, pad_idx)) {
-            const int l = static_cast<int>(t % len);
+            const uint32_t t32 = static_cast<uint32_t>(t);           // tokens of a call are below 2^31 (checked at the entry)
+            const int l = static_cast<int>(t32 - fastdiv(t32, by_len) * static_cast<uint32_t>(len));
             float e[8], pp[8];
             load8<T>(emb + (static_cast<int64_t>(w) * ppr + cp) * kPack, e);
             load8<T>(pos + (static_cast<int64_t>(l) * ppr + cp) * kPack, pp);
@@ -613,8 +614,9 @@ static lsq_status emb_fwd_dispatch(void* out, const int32_t* tokens, const void*
         int64_t rb = ceil_div(rows, kEmbWaves);
         if (rb > 16384) rb = 16384;
         const dim3 grid(static_cast<unsigned>(ceil_div(ppr, 64)), static_cast<unsigned>(rb)), block(256);
-        if (d.on) hipLaunchKernelGGL((emb_fwd_cols<T, true>), grid, block, 0, s, o, tokens, e, p, rows, len, ppr, vocab, pad_idx, scale, d);
-        else hipLaunchKernelGGL((emb_fwd_cols<T, false>), grid, block, 0, s, o, tokens, e, p, rows, len, ppr, vocab, pad_idx, scale, d);
+        const FastDiv by_len = make_fastdiv(static_cast<uint32_t>(len));
+        if (d.on) hipLaunchKernelGGL((emb_fwd_cols<T, true>), grid, block, 0, s, o, tokens, e, p, rows, len, ppr, vocab, pad_idx, scale, d, by_len);
+        else hipLaunchKernelGGL((emb_fwd_cols<T, false>), grid, block, 0, s, o, tokens, e, p, rows, len, ppr, vocab, pad_idx, scale, d, by_len);
     } else {
         hipLaunchKernelGGL((emb_fwd_flat<T>), dim3(static_cast<unsigned>(ceil_div(rows * hidden, 256))), dim3(256), 0, s,
                            o, tokens, e, p, rows, len, hidden, vocab, pad_idx, scale, d);
@@ -711,6 +713,7 @@ extern "C" lsq_status lsq_embedding_fwd(void* out, const int32_t* tokens, const 
     if (rows == 0) return LSQ_OK;
     LSQ_REQUIRE(out && tokens && emb && pos);
     LSQ_ALIGNED(out); LSQ_ALIGNED(emb); LSQ_ALIGNED(pos);
+    LSQ_REQUIRE(rows <= 0x7FFFFFFF);
     LSQ_REQUIRE(ceil_div(rows * hidden, 256) <= 0x7FFFFFFF);
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (dt) {

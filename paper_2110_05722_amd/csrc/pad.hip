@@ -23,6 +23,7 @@ struct PadGeom {
     int64_t packed_rows;    // capacity of the packed tensor, rows
     int batch, max_len, hidden;
     int ppr;                // packs per row (hidden / 8), pack path only
+    FastDiv by_max_len;     // padded row -> sentence (rows are below 2^31)
 };
 
 // offsets[b] = number of real rows before sentence b; offsets[batch] = total.  One
@@ -63,7 +64,7 @@ __global__ __launch_bounds__(256) void pad_offsets_kernel(int32_t* __restrict__ 
 __device__ __forceinline__ int64_t packed_row(const PadGeom& g, const int32_t* __restrict__ offsets, int64_t t)
 {
     if (t >= g.rows) return -1;
-    const int b = static_cast<int>(t / g.max_len);
+    const int b = static_cast<int>(fastdiv(static_cast<uint32_t>(t), g.by_max_len));
     const int i = static_cast<int>(t - static_cast<int64_t>(b) * g.max_len);
     const int first = offsets[b];
     const int lb = min(offsets[b + 1] - first, g.max_len);
@@ -148,6 +149,7 @@ static lsq_status pad_geom(PadGeom* g, int32_t batch, int32_t max_len, int32_t h
     if (g->rows > 0x7FFFFFFF) return LSQ_INVALID_ARG;          // offsets are int32
     g->packed_rows = packed_rows;
     g->batch = batch; g->max_len = max_len; g->hidden = hidden;
+    g->by_max_len = make_fastdiv(static_cast<uint32_t>(max_len));
     g->ppr = hidden / kPack;
     if (ceil_div(g->rows * hidden, 256) > 0x7FFFFFFF) return LSQ_INVALID_ARG;
     return LSQ_OK;
