@@ -174,7 +174,9 @@ lsq_status lsq_bias_dropout_residual_bwd(void* dx, float* dbias, const void* dy,
  * key_len: nullable int32[batch] (NULL = every key allowed), values clamped to
  * [0, k_len].  y_drop must be non-NULL iff p_attn > 0.  y may alias x.
  * Speed: key axes that are a multiple of 8 (any length up to 16384) take the 128-bit
- * register paths; other lengths up to 2048 go through LDS staging, 10-30 % slower. */
+ * register paths; other lengths up to 2048 go through LDS staging, 10-30 % slower.
+ * scale: any finite value; a scale that is not positive (never an attention scale) takes
+ * the LDS-staging kernels as well.  batch*heads*q_len must be below 2^31. */
 lsq_status lsq_softmax_fwd(void* y, void* y_drop, const void* x, const int32_t* key_len,
                            int32_t batch, int32_t heads, int32_t q_len, int32_t k_len,
                            int32_t causal, float scale,
